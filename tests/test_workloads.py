@@ -1,0 +1,40 @@
+"""Layer tables and seeded generators: shapes, MAC counts, determinism.  No GPU."""
+import numpy as np
+
+from workloads import inputs, nets
+
+
+def test_resnet18_table():
+    ops = nets.resnet18()
+    convs = [o for o in ops if o.kind == "conv"]
+    assert len(convs) == 20
+    shp = nets.trace_shapes(ops, 224, 224)
+    assert shp["c1"] == (64, 112, 112) and shp["s1.in"] == (64, 56, 56)
+    assert shp["l4.b1.out"] == (512, 7, 7) and shp["logits"] == (1000, 1, 1)
+    macs = nets.macs_per_image(nets.resnet18(with_dense=False), 224, 224)
+    assert abs(macs / 1e6 - 1813.6) < 0.1                      # standard ResNet-18 conv MACs
+    assert sum(1 for o in convs if o.res) == 8 and sum(1 for o in convs if not o.relu) == 3
+
+
+def test_mobilenet_v1_table():
+    ops = nets.mobilenet_v1()
+    assert sum(1 for o in ops if o.kind == "dwconv") == 13
+    shp = nets.trace_shapes(ops, 224, 224)
+    assert shp["b13.out"] == (1024, 7, 7)
+    macs = nets.macs_per_image(nets.mobilenet_v1(with_dense=False), 224, 224)
+    assert abs(macs / 1e6 - 567.7) < 0.1
+    dw = sum(shp[o.dst][0] * shp[o.dst][1] * shp[o.dst][2] * 9 for o in ops if o.kind == "dwconv")
+    assert abs(dw / 1e6 - 17.4) < 0.1
+
+
+def test_generators_are_seeded_and_typed():
+    op = nets.resnet18()[0]
+    a = inputs.layer_params(op, 3, 0, "f16")
+    b = inputs.layer_params(op, 3, 0, "f16")
+    assert a["w"].dtype == np.float16 and np.array_equal(a["w"], b["w"]) and a["scale"].dtype == np.float32
+    assert abs(float(a["w"].astype(np.float64).std()) - (2 / 147) ** 0.5) < 0.01
+    q = inputs.layer_params(op, 4, 0, "i8")
+    assert q["w"].dtype == np.int8 and q["w"].min() >= -127 and "scale" not in q
+    x = inputs.image(1, 1, 3, 32, 32, "f32")
+    assert x.dtype == np.float32 and x.min() >= -1 and x.max() < 1
+    assert inputs.default_out_rshift(576) == 12 and inputs.default_out_rshift(147) == 11

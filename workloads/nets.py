@@ -1,0 +1,129 @@
+"""Layer tables of the vision networks the paper evaluates (Section 5, "vision" workloads).
+
+The paper names ResNet-18 and MobileNet but does not list their layers; the tables
+here are the standard published definitions of those architectures (shapes only).
+A network is a list of op records over named tensors.  A record holds shapes and
+which elementwise operators are fused behind the contraction -- no arithmetic.
+
+Every conv record describes one *fused primitive function* in the sense of the
+paper's operator-fusion section: the contraction plus the elementwise operators
+that post-dominate it (bias add, folded batch-norm scale/shift, residual add, relu).
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import List, Optional
+
+
+@dataclass(frozen=True)
+class Op:
+    kind: str                 # "conv" | "dwconv" | "dense" | "maxpool" | "avgpool"
+    name: str
+    src: str                  # input tensor name
+    dst: str                  # output tensor name
+    cin: int = 0
+    cout: int = 0
+    r: int = 1                # square kernel
+    stride: int = 1
+    pad: int = 0
+    bias: bool = False
+    bn: bool = False
+    relu: bool = False
+    res: Optional[str] = None  # tensor added before relu (residual), or None
+
+
+def conv(name, src, dst, cin, cout, r, stride, pad, *, bn=True, relu=True, res=None, bias=False):
+    return Op("conv", name, src, dst, cin, cout, r, stride, pad, bias, bn, relu, res)
+
+
+def resnet18(with_dense: bool = True) -> List[Op]:
+    """20 fused convs (+ maxpool, global average pool and the 512->1000 dense)."""
+    ops: List[Op] = [
+        conv("conv1", "x", "c1", 3, 64, 7, 2, 3),
+        Op("maxpool", "maxpool", "c1", "s1.in", cin=64, cout=64, r=3, stride=2, pad=1),
+    ]
+    cin = 64
+    cur = "s1.in"
+    for stage, cout in enumerate((64, 128, 256, 512), start=1):
+        for blk in range(2):
+            stride = 2 if (stage > 1 and blk == 0) else 1
+            p = f"l{stage}.b{blk}"
+            ops.append(conv(f"{p}.conv1", cur, f"{p}.t", cin, cout, 3, stride, 1))
+            if stride != 1 or cin != cout:
+                ops.append(conv(f"{p}.down", cur, f"{p}.d", cin, cout, 1, stride, 0, relu=False))
+                shortcut = f"{p}.d"
+            else:
+                shortcut = cur
+            ops.append(conv(f"{p}.conv2", f"{p}.t", f"{p}.out", cout, cout, 3, 1, 1, res=shortcut))
+            cur = f"{p}.out"
+            cin = cout
+    if with_dense:
+        ops.append(Op("avgpool", "avgpool", cur, "pooled", cin=512, cout=512))
+        ops.append(Op("dense", "fc", "pooled", "logits", cin=512, cout=1000, bias=True))
+    return ops
+
+
+MOBILENET_V1_BLOCKS = (
+    # (cin, cout, depthwise stride)
+    (32, 64, 1), (64, 128, 2), (128, 128, 1), (128, 256, 2), (256, 256, 1), (256, 512, 2),
+    (512, 512, 1), (512, 512, 1), (512, 512, 1), (512, 512, 1), (512, 512, 1),
+    (512, 1024, 2), (1024, 1024, 1),
+)
+
+
+def mobilenet_v1(with_dense: bool = True) -> List[Op]:
+    """3x3/s2 stem, 13 depthwise-separable blocks, global average pool, 1024->1000 dense."""
+    ops: List[Op] = [conv("stem", "x", "b0.out", 3, 32, 3, 2, 1)]
+    cur = "b0.out"
+    for i, (cin, cout, s) in enumerate(MOBILENET_V1_BLOCKS, start=1):
+        ops.append(Op("dwconv", f"b{i}.dw", cur, f"b{i}.t", cin=cin, cout=cin, r=3, stride=s,
+                      pad=1, bn=True, relu=True))
+        ops.append(conv(f"b{i}.pw", f"b{i}.t", f"b{i}.out", cin, cout, 1, 1, 0))
+        cur = f"b{i}.out"
+    if with_dense:
+        ops.append(Op("avgpool", "avgpool", cur, "pooled", cin=1024, cout=1024))
+        ops.append(Op("dense", "fc", "pooled", "logits", cin=1024, cout=1000, bias=True))
+    return ops
+
+
+def basic_block(c: int = 64) -> List[Op]:
+    """One ResNet basic block at constant width (the two-conv diamond with a residual edge)."""
+    return [
+        conv("blk.conv1", "x", "blk.t", c, c, 3, 1, 1),
+        conv("blk.conv2", "blk.t", "blk.out", c, c, 3, 1, 1, res="x"),
+    ]
+
+
+def out_hw(h: int, r: int, stride: int, pad: int) -> int:
+    return (h + 2 * pad - r) // stride + 1
+
+
+def trace_shapes(ops: List[Op], h: int, w: int, c: int = 3):
+    """Spatial size and channel count of every named tensor: {name: (C, H, W)}."""
+    shp = {"x": (c, h, w)}
+    for op in ops:
+        ci, hi, wi = shp[op.src]
+        if op.kind in ("conv", "dwconv", "maxpool"):
+            shp[op.dst] = (op.cout, out_hw(hi, op.r, op.stride, op.pad), out_hw(wi, op.r, op.stride, op.pad))
+        elif op.kind == "avgpool":
+            shp[op.dst] = (ci, 1, 1)
+        elif op.kind == "dense":
+            shp[op.dst] = (op.cout, 1, 1)
+        else:
+            raise ValueError(op.kind)
+    return shp
+
+
+def macs_per_image(ops: List[Op], h: int, w: int, c: int = 3) -> int:
+    """Multiply-accumulates of the contractions only (epilogues and pools not counted)."""
+    shp = trace_shapes(ops, h, w, c)
+    total = 0
+    for op in ops:
+        co, ho, wo = shp[op.dst]
+        if op.kind == "conv":
+            total += co * ho * wo * op.cin * op.r * op.r
+        elif op.kind == "dwconv":
+            total += co * ho * wo * op.r * op.r
+        elif op.kind == "dense":
+            total += op.cin * op.cout
+    return total
