@@ -1,0 +1,148 @@
+/*
+ * relay_fused.h -- C ABI of the fused primitive operators for MI355X (gfx950).
+ *
+ * A "fused primitive function" is what the paper's operator-fusion pass produces
+ * (Section 4.1, "Extraction"): a contraction (conv2d, depthwise conv2d, dense) together
+ * with the elementwise operators that post-dominate it, factored into one function whose
+ * parameters are the group's free variables.  The compiled form of such a function uses
+ * a fixed calling convention and preallocated inputs and outputs (Section 3.3,
+ * "Backends"); the entry points below are that calling convention.
+ *
+ * Conventions common to every entry point
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library never
+ *     allocates, frees or synchronises; work is enqueued on `hip_stream` (a hipStream_t
+ *     passed as void*, NULL = the default stream) and the call returns at once.
+ *   - Shapes are static and carried by value in the descriptor (the paper's lowered code
+ *     is shape specific, Section 4.1 "Lowering").
+ *   - Optional operands are NULL exactly when their flag bit is clear; a mismatch is
+ *     RELAY_ERR_NULL.  Outputs must not alias inputs.
+ *   - All argument checks run on the host before any HIP call.  A failed check returns
+ *     a status and leaves a message for relay_last_error(); nothing is launched.
+ *   - No C++ exception crosses this boundary.
+ */
+#ifndef RELAY_FUSED_H_
+#define RELAY_FUSED_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  RELAY_OK = 0,
+  RELAY_ERR_NULL = 1,        /* a required pointer is NULL, or an optional one disagrees with flags */
+  RELAY_ERR_SHAPE = 2,       /* a non-positive extent, an empty output, padding >= kernel ... */
+  RELAY_ERR_DTYPE = 3,       /* dtype not valid for this entry point */
+  RELAY_ERR_UNSUPPORTED = 4, /* a valid request this build has no kernel for */
+  RELAY_ERR_ALIGN = 5,       /* pointer or channel count not aligned for vector access */
+  RELAY_ERR_WORKSPACE = 6,   /* workspace smaller than relay_workspace_bytes() asks */
+  RELAY_ERR_DEVICE = 7       /* the HIP runtime refused the launch */
+} relay_status;
+
+typedef enum { RELAY_F32 = 0, RELAY_F16 = 1, RELAY_I8 = 2 } relay_dtype;
+typedef enum { RELAY_NCHW = 0, RELAY_NHWC = 1 } relay_layout;
+
+/* which elementwise operators are fused behind the contraction */
+enum { RELAY_HAS_BIAS = 1, RELAY_HAS_BN = 2, RELAY_HAS_RESIDUAL = 4, RELAY_RELU = 8 };
+
+/* Static type of a conv2d primitive function.  Dilation is 1.  Input [n,c,h,w], filters
+ * [k,c,r,s] (depthwise: k == c, one [r,s] filter per channel).
+ * Supported (dtype, layout): (F32, NCHW) direct kernel; (F16, NHWC) and (I8, NHWC)
+ * implicit-GEMM MFMA kernels, which need c % 8 == 0 (F16) or c % 16 == 0 (I8): pad the
+ * channel axis with zeros (relay_nchw_to_nhwc does). */
+typedef struct {
+  int32_t n, c, h, w;
+  int32_t k, r, s;
+  int32_t stride_h, stride_w, pad_h, pad_w;
+  int32_t dtype;   /* relay_dtype  */
+  int32_t layout;  /* relay_layout */
+  uint32_t flags;  /* RELAY_HAS_* | RELAY_RELU */
+} relay_conv2d_desc;
+
+/* Ho = floor((h + 2*pad_h - r)/stride_h) + 1, Wo likewise.  Validates the geometry. */
+relay_status relay_conv2d_out_shape(const relay_conv2d_desc* d, int32_t* ho, int32_t* wo);
+
+/* Bytes of device scratch the conv entry points need for this descriptor (may be 0). */
+relay_status relay_workspace_bytes(const relay_conv2d_desc* d, size_t* bytes);
+
+/* Size of the packed filter tensor, and the packing itself -- compile-time work in the
+ * paper's terms (constant folding and layout alteration, Sections 3.3 and 5.3).
+ * w_oihw: device, [k, c_src, r, s] in the descriptor's dtype with c_src <= d->c (channels
+ * c_src..c-1 are filled with zeros).  w_packed: device, packed_bytes >= the size reported.
+ * NHWC kernels read [k][r][s][c] with the reduction axis zero-padded to a whole number of
+ * 64-byte chunks; the NCHW F32 kernel reads OIHW unchanged. */
+relay_status relay_packed_weight_bytes(const relay_conv2d_desc* d, size_t* bytes);
+relay_status relay_prepack_conv2d_weights(const relay_conv2d_desc* d, const void* w_oihw, int32_t c_src,
+                                          void* w_packed, size_t packed_bytes, void* hip_stream);
+
+/* conv2d -> [+bias[k]] -> [*bn_scale[k] + bn_shift[k]] -> [+residual] -> [relu] -> cast.
+ * (paper Section 4.1; the order is this library's reading, the paper leaves it open.)
+ * dtype F32 (NCHW) or F16 (NHWC, fp32 accumulation, output rounded to nearest even).
+ * x [n,c,h,w]; residual and y [n,k,ho,wo] in the descriptor's layout and dtype;
+ * bias / bn_scale / bn_shift: fp32 [k].  F16: x, w_packed, residual, y 16-byte aligned. */
+relay_status relay_fused_conv2d_bias_bn_relu(const relay_conv2d_desc* d, const void* x, const void* w_packed,
+                                             const float* bias, const float* bn_scale, const float* bn_shift,
+                                             const void* residual, void* y, void* workspace,
+                                             size_t workspace_bytes, void* hip_stream);
+
+/* Quantized conv2d (paper Section 4.2, "Realize": Q = cast(clip(round(x * 2^-s)))
+ * expanded into elementwise operators and fused behind the convolution):
+ *   acc = conv2d(x_i8, w_i8) in int32  [+ bias[k]]  [+ residual_i8 * 2^residual_lshift]
+ *   q   = out_rshift == 0 ? acc : (acc + 2^(out_rshift-1)) >> out_rshift   (arithmetic shift:
+ *         round to nearest, ties toward +infinity)
+ *   q   = min(max(q, -127), 127);  [relu: q = max(q, 0)];  y = (int8) q
+ * d->dtype == RELAY_I8, layout NHWC, d->flags may hold HAS_BIAS | HAS_RESIDUAL | RELU.
+ * 0 <= out_rshift <= 31, 0 <= residual_lshift <= 23.  Precondition: |acc| < 2^31 (wraps
+ * silently otherwise). */
+relay_status relay_qconv2d_requant(const relay_conv2d_desc* d, const int8_t* x, const int8_t* w_packed,
+                                   const int32_t* bias, const int8_t* residual, int32_t residual_lshift,
+                                   int32_t out_rshift, int8_t* y, void* workspace, size_t workspace_bytes,
+                                   void* hip_stream);
+
+/* Depthwise conv2d (k == c) -> [+bias] -> [*scale + shift] -> [relu] -> cast.  F16 NHWC,
+ * c % 8 == 0, fp32 accumulation.  w_rsc: filters repacked [r][s][c] by
+ * relay_prepack_dwconv_weights from [c][r][s]. */
+relay_status relay_prepack_dwconv_weights(const relay_conv2d_desc* d, const void* w_crs, void* w_rsc,
+                                          void* hip_stream);
+relay_status relay_fused_dwconv_bias_relu(const relay_conv2d_desc* d, const void* x, const void* w_rsc,
+                                          const float* bias, const float* bn_scale, const float* bn_shift,
+                                          void* y, void* hip_stream);
+
+/* dense: y[m,j] = sum_i x[m,i] * w[j,i]  [+ bias[j]]  [act: 0 none, 1 relu].
+ * dtype F16 (fp32 accumulation; k % 8 == 0, x and w 16-byte aligned) or F32.
+ * x [m,k], w [n,k] (one row per output unit), bias fp32 [n] or NULL, y [m,n]. */
+relay_status relay_fused_dense_bias_act(int32_t m, int32_t n, int32_t k, int32_t dtype, const void* x,
+                                        const void* w, const float* bias, int32_t act, void* y,
+                                        void* hip_stream);
+
+/* Operators that only chain real layer shapes (standard architectures, not the paper's
+ * subject).  NHWC; F16 needs c % 8 == 0, I8 c % 16 == 0. */
+relay_status relay_maxpool2d(int32_t dtype, int32_t n, int32_t c, int32_t h, int32_t w, int32_t r,
+                             int32_t stride, int32_t pad, const void* x, void* y, void* hip_stream);
+relay_status relay_global_avgpool(int32_t dtype, int32_t n, int32_t c, int32_t hw, const void* x, void* y,
+                                  void* hip_stream);
+/* [n,c,h,w] -> [n,h,w,c_pad], channels c..c_pad-1 zero.  Any dtype; c_pad >= c. */
+relay_status relay_nchw_to_nhwc(int32_t dtype, int32_t n, int32_t c, int32_t h, int32_t w, int32_t c_pad,
+                                const void* x, void* y, void* hip_stream);
+
+/* Tuning aid: force the implicit-GEMM workgroup tile of later fp16 / int8 conv calls made
+ * by this process (0 .. count-1, largest first; negative = choose by layer shape, the
+ * default).  Results do not depend on the tile (int8: bit for bit). */
+relay_status relay_set_conv_tile(int32_t tile);
+
+/* Profiling aid: which implicit-GEMM kernel variant a fp16 / int8 descriptor runs on --
+ * workgroup tile (bm output pixels x bn output channels), its wave grid, and whether the
+ * reduction chunks align with filter taps (fast = 1).  The kernel is
+ * igemm_conv_kernel<is_i8, bm, bn, waves_m, waves_n, fast> in a kernel trace. */
+relay_status relay_conv2d_kernel_info(const relay_conv2d_desc* d, int32_t* bm, int32_t* bn, int32_t* waves_m,
+                                      int32_t* waves_n, int32_t* fast);
+
+/* Message of the calling thread's last failed call (static storage, never NULL). */
+const char* relay_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RELAY_FUSED_H_ */

@@ -1,0 +1,176 @@
+"""ctypes binding of librelayfused.so: argument marshalling only.
+
+Each function has the name of the C entry point it calls (include/relay_fused.h) and
+takes torch tensors on the GPU purely as (pointer, shape) carriers; PyTorch supplies device
+memory and the stream, every step of the computation runs in the library's own kernels.
+There is no fallback: if the library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librelayfused.so")
+
+RELAY_F32, RELAY_F16, RELAY_I8 = 0, 1, 2
+RELAY_NCHW, RELAY_NHWC = 0, 1
+HAS_BIAS, HAS_BN, HAS_RESIDUAL, RELU = 1, 2, 4, 8
+
+STATUS_NAMES = {0: "RELAY_OK", 1: "RELAY_ERR_NULL", 2: "RELAY_ERR_SHAPE", 3: "RELAY_ERR_DTYPE",
+                4: "RELAY_ERR_UNSUPPORTED", 5: "RELAY_ERR_ALIGN", 6: "RELAY_ERR_WORKSPACE",
+                7: "RELAY_ERR_DEVICE"}
+
+
+class RelayError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{STATUS_NAMES.get(status, status)}: {message}")
+        self.status = status
+
+
+class ConvDesc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n", "c", "h", "w", "k", "r", "s", "stride_h", "stride_w",
+                                         "pad_h", "pad_w", "dtype", "layout")] + [("flags", C.c_uint32)]
+
+
+_lib = None
+
+# name -> argtypes; every symbol the header declares
+_P, _I, _SZ = C.c_void_p, C.c_int32, C.c_size_t
+_DP = C.POINTER(ConvDesc)
+SIGNATURES = {
+    "relay_conv2d_out_shape": [_DP, C.POINTER(_I), C.POINTER(_I)],
+    "relay_workspace_bytes": [_DP, C.POINTER(_SZ)],
+    "relay_packed_weight_bytes": [_DP, C.POINTER(_SZ)],
+    "relay_prepack_conv2d_weights": [_DP, _P, _I, _P, _SZ, _P],
+    "relay_fused_conv2d_bias_bn_relu": [_DP, _P, _P, _P, _P, _P, _P, _P, _P, _SZ, _P],
+    "relay_qconv2d_requant": [_DP, _P, _P, _P, _P, _I, _I, _P, _P, _SZ, _P],
+    "relay_prepack_dwconv_weights": [_DP, _P, _P, _P],
+    "relay_fused_dwconv_bias_relu": [_DP, _P, _P, _P, _P, _P, _P, _P],
+    "relay_fused_dense_bias_act": [_I, _I, _I, _I, _P, _P, _P, _I, _P, _P],
+    "relay_maxpool2d": [_I, _I, _I, _I, _I, _I, _I, _I, _P, _P, _P],
+    "relay_global_avgpool": [_I, _I, _I, _I, _P, _P, _P],
+    "relay_nchw_to_nhwc": [_I, _I, _I, _I, _I, _I, _P, _P, _P],
+    "relay_set_conv_tile": [_I],
+    "relay_conv2d_kernel_info": [_DP] + [C.POINTER(_I)] * 5,
+}
+
+
+def lib():
+    """Load the library (built in-tree by build.py); fail loudly if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        l = C.CDLL(LIB_PATH)
+        for name, argtypes in SIGNATURES.items():
+            fn = getattr(l, name)
+            fn.argtypes = argtypes
+            fn.restype = C.c_int
+        l.relay_last_error.restype = C.c_char_p
+        l.relay_last_error.argtypes = []
+        _lib = l
+    return _lib
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise RelayError(status, lib().relay_last_error().decode())
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream() -> Optional[int]:
+    import torch
+    return torch.cuda.current_stream().cuda_stream or None
+
+
+def conv_desc(n, c, h, w, k, r, s, stride, pad, dtype, layout, flags) -> ConvDesc:
+    sh, sw = (stride, stride) if isinstance(stride, int) else stride
+    ph, pw = (pad, pad) if isinstance(pad, int) else pad
+    return ConvDesc(n, c, h, w, k, r, s, sh, sw, ph, pw, dtype, layout, flags)
+
+
+def flags_of(bias=None, bn_scale=None, residual=None, relu=False) -> int:
+    return ((HAS_BIAS if bias is not None else 0) | (HAS_BN if bn_scale is not None else 0) |
+            (HAS_RESIDUAL if residual is not None else 0) | (RELU if relu else 0))
+
+
+# --------------------------------------------------------------------------- entry points
+def relay_conv2d_out_shape(d: ConvDesc) -> Tuple[int, int]:
+    ho, wo = _I(), _I()
+    _check(lib().relay_conv2d_out_shape(C.byref(d), C.byref(ho), C.byref(wo)))
+    return ho.value, wo.value
+
+
+def relay_workspace_bytes(d: ConvDesc) -> int:
+    b = _SZ()
+    _check(lib().relay_workspace_bytes(C.byref(d), C.byref(b)))
+    return b.value
+
+
+def relay_packed_weight_bytes(d: ConvDesc) -> int:
+    b = _SZ()
+    _check(lib().relay_packed_weight_bytes(C.byref(d), C.byref(b)))
+    return b.value
+
+
+def relay_prepack_conv2d_weights(d: ConvDesc, w_oihw, c_src: int, w_packed) -> None:
+    _check(lib().relay_prepack_conv2d_weights(C.byref(d), _ptr(w_oihw), c_src, _ptr(w_packed),
+                                              w_packed.numel() * w_packed.element_size(), _stream()))
+
+
+def relay_fused_conv2d_bias_bn_relu(d: ConvDesc, x, w_packed, bias, bn_scale, bn_shift, residual, y,
+                                    workspace=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().relay_fused_conv2d_bias_bn_relu(C.byref(d), _ptr(x), _ptr(w_packed), _ptr(bias), _ptr(bn_scale),
+                                                 _ptr(bn_shift), _ptr(residual), _ptr(y), _ptr(workspace),
+                                                 ws_bytes, _stream()))
+
+
+def relay_qconv2d_requant(d: ConvDesc, x, w_packed, bias, residual, residual_lshift: int, out_rshift: int, y,
+                          workspace=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().relay_qconv2d_requant(C.byref(d), _ptr(x), _ptr(w_packed), _ptr(bias), _ptr(residual),
+                                       residual_lshift, out_rshift, _ptr(y), _ptr(workspace), ws_bytes, _stream()))
+
+
+def relay_prepack_dwconv_weights(d: ConvDesc, w_crs, w_rsc) -> None:
+    _check(lib().relay_prepack_dwconv_weights(C.byref(d), _ptr(w_crs), _ptr(w_rsc), _stream()))
+
+
+def relay_fused_dwconv_bias_relu(d: ConvDesc, x, w_rsc, bias, bn_scale, bn_shift, y) -> None:
+    _check(lib().relay_fused_dwconv_bias_relu(C.byref(d), _ptr(x), _ptr(w_rsc), _ptr(bias), _ptr(bn_scale),
+                                              _ptr(bn_shift), _ptr(y), _stream()))
+
+
+def relay_fused_dense_bias_act(m: int, n: int, k: int, dtype: int, x, w, bias, act: int, y) -> None:
+    _check(lib().relay_fused_dense_bias_act(m, n, k, dtype, _ptr(x), _ptr(w), _ptr(bias), act, _ptr(y), _stream()))
+
+
+def relay_maxpool2d(dtype, n, c, h, w, r, stride, pad, x, y) -> None:
+    _check(lib().relay_maxpool2d(dtype, n, c, h, w, r, stride, pad, _ptr(x), _ptr(y), _stream()))
+
+
+def relay_global_avgpool(dtype, n, c, hw, x, y) -> None:
+    _check(lib().relay_global_avgpool(dtype, n, c, hw, _ptr(x), _ptr(y), _stream()))
+
+
+def relay_nchw_to_nhwc(dtype, n, c, h, w, c_pad, x, y) -> None:
+    _check(lib().relay_nchw_to_nhwc(dtype, n, c, h, w, c_pad, _ptr(x), _ptr(y), _stream()))
+
+
+def relay_conv2d_kernel_info(d: ConvDesc) -> dict:
+    v = [_I() for _ in range(5)]
+    _check(lib().relay_conv2d_kernel_info(C.byref(d), *[C.byref(t) for t in v]))
+    bm, bn, wm, wn, fast = (t.value for t in v)
+    is_i8 = "true" if d.dtype == RELAY_I8 else "false"
+    return {"bm": bm, "bn": bn, "waves_m": wm, "waves_n": wn, "fast": bool(fast),
+            "kernel": f"igemm_conv_kernel<{is_i8}, {bm}, {bn}, {wm}, {wn}, {'true' if fast else 'false'}>"}
+
+
+def relay_set_conv_tile(tile: int) -> None:
+    _check(lib().relay_set_conv_tile(tile))

@@ -1,0 +1,331 @@
+// C-ABI layer: argument checks on the host, then dispatch to the gfx950 kernels.
+// Every check runs before the first HIP call, so the error paths are testable on a
+// machine without a GPU.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "../../include/relay_fused.h"
+#include "kernels.hpp"
+
+namespace {
+
+thread_local char g_err[256] = "";
+
+relay_status fail(relay_status st, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return st;
+}
+
+int esize_of(int dtype) { return dtype == RELAY_F32 ? 4 : dtype == RELAY_F16 ? 2 : dtype == RELAY_I8 ? 1 : 0; }
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+constexpr long kMaxElems = (1L << 31) - 1;  // kernels index activations with 32-bit element offsets
+
+// Geometry checks shared by every conv-like entry point.
+relay_status check_geometry(const relay_conv2d_desc* d, int* ho, int* wo) {
+  if (!d) return fail(RELAY_ERR_NULL, "descriptor is NULL");
+  if (d->n <= 0 || d->c <= 0 || d->h <= 0 || d->w <= 0 || d->k <= 0 || d->r <= 0 || d->s <= 0)
+    return fail(RELAY_ERR_SHAPE, "non-positive extent (n=%d c=%d h=%d w=%d k=%d r=%d s=%d)", d->n, d->c, d->h, d->w,
+                d->k, d->r, d->s);
+  if (d->stride_h <= 0 || d->stride_w <= 0) return fail(RELAY_ERR_SHAPE, "stride must be positive");
+  if (d->pad_h < 0 || d->pad_w < 0) return fail(RELAY_ERR_SHAPE, "padding must be non-negative");
+  if (d->pad_h >= d->r || d->pad_w >= d->s)
+    return fail(RELAY_ERR_SHAPE, "padding (%d,%d) must be smaller than the kernel (%d,%d)", d->pad_h, d->pad_w, d->r,
+                d->s);
+  if (d->h + 2 * d->pad_h < d->r || d->w + 2 * d->pad_w < d->s)
+    return fail(RELAY_ERR_SHAPE, "kernel larger than the padded input: empty output");
+  if (esize_of(d->dtype) == 0) return fail(RELAY_ERR_DTYPE, "unknown dtype %d", d->dtype);
+  if (d->layout != RELAY_NCHW && d->layout != RELAY_NHWC) return fail(RELAY_ERR_UNSUPPORTED, "unknown layout %d", d->layout);
+  if (d->flags & ~(uint32_t)(RELAY_HAS_BIAS | RELAY_HAS_BN | RELAY_HAS_RESIDUAL | RELAY_RELU))
+    return fail(RELAY_ERR_UNSUPPORTED, "unknown flag bits 0x%x", d->flags);
+  const int oh = (d->h + 2 * d->pad_h - d->r) / d->stride_h + 1;
+  const int ow = (d->w + 2 * d->pad_w - d->s) / d->stride_w + 1;
+  if ((long)d->n * d->c * d->h * d->w > kMaxElems || (long)d->n * d->k * oh * ow > kMaxElems ||
+      (long)d->k * d->c * d->r * d->s > kMaxElems)
+    return fail(RELAY_ERR_SHAPE, "tensor exceeds 2^31-1 elements");
+  *ho = oh;
+  *wo = ow;
+  return RELAY_OK;
+}
+
+relay_status check_optional(const void* p, bool wanted, const char* name) {
+  if (wanted && !p) return fail(RELAY_ERR_NULL, "%s is NULL but its flag is set", name);
+  if (!wanted && p) return fail(RELAY_ERR_NULL, "%s is given but its flag is clear", name);
+  return RELAY_OK;
+}
+
+relay::ConvArgs make_args(const relay_conv2d_desc* d, int ho, int wo) {
+  relay::ConvArgs a;
+  memset(&a, 0, sizeof(a));
+  a.N = d->n; a.H = d->h; a.W = d->w; a.C = d->c; a.K = d->k; a.R = d->r; a.S = d->s;
+  a.sh = d->stride_h; a.sw = d->stride_w; a.ph = d->pad_h; a.pw = d->pad_w;
+  a.Ho = ho; a.Wo = wo;
+  a.M = d->n * ho * wo;
+  a.Kred = d->r * d->s * d->c;
+  a.Kp = relay::packed_pitch(a.Kred, esize_of(d->dtype));
+  a.flags = d->flags;
+  return a;
+}
+
+relay_status device_status(hipError_t e, const char* what) {
+  if (e == hipSuccess) return RELAY_OK;
+  return fail(RELAY_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
+}
+
+int g_force_tile = -1;
+
+// implicit-GEMM paths: which (dtype, layout, channel count) combinations have a kernel
+relay_status check_igemm_support(const relay_conv2d_desc* d) {
+  if (d->layout != RELAY_NHWC)
+    return fail(RELAY_ERR_UNSUPPORTED, "fp16 / int8 conv2d needs NHWC activations");
+  const int ve = d->dtype == RELAY_I8 ? 16 : 8;
+  if (d->c % ve) return fail(RELAY_ERR_ALIGN, "c=%d must be a multiple of %d (pad the channel axis)", d->c, ve);
+  return RELAY_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* relay_last_error(void) { return g_err; }
+
+relay_status relay_conv2d_out_shape(const relay_conv2d_desc* d, int32_t* ho, int32_t* wo) {
+  if (!ho || !wo) return fail(RELAY_ERR_NULL, "output pointers are NULL");
+  int oh, ow;
+  relay_status st = check_geometry(d, &oh, &ow);
+  if (st != RELAY_OK) return st;
+  *ho = oh;
+  *wo = ow;
+  return RELAY_OK;
+}
+
+relay_status relay_workspace_bytes(const relay_conv2d_desc* d, size_t* bytes) {
+  if (!bytes) return fail(RELAY_ERR_NULL, "bytes is NULL");
+  int oh, ow;
+  relay_status st = check_geometry(d, &oh, &ow);
+  if (st != RELAY_OK) return st;
+  *bytes = 0;  // every kernel keeps its partial sums in registers
+  return RELAY_OK;
+}
+
+relay_status relay_packed_weight_bytes(const relay_conv2d_desc* d, size_t* bytes) {
+  if (!bytes) return fail(RELAY_ERR_NULL, "bytes is NULL");
+  int oh, ow;
+  relay_status st = check_geometry(d, &oh, &ow);
+  if (st != RELAY_OK) return st;
+  const int es = esize_of(d->dtype);
+  if (d->dtype == RELAY_F32) {
+    if (d->layout != RELAY_NCHW) return fail(RELAY_ERR_UNSUPPORTED, "fp32 conv2d is NCHW only");
+    *bytes = (size_t)d->k * d->c * d->r * d->s * es;
+  } else {
+    if ((st = check_igemm_support(d)) != RELAY_OK) return st;
+    *bytes = (size_t)d->k * relay::packed_pitch(d->r * d->s * d->c, es) * es;
+  }
+  return RELAY_OK;
+}
+
+relay_status relay_prepack_conv2d_weights(const relay_conv2d_desc* d, const void* w_oihw, int32_t c_src,
+                                          void* w_packed, size_t packed_bytes, void* hip_stream) {
+  size_t need = 0;
+  relay_status st = relay_packed_weight_bytes(d, &need);
+  if (st != RELAY_OK) return st;
+  if (!w_oihw || !w_packed) return fail(RELAY_ERR_NULL, "weight pointer is NULL");
+  if (c_src <= 0 || c_src > d->c) return fail(RELAY_ERR_SHAPE, "c_src=%d must lie in 1..c=%d", c_src, d->c);
+  if (packed_bytes < need) return fail(RELAY_ERR_WORKSPACE, "packed buffer has %zu bytes, %zu needed", packed_bytes, need);
+  const int es = esize_of(d->dtype);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (d->dtype == RELAY_F32) {
+    if (c_src != d->c) return fail(RELAY_ERR_SHAPE, "fp32 NCHW filters are not channel-padded");
+    return device_status(hipMemcpyAsync(w_packed, w_oihw, need, hipMemcpyDeviceToDevice, s), "filter copy");
+  }
+  if (!aligned(w_packed, 16)) return fail(RELAY_ERR_ALIGN, "w_packed must be 16-byte aligned");
+  const int kp = relay::packed_pitch(d->r * d->s * d->c, es);
+  return device_status(relay::launch_pack_filters(w_oihw, w_packed, d->k, c_src, d->c, d->r, d->s, kp, es, s),
+                       "filter packing");
+}
+
+relay_status relay_set_conv_tile(int32_t tile) {
+  if (tile >= relay::igemm_tile_count()) return fail(RELAY_ERR_UNSUPPORTED, "no tile %d", tile);
+  g_force_tile = tile < 0 ? -1 : tile;
+  return RELAY_OK;
+}
+
+relay_status relay_conv2d_kernel_info(const relay_conv2d_desc* d, int32_t* bm, int32_t* bn, int32_t* waves_m,
+                                      int32_t* waves_n, int32_t* fast) {
+  if (!bm || !bn || !waves_m || !waves_n || !fast) return fail(RELAY_ERR_NULL, "output pointers are NULL");
+  int ho, wo;
+  relay_status st = check_geometry(d, &ho, &wo);
+  if (st != RELAY_OK) return st;
+  if (d->dtype != RELAY_F16 && d->dtype != RELAY_I8) return fail(RELAY_ERR_DTYPE, "only the MFMA paths have tile variants");
+  if ((st = check_igemm_support(d)) != RELAY_OK) return st;
+  relay::ConvArgs a = make_args(d, ho, wo);
+  relay::igemm_kernel_info(a, d->dtype == RELAY_I8, g_force_tile, bm, bn, waves_m, waves_n, fast);
+  return RELAY_OK;
+}
+
+relay_status relay_fused_conv2d_bias_bn_relu(const relay_conv2d_desc* d, const void* x, const void* w_packed,
+                                             const float* bias, const float* bn_scale, const float* bn_shift,
+                                             const void* residual, void* y, void* workspace,
+                                             size_t workspace_bytes, void* hip_stream) {
+  (void)workspace;
+  (void)workspace_bytes;
+  int ho, wo;
+  relay_status st = check_geometry(d, &ho, &wo);
+  if (st != RELAY_OK) return st;
+  if (d->dtype != RELAY_F32 && d->dtype != RELAY_F16)
+    return fail(RELAY_ERR_DTYPE, "float conv2d takes F32 or F16 (int8 goes through relay_qconv2d_requant)");
+  if (!x || !w_packed || !y) return fail(RELAY_ERR_NULL, "x, w_packed and y are required");
+  if ((st = check_optional(bias, d->flags & RELAY_HAS_BIAS, "bias")) != RELAY_OK) return st;
+  if ((st = check_optional(bn_scale, d->flags & RELAY_HAS_BN, "bn_scale")) != RELAY_OK) return st;
+  if ((st = check_optional(bn_shift, d->flags & RELAY_HAS_BN, "bn_shift")) != RELAY_OK) return st;
+  if ((st = check_optional(residual, d->flags & RELAY_HAS_RESIDUAL, "residual")) != RELAY_OK) return st;
+  if (y == x || y == residual) return fail(RELAY_ERR_UNSUPPORTED, "output must not alias an input");
+  relay::ConvArgs a = make_args(d, ho, wo);
+  a.x = x; a.w = w_packed; a.y = y; a.res = residual; a.bias = bias; a.scale = bn_scale; a.shift = bn_shift;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (d->dtype == RELAY_F32) {
+    if (d->layout != RELAY_NCHW) return fail(RELAY_ERR_UNSUPPORTED, "fp32 conv2d is NCHW only");
+    if (!aligned(x, 4) || !aligned(w_packed, 4) || !aligned(y, 4)) return fail(RELAY_ERR_ALIGN, "fp32 pointers must be 4-byte aligned");
+    return device_status(relay::launch_conv_direct_f32(a, s), "conv2d fp32 launch");
+  }
+  if ((st = check_igemm_support(d)) != RELAY_OK) return st;
+  if (!aligned(x, 16) || !aligned(w_packed, 16) || !aligned(y, 16) || (residual && !aligned(residual, 16)))
+    return fail(RELAY_ERR_ALIGN, "fp16 tensors must be 16-byte aligned");
+  return device_status(relay::launch_conv_igemm(a, false, g_force_tile, s), "conv2d fp16 launch");
+}
+
+relay_status relay_qconv2d_requant(const relay_conv2d_desc* d, const int8_t* x, const int8_t* w_packed,
+                                   const int32_t* bias, const int8_t* residual, int32_t residual_lshift,
+                                   int32_t out_rshift, int8_t* y, void* workspace, size_t workspace_bytes,
+                                   void* hip_stream) {
+  (void)workspace;
+  (void)workspace_bytes;
+  int ho, wo;
+  relay_status st = check_geometry(d, &ho, &wo);
+  if (st != RELAY_OK) return st;
+  if (d->dtype != RELAY_I8) return fail(RELAY_ERR_DTYPE, "quantized conv2d takes I8");
+  if (d->flags & RELAY_HAS_BN) return fail(RELAY_ERR_UNSUPPORTED, "the quantized epilogue has no float scale/shift");
+  if (!x || !w_packed || !y) return fail(RELAY_ERR_NULL, "x, w_packed and y are required");
+  if ((st = check_optional(bias, d->flags & RELAY_HAS_BIAS, "bias")) != RELAY_OK) return st;
+  if ((st = check_optional(residual, d->flags & RELAY_HAS_RESIDUAL, "residual")) != RELAY_OK) return st;
+  if (out_rshift < 0 || out_rshift > 31) return fail(RELAY_ERR_UNSUPPORTED, "out_rshift=%d outside 0..31", out_rshift);
+  if (residual_lshift < 0 || residual_lshift > 23)
+    return fail(RELAY_ERR_UNSUPPORTED, "residual_lshift=%d outside 0..23", residual_lshift);
+  if (y == x || y == residual) return fail(RELAY_ERR_UNSUPPORTED, "output must not alias an input");
+  if ((st = check_igemm_support(d)) != RELAY_OK) return st;
+  if (!aligned(x, 16) || !aligned(w_packed, 16) || !aligned(y, 4) || (residual && !aligned(residual, 4)) ||
+      (bias && !aligned(bias, 4)))
+    return fail(RELAY_ERR_ALIGN, "int8 x / w_packed must be 16-byte aligned, y / residual / bias 4-byte aligned");
+  relay::ConvArgs a = make_args(d, ho, wo);
+  a.x = x; a.w = w_packed; a.y = y; a.res = residual; a.qbias = bias;
+  a.lshift = residual_lshift; a.rshift = out_rshift;
+  return device_status(relay::launch_conv_igemm(a, true, g_force_tile, static_cast<hipStream_t>(hip_stream)),
+                       "qconv2d launch");
+}
+
+static relay_status check_dw(const relay_conv2d_desc* d, int* ho, int* wo) {
+  relay_status st = check_geometry(d, ho, wo);
+  if (st != RELAY_OK) return st;
+  if (d->dtype != RELAY_F16) return fail(RELAY_ERR_DTYPE, "depthwise conv2d takes F16");
+  if (d->layout != RELAY_NHWC) return fail(RELAY_ERR_UNSUPPORTED, "depthwise conv2d needs NHWC activations");
+  if (d->k != d->c) return fail(RELAY_ERR_SHAPE, "depthwise conv2d needs k == c (k=%d c=%d)", d->k, d->c);
+  if (d->c % 8) return fail(RELAY_ERR_ALIGN, "c=%d must be a multiple of 8", d->c);
+  if (d->r != 3 || d->s != 3) return fail(RELAY_ERR_UNSUPPORTED, "depthwise kernel must be 3x3");
+  if (d->stride_h != d->stride_w || (d->stride_h != 1 && d->stride_h != 2))
+    return fail(RELAY_ERR_UNSUPPORTED, "depthwise stride must be 1 or 2");
+  if (d->flags & RELAY_HAS_RESIDUAL) return fail(RELAY_ERR_UNSUPPORTED, "depthwise conv2d has no residual input");
+  return RELAY_OK;
+}
+
+relay_status relay_prepack_dwconv_weights(const relay_conv2d_desc* d, const void* w_crs, void* w_rsc,
+                                          void* hip_stream) {
+  int ho, wo;
+  relay_status st = check_dw(d, &ho, &wo);
+  if (st != RELAY_OK) return st;
+  if (!w_crs || !w_rsc) return fail(RELAY_ERR_NULL, "weight pointer is NULL");
+  if (!aligned(w_rsc, 16)) return fail(RELAY_ERR_ALIGN, "w_rsc must be 16-byte aligned");
+  return device_status(relay::launch_pack_dw_filters(w_crs, w_rsc, d->c, d->r * d->s, static_cast<hipStream_t>(hip_stream)),
+                       "depthwise filter packing");
+}
+
+relay_status relay_fused_dwconv_bias_relu(const relay_conv2d_desc* d, const void* x, const void* w_rsc,
+                                          const float* bias, const float* bn_scale, const float* bn_shift,
+                                          void* y, void* hip_stream) {
+  int ho, wo;
+  relay_status st = check_dw(d, &ho, &wo);
+  if (st != RELAY_OK) return st;
+  if (!x || !w_rsc || !y) return fail(RELAY_ERR_NULL, "x, w_rsc and y are required");
+  if ((st = check_optional(bias, d->flags & RELAY_HAS_BIAS, "bias")) != RELAY_OK) return st;
+  if ((st = check_optional(bn_scale, d->flags & RELAY_HAS_BN, "bn_scale")) != RELAY_OK) return st;
+  if ((st = check_optional(bn_shift, d->flags & RELAY_HAS_BN, "bn_shift")) != RELAY_OK) return st;
+  if (y == x) return fail(RELAY_ERR_UNSUPPORTED, "output must not alias an input");
+  if (!aligned(x, 16) || !aligned(w_rsc, 16) || !aligned(y, 16)) return fail(RELAY_ERR_ALIGN, "fp16 tensors must be 16-byte aligned");
+  relay::ConvArgs a = make_args(d, ho, wo);
+  a.x = x; a.w = w_rsc; a.y = y; a.bias = bias; a.scale = bn_scale; a.shift = bn_shift;
+  return device_status(relay::launch_dwconv_f16(a, static_cast<hipStream_t>(hip_stream)), "depthwise launch");
+}
+
+relay_status relay_fused_dense_bias_act(int32_t m, int32_t n, int32_t k, int32_t dtype, const void* x,
+                                        const void* w, const float* bias, int32_t act, void* y,
+                                        void* hip_stream) {
+  if (m <= 0 || n <= 0 || k <= 0) return fail(RELAY_ERR_SHAPE, "non-positive extent (m=%d n=%d k=%d)", m, n, k);
+  if (dtype != RELAY_F16 && dtype != RELAY_F32) return fail(RELAY_ERR_DTYPE, "dense takes F16 or F32");
+  if (act != 0 && act != 1) return fail(RELAY_ERR_UNSUPPORTED, "act=%d (0 none, 1 relu)", act);
+  if (!x || !w || !y) return fail(RELAY_ERR_NULL, "x, w and y are required");
+  if ((long)m * k > kMaxElems || (long)n * k > kMaxElems || (long)m * n > kMaxElems)
+    return fail(RELAY_ERR_SHAPE, "tensor exceeds 2^31-1 elements");
+  const int ve = dtype == RELAY_F16 ? 8 : 4;
+  if (k % ve) return fail(RELAY_ERR_ALIGN, "k=%d must be a multiple of %d", k, ve);
+  if (!aligned(x, 16) || !aligned(w, 16) || !aligned(y, dtype == RELAY_F16 ? 2 : 4))
+    return fail(RELAY_ERR_ALIGN, "x and w must be 16-byte aligned");
+  if (y == x || y == w) return fail(RELAY_ERR_UNSUPPORTED, "output must not alias an input");
+  return device_status(relay::launch_dense(m, n, k, dtype == RELAY_F16, x, w, bias, act, y, static_cast<hipStream_t>(hip_stream)),
+                       "dense launch");
+}
+
+relay_status relay_maxpool2d(int32_t dtype, int32_t n, int32_t c, int32_t h, int32_t w, int32_t r, int32_t stride,
+                             int32_t pad, const void* x, void* y, void* hip_stream) {
+  if (n <= 0 || c <= 0 || h <= 0 || w <= 0 || r <= 0 || stride <= 0 || pad < 0 || pad >= r || h + 2 * pad < r ||
+      w + 2 * pad < r)
+    return fail(RELAY_ERR_SHAPE, "bad pooling geometry");
+  if (dtype != RELAY_F16 && dtype != RELAY_I8) return fail(RELAY_ERR_DTYPE, "maxpool takes F16 or I8");
+  const int ve = dtype == RELAY_I8 ? 16 : 8;
+  if (c % ve) return fail(RELAY_ERR_ALIGN, "c=%d must be a multiple of %d", c, ve);
+  if (!x || !y) return fail(RELAY_ERR_NULL, "x and y are required");
+  if (!aligned(x, 16) || !aligned(y, 16)) return fail(RELAY_ERR_ALIGN, "tensors must be 16-byte aligned");
+  if ((long)n * c * h * w > kMaxElems) return fail(RELAY_ERR_SHAPE, "tensor exceeds 2^31-1 elements");
+  const int ho = (h + 2 * pad - r) / stride + 1, wo = (w + 2 * pad - r) / stride + 1;
+  return device_status(relay::launch_maxpool(dtype == RELAY_I8, n, c, h, w, r, stride, pad, ho, wo, x, y,
+                                             static_cast<hipStream_t>(hip_stream)),
+                       "maxpool launch");
+}
+
+relay_status relay_global_avgpool(int32_t dtype, int32_t n, int32_t c, int32_t hw, const void* x, void* y,
+                                  void* hip_stream) {
+  if (n <= 0 || c <= 0 || hw <= 0) return fail(RELAY_ERR_SHAPE, "non-positive extent");
+  if (dtype != RELAY_F16) return fail(RELAY_ERR_DTYPE, "global average pool takes F16");
+  if (c % 8) return fail(RELAY_ERR_ALIGN, "c=%d must be a multiple of 8", c);
+  if (!x || !y) return fail(RELAY_ERR_NULL, "x and y are required");
+  if (!aligned(x, 16) || !aligned(y, 16)) return fail(RELAY_ERR_ALIGN, "tensors must be 16-byte aligned");
+  if ((long)n * c * hw > kMaxElems) return fail(RELAY_ERR_SHAPE, "tensor exceeds 2^31-1 elements");
+  return device_status(relay::launch_avgpool_f16(n, c, hw, x, y, static_cast<hipStream_t>(hip_stream)), "avgpool launch");
+}
+
+relay_status relay_nchw_to_nhwc(int32_t dtype, int32_t n, int32_t c, int32_t h, int32_t w, int32_t c_pad,
+                                const void* x, void* y, void* hip_stream) {
+  if (n <= 0 || c <= 0 || h <= 0 || w <= 0 || c_pad < c) return fail(RELAY_ERR_SHAPE, "bad layout-conversion shape");
+  const int es = esize_of(dtype);
+  if (!es) return fail(RELAY_ERR_DTYPE, "unknown dtype %d", dtype);
+  if (!x || !y) return fail(RELAY_ERR_NULL, "x and y are required");
+  if (x == y) return fail(RELAY_ERR_UNSUPPORTED, "output must not alias an input");
+  if ((long)n * c_pad * h * w > kMaxElems) return fail(RELAY_ERR_SHAPE, "tensor exceeds 2^31-1 elements");
+  return device_status(relay::launch_nchw_to_nhwc(es, n, c, h, w, c_pad, x, y, static_cast<hipStream_t>(hip_stream)),
+                       "layout conversion launch");
+}
+
+}  // extern "C"

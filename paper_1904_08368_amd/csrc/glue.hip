@@ -1,0 +1,171 @@
+// Small kernels around the fused primitive functions: filter packing and the NCHW->NHWC
+// conversion (compile-time layout alteration in the paper's terms, Section 5.3), and the
+// two pools that chain ResNet / MobileNet layer shapes.
+#include "kernels.hpp"
+
+namespace relay {
+namespace {
+
+// OIHW [K][Csrc][R][S] -> [K][Kp] with reduction index (r, s, c), c < C, zero elsewhere.
+template <typename T>
+__global__ __launch_bounds__(256) void pack_filters_kernel(const T* w, T* out, int K, int Csrc, int C, int R, int S,
+                                                           int Kp) {
+  const long total = (long)K * Kp;
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int kk = (int)(idx % Kp);
+  const int k = (int)(idx / Kp);
+  T v = 0;
+  if (kk < R * S * C) {
+    const int tap = kk / C, c = kk - tap * C;
+    const int r = tap / S, s = tap - r * S;
+    if (c < Csrc) v = w[(((long)k * Csrc + c) * R + r) * S + s];
+  }
+  out[idx] = v;
+}
+
+// depthwise filters [C][RS] -> [RS][C]
+__global__ __launch_bounds__(256) void pack_dw_kernel(const uint16_t* w, uint16_t* out, int C, int RS) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= C * RS) return;
+  const int c = idx % C, t = idx / C;
+  out[idx] = w[c * RS + t];
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void nchw_to_nhwc_kernel(const T* x, T* y, int N, int C, int H, int W, int Cpad) {
+  const long total = (long)N * H * W * Cpad;
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int c = (int)(idx % Cpad);
+  long t = idx / Cpad;
+  const int w_ = (int)(t % W);
+  t /= W;
+  const int h = (int)(t % H);
+  const int n = (int)(t / H);
+  y[idx] = c < C ? x[(((long)n * C + c) * H + h) * W + w_] : (T)0;
+}
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef signed char char16 __attribute__((ext_vector_type(16)));
+
+// max pool, NHWC, one 16-byte channel vector per thread; padding taps are skipped.
+template <typename V, int VE>
+__global__ __launch_bounds__(256) void maxpool_kernel(const V* x, V* y, int N, int CV, int H, int W, int R, int stride,
+                                                      int pad, int Ho, int Wo) {
+  const long total = (long)N * Ho * Wo * CV;
+  long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int cv = (int)(idx % CV);
+  long t = idx / CV;
+  const int q = (int)(t % Wo);
+  t /= Wo;
+  const int p = (int)(t % Ho);
+  const int n = (int)(t / Ho);
+  V best;
+  bool have = false;
+  for (int r = 0; r < R; ++r) {
+    const int ih = p * stride - pad + r;
+    if ((unsigned)ih >= (unsigned)H) continue;
+    for (int s = 0; s < R; ++s) {
+      const int iw = q * stride - pad + s;
+      if ((unsigned)iw >= (unsigned)W) continue;
+      const V v = x[(((long)n * H + ih) * W + iw) * CV + cv];
+      if (!have) {
+        best = v;
+        have = true;
+      } else {
+#pragma unroll
+        for (int e = 0; e < VE; ++e) best[e] = v[e] > best[e] ? v[e] : best[e];
+      }
+    }
+  }
+  if (!have) {
+#pragma unroll
+    for (int e = 0; e < VE; ++e) best[e] = 0;
+  }
+  y[idx] = best;
+}
+
+// global average pool, NHWC fp16 -> [N][C] fp16, fp32 sum.
+__global__ __launch_bounds__(256) void avgpool_f16_kernel(const half8* x, half8* y, int N, int CV, int HW) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= N * CV) return;
+  const int cv = idx % CV, n = idx / CV;
+  float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  for (int i = 0; i < HW; ++i) {
+    const half8 v = x[((long)n * HW + i) * CV + cv];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] += (float)v[e];
+  }
+  half8 o;
+  const float inv = 1.0f / (float)HW;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o[e] = (_Float16)(acc[e] * inv);
+  y[idx] = o;
+}
+
+inline unsigned blocks_for(long total) { return (unsigned)((total + 255) / 256); }
+
+}  // namespace
+
+hipError_t launch_pack_filters(const void* w, void* out, int K, int Csrc, int C, int R, int S, int Kp, int esize,
+                               hipStream_t st) {
+  const long total = (long)K * Kp;
+  dim3 grid(blocks_for(total)), block(256);
+  if (esize == 1)
+    hipLaunchKernelGGL((pack_filters_kernel<int8_t>), grid, block, 0, st, (const int8_t*)w, (int8_t*)out, K, Csrc, C,
+                       R, S, Kp);
+  else if (esize == 2)
+    hipLaunchKernelGGL((pack_filters_kernel<uint16_t>), grid, block, 0, st, (const uint16_t*)w, (uint16_t*)out, K,
+                       Csrc, C, R, S, Kp);
+  else
+    hipLaunchKernelGGL((pack_filters_kernel<uint32_t>), grid, block, 0, st, (const uint32_t*)w, (uint32_t*)out, K,
+                       Csrc, C, R, S, Kp);
+  return hipGetLastError();
+}
+
+hipError_t launch_pack_dw_filters(const void* w, void* out, int C, int RS, hipStream_t st) {
+  hipLaunchKernelGGL(pack_dw_kernel, dim3(blocks_for((long)C * RS)), dim3(256), 0, st, (const uint16_t*)w,
+                     (uint16_t*)out, C, RS);
+  return hipGetLastError();
+}
+
+hipError_t launch_maxpool(bool is_i8, int N, int C, int H, int W, int R, int stride, int pad, int Ho, int Wo,
+                          const void* x, void* y, hipStream_t st) {
+  if (is_i8) {
+    const int cv = C / 16;
+    hipLaunchKernelGGL((maxpool_kernel<char16, 16>), dim3(blocks_for((long)N * Ho * Wo * cv)), dim3(256), 0, st,
+                       (const char16*)x, (char16*)y, N, cv, H, W, R, stride, pad, Ho, Wo);
+  } else {
+    const int cv = C / 8;
+    hipLaunchKernelGGL((maxpool_kernel<half8, 8>), dim3(blocks_for((long)N * Ho * Wo * cv)), dim3(256), 0, st,
+                       (const half8*)x, (half8*)y, N, cv, H, W, R, stride, pad, Ho, Wo);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_avgpool_f16(int N, int C, int HW, const void* x, void* y, hipStream_t st) {
+  const int cv = C / 8;
+  hipLaunchKernelGGL(avgpool_f16_kernel, dim3(blocks_for((long)N * cv)), dim3(256), 0, st, (const half8*)x, (half8*)y,
+                     N, cv, HW);
+  return hipGetLastError();
+}
+
+hipError_t launch_nchw_to_nhwc(int esize, int N, int C, int H, int W, int Cpad, const void* x, void* y,
+                               hipStream_t st) {
+  const long total = (long)N * H * W * Cpad;
+  dim3 grid(blocks_for(total)), block(256);
+  if (esize == 1)
+    hipLaunchKernelGGL((nchw_to_nhwc_kernel<int8_t>), grid, block, 0, st, (const int8_t*)x, (int8_t*)y, N, C, H, W,
+                       Cpad);
+  else if (esize == 2)
+    hipLaunchKernelGGL((nchw_to_nhwc_kernel<uint16_t>), grid, block, 0, st, (const uint16_t*)x, (uint16_t*)y, N, C, H,
+                       W, Cpad);
+  else
+    hipLaunchKernelGGL((nchw_to_nhwc_kernel<uint32_t>), grid, block, 0, st, (const uint32_t*)x, (uint32_t*)y, N, C, H,
+                       W, Cpad);
+  return hipGetLastError();
+}
+
+}  // namespace relay

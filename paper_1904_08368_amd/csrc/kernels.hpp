@@ -1,0 +1,55 @@
+// Internal interface between the C-ABI layer (api.cpp) and the gfx950 kernels.
+// Launchers enqueue on the given stream and return the HIP status of the launch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace relay {
+
+enum : unsigned { F_BIAS = 1, F_BN = 2, F_RES = 4, F_RELU = 8 };
+
+// Geometry and operands of one conv-like primitive function.
+struct ConvArgs {
+  const void* x;
+  const void* w;
+  void* y;
+  const void* res;
+  const float* bias;
+  const float* scale;
+  const float* shift;
+  const int32_t* qbias;
+  int N, H, W, C, K, R, S, sh, sw, ph, pw, Ho, Wo;
+  int M;        // N*Ho*Wo  (rows of the implicit GEMM)
+  int Kred;     // R*S*C    (reduction length)
+  int Kp;       // row pitch of the packed filters, elements
+  int lshift, rshift;
+  unsigned flags;
+};
+
+// Row pitch (elements) of packed filters for a reduction of kred elements of esize bytes:
+// whole 128-byte groups.
+inline int packed_pitch(int kred, int esize) {
+  const int per = 128 / esize;
+  return (kred + per - 1) / per * per;
+}
+
+hipError_t launch_conv_direct_f32(const ConvArgs& a, hipStream_t st);
+// tile < 0: pick by heuristic.
+hipError_t launch_conv_igemm(const ConvArgs& a, bool is_i8, int tile, hipStream_t st);
+int igemm_tile_count();
+// Which instantiation launch_conv_igemm would use: tile extents, wave grid, fast tap decode.
+void igemm_kernel_info(const ConvArgs& a, bool is_i8, int tile, int* bm, int* bn, int* waves_m, int* waves_n,
+                       int* fast);
+hipError_t launch_dwconv_f16(const ConvArgs& a, hipStream_t st);
+hipError_t launch_dense(int m, int n, int k, bool is_f16, const void* x, const void* w, const float* bias,
+                        int act, void* y, hipStream_t st);
+hipError_t launch_pack_filters(const void* w_oihw, void* w_packed, int K, int Csrc, int C, int R, int S,
+                               int Kp, int esize, hipStream_t st);
+hipError_t launch_pack_dw_filters(const void* w_crs, void* w_rsc, int C, int RS, hipStream_t st);
+hipError_t launch_maxpool(bool is_i8, int N, int C, int H, int W, int R, int stride, int pad, int Ho, int Wo,
+                          const void* x, void* y, hipStream_t st);
+hipError_t launch_avgpool_f16(int N, int C, int HW, const void* x, void* y, hipStream_t st);
+hipError_t launch_nchw_to_nhwc(int esize, int N, int C, int H, int W, int Cpad, const void* x, void* y,
+                               hipStream_t st);
+
+}  // namespace relay

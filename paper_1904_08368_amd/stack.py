@@ -1,0 +1,142 @@
+"""A network as a sequence of fused primitive functions called one after another on
+preallocated buffers (paper Section 3.3: operator invocations replaced by calls to the
+compiled operators, inputs and outputs preallocated).
+
+Set-up (filter packing, channel padding of filters, buffer allocation) is compile-time
+work and happens once in the constructor; ``run()`` only enqueues kernels of the library
+on torch's current stream, so it can also be captured into a HIP graph.
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Optional
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+def _round_up(a: int, b: int) -> int:
+    return (a + b - 1) // b * b
+
+
+class FusedNet:
+    """mode 'f16': fp16 NHWC, fp32 accumulation.  mode 'i8': int8 NHWC, int32 accumulation,
+    ``shifts[i] = {'s': out_rshift, 'l': residual_lshift}`` per conv."""
+
+    def __init__(self, ops, params: List[dict], batch: int, h: int, w: int, mode: str = "f16",
+                 shifts: Optional[List[dict]] = None, in_channels: int = 3, device: str = "cuda:0"):
+        assert mode in ("f16", "i8")
+        self.ops, self.mode, self.batch = ops, mode, batch
+        self.dev = torch.device(device)
+        self.dtype = B.RELAY_F16 if mode == "f16" else B.RELAY_I8
+        self.tdtype = torch.float16 if mode == "f16" else torch.int8
+        self.ve = 8 if mode == "f16" else 16
+        self.calls = []                      # (callable, args) in execution order
+        self.call_names: List[str] = []
+        self.bufs: Dict[str, torch.Tensor] = {}
+        self.shape: Dict[str, tuple] = {}    # name -> (C_logical, H, W), physical C = padded
+        self.keep = []                       # parameter tensors kept alive
+
+        cpad = _round_up(in_channels, self.ve)
+        self.x_nchw = torch.zeros((batch, in_channels, h, w), dtype=self.tdtype, device=self.dev)
+        self.bufs["x"] = torch.zeros((batch, h, w, cpad), dtype=self.tdtype, device=self.dev)
+        self.shape["x"] = (in_channels, h, w)
+        self._add("nchw_to_nhwc", B.relay_nchw_to_nhwc,
+                  (self.dtype, batch, in_channels, h, w, cpad, self.x_nchw, self.bufs["x"]))
+
+        for i, (op, p) in enumerate(zip(ops, params)):
+            cin_l, hi, wi = self.shape[op.src]
+            src = self.bufs[op.src]
+            cin_p = src.shape[-1]
+            if op.kind == "conv":
+                flags = B.flags_of(p.get("bias"), p.get("scale"), op.res, op.relu)
+                d = B.conv_desc(batch, cin_p, hi, wi, op.cout, op.r, op.r, op.stride, op.pad, self.dtype,
+                                B.RELAY_NHWC, flags)
+                ho, wo = B.relay_conv2d_out_shape(d)
+                wsrc = torch.from_numpy(np.ascontiguousarray(p["w"])).to(self.dev)
+                wp = torch.empty(B.relay_packed_weight_bytes(d), dtype=torch.uint8, device=self.dev)
+                B.relay_prepack_conv2d_weights(d, wsrc, cin_l, wp)
+                y = torch.empty((batch, ho, wo, op.cout), dtype=self.tdtype, device=self.dev)
+                res = self.bufs[op.res] if op.res else None
+                if mode == "f16":
+                    bias, sc, sf = (self._f32(p.get(k)) for k in ("bias", "scale", "shift"))
+                    self._add(op.name, B.relay_fused_conv2d_bias_bn_relu, (d, src, wp, bias, sc, sf, res, y))
+                else:
+                    sh = shifts[i]
+                    self._add(op.name, B.relay_qconv2d_requant,
+                              (d, src, wp, None, res, int(sh.get("l", 0)), int(sh["s"]), y))
+                self.keep += [wp, d]
+                self.bufs[op.dst], self.shape[op.dst] = y, (op.cout, ho, wo)
+            elif op.kind == "dwconv":
+                flags = B.flags_of(p.get("bias"), p.get("scale"), None, op.relu)
+                d = B.conv_desc(batch, cin_p, hi, wi, cin_p, op.r, op.r, op.stride, op.pad, self.dtype,
+                                B.RELAY_NHWC, flags)
+                ho, wo = B.relay_conv2d_out_shape(d)
+                wsrc = torch.from_numpy(np.ascontiguousarray(p["w"])).to(self.dev)
+                wp = torch.empty((op.r * op.r, cin_p), dtype=self.tdtype, device=self.dev)
+                B.relay_prepack_dwconv_weights(d, wsrc, wp)
+                y = torch.empty((batch, ho, wo, cin_p), dtype=self.tdtype, device=self.dev)
+                bias, sc, sf = (self._f32(p.get(k)) for k in ("bias", "scale", "shift"))
+                self._add(op.name, B.relay_fused_dwconv_bias_relu, (d, src, wp, bias, sc, sf, y))
+                self.keep += [wp, d]
+                self.bufs[op.dst], self.shape[op.dst] = y, (op.cout, ho, wo)
+            elif op.kind == "maxpool":
+                ho = (hi + 2 * op.pad - op.r) // op.stride + 1
+                wo = (wi + 2 * op.pad - op.r) // op.stride + 1
+                y = torch.empty((batch, ho, wo, cin_p), dtype=self.tdtype, device=self.dev)
+                self._add(op.name, B.relay_maxpool2d, (self.dtype, batch, cin_p, hi, wi, op.r, op.stride, op.pad, src, y))
+                self.bufs[op.dst], self.shape[op.dst] = y, (cin_l, ho, wo)
+            elif op.kind == "avgpool":
+                y = torch.empty((batch, 1, 1, cin_p), dtype=self.tdtype, device=self.dev)
+                self._add(op.name, B.relay_global_avgpool, (self.dtype, batch, cin_p, hi * wi, src, y))
+                self.bufs[op.dst], self.shape[op.dst] = y, (cin_l, 1, 1)
+            elif op.kind == "dense":
+                wd = torch.from_numpy(np.ascontiguousarray(p["w"])).to(self.dev)
+                bias = self._f32(p.get("bias"))
+                y = torch.empty((batch, 1, 1, op.cout), dtype=self.tdtype, device=self.dev)
+                self._add(op.name, B.relay_fused_dense_bias_act,
+                          (batch, op.cout, op.cin, self.dtype, src, wd, bias, 1 if op.relu else 0, y))
+                self.keep += [wd]
+                self.bufs[op.dst], self.shape[op.dst] = y, (op.cout, 1, 1)
+            else:
+                raise ValueError(op.kind)
+        torch.cuda.synchronize(self.dev)
+        self.graph = None
+
+    def _f32(self, a):
+        if a is None:
+            return None
+        t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(self.dev)
+        self.keep.append(t)
+        return t
+
+    def _add(self, name, fn, args):
+        self.calls.append((fn, args))
+        self.call_names.append(name)
+
+    def load_input(self, x_nchw: np.ndarray) -> None:
+        self.x_nchw.copy_(torch.from_numpy(np.ascontiguousarray(x_nchw)).to(self.dev))
+
+    def run(self) -> None:
+        """Enqueue the whole network on the current stream (layout conversion included)."""
+        for fn, args in self.calls:
+            fn(*args)
+
+    def capture(self) -> None:
+        """Record run() into a HIP graph (kernel launches only; nothing in it clears memory)."""
+        self.run()
+        torch.cuda.synchronize(self.dev)
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            self.run()
+        self.graph = g
+
+    def replay(self) -> None:
+        self.graph.replay()
+
+    def tensor(self, name: str) -> np.ndarray:
+        """Download a named tensor as NCHW with the logical channel count."""
+        c, _, _ = self.shape[name]
+        t = self.bufs[name][..., :c].permute(0, 3, 1, 2).contiguous().cpu().numpy()
+        return t

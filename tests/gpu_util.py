@@ -1,0 +1,88 @@
+"""Helpers of the GPU parity tests: move numpy NCHW tensors to the device in the layout the
+library wants, call one entry point through the binding, bring the result back as NCHW."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from paper_1904_08368_amd import binding as B
+
+DEV = "cuda:0"
+
+
+def up(a):
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def to_nhwc(x_nchw: np.ndarray, cpad: int, dtype: int) -> torch.Tensor:
+    n, c, h, w = x_nchw.shape
+    src = up(x_nchw)
+    dst = torch.empty((n, h, w, cpad), dtype=src.dtype, device=DEV)
+    B.relay_nchw_to_nhwc(dtype, n, c, h, w, cpad, src, dst)
+    return dst
+
+
+def from_nhwc(t: torch.Tensor, c: int) -> np.ndarray:
+    return t[..., :c].permute(0, 3, 1, 2).contiguous().cpu().numpy()
+
+
+def round_up(a, b):
+    return (a + b - 1) // b * b
+
+
+def run_conv_f16(x, w, stride, pad, bias=None, scale=None, shift=None, residual=None, relu=False, tile=-1):
+    """x [N,C,H,W] fp16, w [K,C,R,S] fp16 (numpy) -> y NCHW fp16 (numpy), via the C ABI."""
+    n, c, h, wd = x.shape
+    k, _, r, s = w.shape
+    cp = round_up(c, 8)
+    flags = B.flags_of(bias, scale, residual, relu)
+    d = B.conv_desc(n, cp, h, wd, k, r, s, stride, pad, B.RELAY_F16, B.RELAY_NHWC, flags)
+    ho, wo = B.relay_conv2d_out_shape(d)
+    xd = to_nhwc(x, cp, B.RELAY_F16)
+    wp = torch.empty(B.relay_packed_weight_bytes(d), dtype=torch.uint8, device=DEV)
+    B.relay_prepack_conv2d_weights(d, up(w), c, wp)
+    rd = None if residual is None else to_nhwc(residual, k, B.RELAY_F16)
+    y = torch.full((n, ho, wo, k), float("nan"), dtype=torch.float16, device=DEV)
+    B.relay_set_conv_tile(tile)
+    try:
+        B.relay_fused_conv2d_bias_bn_relu(d, xd, wp, up(bias), up(scale), up(shift), rd, y)
+    finally:
+        B.relay_set_conv_tile(-1)
+    torch.cuda.synchronize()
+    return from_nhwc(y, k)
+
+
+def run_qconv(x, w, stride, pad, bias=None, residual=None, lshift=0, rshift=0, relu=False, tile=-1):
+    n, c, h, wd = x.shape
+    k, _, r, s = w.shape
+    cp = round_up(c, 16)
+    flags = B.flags_of(bias, None, residual, relu)
+    d = B.conv_desc(n, cp, h, wd, k, r, s, stride, pad, B.RELAY_I8, B.RELAY_NHWC, flags)
+    ho, wo = B.relay_conv2d_out_shape(d)
+    xd = to_nhwc(x, cp, B.RELAY_I8)
+    wp = torch.empty(B.relay_packed_weight_bytes(d), dtype=torch.uint8, device=DEV)
+    B.relay_prepack_conv2d_weights(d, up(w), c, wp)
+    rd = None if residual is None else to_nhwc(residual, k, B.RELAY_I8)
+    y = torch.full((n, ho, wo, k), -128, dtype=torch.int8, device=DEV)
+    bd = None if bias is None else up(np.asarray(bias, dtype=np.int32))
+    B.relay_set_conv_tile(tile)
+    try:
+        B.relay_qconv2d_requant(d, xd, wp, bd, rd, lshift, rshift, y)
+    finally:
+        B.relay_set_conv_tile(-1)
+    torch.cuda.synchronize()
+    return from_nhwc(y, k)
+
+
+def run_dwconv_f16(x, w, stride, pad, bias=None, scale=None, shift=None, relu=False):
+    n, c, h, wd = x.shape
+    flags = B.flags_of(bias, scale, None, relu)
+    d = B.conv_desc(n, c, h, wd, c, 3, 3, stride, pad, B.RELAY_F16, B.RELAY_NHWC, flags)
+    ho, wo = B.relay_conv2d_out_shape(d)
+    xd = to_nhwc(x, c, B.RELAY_F16)
+    wp = torch.empty((9, c), dtype=torch.float16, device=DEV)
+    B.relay_prepack_dwconv_weights(d, up(w), wp)
+    y = torch.full((n, ho, wo, c), float("nan"), dtype=torch.float16, device=DEV)
+    B.relay_fused_dwconv_bias_relu(d, xd, wp, up(bias), up(scale), up(shift), y)
+    torch.cuda.synchronize()
+    return from_nhwc(y, c)
