@@ -1,0 +1,220 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused-operator hot path on one MI355X.
+
+A step = one pass of the full ResNet-18 stack (layout conversion, 20 fused convs, both
+pools, fused dense) over one batch of 32 synthetic 3x224x224 fp16 images, every kernel
+coming from librelayfused.so.  Inputs and packed filters are resident in HBM before the
+timed region; filter packing and batch-norm folding are compile-time work and untimed.
+
+Prints ONE JSON line.  `value` = contraction FLOP (2*MAC of the convs and the dense) per
+second over the whole step.  `roofline` covers the implicit-GEMM kernel variant that
+takes the most time; `cpu_baseline` is the CPU oracle timed on this host on a bounded
+sample.  `extra` holds per-layer figures and the int8 / MobileNet configurations.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK = {"f16": 2500.0, "i8": 5000.0}     # dense MFMA peaks, TFLOP/s and TOP/s
+HBM_PEAK_GBS = 8000.0
+
+
+def _layer_table(net, ops, batch, reps, trials):
+    """Per-launch duration of every call of the network: `reps` back-to-back launches
+    between two events on the launch stream, median of `trials`."""
+    import torch
+    from paper_1904_08368_amd import binding as B
+    rows = []
+    shp_in = {}
+    for (fn, args), name in zip(net.calls, net.call_names):
+        for _ in range(3):
+            fn(*args)
+        ts = []
+        for _ in range(trials):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn(*args)
+            e1.record()
+            e1.synchronize()
+            ts.append(e0.elapsed_time(e1) * 1e3 / reps)      # us per launch
+        row = {"name": name, "us": statistics.median(ts)}
+        d = args[0]
+        if isinstance(d, B.ConvDesc):
+            ho, wo = B.relay_conv2d_out_shape(d)
+            es = 2 if d.dtype == B.RELAY_F16 else 1
+            if fn in (B.relay_fused_conv2d_bias_bn_relu, B.relay_qconv2d_requant):
+                # logical reduction length: padded input channels of the stem carry zeros
+                op = next(o for o in ops if o.name == name)
+                macs = d.n * ho * wo * d.k * op.cin * d.r * d.s
+                row["gflop"] = 2 * macs / 1e9
+                row["kernel"] = B.relay_conv2d_kernel_info(d)["kernel"]
+                byts = (d.n * d.h * d.w * op.cin + d.n * ho * wo * d.k * (2 if (d.flags & B.HAS_RESIDUAL) else 1)
+                        + d.k * op.cin * d.r * d.s) * es
+                row["mbytes"] = byts / 1e6
+            else:   # depthwise: input + output + filters
+                row["gflop"] = 2 * d.n * ho * wo * d.c * 9 / 1e9
+                row["kernel"] = "dwconv3x3_f16_kernel"
+                row["mbytes"] = (d.n * d.h * d.w * d.c + d.n * ho * wo * d.c + 9 * d.c) * es / 1e6
+            row["tflops"] = row["gflop"] / row["us"] * 1e3           # GFLOP/us = 1000 TFLOP/s
+            row["gbs"] = row["mbytes"] / row["us"] * 1e3              # MB/us = 1000 GB/s
+        rows.append(row)
+    return rows
+
+
+def _time_steps(net, steps, warmup, use_graph):
+    import torch
+    step = net.replay if use_graph else net.run
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--batch", type=int, default=32)
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    ap.add_argument("--no-extra", action="store_true", help="skip the int8 / MobileNet / batch-1 sections")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--layer-reps", type=int, default=20)
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; the path shards over the batch axis with no "
+              "collective (see DESIGN.md) but nothing here launches more than one rank.", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_1904_08368_amd import binding as B
+    from paper_1904_08368_amd.stack import FusedNet
+    from workloads import inputs, nets
+
+    B.lib()                                   # fail loudly if the HIP library is not built
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    use_graph = not a.no_graph
+
+    # ------------------------------------------------ headline: ResNet-18 fp16, batch 32
+    ops = nets.resnet18()
+    params = inputs.net_params(ops, 3, "f16")
+    net = FusedNet(ops, params, a.batch, 224, 224, "f16")
+    net.load_input(inputs.image(3, a.batch, 3, 224, 224, "f16"))
+    if use_graph:
+        net.capture()
+    sec = _time_steps(net, a.steps, a.warmup, use_graph)
+    flop = 2.0 * nets.macs_per_image(ops, 224, 224) * a.batch
+    value = flop / sec / 1e12
+
+    rows = _layer_table(net, ops, a.batch, a.layer_reps, 5)
+    by_kernel = {}
+    for r in rows:
+        if "kernel" in r and r["kernel"].startswith("igemm"):
+            k = by_kernel.setdefault(r["kernel"], {"us": 0.0, "gflop": 0.0, "launches": 0, "layers": []})
+            k["us"] += r["us"]
+            k["gflop"] += r["gflop"]
+            k["launches"] += 1
+            k["layers"].append(r["name"])
+    dom_name, dom = max(by_kernel.items(), key=lambda kv: kv[1]["us"])
+    achieved = dom["gflop"] / dom["us"] * 1e3          # TFLOP/s
+    roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK["f16"], "unit": "TFLOP/s",
+                "frac": round(achieved / PEAK["f16"], 4), "traffic": None, "kernel": dom_name,
+                "launches_per_step": dom["launches"], "avg_launch_us": round(dom["us"] / dom["launches"], 2),
+                "gflop_per_launch": round(dom["gflop"] / dom["launches"], 3), "layers": dom["layers"]}
+    conv_us = sum(r["us"] for r in rows if r.get("kernel", "").startswith("igemm"))
+    conv_gf = sum(r["gflop"] for r in rows if r.get("kernel", "").startswith("igemm"))
+
+    out = {
+        "metric": "resnet18_fp16_fused_conv_stack_tflops", "value": round(value, 3), "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(sec * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "configs[2]: full ResNet-18 stack (20 fused convs + pools + dense 512->1000), "
+                               f"fp16 / fp32 accumulate, batch {a.batch}, 3x224x224, NHWC",
+                   "batch": a.batch, "hip_graph": use_graph},
+        "ms_per_img": round(sec * 1e3 / a.batch, 5),
+        "roofline": roofline,
+    }
+    extra = {"conv_kernels_only_tflops": round(conv_gf / conv_us * 1e3, 2),
+             "sum_of_kernel_us": round(sum(r["us"] for r in rows), 1),
+             "layers": [{k: (round(v, 3) if isinstance(v, float) else v) for k, v in r.items()} for r in rows]}
+
+    if not a.no_extra:
+        # ---- batch 1 latency of the same stack
+        n1 = FusedNet(ops, params, 1, 224, 224, "f16")
+        n1.load_input(inputs.image(3, 1, 3, 224, 224, "f16"))
+        if use_graph:
+            n1.capture()
+        extra["resnet18_fp16_batch1_ms_per_img"] = round(_time_steps(n1, a.steps, a.warmup, use_graph) * 1e3, 4)
+        del n1
+        # ---- config 4: int8 stack, batch 16
+        qops = nets.resnet18(with_dense=False)
+        qp = inputs.net_params(qops, 4, "i8")
+        qn = FusedNet(qops, qp, 16, 224, 224, "i8", shifts=inputs.chain_shifts(qops))
+        qn.load_input(inputs.image(4, 16, 3, 224, 224, "i8"))
+        if use_graph:
+            qn.capture()
+        qsec = _time_steps(qn, a.steps, a.warmup, use_graph)
+        qrows = _layer_table(qn, qops, 16, a.layer_reps, 3)
+        qus = sum(r["us"] for r in qrows if "gflop" in r)
+        qgf = sum(r["gflop"] for r in qrows if "gflop" in r)
+        extra["resnet18_int8_batch16"] = {
+            "tops": round(2.0 * nets.macs_per_image(qops, 224, 224) * 16 / qsec / 1e12, 3),
+            "ms_per_img": round(qsec * 1e3 / 16, 5), "conv_kernels_only_tops": round(qgf / qus * 1e3, 2),
+            "frac_of_int8_mfma_peak": round(qgf / qus * 1e3 / PEAK["i8"], 4),
+            "layers": [{k: (round(v, 3) if isinstance(v, float) else v) for k, v in r.items()} for r in qrows]}
+        del qn
+        # ---- config 5: MobileNet-v1, batch 32
+        mops = nets.mobilenet_v1()
+        mp = inputs.net_params(mops, 5, "f16")
+        mn = FusedNet(mops, mp, 32, 224, 224, "f16")
+        mn.load_input(inputs.image(5, 32, 3, 224, 224, "f16"))
+        if use_graph:
+            mn.capture()
+        msec = _time_steps(mn, a.steps, a.warmup, use_graph)
+        mrows = _layer_table(mn, mops, 32, a.layer_reps, 3)
+        dw = [r for r in mrows if r.get("kernel") == "dwconv3x3_f16_kernel"]
+        pw = [r for r in mrows if r.get("kernel", "").startswith("igemm")]
+        dw_gbs = sum(r["mbytes"] for r in dw) / sum(r["us"] for r in dw) * 1e3
+        extra["mobilenet_v1_fp16_batch32"] = {
+            "ms_per_img": round(msec * 1e3 / 32, 5),
+            "tflops": round(2.0 * nets.macs_per_image(mops, 224, 224) * 32 / msec / 1e12, 3),
+            "depthwise_gbs": round(dw_gbs, 1), "depthwise_frac_of_hbm_peak": round(dw_gbs / HBM_PEAK_GBS, 4),
+            "pointwise_tflops": round(sum(r["gflop"] for r in pw) / sum(r["us"] for r in pw) * 1e3, 2),
+            "layers": [{k: (round(v, 3) if isinstance(v, float) else v) for k, v in r.items()} for r in mrows]}
+        del mn
+
+    if not a.no_cpu:
+        # ---- the CPU oracle on this host: 4 of the 32 images, one pass of the same stack
+        import oracle
+        from oracle.stack import run_float
+        nimg = 4
+        xs = inputs.image(3, a.batch, 3, 224, 224, "f16")[:nimg]
+        run_float(ops[:1], params[:1], xs[:1], "f16")            # load the library, page in
+        t0 = time.perf_counter()
+        run_float(ops, params, xs, "f16")
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(2.0 * nets.macs_per_image(ops, 224, 224) * nimg / dt / 1e12, 5),
+                               "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+                               "sample": f"{nimg} of the {a.batch} images, one pass of the full stack, fp64 loops",
+                               "seconds": round(dt, 2)}
+    out["extra"] = extra
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

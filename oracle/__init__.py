@@ -55,6 +55,11 @@ def lib():
     return _lib
 
 
+def num_threads() -> int:
+    """Host threads the conv / dense loop nests use (OpenMP over independent outputs)."""
+    return int(lib().oracle_num_threads())
+
+
 def _p(a: np.ndarray):
     return a.ctypes.data_as(C.c_void_p)
 

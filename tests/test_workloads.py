@@ -38,3 +38,20 @@ def test_generators_are_seeded_and_typed():
     x = inputs.image(1, 1, 3, 32, 32, "f32")
     assert x.dtype == np.float32 and x.min() >= -1 and x.max() < 1
     assert inputs.default_out_rshift(576) == 12 and inputs.default_out_rshift(147) == 11
+
+
+def test_int8_chain_recipe_keeps_activations_alive():
+    """The closed-form shift rule must neither kill nor saturate a 20-conv int8 chain,
+    otherwise end-to-end parity would compare constants."""
+    from oracle.stack import run_quantized
+    ops = nets.resnet18(with_dense=False)
+    params = inputs.net_params(ops, 4, "i8")
+    shifts = inputs.chain_shifts(ops)
+    t = run_quantized(ops, params, shifts, inputs.image(4, 1, 3, 224, 224, "i8"))
+    for op in ops:
+        if op.kind != "conv":
+            continue
+        y = t[op.dst].astype(np.int64)
+        assert (np.abs(y) == 127).mean() < 0.5, op.name
+        assert (y != 0).mean() > 0.3, op.name
+        assert y.min() >= -127

@@ -36,6 +36,28 @@ def default_out_rshift(k_red: int) -> int:
     return 7 + int(math.ceil(math.log2(k_red) / 2.0))
 
 
+def chain_out_rshift(k_red: int) -> int:
+    """Right shift of a conv inside a chained int8 network: round(log2(sigma_w * sqrt(K))) with
+    sigma_w = 73.3, the standard deviation of U{-127..127}.  The accumulator of a conv over
+    zero-mean weights has rms = sigma_w * sqrt(K) * rms(x), so this shift hands the next layer
+    activations of about the same rms as it received (a closed-form stand-in for the paper's
+    calibration sweep, which needs real activations)."""
+    return int(round(math.log2(73.3 * math.sqrt(k_red))))
+
+
+def chain_shifts(ops: List[Op]) -> List[dict]:
+    """Per-op {'s': out_rshift, 'l': residual_lshift} for a chained int8 network; the residual
+    carries the output's scale, so l = s."""
+    out = []
+    for op in ops:
+        if op.kind == "conv":
+            s = chain_out_rshift(op.cin * op.r * op.r)
+            out.append({"s": s, "l": s if op.res else 0})
+        else:
+            out.append({})
+    return out
+
+
 def image(config: int, n: int, c: int, h: int, w: int, mode: str) -> np.ndarray:
     """Network input, NCHW.  mode: 'f32' U[-1,1) | 'f16' N(0,1) rounded to fp16 | 'i8' U{-127..127}."""
     g = rng_for(config, 999)
