@@ -57,7 +57,7 @@ def _layer_table(net, ops, batch, reps, trials):
                 op = next(o for o in ops if o.name == name)
                 macs = d.n * ho * wo * d.k * op.cin * d.r * d.s
                 row["gflop"] = 2 * macs / 1e9
-                row["kernel"] = B.relay_conv2d_kernel_info(d)["kernel"]
+                row["kernel"] = B.relay_conv2d_kernel_name(d)
                 byts = (d.n * d.h * d.w * op.cin + d.n * ho * wo * d.k * (2 if (d.flags & B.HAS_RESIDUAL) else 1)
                         + d.k * op.cin * d.r * d.s) * es
                 row["mbytes"] = byts / 1e6

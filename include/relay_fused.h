@@ -132,12 +132,10 @@ relay_status relay_nchw_to_nhwc(int32_t dtype, int32_t n, int32_t c, int32_t h, 
  * default).  Results do not depend on the tile (int8: bit for bit). */
 relay_status relay_set_conv_tile(int32_t tile);
 
-/* Profiling aid: which implicit-GEMM kernel variant a fp16 / int8 descriptor runs on --
- * workgroup tile (bm output pixels x bn output channels), its wave grid, and whether the
- * reduction chunks align with filter taps (fast = 1).  The kernel is
- * igemm_conv_kernel<is_i8, bm, bn, waves_m, waves_n, fast> in a kernel trace. */
-relay_status relay_conv2d_kernel_info(const relay_conv2d_desc* d, int32_t* bm, int32_t* bn, int32_t* waves_m,
-                                      int32_t* waves_n, int32_t* fast);
+/* Profiling aid: the name, as a kernel trace prints it, of the implicit-GEMM kernel variant
+ * a fp16 / int8 descriptor runs on (template arguments give the workgroup's wave grid and
+ * per-wave MFMA tile).  buf receives a NUL-terminated string of at most len bytes. */
+relay_status relay_conv2d_kernel_name(const relay_conv2d_desc* d, char* buf, size_t len);
 
 /* Message of the calling thread's last failed call (static storage, never NULL). */
 const char* relay_last_error(void);

@@ -53,7 +53,7 @@ SIGNATURES = {
     "relay_global_avgpool": [_I, _I, _I, _I, _P, _P, _P],
     "relay_nchw_to_nhwc": [_I, _I, _I, _I, _I, _I, _P, _P, _P],
     "relay_set_conv_tile": [_I],
-    "relay_conv2d_kernel_info": [_DP] + [C.POINTER(_I)] * 5,
+    "relay_conv2d_kernel_name": [_DP, C.c_char_p, _SZ],
 }
 
 
@@ -163,13 +163,10 @@ def relay_nchw_to_nhwc(dtype, n, c, h, w, c_pad, x, y) -> None:
     _check(lib().relay_nchw_to_nhwc(dtype, n, c, h, w, c_pad, _ptr(x), _ptr(y), _stream()))
 
 
-def relay_conv2d_kernel_info(d: ConvDesc) -> dict:
-    v = [_I() for _ in range(5)]
-    _check(lib().relay_conv2d_kernel_info(C.byref(d), *[C.byref(t) for t in v]))
-    bm, bn, wm, wn, fast = (t.value for t in v)
-    is_i8 = "true" if d.dtype == RELAY_I8 else "false"
-    return {"bm": bm, "bn": bn, "waves_m": wm, "waves_n": wn, "fast": bool(fast),
-            "kernel": f"igemm_conv_kernel<{is_i8}, {bm}, {bn}, {wm}, {wn}, {'true' if fast else 'false'}>"}
+def relay_conv2d_kernel_name(d: ConvDesc) -> str:
+    buf = C.create_string_buffer(128)
+    _check(lib().relay_conv2d_kernel_name(C.byref(d), buf, 128))
+    return buf.value.decode()
 
 
 def relay_set_conv_tile(tile: int) -> None:

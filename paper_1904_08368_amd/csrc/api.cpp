@@ -150,21 +150,31 @@ relay_status relay_prepack_conv2d_weights(const relay_conv2d_desc* d, const void
 }
 
 relay_status relay_set_conv_tile(int32_t tile) {
-  if (tile >= relay::igemm_tile_count()) return fail(RELAY_ERR_UNSUPPORTED, "no tile %d", tile);
+  const int most = relay::igemm_dma_tile_count() > relay::igemm_tile_count() ? relay::igemm_dma_tile_count()
+                                                                             : relay::igemm_tile_count();
+  if (tile >= most) return fail(RELAY_ERR_UNSUPPORTED, "no tile %d", tile);
   g_force_tile = tile < 0 ? -1 : tile;
   return RELAY_OK;
 }
 
-relay_status relay_conv2d_kernel_info(const relay_conv2d_desc* d, int32_t* bm, int32_t* bn, int32_t* waves_m,
-                                      int32_t* waves_n, int32_t* fast) {
-  if (!bm || !bn || !waves_m || !waves_n || !fast) return fail(RELAY_ERR_NULL, "output pointers are NULL");
+static hipError_t launch_igemm(const relay::ConvArgs& a, bool is_i8, hipStream_t s) {
+  if (relay::igemm_dma_supported(a, is_i8)) return relay::launch_conv_igemm_dma(a, is_i8, g_force_tile, s);
+  return relay::launch_conv_igemm(a, is_i8, g_force_tile, s);
+}
+
+relay_status relay_conv2d_kernel_name(const relay_conv2d_desc* d, char* buf, size_t len) {
+  if (!buf || len == 0) return fail(RELAY_ERR_NULL, "name buffer is NULL or empty");
   int ho, wo;
   relay_status st = check_geometry(d, &ho, &wo);
   if (st != RELAY_OK) return st;
-  if (d->dtype != RELAY_F16 && d->dtype != RELAY_I8) return fail(RELAY_ERR_DTYPE, "only the MFMA paths have tile variants");
+  if (d->dtype != RELAY_F16 && d->dtype != RELAY_I8) return fail(RELAY_ERR_DTYPE, "only the MFMA paths have kernel variants");
   if ((st = check_igemm_support(d)) != RELAY_OK) return st;
   relay::ConvArgs a = make_args(d, ho, wo);
-  relay::igemm_kernel_info(a, d->dtype == RELAY_I8, g_force_tile, bm, bn, waves_m, waves_n, fast);
+  const bool i8 = d->dtype == RELAY_I8;
+  if (relay::igemm_dma_supported(a, i8))
+    relay::igemm_dma_kernel_name(a, i8, g_force_tile, buf, len);
+  else
+    relay::igemm_kernel_name(a, i8, g_force_tile, buf, len);
   return RELAY_OK;
 }
 
@@ -196,7 +206,7 @@ relay_status relay_fused_conv2d_bias_bn_relu(const relay_conv2d_desc* d, const v
   if ((st = check_igemm_support(d)) != RELAY_OK) return st;
   if (!aligned(x, 16) || !aligned(w_packed, 16) || !aligned(y, 16) || (residual && !aligned(residual, 16)))
     return fail(RELAY_ERR_ALIGN, "fp16 tensors must be 16-byte aligned");
-  return device_status(relay::launch_conv_igemm(a, false, g_force_tile, s), "conv2d fp16 launch");
+  return device_status(launch_igemm(a, false, s), "conv2d fp16 launch");
 }
 
 relay_status relay_qconv2d_requant(const relay_conv2d_desc* d, const int8_t* x, const int8_t* w_packed,
@@ -224,8 +234,7 @@ relay_status relay_qconv2d_requant(const relay_conv2d_desc* d, const int8_t* x, 
   relay::ConvArgs a = make_args(d, ho, wo);
   a.x = x; a.w = w_packed; a.y = y; a.res = residual; a.qbias = bias;
   a.lshift = residual_lshift; a.rshift = out_rshift;
-  return device_status(relay::launch_conv_igemm(a, true, g_force_tile, static_cast<hipStream_t>(hip_stream)),
-                       "qconv2d launch");
+  return device_status(launch_igemm(a, true, static_cast<hipStream_t>(hip_stream)), "qconv2d launch");
 }
 
 static relay_status check_dw(const relay_conv2d_desc* d, int* ho, int* wo) {

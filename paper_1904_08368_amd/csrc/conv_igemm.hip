@@ -16,41 +16,12 @@
 // BM+BN rows through LDS (double buffered, one barrier per chunk); global loads of chunk
 // i+1 are in flight while the MFMAs of chunk i run.  Padding taps and ragged rows are
 // loaded as zeros, so the main loop has no special cases.
-#include "kernels.hpp"
+#include <cstdio>
+
+#include "igemm_common.hpp"
 
 namespace relay {
 namespace {
-
-typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-typedef _Float16 half4 __attribute__((ext_vector_type(4)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef int intx4 __attribute__((ext_vector_type(4)));
-typedef int intx16 __attribute__((ext_vector_type(16)));
-
-constexpr int BKV = 4;  // 16-byte k-vectors per row per chunk (64 bytes of reduction)
-
-// LDS slot of k-vector kv in a row: XOR swizzle so that the 32 rows one MFMA operand read
-// touches spread over the banks.
-__device__ __forceinline__ int lds_slot(int row, int kv) { return row * BKV + (kv ^ ((row >> 1) & (BKV - 1))); }
-
-template <bool IS_I8>
-struct Acc;
-template <>
-struct Acc<false> {
-  typedef floatx16 type;
-  static __device__ __forceinline__ type mma(const uint4& a, const uint4& b, type c) {
-    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, a), __builtin_bit_cast(half8, b), c, 0,
-                                                  0, 0);
-  }
-};
-template <>
-struct Acc<true> {
-  typedef intx16 type;
-  static __device__ __forceinline__ type mma(const uint4& a, const uint4& b, type c) {
-    return __builtin_amdgcn_mfma_i32_32x32x32_i8(__builtin_bit_cast(intx4, a), __builtin_bit_cast(intx4, b), c, 0, 0,
-                                                 0);
-  }
-};
 
 template <bool IS_I8, int BM, int BN, int WAVES_M, int WAVES_N, bool FAST>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_conv_kernel(const ConvArgs a) {
@@ -64,7 +35,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_conv_kernel(cons
   constexpr int ROWS_PER_PASS = NT / BKV;
   static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be whole 32x32 blocks");
   static_assert((BM * BKV) % NT == 0 && (BN * BKV) % NT == 0, "staging must divide evenly");
-  typedef typename Acc<IS_I8>::type acc_t;
+  typedef typename Mma<IS_I8>::acc_t acc_t;
+  typedef typename Mma<IS_I8>::scalar_t scalar_t;
 
   __shared__ uint4 lds[2][(BM + BN) * BKV];
 
@@ -184,7 +156,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_conv_kernel(cons
 #pragma unroll
       for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
-        for (int tm = 0; tm < TM; ++tm) acc[tn][tm] = Acc<IS_I8>::mma(wf[tn], xf[tm], acc[tn][tm]);
+        for (int tm = 0; tm < TM; ++tm) acc[tn][tm] = Mma<IS_I8>::mma(wf[tn], xf[tm], acc[tn][tm]);
     }
     if (kc + 1 < nchunks) store_chunk(buf ^ 1);
     __syncthreads();
@@ -193,79 +165,25 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_conv_kernel(cons
   // ---- epilogue: accumulator element v of a 32x32 block is channel 8*(v/4) + 4*(lane/32) + v%4
   //      (block row) of pixel lane%32 (block column).
   const bool vec_ok = (a.K & 3) == 0;
+  EpiParams ep[TN][4];
+#pragma unroll
+  for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) ep[tn][g] = load_epi_params<IS_I8>(a, n0 + wn * WTN + tn * 32 + 8 * g + 4 * lhalf);
 #pragma unroll
   for (int tm = 0; tm < TM; ++tm) {
     const int m = m0 + wm * WTM + tm * 32 + lrow;
     if (m >= a.M) continue;
 #pragma unroll
-    for (int tn = 0; tn < TN; ++tn) {
+    for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int ch = n0 + wn * WTN + tn * 32 + 8 * g + 4 * lhalf;
         if (ch >= a.K) continue;
-        const size_t o = (size_t)m * a.K + ch;
-        if constexpr (!IS_I8) {
-          float t[4];
-          _Float16 rs[4] = {0, 0, 0, 0};
-          if (a.flags & F_RES) {
-            if (vec_ok) {
-              const half4 rv = *reinterpret_cast<const half4*>(static_cast<const _Float16*>(a.res) + o);
-#pragma unroll
-              for (int e = 0; e < 4; ++e) rs[e] = rv[e];
-            } else {
-#pragma unroll
-              for (int e = 0; e < 4; ++e)
-                if (ch + e < a.K) rs[e] = static_cast<const _Float16*>(a.res)[o + e];
-            }
-          }
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int c = (ch + e < a.K) ? ch + e : ch;
-            float v = acc[tn][tm][4 * g + e];
-            if (a.flags & F_BIAS) v += a.bias[c];
-            if (a.flags & F_BN) v = v * a.scale[c] + a.shift[c];
-            if (a.flags & F_RES) v += (float)rs[e];
-            if (a.flags & F_RELU) v = v > 0.f ? v : 0.f;
-            t[e] = v;
-          }
-          _Float16* yp = static_cast<_Float16*>(a.y) + o;
-          if (vec_ok) {
-            half4 hv;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) hv[e] = (_Float16)t[e];
-            *reinterpret_cast<half4*>(yp) = hv;
-          } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-              if (ch + e < a.K) yp[e] = (_Float16)t[e];
-          }
-        } else {
-          int qv[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int c = (ch + e < a.K) ? ch + e : ch;
-            int v = acc[tn][tm][4 * g + e];
-            if (a.flags & F_BIAS) v += a.qbias[c];
-            if ((a.flags & F_RES) && ch + e < a.K)
-              v += (int)static_cast<const int8_t*>(a.res)[o + e] * (1 << a.lshift);
-            if (a.rshift > 0) v = (v + (1 << (a.rshift - 1))) >> a.rshift;  // arithmetic shift
-            v = v < -127 ? -127 : (v > 127 ? 127 : v);
-            if (a.flags & F_RELU) v = v > 0 ? v : 0;
-            qv[e] = v;
-          }
-          int8_t* yp = static_cast<int8_t*>(a.y) + o;
-          if (vec_ok) {
-            const unsigned pk = (unsigned)(qv[0] & 0xff) | ((unsigned)(qv[1] & 0xff) << 8) |
-                                ((unsigned)(qv[2] & 0xff) << 16) | ((unsigned)(qv[3] & 0xff) << 24);
-            *reinterpret_cast<unsigned*>(yp) = pk;
-          } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-              if (ch + e < a.K) yp[e] = (int8_t)qv[e];
-          }
-        }
+        const scalar_t v[4] = {acc[tn][tm][4 * g], acc[tn][tm][4 * g + 1], acc[tn][tm][4 * g + 2],
+                               acc[tn][tm][4 * g + 3]};
+        epilogue_store4<IS_I8>(a, v, m, ch, ep[tn][g], vec_ok);
       }
-    }
   }
 }
 
@@ -313,14 +231,11 @@ int pick_tile(const ConvArgs& a) {
 
 int igemm_tile_count() { return kNumTiles; }
 
-void igemm_kernel_info(const ConvArgs& a, bool is_i8, int tile, int* bm, int* bn, int* waves_m, int* waves_n,
-                       int* fast) {
+void igemm_kernel_name(const ConvArgs& a, bool is_i8, int tile, char* buf, size_t len) {
   if (tile < 0 || tile >= kNumTiles) tile = pick_tile(a);
-  *bm = kTiles[tile].bm;
-  *bn = kTiles[tile].bn;
-  *waves_m = kTiles[tile].waves_m;
-  *waves_n = kTiles[tile].waves_n;
-  *fast = (a.C % (BKV * (is_i8 ? 16 : 8))) == 0;
+  const bool fast = (a.C % (BKV * (is_i8 ? 16 : 8))) == 0;
+  snprintf(buf, len, "igemm_conv_kernel<%s, %d, %d, %d, %d, %s>", is_i8 ? "true" : "false", kTiles[tile].bm,
+           kTiles[tile].bn, kTiles[tile].waves_m, kTiles[tile].waves_n, fast ? "true" : "false");
 }
 
 hipError_t launch_conv_igemm(const ConvArgs& a, bool is_i8, int tile, hipStream_t st) {

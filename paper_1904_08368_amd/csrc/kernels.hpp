@@ -2,6 +2,7 @@
 // Launchers enqueue on the given stream and return the HIP status of the launch.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <stddef.h>
 #include <stdint.h>
 
 namespace relay {
@@ -37,9 +38,13 @@ hipError_t launch_conv_direct_f32(const ConvArgs& a, hipStream_t st);
 // tile < 0: pick by heuristic.
 hipError_t launch_conv_igemm(const ConvArgs& a, bool is_i8, int tile, hipStream_t st);
 int igemm_tile_count();
-// Which instantiation launch_conv_igemm would use: tile extents, wave grid, fast tap decode.
-void igemm_kernel_info(const ConvArgs& a, bool is_i8, int tile, int* bm, int* bn, int* waves_m, int* waves_n,
-                       int* fast);
+// Name, as a kernel trace prints it, of the instantiation launch_conv_igemm would use.
+void igemm_kernel_name(const ConvArgs& a, bool is_i8, int tile, char* buf, size_t len);
+// The direct-to-LDS variant (conv_igemm_dma.hip) and the shapes it takes.
+bool igemm_dma_supported(const ConvArgs& a, bool is_i8);
+hipError_t launch_conv_igemm_dma(const ConvArgs& a, bool is_i8, int tile, hipStream_t st);
+int igemm_dma_tile_count();
+void igemm_dma_kernel_name(const ConvArgs& a, bool is_i8, int tile, char* buf, size_t len);
 hipError_t launch_dwconv_f16(const ConvArgs& a, hipStream_t st);
 hipError_t launch_dense(int m, int n, int k, bool is_f16, const void* x, const void* w, const float* bias,
                         int act, void* y, hipStream_t st);

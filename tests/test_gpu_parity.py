@@ -102,10 +102,11 @@ def test_fp16_conv_full_epilogue(G, case):
     assert O.max_rel_err(G.run_conv_f16(x, wt, st, pd), ref0) <= TOL_F16
 
 
-@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4])
-def test_fp16_conv_every_tile_shape(G, tile):
+@pytest.mark.parametrize("c", [64, 24])          # 64: direct-to-LDS kernel; 24: register-staged kernel
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4, 5])
+def test_fp16_conv_every_tile_shape(G, tile, c):
     g = _rng(50)
-    n, c, h, w, k = 2, 64, 23, 27, 192
+    n, h, w, k = 2, 23, 27, 192
     x = _h(g.standard_normal((n, c, h, w)))
     wt = _h(g.standard_normal((k, c, 3, 3)) * np.sqrt(2.0 / (c * 9)))
     sc = (1 + g.standard_normal(k) * 0.1).astype(np.float32)
@@ -167,11 +168,12 @@ def test_int8_qconv_bit_exact(G, case):
         assert np.array_equal(G.run_qconv(x, wt, st, pd, rshift=s2), ref)
 
 
-@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4])
-def test_int8_every_tile_shape_and_repeatable(G, tile):
+@pytest.mark.parametrize("c", [64, 48])
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4, 5])
+def test_int8_every_tile_shape_and_repeatable(G, tile, c):
     g = _rng(150)
-    x = g.integers(-127, 128, (2, 64, 23, 27)).astype(np.int8)
-    wt = g.integers(-127, 128, (192, 64, 3, 3)).astype(np.int8)
+    x = g.integers(-127, 128, (2, c, 23, 27)).astype(np.int8)
+    wt = g.integers(-127, 128, (192, c, 3, 3)).astype(np.int8)
     ref = O.qconv2d_requant(x, wt, stride=(1, 1), pad=(1, 1), out_rshift=12, relu_flag=True)
     for _ in range(3):
         assert np.array_equal(G.run_qconv(x, wt, 1, 1, rshift=12, relu=True, tile=tile), ref)
