@@ -1,22 +1,29 @@
 // Implicit-GEMM conv2d for gfx950: MFMA main loop fed by direct global->LDS loads through a
-// multi-stage LDS ring, fused epilogue in registers (paper Section 4.1 / 4.2).
+// multi-stage LDS ring, fused epilogue (paper Section 4.1 / 4.2).
 //
 // GEMM view: rows m = (image, p, q) output pixels, columns = output channels, reduction
 // kk = (r, s, c).  NHWC activations and [k][r][s][c] filters are both contiguous along the
 // reduction axis and move as 16-byte k-vectors.  A workgroup owns BM pixels x BN channels;
-// a wave owns TM x TN MFMA blocks of 32x32 (filters are the A operand, so a lane ends up
-// with 4 consecutive channels of one pixel per accumulator group = one NHWC store).
+// a wave owns TM x TN MFMA blocks of 32x32 (filters are the A operand).
 //
 // Staging: per 64-byte reduction chunk every wave issues `buffer_load_dwordx4 ... lds`
 // instructions, each moving 16 tile rows x 64 B straight into LDS (lane i writes 16 bytes
 // at base + 16*i), no VGPRs involved.  The LDS bank swizzle is applied on the global side:
 // lane i fetches the k-vector that belongs in its fixed LDS slot.  Filter taps that fall in
-// the padding, rows past the end of the tensor and channels past Cout are given a buffer
-// offset beyond num_records; the buffer unit then writes zeros (checked on hardware), so
-// the MFMA loop has no special cases.  NS ring stages keep NS-1 chunks in flight behind one
-// barrier per chunk.  The loads are inline asm on purpose: the compiler, not seeing LDS
-// written, does not drain the memory pipeline before every LDS read; ordering is by the
-// explicit vmcnt waits and barriers below.
+// the padding, rows past the end of the tensor and channels past Cout get a buffer offset
+// beyond num_records; the buffer unit then writes zeros (checked on hardware), so the MFMA
+// loop has no special cases.  NS ring stages keep NS-1 chunks in flight behind one barrier
+// per chunk.  The loads are inline asm on purpose: the compiler, not seeing LDS written,
+// does not drain the memory pipeline before every LDS read; ordering is by the explicit
+// vmcnt waits and barriers below.  The texture addresser takes 64 B/clk per CU, about as
+// long per chunk as the MFMAs of a 256x128 tile take, so the loads of chunk kc+NS-1 are
+// issued one at a time between the MFMAs of chunk kc instead of in a burst after the
+// barrier, where all waves would queue for the addresser while the matrix pipe idles.
+//
+// Epilogue: accumulators go through LDS once (wave-private, 32 pixels at a time) so that a
+// lane ends up with 8 consecutive channels of one pixel: per-channel constants are then the
+// same for every pixel a lane handles, the residual is one 16-byte load and the result one
+// 16-byte (fp16) or 8-byte (int8) store in full NHWC rows.
 //
 // Needs C to be a whole number of chunks (32 halves / 64 int8) and R*S <= 32; other shapes
 // go to the register-staged kernel in conv_igemm.hip.
@@ -51,23 +58,49 @@ __device__ __forceinline__ intx4 make_rsrc(const void* p, unsigned bytes) {
   return r;
 }
 
+// 32-bit pattern of an accumulator element (taken by value: a bit cast applied directly to a
+// vector-element lvalue is not reliable)
+__device__ __forceinline__ unsigned as_u32(float f) { return __builtin_bit_cast(unsigned, f); }
+__device__ __forceinline__ unsigned as_u32(int i) { return (unsigned)i; }
+
 constexpr unsigned kOob = 0x80000000u;  // beyond any num_records this library accepts
 
-template <bool IS_I8, int WAVES_M, int WAVES_N, int TM, int TN, int NS>
+// floor(t / d) and remainder for 0 <= t < 2^22, d > 0: float reciprocal plus one fix-up step.
+__device__ __forceinline__ void small_divmod(int t, int d, float rcp_d, int& q, int& r) {
+  q = (int)((float)t * rcp_d);
+  r = t - q * d;
+  if (r < 0) {
+    r += d;
+    --q;
+  } else if (r >= d) {
+    r -= d;
+    ++q;
+  }
+}
+
+// KP = 64-byte planes per ring chunk (a chunk covers KP*64 bytes of reduction; each plane is
+// a [rows][64 B] sub-tile with its own swizzle, because 128-byte LDS rows cannot be read
+// conflict-free).  More planes = fewer barriers and fewer exposed LDS latencies per MFMA.
+template <bool IS_I8, int WAVES_M, int WAVES_N, int TM, int TN, int NS, int KP>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void igemm_dma_kernel(const ConvArgs a) {
   constexpr int NW = WAVES_M * WAVES_N;
   constexpr int VE = IS_I8 ? 16 : 8;
   constexpr int ES = IS_I8 ? 1 : 2;
-  constexpr int CK = BKV * VE;
+  constexpr int CK = KP * BKV * VE;
   constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
   constexpr int WTM = TM * 32, WTN = TN * 32;
   constexpr int XB = BM / 16, WB = BN / 16;  // 1 KiB staging blocks: 16 rows x 64 B
   static_assert(XB % NW == 0 && WB % NW == 0, "staging blocks must divide over the waves");
-  constexpr int XL = XB / NW, WL = WB / NW, LPC = XL + WL;  // loads per chunk per wave
-  constexpr int STAGE = (BM + BN) * BKV;                    // 16-byte slots per ring stage
+  constexpr int XL = XB / NW, WL = WB / NW;    // loads per plane per wave
+  constexpr int LPC = KP * (XL + WL);          // loads per chunk per wave
+  constexpr int PLANE = (BM + BN) * BKV;       // 16-byte slots per plane
+  constexpr int STAGE = KP * PLANE;            // ... per ring stage
+  constexpr int KSTEPS = KP * (BKV / 2);       // MFMA k-steps per chunk
   static_assert((NS - 1) * LPC <= 63, "vmcnt is a 6-bit counter");
+  static_assert(LPC <= TM * TN * KSTEPS, "one load is issued behind each MFMA of a chunk");
+  constexpr int EP = WTN / 4 + 1;  // epilogue staging pitch (16-byte slots) of one pixel row, padded
+  static_assert(NW * 32 * EP <= NS * STAGE, "epilogue staging reuses the ring");
   typedef typename Mma<IS_I8>::acc_t acc_t;
-  typedef typename Mma<IS_I8>::scalar_t scalar_t;
 
   __shared__ uint4 ring[NS * STAGE];
 
@@ -80,32 +113,55 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void igemm_dma_kernel(co
   const int tile_n = tile % tiles_n, tile_m = tile / tiles_n;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
-  // ---- staging role of this lane inside a 16-row block: row srow, physical slot sphys
+  // ---- epilogue constants of this lane: after the transposition it owns channels
+  //      [ech, ech + 8) of whichever pixels it handles.  Fetched first so that the latency
+  //      hides under the main loop (older than every ring load, so vmcnt accounting holds).
+  constexpr int CG = WTN / 8;  // lanes per pixel row in the epilogue
+  const int ech = n0 + wn * WTN + (lane % CG) * 8;
+  float emul[8], eadd[8];
+  int ebias[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int c = ech + e < a.K ? ech + e : a.K - 1;
+    if constexpr (IS_I8) {
+      ebias[e] = (a.flags & F_BIAS) ? a.qbias[c] : 0;
+    } else {
+      const float sc = (a.flags & F_BN) ? a.scale[c] : 1.f;
+      const float sf = (a.flags & F_BN) ? a.shift[c] : 0.f;
+      const float b = (a.flags & F_BIAS) ? a.bias[c] : 0.f;
+      emul[e] = sc;
+      eadd[e] = b * sc + sf;  // (acc + b)*sc + sf
+    }
+  }
+
+  // ---- staging role of this lane inside a 16-row block: row srow, physical slot sphys.
+  //      The tile's first pixel is decoded once (uniform); rows are small offsets from it.
   const int srow = lane >> 2, sphys = lane & 3;
+  const int HoWo = a.Ho * a.Wo;
+  const int n_0 = m0 / HoWo;
+  const int rem_0 = m0 - n_0 * HoWo;
+  const int p_0 = rem_0 / a.Wo;
+  const int q_0 = rem_0 - p_0 * a.Wo;
+  const float rcp_wo = 1.0f / (float)a.Wo, rcp_ho = 1.0f / (float)a.Ho;
   int x_off[XL];        // byte offset of tap (0,0), channel 0 of the row's k-vector
   unsigned x_taps[XL];  // bit t set: tap t of this row lies inside the image
-  const int HoWo = a.Ho * a.Wo;
 #pragma unroll
   for (int j = 0; j < XL; ++j) {
     const int row = (wave * XL + j) * 16 + srow;
     const int kvl = sphys ^ ((row >> 1) & (BKV - 1));
-    const int m = m0 + row;
+    int dp, q, dn, p;
+    small_divmod(q_0 + row, a.Wo, rcp_wo, dp, q);
+    small_divmod(p_0 + dp, a.Ho, rcp_ho, dn, p);
+    const int n = n_0 + dn;
+    const int ih0 = p * a.sh - a.ph, iw0 = q * a.sw - a.pw;
+    unsigned rowbits = 0, colbits = 0;
+    for (int r = 0; r < a.R; ++r) rowbits |= ((unsigned)(ih0 + r) < (unsigned)a.H ? 1u : 0u) << r;
+    for (int s = 0; s < a.S; ++s) colbits |= ((unsigned)(iw0 + s) < (unsigned)a.W ? 1u : 0u) << s;
     unsigned taps = 0;
-    int off = 0;
-    if (m < a.M) {
-      const int n = m / HoWo;
-      const int rem = m - n * HoWo;
-      const int p = rem / a.Wo;
-      const int q = rem - p * a.Wo;
-      const int ih0 = p * a.sh - a.ph, iw0 = q * a.sw - a.pw;
-      off = (((n * a.H + ih0) * a.W + iw0) * a.C + kvl * VE) * ES;
-      int t = 0;
-      for (int r = 0; r < a.R; ++r)
-        for (int s = 0; s < a.S; ++s, ++t)
-          if ((unsigned)(ih0 + r) < (unsigned)a.H && (unsigned)(iw0 + s) < (unsigned)a.W) taps |= 1u << t;
-    }
-    x_off[j] = off;
-    x_taps[j] = taps;
+    for (int r = 0; r < a.R; ++r)
+      if ((rowbits >> r) & 1u) taps |= colbits << (r * a.S);
+    x_taps[j] = (m0 + row < a.M) ? taps : 0u;
+    x_off[j] = (((n * a.H + ih0) * a.W + iw0) * a.C + kvl * VE) * ES;
   }
   unsigned w_off[WL];
 #pragma unroll
@@ -119,20 +175,26 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void igemm_dma_kernel(co
   const intx4 rs_w = make_rsrc(a.w, (unsigned)((size_t)a.K * a.Kp * ES));
   const unsigned ring_base = (unsigned)(size_t)(__attribute__((address_space(3))) uint4*)(&ring[0]);
 
-  // reduction position of the next chunk to be issued (wave-uniform)
+  const int nchunks = a.Kred / CK;
+  // reduction position of the chunk being issued (wave-uniform); chunks past the end are
+  // issued as all-out-of-range loads into a free stage so that every iteration looks alike
   int is_tap = 0, is_r = 0, is_s = 0, is_c = 0, is_kc = 0;
-  auto issue_chunk = [&](int stage) {
-    const unsigned delta = (unsigned)(((is_r * a.W + is_s) * a.C + is_c) * ES);
-    const unsigned sbase = ring_base + (unsigned)(stage * STAGE) * 16u;
-#pragma unroll
-    for (int j = 0; j < XL; ++j) {
-      const unsigned voff = ((x_taps[j] >> is_tap) & 1u) ? (unsigned)x_off[j] + delta : kOob;
-      lds_dma16(rs_x, sbase + (unsigned)((wave * XL + j) * 64) * 16u, voff);
+  unsigned is_delta = 0, is_sbase = ring_base;
+  bool is_live = nchunks > 0;
+  auto issue_one = [&](int idx) {  // idx-th load of the chunk: per plane XL activation blocks, then WL filter blocks
+    const int plane = idx / (XL + WL), i = idx % (XL + WL);
+    const unsigned pbase = is_sbase + (unsigned)(plane * PLANE) * 16u;
+    if (i < XL) {
+      const unsigned voff =
+          (is_live && ((x_taps[i] >> is_tap) & 1u)) ? (unsigned)x_off[i] + is_delta + (unsigned)(plane * 64) : kOob;
+      lds_dma16(rs_x, pbase + (unsigned)((wave * XL + i) * 64) * 16u, voff);
+    } else {
+      const int j = i - XL;
+      const unsigned voff = is_live ? w_off[j] + (unsigned)(is_kc * CK * ES + plane * 64) : kOob;
+      lds_dma16(rs_w, pbase + (unsigned)(BM * BKV + (wave * WL + j) * 64) * 16u, voff);
     }
-    const unsigned wdelta = (unsigned)(is_kc * CK * ES);
-#pragma unroll
-    for (int j = 0; j < WL; ++j)
-      lds_dma16(rs_w, sbase + (unsigned)(BM * BKV + (wave * WL + j) * 64) * 16u, w_off[j] + wdelta);
+  };
+  auto next_chunk = [&](int stage) {  // advance the issue position to the next chunk, landing in `stage`
     ++is_kc;
     is_c += CK;
     if (is_c == a.C) {
@@ -143,6 +205,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void igemm_dma_kernel(co
         ++is_r;
       }
     }
+    is_live = is_kc < nchunks;
+    is_delta = (unsigned)(((is_r * a.W + is_s) * a.C + is_c) * ES);
+    is_sbase = ring_base + (unsigned)(stage * STAGE) * 16u;
   };
 
   acc_t acc[TN][TM];
@@ -153,99 +218,209 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void igemm_dma_kernel(co
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[tn][tm][v] = 0;
 
-  const int nchunks = a.Kred / CK;
 #pragma unroll
-  for (int s = 0; s < NS - 1; ++s)
-    if (s < nchunks) issue_chunk(s);
+  for (int s = 0; s < NS - 1; ++s) {
+#pragma unroll
+    for (int i = 0; i < LPC; ++i) issue_one(i);
+    next_chunk(s + 1 == NS ? 0 : s + 1);
+  }
 
   const int lrow = lane & 31, lhalf = lane >> 5;
-  int stage = 0;           // ring stage of chunk kc
-  int fill = NS - 1;       // ring stage the next issued chunk goes to
+  int stage = 0;      // ring stage of chunk kc
+  int fill = NS - 1;  // ring stage the chunk issued during this iteration lands in (set by next_chunk above)
   for (int kc = 0; kc < nchunks; ++kc) {
-    // chunk kc has landed once at most the loads of the chunks issued after it are pending
-    if (kc + NS - 2 < nchunks)
-      wait_loads<(NS - 2) * LPC>();
-    else
-      wait_loads<0>();
+    // chunk kc has landed once only the loads of the NS-2 chunks issued after it are pending
+    wait_loads<(NS - 2) * LPC>();
     __builtin_amdgcn_s_barrier();  // everyone's part of chunk kc is in LDS; stage `fill` is free again
-    if (kc + NS - 1 < nchunks) issue_chunk(fill);
-    const uint4* xs = ring + stage * STAGE;
-    const uint4* ws = xs + BM * BKV;
-#pragma unroll
-    for (int ks = 0; ks < BKV / 2; ++ks) {
-      const int kq = 2 * ks + lhalf;
-      uint4 wf[TN], xf[TM];
+    const uint4* st = ring + stage * STAGE;
+    // operand fetch of k-step k: plane k/2, k-vectors 2*(k%2) + lane/32
+    auto fetch = [&](int k, uint4(&wf)[TN], uint4(&xf)[TM]) {
+      const uint4* xs = st + (k >> 1) * PLANE;
+      const uint4* ws = xs + BM * BKV;
+      const int kq = 2 * (k & 1) + lhalf;
 #pragma unroll
       for (int tn = 0; tn < TN; ++tn) wf[tn] = ws[lds_slot(wn * WTN + tn * 32 + lrow, kq)];
 #pragma unroll
       for (int tm = 0; tm < TM; ++tm) xf[tm] = xs[lds_slot(wm * WTM + tm * 32 + lrow, kq)];
+    };
+    auto mma_step = [&](int k, const uint4(&wf)[TN], const uint4(&xf)[TM]) {
 #pragma unroll
       for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
-        for (int tm = 0; tm < TM; ++tm) acc[tn][tm] = Mma<IS_I8>::mma(wf[tn], xf[tm], acc[tn][tm]);
+        for (int tm = 0; tm < TM; ++tm) {
+          acc[tn][tm] = Mma<IS_I8>::mma(wf[tn], xf[tm], acc[tn][tm]);
+          const int i = (k * TN + tn) * TM + tm;  // one ring load rides behind each MFMA
+          if (i < LPC) {
+            __builtin_amdgcn_sched_barrier(0);  // keep the load behind this MFMA, not hoisted above all of them
+            issue_one(i);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+    };
+    // operands of k-step k+1 are fetched while the MFMAs of k-step k run (two register sets)
+    uint4 wfa[TN], xfa[TM], wfb[TN], xfb[TM];
+    fetch(0, wfa, xfa);
+#pragma unroll
+    for (int k = 0; k < KSTEPS; k += 2) {
+      fetch(k + 1, wfb, xfb);
+      mma_step(k, wfa, xfa);
+      if (k + 2 < KSTEPS) fetch(k + 2, wfa, xfa);
+      mma_step(k + 1, wfb, xfb);
     }
-    stage = stage + 1 == NS ? 0 : stage + 1;
     fill = fill + 1 == NS ? 0 : fill + 1;
+    next_chunk(fill);
+    stage = stage + 1 == NS ? 0 : stage + 1;
   }
 
-  // ---- epilogue: element v of a 32x32 accumulator block is channel 8*(v/4) + 4*(lane/32) + v%4
-  //      of pixel lane%32.  Per-channel constants are fetched before any store.
-  const bool vec_ok = (a.K & 3) == 0;
+  // ---- epilogue.  Element v of a 32x32 accumulator block is channel 8*(v/4) + 4*(lane/32) + v%4
+  //      of pixel lane%32.  Each wave transposes its blocks through a private LDS region.
+  wait_loads<0>();               // the trailing out-of-range loads still write zeros into the ring
+  __builtin_amdgcn_s_barrier();  // every wave is done reading the ring
+  uint4* stg = ring + wave * (32 * EP);
+  constexpr int PPI = 64 / CG;  // pixels per pass of 64 lanes
+  const int epix = lane / CG, ecg = lane % CG;
+  const bool vec_ok = (a.K & 7) == 0;
 #pragma unroll
-  for (int tn = 0; tn < TN; ++tn) {
-    EpiParams ep[4];
+  for (int tm = 0; tm < TM; ++tm) {
 #pragma unroll
-    for (int g = 0; g < 4; ++g) ep[g] = load_epi_params<IS_I8>(a, n0 + wn * WTN + tn * 32 + 8 * g + 4 * lhalf);
-#pragma unroll
-    for (int tm = 0; tm < TM; ++tm) {
-      const int m = m0 + wm * WTM + tm * 32 + lrow;
-      if (m >= a.M) continue;
+    for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const int ch = n0 + wn * WTN + tn * 32 + 8 * g + 4 * lhalf;
-        if (ch >= a.K) continue;
-        const scalar_t v[4] = {acc[tn][tm][4 * g], acc[tn][tm][4 * g + 1], acc[tn][tm][4 * g + 2],
-                               acc[tn][tm][4 * g + 3]};
-        epilogue_store4<IS_I8>(a, v, m, ch, ep[g], vec_ok);
+        uint4 v;
+        v.x = as_u32(acc[tn][tm][4 * g]);
+        v.y = as_u32(acc[tn][tm][4 * g + 1]);
+        v.z = as_u32(acc[tn][tm][4 * g + 2]);
+        v.w = as_u32(acc[tn][tm][4 * g + 3]);
+        stg[lrow * EP + tn * 8 + 2 * g + lhalf] = v;
+      }
+    // same wave wrote what it now reads: LDS operations of a wave execute in order
+#pragma unroll
+    for (int it = 0; it < 32 / PPI; ++it) {
+      const int pix = it * PPI + epix;
+      const uint4 lo = stg[pix * EP + ecg * 2], hi = stg[pix * EP + ecg * 2 + 1];
+      const unsigned raw[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+      const int m = m0 + wm * WTM + tm * 32 + pix;
+      if (m >= a.M || ech >= a.K) continue;
+      const size_t o = (size_t)m * a.K + ech;
+      if constexpr (!IS_I8) {
+        float t[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) t[e] = __builtin_bit_cast(float, raw[e]) * emul[e] + eadd[e];
+        if (a.flags & F_RES) {
+          const _Float16* rp = static_cast<const _Float16*>(a.res) + o;
+          if (vec_ok) {
+            const half8 rv = *reinterpret_cast<const half8*>(rp);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) t[e] += (float)rv[e];
+          } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+              if (ech + e < a.K) t[e] += (float)rp[e];
+          }
+        }
+        half8 hv;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          if (a.flags & F_RELU) t[e] = t[e] > 0.f ? t[e] : 0.f;
+          hv[e] = (_Float16)t[e];
+        }
+        _Float16* yp = static_cast<_Float16*>(a.y) + o;
+        if (vec_ok) {
+          *reinterpret_cast<half8*>(yp) = hv;
+        } else {
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            if (ech + e < a.K) yp[e] = hv[e];
+        }
+      } else {
+        int t[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) t[e] = (int)raw[e] + ebias[e];
+        if (a.flags & F_RES) {
+          const int8_t* rp = static_cast<const int8_t*>(a.res) + o;
+          if (vec_ok) {
+            const uint2 rv = *reinterpret_cast<const uint2*>(rp);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              t[e] += (int)(int8_t)(rv.x >> (8 * e)) * (1 << a.lshift);
+              t[4 + e] += (int)(int8_t)(rv.y >> (8 * e)) * (1 << a.lshift);
+            }
+          } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+              if (ech + e < a.K) t[e] += (int)rp[e] * (1 << a.lshift);
+          }
+        }
+        unsigned pk[2] = {0u, 0u};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          int q = t[e];
+          if (a.rshift > 0) q = (q + (1 << (a.rshift - 1))) >> a.rshift;  // arithmetic shift: floor
+          q = q < -127 ? -127 : (q > 127 ? 127 : q);
+          if (a.flags & F_RELU) q = q > 0 ? q : 0;
+          t[e] = q;
+          pk[e >> 2] |= (unsigned)(q & 0xff) << (8 * (e & 3));
+        }
+        int8_t* yp = static_cast<int8_t*>(a.y) + o;
+        if (vec_ok) {
+          *reinterpret_cast<uint2*>(yp) = make_uint2(pk[0], pk[1]);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            if (ech + e < a.K) yp[e] = (int8_t)t[e];
+        }
       }
     }
   }
 }
 
 struct DmaTile {
-  int waves_m, waves_n, tm, tn, ns;
+  int waves_m, waves_n, tm, tn, ns, kp;
   constexpr int bm() const { return waves_m * tm * 32; }
   constexpr int bn() const { return waves_n * tn * 32; }
 };
 // largest first; must match launch_typed
 constexpr DmaTile kTiles[] = {
-    {2, 2, 4, 2, 3},  // 256 x 128
-    {4, 1, 4, 2, 3},  // 512 x 64
-    {2, 1, 4, 2, 3},  // 256 x 64, two waves
-    {2, 2, 2, 2, 3},  // 128 x 128
-    {2, 2, 2, 1, 4},  // 128 x 64
-    {2, 2, 1, 1, 4},  // 64 x 64
+    {2, 2, 4, 2, 3, 1},  // 256 x 128
+    {4, 1, 4, 2, 3, 1},  // 512 x 64
+    {2, 1, 4, 2, 3, 1},  // 256 x 64, two waves
+    {2, 2, 2, 2, 3, 1},  // 128 x 128
+    {2, 2, 2, 1, 4, 1},  // 128 x 64
+    {2, 2, 1, 1, 4, 1},  // 64 x 64
+    // 128-byte chunks (need C % 64 == 0 for fp16, C % 128 == 0 for int8)
+    {2, 2, 4, 2, 3, 2},  // 256 x 128
+    {2, 2, 4, 2, 2, 2},  // 256 x 128, two stages
+    {2, 2, 2, 2, 3, 2},  // 128 x 128
+    {2, 2, 2, 1, 3, 2},  // 128 x 64
+    {2, 2, 1, 1, 3, 2},  // 64 x 64
+    {2, 1, 4, 2, 3, 2},  // 256 x 64, two waves
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
-template <bool IS_I8, int WAVES_M, int WAVES_N, int TM, int TN, int NS>
+template <bool IS_I8, int WAVES_M, int WAVES_N, int TM, int TN, int NS, int KP>
 hipError_t launch_one(const ConvArgs& a, hipStream_t st) {
   constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
   const int tiles = ((a.M + BM - 1) / BM) * ((a.K + BN - 1) / BN);
-  hipLaunchKernelGGL((igemm_dma_kernel<IS_I8, WAVES_M, WAVES_N, TM, TN, NS>), dim3(tiles), dim3(64 * WAVES_M * WAVES_N),
-                     0, st, a);
+  hipLaunchKernelGGL((igemm_dma_kernel<IS_I8, WAVES_M, WAVES_N, TM, TN, NS, KP>), dim3(tiles),
+                     dim3(64 * WAVES_M * WAVES_N), 0, st, a);
   return hipGetLastError();
 }
 
 template <bool IS_I8>
 hipError_t launch_typed(const ConvArgs& a, int tile, hipStream_t st) {
   switch (tile) {
-    case 0: return launch_one<IS_I8, 2, 2, 4, 2, 3>(a, st);
-    case 1: return launch_one<IS_I8, 4, 1, 4, 2, 3>(a, st);
-    case 2: return launch_one<IS_I8, 2, 1, 4, 2, 3>(a, st);
-    case 3: return launch_one<IS_I8, 2, 2, 2, 2, 3>(a, st);
-    case 4: return launch_one<IS_I8, 2, 2, 2, 1, 4>(a, st);
-    default: return launch_one<IS_I8, 2, 2, 1, 1, 4>(a, st);
+    case 0: return launch_one<IS_I8, 2, 2, 4, 2, 3, 1>(a, st);
+    case 1: return launch_one<IS_I8, 4, 1, 4, 2, 3, 1>(a, st);
+    case 2: return launch_one<IS_I8, 2, 1, 4, 2, 3, 1>(a, st);
+    case 3: return launch_one<IS_I8, 2, 2, 2, 2, 3, 1>(a, st);
+    case 4: return launch_one<IS_I8, 2, 2, 2, 1, 4, 1>(a, st);
+    case 5: return launch_one<IS_I8, 2, 2, 1, 1, 4, 1>(a, st);
+    case 6: return launch_one<IS_I8, 2, 2, 4, 2, 3, 2>(a, st);
+    case 7: return launch_one<IS_I8, 2, 2, 4, 2, 2, 2>(a, st);
+    case 8: return launch_one<IS_I8, 2, 2, 2, 2, 3, 2>(a, st);
+    case 9: return launch_one<IS_I8, 2, 2, 2, 1, 3, 2>(a, st);
+    case 10: return launch_one<IS_I8, 2, 2, 1, 1, 3, 2>(a, st);
+    default: return launch_one<IS_I8, 2, 1, 4, 2, 3, 2>(a, st);
   }
 }
 
@@ -253,14 +428,22 @@ long tiles_of(const ConvArgs& a, const DmaTile& t) {
   return (long)((a.M + t.bm() - 1) / t.bm()) * ((a.K + t.bn() - 1) / t.bn());
 }
 
-// Largest tile that still gives every compute unit a workgroup; smaller tiles as the layer shrinks.
+// can tile t run this layer?  (its chunk must divide the channel count)
+bool tile_fits(const ConvArgs& a, bool is_i8, int t) {
+  return t >= 0 && t < kNumTiles && a.C % (kTiles[t].kp * BKV * (is_i8 ? 16 : 8)) == 0;
+}
+
+// Largest 64-byte-chunk tile that still gives every compute unit a workgroup; smaller tiles
+// as the layer shrinks.
 int pick_tile(const ConvArgs& a) {
-  for (int t = 0; t < kNumTiles; ++t) {
+  for (int t = 0; t < 6; ++t) {
     if (kTiles[t].bn() > 64 && a.K <= 64) continue;
     if (tiles_of(a, kTiles[t]) >= 256) return t;
   }
-  return kNumTiles - 1;
+  return 5;
 }
+
+int resolve_tile(const ConvArgs& a, bool is_i8, int tile) { return tile_fits(a, is_i8, tile) ? tile : pick_tile(a); }
 
 }  // namespace
 
@@ -268,21 +451,21 @@ bool igemm_dma_supported(const ConvArgs& a, bool is_i8) {
   const int es = is_i8 ? 1 : 2;
   const int ck = BKV * 16 / es;
   const size_t lim = 0x7fffffffu;  // buffer offsets are 32-bit and 0x80000000 marks "out of range"
+  // tile rows are decoded as small offsets from the tile's first pixel (float reciprocal, < 2^22)
   return (a.C % ck) == 0 && a.R * a.S <= 32 && (size_t)a.N * a.H * a.W * a.C * es <= lim &&
-         (size_t)a.K * a.Kp * es <= lim;
+         (size_t)a.K * a.Kp * es <= lim && a.Wo < (1 << 20) && a.Ho < (1 << 20);
 }
 
 int igemm_dma_tile_count() { return kNumTiles; }
 
 void igemm_dma_kernel_name(const ConvArgs& a, bool is_i8, int tile, char* buf, size_t len) {
-  if (tile < 0 || tile >= kNumTiles) tile = pick_tile(a);
-  const DmaTile& t = kTiles[tile];
-  snprintf(buf, len, "igemm_dma_kernel<%s, %d, %d, %d, %d, %d>", is_i8 ? "true" : "false", t.waves_m, t.waves_n, t.tm,
-           t.tn, t.ns);
+  const DmaTile& t = kTiles[resolve_tile(a, is_i8, tile)];
+  snprintf(buf, len, "igemm_dma_kernel<%s, %d, %d, %d, %d, %d, %d>", is_i8 ? "true" : "false", t.waves_m, t.waves_n,
+           t.tm, t.tn, t.ns, t.kp);
 }
 
 hipError_t launch_conv_igemm_dma(const ConvArgs& a, bool is_i8, int tile, hipStream_t st) {
-  if (tile < 0 || tile >= kNumTiles) tile = pick_tile(a);
+  tile = resolve_tile(a, is_i8, tile);
   return is_i8 ? launch_typed<true>(a, tile, st) : launch_typed<false>(a, tile, st);
 }
 
