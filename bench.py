@@ -49,10 +49,10 @@ def _layer_table(net, ops, batch, reps, trials):
             ts.append(e0.elapsed_time(e1) * 1e3 / reps)      # us per launch
         row = {"name": name, "us": statistics.median(ts)}
         d = args[0]
-        if isinstance(d, B.ConvDesc):
+        if fn in (B.relay_fused_conv2d_bias_bn_relu, B.relay_qconv2d_requant, B.relay_fused_dwconv_bias_relu):
             ho, wo = B.relay_conv2d_out_shape(d)
             es = 2 if d.dtype == B.RELAY_F16 else 1
-            if fn in (B.relay_fused_conv2d_bias_bn_relu, B.relay_qconv2d_requant):
+            if fn is not B.relay_fused_dwconv_bias_relu:
                 # logical reduction length: padded input channels of the stem carry zeros
                 op = next(o for o in ops if o.name == name)
                 macs = d.n * ho * wo * d.k * op.cin * d.r * d.s

@@ -42,7 +42,12 @@ typedef enum {
 } relay_status;
 
 typedef enum { RELAY_F32 = 0, RELAY_F16 = 1, RELAY_I8 = 2 } relay_dtype;
-typedef enum { RELAY_NCHW = 0, RELAY_NHWC = 1 } relay_layout;
+/* RELAY_NHWC4_PADDED: input of a first-layer conv with c <= 4 channels, stored [n][h + 2*pad_h]
+ * [wp][4] with the zero border, wp - w - 2*pad_w slack columns and channels c..3 all zero
+ * (relay_pack_input_nhwc4 writes it from NCHW; relay_nhwc4_padded_shape gives hp, wp).  The
+ * filter row's taps and channels are then contiguous in memory and one filter row is one
+ * reduction chunk of the MFMA kernel.  Output, residual: plain NHWC. */
+typedef enum { RELAY_NCHW = 0, RELAY_NHWC = 1, RELAY_NHWC4_PADDED = 2 } relay_layout;
 
 /* which elementwise operators are fused behind the contraction */
 enum { RELAY_HAS_BIAS = 1, RELAY_HAS_BN = 2, RELAY_HAS_RESIDUAL = 4, RELAY_RELU = 8 };
@@ -51,7 +56,7 @@ enum { RELAY_HAS_BIAS = 1, RELAY_HAS_BN = 2, RELAY_HAS_RESIDUAL = 4, RELAY_RELU 
  * [k,c,r,s] (depthwise: k == c, one [r,s] filter per channel).
  * Supported (dtype, layout): (F32, NCHW) direct kernel; (F16, NHWC) and (I8, NHWC)
  * implicit-GEMM MFMA kernels, which need c % 8 == 0 (F16) or c % 16 == 0 (I8): pad the
- * channel axis with zeros (relay_nchw_to_nhwc does). */
+ * channel axis with zeros (relay_nchw_to_nhwc does); (F16 | I8, NHWC4_PADDED) for c <= 4. */
 typedef struct {
   int32_t n, c, h, w;
   int32_t k, r, s;
@@ -77,6 +82,13 @@ relay_status relay_packed_weight_bytes(const relay_conv2d_desc* d, size_t* bytes
 relay_status relay_prepack_conv2d_weights(const relay_conv2d_desc* d, const void* w_oihw, int32_t c_src,
                                           void* w_packed, size_t packed_bytes, void* hip_stream);
 
+/* Pre-padded 4-channel input of a RELAY_NHWC4_PADDED conv (F16 or I8): its extents, and the
+ * conversion from NCHW [n,c,h,w] (descriptor geometry; a per-inference layout alteration,
+ * the filter packing above is the compile-time one).  y: device, 16-byte aligned,
+ * n*hp*wp*4 elements. */
+relay_status relay_nhwc4_padded_shape(const relay_conv2d_desc* d, int32_t* hp, int32_t* wp);
+relay_status relay_pack_input_nhwc4(const relay_conv2d_desc* d, const void* x_nchw, void* y, void* hip_stream);
+
 /* conv2d -> [+bias[k]] -> [*bn_scale[k] + bn_shift[k]] -> [+residual] -> [relu] -> cast.
  * (paper Section 4.1; the order is this library's reading, the paper leaves it open.)
  * dtype F32 (NCHW) or F16 (NHWC, fp32 accumulation, output rounded to nearest even).
@@ -95,7 +107,7 @@ relay_status relay_fused_conv2d_bias_bn_relu(const relay_conv2d_desc* d, const v
  *   q   = min(max(q, -127), 127);  [relu: q = max(q, 0)];  y = (int8) q
  * d->dtype == RELAY_I8, layout NHWC, d->flags may hold HAS_BIAS | HAS_RESIDUAL | RELU.
  * 0 <= out_rshift <= 31, 0 <= residual_lshift <= 23.  Precondition: |acc| < 2^31 (wraps
- * silently otherwise). */
+ * silently otherwise).  x, w_packed 16-byte aligned; y, residual 8-byte aligned. */
 relay_status relay_qconv2d_requant(const relay_conv2d_desc* d, const int8_t* x, const int8_t* w_packed,
                                    const int32_t* bias, const int8_t* residual, int32_t residual_lshift,
                                    int32_t out_rshift, int8_t* y, void* workspace, size_t workspace_bytes,

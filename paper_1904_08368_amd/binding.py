@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "librelayfused.so")
 
 RELAY_F32, RELAY_F16, RELAY_I8 = 0, 1, 2
-RELAY_NCHW, RELAY_NHWC = 0, 1
+RELAY_NCHW, RELAY_NHWC, RELAY_NHWC4_PADDED = 0, 1, 2
 HAS_BIAS, HAS_BN, HAS_RESIDUAL, RELU = 1, 2, 4, 8
 
 STATUS_NAMES = {0: "RELAY_OK", 1: "RELAY_ERR_NULL", 2: "RELAY_ERR_SHAPE", 3: "RELAY_ERR_DTYPE",
@@ -52,6 +52,8 @@ SIGNATURES = {
     "relay_maxpool2d": [_I, _I, _I, _I, _I, _I, _I, _I, _P, _P, _P],
     "relay_global_avgpool": [_I, _I, _I, _I, _P, _P, _P],
     "relay_nchw_to_nhwc": [_I, _I, _I, _I, _I, _I, _P, _P, _P],
+    "relay_nhwc4_padded_shape": [_DP, C.POINTER(_I), C.POINTER(_I)],
+    "relay_pack_input_nhwc4": [_DP, _P, _P, _P],
     "relay_set_conv_tile": [_I],
     "relay_conv2d_kernel_name": [_DP, C.c_char_p, _SZ],
 }
@@ -161,6 +163,16 @@ def relay_global_avgpool(dtype, n, c, hw, x, y) -> None:
 
 def relay_nchw_to_nhwc(dtype, n, c, h, w, c_pad, x, y) -> None:
     _check(lib().relay_nchw_to_nhwc(dtype, n, c, h, w, c_pad, _ptr(x), _ptr(y), _stream()))
+
+
+def relay_nhwc4_padded_shape(d: ConvDesc) -> Tuple[int, int]:
+    hp, wp = _I(), _I()
+    _check(lib().relay_nhwc4_padded_shape(C.byref(d), C.byref(hp), C.byref(wp)))
+    return hp.value, wp.value
+
+
+def relay_pack_input_nhwc4(d: ConvDesc, x_nchw, y) -> None:
+    _check(lib().relay_pack_input_nhwc4(C.byref(d), _ptr(x_nchw), _ptr(y), _stream()))
 
 
 def relay_conv2d_kernel_name(d: ConvDesc) -> str:

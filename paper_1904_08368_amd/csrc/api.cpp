@@ -40,7 +40,8 @@ relay_status check_geometry(const relay_conv2d_desc* d, int* ho, int* wo) {
   if (d->h + 2 * d->pad_h < d->r || d->w + 2 * d->pad_w < d->s)
     return fail(RELAY_ERR_SHAPE, "kernel larger than the padded input: empty output");
   if (esize_of(d->dtype) == 0) return fail(RELAY_ERR_DTYPE, "unknown dtype %d", d->dtype);
-  if (d->layout != RELAY_NCHW && d->layout != RELAY_NHWC) return fail(RELAY_ERR_UNSUPPORTED, "unknown layout %d", d->layout);
+  if (d->layout != RELAY_NCHW && d->layout != RELAY_NHWC && d->layout != RELAY_NHWC4_PADDED)
+    return fail(RELAY_ERR_UNSUPPORTED, "unknown layout %d", d->layout);
   if (d->flags & ~(uint32_t)(RELAY_HAS_BIAS | RELAY_HAS_BN | RELAY_HAS_RESIDUAL | RELAY_RELU))
     return fail(RELAY_ERR_UNSUPPORTED, "unknown flag bits 0x%x", d->flags);
   const int oh = (d->h + 2 * d->pad_h - d->r) / d->stride_h + 1;
@@ -59,6 +60,11 @@ relay_status check_optional(const void* p, bool wanted, const char* name) {
   return RELAY_OK;
 }
 
+// width of the pre-padded NHWC4 input: the padded row rounded up to 8 pixels
+int nhwc4_padded_w(const relay_conv2d_desc* d) { return (d->w + 2 * d->pad_w + 7) & ~7; }
+// reduction elements per filter row in the row-packed stem path: one 64-byte chunk
+int nhwc4_row_chunk(const relay_conv2d_desc* d) { return 64 / esize_of(d->dtype); }
+
 relay::ConvArgs make_args(const relay_conv2d_desc* d, int ho, int wo) {
   relay::ConvArgs a;
   memset(&a, 0, sizeof(a));
@@ -66,9 +72,27 @@ relay::ConvArgs make_args(const relay_conv2d_desc* d, int ho, int wo) {
   a.sh = d->stride_h; a.sw = d->stride_w; a.ph = d->pad_h; a.pw = d->pad_w;
   a.Ho = ho; a.Wo = wo;
   a.M = d->n * ho * wo;
-  a.Kred = d->r * d->s * d->c;
-  a.Kp = relay::packed_pitch(a.Kred, esize_of(d->dtype));
   a.flags = d->flags;
+  if (d->layout == RELAY_NHWC4_PADDED) {
+    // Row-packed view: the s taps and 4 channels of one filter row are contiguous in the
+    // padded NHWC4 tensor, so a whole filter row (padded to one 64-byte chunk) is one
+    // "pixel" of C = chunk channels; pixels overlap (xs_w = 4) and nothing is out of range.
+    const int wp = nhwc4_padded_w(d), hp = d->h + 2 * d->pad_h;
+    a.C = nhwc4_row_chunk(d);
+    a.S = 1;
+    a.ph = a.pw = 0;
+    a.H = hp;
+    a.W = wp;
+    a.xs_w = 4;
+    a.xs_h = wp * 4;
+    a.xs_n = hp * wp * 4;
+  } else {
+    a.xs_w = d->c;
+    a.xs_h = d->w * d->c;
+    a.xs_n = d->h * d->w * d->c;
+  }
+  a.Kred = a.R * a.S * a.C;
+  a.Kp = relay::packed_pitch(a.Kred, esize_of(d->dtype));
   return a;
 }
 
@@ -81,6 +105,14 @@ int g_force_tile = -1;
 
 // implicit-GEMM paths: which (dtype, layout, channel count) combinations have a kernel
 relay_status check_igemm_support(const relay_conv2d_desc* d) {
+  if (d->layout == RELAY_NHWC4_PADDED) {
+    if (d->c > 4) return fail(RELAY_ERR_SHAPE, "the pre-padded NHWC4 layout holds at most 4 channels (c=%d)", d->c);
+    if (d->s * 4 > nhwc4_row_chunk(d) || d->r > 32)
+      return fail(RELAY_ERR_UNSUPPORTED, "filter %dx%d too large for the row-packed path", d->r, d->s);
+    if ((long)d->n * (d->h + 2 * d->pad_h) * nhwc4_padded_w(d) * 4 * esize_of(d->dtype) > 0x7fffffffL)
+      return fail(RELAY_ERR_SHAPE, "padded input exceeds 2^31-1 bytes");
+    return RELAY_OK;
+  }
   if (d->layout != RELAY_NHWC)
     return fail(RELAY_ERR_UNSUPPORTED, "fp16 / int8 conv2d needs NHWC activations");
   const int ve = d->dtype == RELAY_I8 ? 16 : 8;
@@ -124,9 +156,35 @@ relay_status relay_packed_weight_bytes(const relay_conv2d_desc* d, size_t* bytes
     *bytes = (size_t)d->k * d->c * d->r * d->s * es;
   } else {
     if ((st = check_igemm_support(d)) != RELAY_OK) return st;
-    *bytes = (size_t)d->k * relay::packed_pitch(d->r * d->s * d->c, es) * es;
+    const int kred = d->layout == RELAY_NHWC4_PADDED ? d->r * nhwc4_row_chunk(d) : d->r * d->s * d->c;
+    *bytes = (size_t)d->k * relay::packed_pitch(kred, es) * es;
   }
   return RELAY_OK;
+}
+
+relay_status relay_nhwc4_padded_shape(const relay_conv2d_desc* d, int32_t* hp, int32_t* wp) {
+  if (!hp || !wp) return fail(RELAY_ERR_NULL, "output pointers are NULL");
+  int oh, ow;
+  relay_status st = check_geometry(d, &oh, &ow);
+  if (st != RELAY_OK) return st;
+  if (d->c > 4) return fail(RELAY_ERR_SHAPE, "the pre-padded NHWC4 layout holds at most 4 channels (c=%d)", d->c);
+  *hp = d->h + 2 * d->pad_h;
+  *wp = nhwc4_padded_w(d);
+  return RELAY_OK;
+}
+
+relay_status relay_pack_input_nhwc4(const relay_conv2d_desc* d, const void* x_nchw, void* y, void* hip_stream) {
+  int oh, ow;
+  relay_status st = check_geometry(d, &oh, &ow);
+  if (st != RELAY_OK) return st;
+  if (d->dtype != RELAY_F16 && d->dtype != RELAY_I8) return fail(RELAY_ERR_DTYPE, "NHWC4 packing takes F16 or I8");
+  if (d->c > 4) return fail(RELAY_ERR_SHAPE, "the pre-padded NHWC4 layout holds at most 4 channels (c=%d)", d->c);
+  if (!x_nchw || !y) return fail(RELAY_ERR_NULL, "x_nchw and y are required");
+  if (x_nchw == y) return fail(RELAY_ERR_UNSUPPORTED, "output must not alias an input");
+  if (!aligned(y, 16)) return fail(RELAY_ERR_ALIGN, "y must be 16-byte aligned");
+  return device_status(relay::launch_pack_input_nhwc4(esize_of(d->dtype), d->n, d->c, d->h, d->w, d->pad_h, d->pad_w,
+                                                      nhwc4_padded_w(d), x_nchw, y, static_cast<hipStream_t>(hip_stream)),
+                       "NHWC4 input packing");
 }
 
 relay_status relay_prepack_conv2d_weights(const relay_conv2d_desc* d, const void* w_oihw, int32_t c_src,
@@ -144,6 +202,12 @@ relay_status relay_prepack_conv2d_weights(const relay_conv2d_desc* d, const void
     return device_status(hipMemcpyAsync(w_packed, w_oihw, need, hipMemcpyDeviceToDevice, s), "filter copy");
   }
   if (!aligned(w_packed, 16)) return fail(RELAY_ERR_ALIGN, "w_packed must be 16-byte aligned");
+  if (d->layout == RELAY_NHWC4_PADDED) {
+    const int ck = nhwc4_row_chunk(d);
+    return device_status(relay::launch_pack_filters_rows(w_oihw, w_packed, d->k, c_src, d->r, d->s, ck,
+                                                         relay::packed_pitch(d->r * ck, es), es, s),
+                         "filter packing");
+  }
   const int kp = relay::packed_pitch(d->r * d->s * d->c, es);
   return device_status(relay::launch_pack_filters(w_oihw, w_packed, d->k, c_src, d->c, d->r, d->s, kp, es, s),
                        "filter packing");
@@ -159,6 +223,7 @@ relay_status relay_set_conv_tile(int32_t tile) {
 
 static hipError_t launch_igemm(const relay::ConvArgs& a, bool is_i8, hipStream_t s) {
   if (relay::igemm_dma_supported(a, is_i8)) return relay::launch_conv_igemm_dma(a, is_i8, g_force_tile, s);
+  if (a.xs_w != a.C) return hipErrorInvalidValue;  // the register-staged kernel reads plain NHWC only
   return relay::launch_conv_igemm(a, is_i8, g_force_tile, s);
 }
 
@@ -228,9 +293,9 @@ relay_status relay_qconv2d_requant(const relay_conv2d_desc* d, const int8_t* x, 
     return fail(RELAY_ERR_UNSUPPORTED, "residual_lshift=%d outside 0..23", residual_lshift);
   if (y == x || y == residual) return fail(RELAY_ERR_UNSUPPORTED, "output must not alias an input");
   if ((st = check_igemm_support(d)) != RELAY_OK) return st;
-  if (!aligned(x, 16) || !aligned(w_packed, 16) || !aligned(y, 4) || (residual && !aligned(residual, 4)) ||
+  if (!aligned(x, 16) || !aligned(w_packed, 16) || !aligned(y, 8) || (residual && !aligned(residual, 8)) ||
       (bias && !aligned(bias, 4)))
-    return fail(RELAY_ERR_ALIGN, "int8 x / w_packed must be 16-byte aligned, y / residual / bias 4-byte aligned");
+    return fail(RELAY_ERR_ALIGN, "int8 x / w_packed must be 16-byte aligned, y / residual 8-byte, bias 4-byte aligned");
   relay::ConvArgs a = make_args(d, ho, wo);
   a.x = x; a.w = w_packed; a.y = y; a.res = residual; a.qbias = bias;
   a.lshift = residual_lshift; a.rshift = out_rshift;

@@ -82,7 +82,10 @@ __device__ __forceinline__ void small_divmod(int t, int d, float rcp_d, int& q, 
 // a [rows][64 B] sub-tile with its own swizzle, because 128-byte LDS rows cannot be read
 // conflict-free).  More planes = fewer barriers and fewer exposed LDS latencies per MFMA.
 template <bool IS_I8, int WAVES_M, int WAVES_N, int TM, int TN, int NS, int KP>
-__global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void igemm_dma_kernel(const ConvArgs a) {
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N,
+                             // two workgroups per CU where their LDS rings fit side by side
+                             (NS * KP * (WAVES_M * TM + WAVES_N * TN) * 32 * 64 <= 80 * 1024 ? 2 : 1))
+    void igemm_dma_kernel(const ConvArgs a) {
   constexpr int NW = WAVES_M * WAVES_N;
   constexpr int VE = IS_I8 ? 16 : 8;
   constexpr int ES = IS_I8 ? 1 : 2;
@@ -161,7 +164,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void igemm_dma_kernel(co
     for (int r = 0; r < a.R; ++r)
       if ((rowbits >> r) & 1u) taps |= colbits << (r * a.S);
     x_taps[j] = (m0 + row < a.M) ? taps : 0u;
-    x_off[j] = (((n * a.H + ih0) * a.W + iw0) * a.C + kvl * VE) * ES;
+    x_off[j] = (n * a.xs_n + ih0 * a.xs_h + iw0 * a.xs_w + kvl * VE) * ES;
   }
   unsigned w_off[WL];
 #pragma unroll
@@ -171,7 +174,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void igemm_dma_kernel(co
     const int ch = n0 + row;
     w_off[j] = ch < a.K ? (unsigned)((ch * a.Kp + kvl * VE) * ES) : kOob;
   }
-  const intx4 rs_x = make_rsrc(a.x, (unsigned)((size_t)a.N * a.H * a.W * a.C * ES));
+  const intx4 rs_x = make_rsrc(a.x, (unsigned)((size_t)a.N * a.xs_n * ES));
   const intx4 rs_w = make_rsrc(a.w, (unsigned)((size_t)a.K * a.Kp * ES));
   const unsigned ring_base = (unsigned)(size_t)(__attribute__((address_space(3))) uint4*)(&ring[0]);
 
@@ -206,7 +209,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void igemm_dma_kernel(co
       }
     }
     is_live = is_kc < nchunks;
-    is_delta = (unsigned)(((is_r * a.W + is_s) * a.C + is_c) * ES);
+    is_delta = (unsigned)((is_r * a.xs_h + is_s * a.xs_w + is_c) * ES);
     is_sbase = ring_base + (unsigned)(stage * STAGE) * 16u;
   };
 
@@ -452,7 +455,7 @@ bool igemm_dma_supported(const ConvArgs& a, bool is_i8) {
   const int ck = BKV * 16 / es;
   const size_t lim = 0x7fffffffu;  // buffer offsets are 32-bit and 0x80000000 marks "out of range"
   // tile rows are decoded as small offsets from the tile's first pixel (float reciprocal, < 2^22)
-  return (a.C % ck) == 0 && a.R * a.S <= 32 && (size_t)a.N * a.H * a.W * a.C * es <= lim &&
+  return (a.C % ck) == 0 && a.R * a.S <= 32 && (size_t)a.N * a.xs_n * es <= lim &&
          (size_t)a.K * a.Kp * es <= lim && a.Wo < (1 << 20) && a.Ho < (1 << 20);
 }
 

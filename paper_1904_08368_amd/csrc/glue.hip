@@ -46,6 +46,47 @@ __global__ __launch_bounds__(256) void nchw_to_nhwc_kernel(const T* x, T* y, int
   y[idx] = c < C ? x[(((long)n * C + c) * H + h) * W + w_] : (T)0;
 }
 
+// [N][C<=4][H][W] -> [N][H+2ph][Wp][4], zeros in the border, in the slack columns and in the
+// channels past C: one thread per output pixel, reads coalesced along w in each plane.
+template <typename T, typename V4>
+__global__ __launch_bounds__(256) void pack_input_nhwc4_kernel(const T* x, V4* y, int N, int C, int H, int W, int ph,
+                                                               int pw, int Hp, int Wp) {
+  const long total = (long)N * Hp * Wp;
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int wq = (int)(idx % Wp);
+  long t = idx / Wp;
+  const int hq = (int)(t % Hp);
+  const int n = (int)(t / Hp);
+  const int h = hq - ph, w_ = wq - pw;
+  T v[4] = {0, 0, 0, 0};
+  if ((unsigned)h < (unsigned)H && (unsigned)w_ < (unsigned)W) {
+    for (int c = 0; c < C; ++c) v[c] = x[(((long)n * C + c) * H + h) * W + w_];
+  }
+  V4 o;
+  o.x = v[0];
+  o.y = v[1];
+  o.z = v[2];
+  o.w = v[3];
+  y[idx] = o;
+}
+
+// OIHW [K][Csrc][R][S] -> [K][Kp], reduction index r*ck + s*4 + c (one filter row per chunk)
+template <typename T>
+__global__ __launch_bounds__(256) void pack_filters_rows_kernel(const T* w, T* out, int K, int Csrc, int R, int S,
+                                                                int ck, int Kp) {
+  const long total = (long)K * Kp;
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int kk = (int)(idx % Kp);
+  const int k = (int)(idx / Kp);
+  T v = 0;
+  const int r = kk / ck, in_row = kk - r * ck;
+  const int s = in_row >> 2, c = in_row & 3;
+  if (r < R && s < S && c < Csrc) v = w[(((long)k * Csrc + c) * R + r) * S + s];
+  out[idx] = v;
+}
+
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef signed char char16 __attribute__((ext_vector_type(16)));
 
@@ -149,6 +190,31 @@ hipError_t launch_avgpool_f16(int N, int C, int HW, const void* x, void* y, hipS
   const int cv = C / 8;
   hipLaunchKernelGGL(avgpool_f16_kernel, dim3(blocks_for((long)N * cv)), dim3(256), 0, st, (const half8*)x, (half8*)y,
                      N, cv, HW);
+  return hipGetLastError();
+}
+
+hipError_t launch_pack_input_nhwc4(int esize, int N, int C, int H, int W, int ph, int pw, int Wp, const void* x,
+                                   void* y, hipStream_t st) {
+  const int Hp = H + 2 * ph;
+  dim3 grid(blocks_for((long)N * Hp * Wp)), block(256);
+  if (esize == 1)
+    hipLaunchKernelGGL((pack_input_nhwc4_kernel<int8_t, char4>), grid, block, 0, st, (const int8_t*)x, (char4*)y, N,
+                       C, H, W, ph, pw, Hp, Wp);
+  else
+    hipLaunchKernelGGL((pack_input_nhwc4_kernel<uint16_t, ushort4>), grid, block, 0, st, (const uint16_t*)x,
+                       (ushort4*)y, N, C, H, W, ph, pw, Hp, Wp);
+  return hipGetLastError();
+}
+
+hipError_t launch_pack_filters_rows(const void* w, void* out, int K, int Csrc, int R, int S, int ck, int Kp,
+                                    int esize, hipStream_t st) {
+  dim3 grid(blocks_for((long)K * Kp)), block(256);
+  if (esize == 1)
+    hipLaunchKernelGGL((pack_filters_rows_kernel<int8_t>), grid, block, 0, st, (const int8_t*)w, (int8_t*)out, K, Csrc,
+                       R, S, ck, Kp);
+  else
+    hipLaunchKernelGGL((pack_filters_rows_kernel<uint16_t>), grid, block, 0, st, (const uint16_t*)w, (uint16_t*)out,
+                       K, Csrc, R, S, ck, Kp);
   return hipGetLastError();
 }
 

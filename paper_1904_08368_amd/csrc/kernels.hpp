@@ -20,6 +20,10 @@ struct ConvArgs {
   const float* shift;
   const int32_t* qbias;
   int N, H, W, C, K, R, S, sh, sw, ph, pw, Ho, Wo;
+  // element strides of x along image, row and pixel (NHWC: H*W*C, W*C, C).  The row-packed
+  // stem path views a [.., Wp, 4] tensor as 32- or 64-"channel" pixels that overlap: then
+  // xs_w = 4 while C is the chunk length.
+  int xs_n, xs_h, xs_w;
   int M;        // N*Ho*Wo  (rows of the implicit GEMM)
   int Kred;     // R*S*C    (reduction length)
   int Kp;       // row pitch of the packed filters, elements
@@ -56,5 +60,11 @@ hipError_t launch_maxpool(bool is_i8, int N, int C, int H, int W, int R, int str
 hipError_t launch_avgpool_f16(int N, int C, int HW, const void* x, void* y, hipStream_t st);
 hipError_t launch_nchw_to_nhwc(int esize, int N, int C, int H, int W, int Cpad, const void* x, void* y,
                                hipStream_t st);
+// [N,C<=4,H,W] -> zero-padded [N, H+2ph, Wp, 4]
+hipError_t launch_pack_input_nhwc4(int esize, int N, int C, int H, int W, int ph, int pw, int Wp, const void* x,
+                                   void* y, hipStream_t st);
+// OIHW [K][Csrc<=4][R][S] -> [K][Kp] with reduction index r*ck + s*4 + c, zero elsewhere
+hipError_t launch_pack_filters_rows(const void* w_oihw, void* w_packed, int K, int Csrc, int R, int S, int ck,
+                                    int Kp, int esize, hipStream_t st);
 
 }  // namespace relay

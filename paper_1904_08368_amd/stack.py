@@ -40,10 +40,22 @@ class FusedNet:
 
         cpad = _round_up(in_channels, self.ve)
         self.x_nchw = torch.zeros((batch, in_channels, h, w), dtype=self.tdtype, device=self.dev)
-        self.bufs["x"] = torch.zeros((batch, h, w, cpad), dtype=self.tdtype, device=self.dev)
         self.shape["x"] = (in_channels, h, w)
-        self._add("nchw_to_nhwc", B.relay_nchw_to_nhwc,
-                  (self.dtype, batch, in_channels, h, w, cpad, self.x_nchw, self.bufs["x"]))
+        first = ops[0]
+        # a first-layer conv on <= 4 channels reads the pre-padded NHWC4 form of the image
+        self.stem_nhwc4 = first.kind == "conv" and first.src == "x" and in_channels <= 4 and \
+            sum(1 for o in ops if o.src == "x" or o.res == "x") == 1
+        if self.stem_nhwc4:
+            d0 = B.conv_desc(batch, in_channels, h, w, first.cout, first.r, first.r, first.stride, first.pad,
+                             self.dtype, B.RELAY_NHWC4_PADDED, 0)
+            hp, wp = B.relay_nhwc4_padded_shape(d0)
+            self.bufs["x"] = torch.zeros((batch, hp, wp, 4), dtype=self.tdtype, device=self.dev)
+            self._add("pack_input_nhwc4", B.relay_pack_input_nhwc4, (d0, self.x_nchw, self.bufs["x"]))
+            self.keep.append(d0)
+        else:
+            self.bufs["x"] = torch.zeros((batch, h, w, cpad), dtype=self.tdtype, device=self.dev)
+            self._add("nchw_to_nhwc", B.relay_nchw_to_nhwc,
+                      (self.dtype, batch, in_channels, h, w, cpad, self.x_nchw, self.bufs["x"]))
 
         for i, (op, p) in enumerate(zip(ops, params)):
             cin_l, hi, wi = self.shape[op.src]
@@ -51,8 +63,12 @@ class FusedNet:
             cin_p = src.shape[-1]
             if op.kind == "conv":
                 flags = B.flags_of(p.get("bias"), p.get("scale"), op.res, op.relu)
-                d = B.conv_desc(batch, cin_p, hi, wi, op.cout, op.r, op.r, op.stride, op.pad, self.dtype,
-                                B.RELAY_NHWC, flags)
+                if i == 0 and self.stem_nhwc4:
+                    d = B.conv_desc(batch, cin_l, hi, wi, op.cout, op.r, op.r, op.stride, op.pad, self.dtype,
+                                    B.RELAY_NHWC4_PADDED, flags)
+                else:
+                    d = B.conv_desc(batch, cin_p, hi, wi, op.cout, op.r, op.r, op.stride, op.pad, self.dtype,
+                                    B.RELAY_NHWC, flags)
                 ho, wo = B.relay_conv2d_out_shape(d)
                 wsrc = torch.from_numpy(np.ascontiguousarray(p["w"])).to(self.dev)
                 wp = torch.empty(B.relay_packed_weight_bytes(d), dtype=torch.uint8, device=self.dev)
@@ -137,6 +153,8 @@ class FusedNet:
 
     def tensor(self, name: str) -> np.ndarray:
         """Download a named tensor as NCHW with the logical channel count."""
+        if name == "x":
+            return self.x_nchw.cpu().numpy()
         c, _, _ = self.shape[name]
         t = self.bufs[name][..., :c].permute(0, 3, 1, 2).contiguous().cpu().numpy()
         return t

@@ -30,15 +30,29 @@ def round_up(a, b):
     return (a + b - 1) // b * b
 
 
-def run_conv_f16(x, w, stride, pad, bias=None, scale=None, shift=None, residual=None, relu=False, tile=-1):
+def _input(x, k, r, s, stride, pad, dtype, ve, flags, nhwc4):
+    """Descriptor and device input: plain (channel-padded) NHWC, or the pre-padded NHWC4 form
+    for inputs of at most 4 channels."""
+    n, c, h, wd = x.shape
+    if nhwc4 and c <= 4:
+        d = B.conv_desc(n, c, h, wd, k, r, s, stride, pad, dtype, B.RELAY_NHWC4_PADDED, flags)
+        hp, wp = B.relay_nhwc4_padded_shape(d)
+        xd = torch.full((n, hp, wp, 4), 7, dtype=torch.float16 if dtype == B.RELAY_F16 else torch.int8, device=DEV)
+        B.relay_pack_input_nhwc4(d, up(x), xd)
+        return d, xd
+    cp = round_up(c, ve)
+    d = B.conv_desc(n, cp, h, wd, k, r, s, stride, pad, dtype, B.RELAY_NHWC, flags)
+    return d, to_nhwc(x, cp, dtype)
+
+
+def run_conv_f16(x, w, stride, pad, bias=None, scale=None, shift=None, residual=None, relu=False, tile=-1,
+                 nhwc4=True):
     """x [N,C,H,W] fp16, w [K,C,R,S] fp16 (numpy) -> y NCHW fp16 (numpy), via the C ABI."""
     n, c, h, wd = x.shape
     k, _, r, s = w.shape
-    cp = round_up(c, 8)
     flags = B.flags_of(bias, scale, residual, relu)
-    d = B.conv_desc(n, cp, h, wd, k, r, s, stride, pad, B.RELAY_F16, B.RELAY_NHWC, flags)
+    d, xd = _input(x, k, r, s, stride, pad, B.RELAY_F16, 8, flags, nhwc4)
     ho, wo = B.relay_conv2d_out_shape(d)
-    xd = to_nhwc(x, cp, B.RELAY_F16)
     wp = torch.empty(B.relay_packed_weight_bytes(d), dtype=torch.uint8, device=DEV)
     B.relay_prepack_conv2d_weights(d, up(w), c, wp)
     rd = None if residual is None else to_nhwc(residual, k, B.RELAY_F16)
@@ -52,14 +66,12 @@ def run_conv_f16(x, w, stride, pad, bias=None, scale=None, shift=None, residual=
     return from_nhwc(y, k)
 
 
-def run_qconv(x, w, stride, pad, bias=None, residual=None, lshift=0, rshift=0, relu=False, tile=-1):
+def run_qconv(x, w, stride, pad, bias=None, residual=None, lshift=0, rshift=0, relu=False, tile=-1, nhwc4=True):
     n, c, h, wd = x.shape
     k, _, r, s = w.shape
-    cp = round_up(c, 16)
     flags = B.flags_of(bias, None, residual, relu)
-    d = B.conv_desc(n, cp, h, wd, k, r, s, stride, pad, B.RELAY_I8, B.RELAY_NHWC, flags)
+    d, xd = _input(x, k, r, s, stride, pad, B.RELAY_I8, 16, flags, nhwc4)
     ho, wo = B.relay_conv2d_out_shape(d)
-    xd = to_nhwc(x, cp, B.RELAY_I8)
     wp = torch.empty(B.relay_packed_weight_bytes(d), dtype=torch.uint8, device=DEV)
     B.relay_prepack_conv2d_weights(d, up(w), c, wp)
     rd = None if residual is None else to_nhwc(residual, k, B.RELAY_I8)

@@ -116,6 +116,29 @@ def test_fp16_conv_every_tile_shape(G, tile, c):
     assert O.max_rel_err(got, ref) <= TOL_F16
 
 
+@pytest.mark.parametrize("case", [(2, 3, 37, 41, 64, 7, 2, 3), (1, 3, 20, 33, 32, 3, 2, 1), (2, 4, 9, 9, 16, 5, 1, 2),
+                                  (1, 1, 12, 12, 8, 3, 1, 0)])
+def test_first_layer_both_input_layouts(G, case):
+    """<= 4 input channels: the pre-padded NHWC4 path and the channel-padded NHWC path agree
+    with the oracle (fp16) and bit for bit (int8)."""
+    n, c, h, w, k, r, st, pd = case
+    g = _rng(60 + h)
+    x = _h(g.standard_normal((n, c, h, w)))
+    wt = _h(g.standard_normal((k, c, r, r)) * np.sqrt(2.0 / (c * r * r)))
+    sc = (1 + g.standard_normal(k) * 0.1).astype(np.float32)
+    sf = (g.standard_normal(k) * 0.1).astype(np.float32)
+    ref = O.fused_conv2d(x, wt, stride=(st, st), pad=(pd, pd), scale=sc, shift=sf, relu_flag=True)
+    for nhwc4 in (True, False):
+        got = G.run_conv_f16(x, wt, st, pd, scale=sc, shift=sf, relu=True, nhwc4=nhwc4)
+        assert got.shape == ref.shape and O.max_rel_err(got, ref) <= TOL_F16, nhwc4
+    xi = g.integers(-127, 128, (n, c, h, w)).astype(np.int8)
+    wi = g.integers(-127, 128, (k, c, r, r)).astype(np.int8)
+    s = inputs.default_out_rshift(c * r * r)
+    refq = O.qconv2d_requant(xi, wi, stride=(st, st), pad=(pd, pd), out_rshift=s, relu_flag=True)
+    for nhwc4 in (True, False):
+        assert np.array_equal(G.run_qconv(xi, wi, st, pd, rshift=s, relu=True, nhwc4=nhwc4), refq), nhwc4
+
+
 def test_fp16_delta_kernel_reproduces_input(G):
     g = _rng(51)
     x = _h(g.standard_normal((1, 64, 14, 14)))
