@@ -436,17 +436,20 @@ bool tile_fits(const ConvArgs& a, bool is_i8, int t) {
   return t >= 0 && t < kNumTiles && a.C % (kTiles[t].kp * BKV * (is_i8 ? 16 : 8)) == 0;
 }
 
-// Largest 64-byte-chunk tile that still gives every compute unit a workgroup; smaller tiles
-// as the layer shrinks.
-int pick_tile(const ConvArgs& a) {
-  for (int t = 0; t < 6; ++t) {
-    if (kTiles[t].bn() > 64 && a.K <= 64) continue;
-    if (tiles_of(a, kTiles[t]) >= 256) return t;
-  }
-  return 5;
+// Tile choice from measured sweeps over the ResNet / MobileNet layer shapes: the 256x128
+// tile once it gives every CU two workgroups, else 128x64, else 64x64 (small-M layers need
+// the workgroup count more than the per-tile intensity); 128-byte chunks where C allows.
+int pick_tile(const ConvArgs& a, bool is_i8) {
+  const bool kp2 = a.C % (2 * BKV * (is_i8 ? 16 : 8)) == 0;
+  if (a.K > 64 && tiles_of(a, kTiles[0]) >= 512) return 0;
+  const int mid = kp2 ? 9 : 4;
+  if (tiles_of(a, kTiles[mid]) >= 190) return mid;
+  return kp2 ? 10 : 5;
 }
 
-int resolve_tile(const ConvArgs& a, bool is_i8, int tile) { return tile_fits(a, is_i8, tile) ? tile : pick_tile(a); }
+int resolve_tile(const ConvArgs& a, bool is_i8, int tile) {
+  return tile_fits(a, is_i8, tile) ? tile : pick_tile(a, is_i8);
+}
 
 }  // namespace
 

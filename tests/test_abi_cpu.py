@@ -1,0 +1,176 @@
+"""The C-ABI library without a GPU: it loads, exports every symbol the header declares, and
+rejects bad arguments on the host before any HIP call (no compute call is made here: every
+case below must fail validation, so nothing is ever launched)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_1904_08368_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x7F0000001000            # a non-NULL, 4096-byte aligned address that is never dereferenced
+
+
+def _header_symbols():
+    text = open(os.path.join(ROOT, "include", "relay_fused.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(relay_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.lib()
+    names = _header_symbols()
+    assert len(names) >= 16
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in relay_fused.h but not exported"
+    # and the binding wraps each of them under the same name
+    for n in names:
+        if n != "relay_last_error":
+            assert hasattr(B, n), f"binding has no {n}"
+
+
+def _d(**kw):
+    base = dict(n=1, c=64, h=8, w=8, k=64, r=3, s=3, stride=1, pad=1, dtype=B.RELAY_F16, layout=B.RELAY_NHWC, flags=0)
+    base.update(kw)
+    return B.conv_desc(base["n"], base["c"], base["h"], base["w"], base["k"], base["r"], base["s"], base["stride"],
+                       base["pad"], base["dtype"], base["layout"], base["flags"])
+
+
+def _status(fn, *args):
+    lib = B.lib()
+    return getattr(lib, fn)(*args)
+
+
+def test_out_shape_formula_exhaustive():
+    for h in range(1, 12):
+        for r in (1, 2, 3, 5, 7):
+            for st in (1, 2, 3):
+                for pd in range(0, r):
+                    if h + 2 * pd < r:
+                        with pytest.raises(B.RelayError) as e:
+                            B.relay_conv2d_out_shape(_d(h=h, w=h, r=r, s=r, stride=st, pad=pd))
+                        assert e.value.status == 2
+                        continue
+                    ho, wo = B.relay_conv2d_out_shape(_d(h=h, w=h + 3, r=r, s=r, stride=st, pad=pd))
+                    assert ho == (h + 2 * pd - r) // st + 1 and wo == (h + 3 + 2 * pd - r) // st + 1
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(n=0), 2), (dict(c=-1), 2), (dict(k=0), 2), (dict(stride=0), 2), (dict(pad=3), 2), (dict(pad=-1), 2),
+    (dict(h=1, w=1, pad=0), 2), (dict(dtype=9), 3), (dict(layout=7), 4), (dict(flags=64), 4),
+    (dict(n=40000, c=512, h=512, w=512), 2),
+])
+def test_geometry_is_validated(kw, status):
+    with pytest.raises(B.RelayError) as e:
+        B.relay_conv2d_out_shape(_d(**kw))
+    assert e.value.status == status
+    assert B.lib().relay_last_error()           # a message is left behind
+
+
+def test_null_descriptor_and_outputs():
+    i = C.c_int32()
+    assert _status("relay_conv2d_out_shape", None, C.byref(i), C.byref(i)) == 1
+    assert _status("relay_conv2d_out_shape", C.byref(_d()), None, C.byref(i)) == 1
+    assert _status("relay_workspace_bytes", C.byref(_d()), None) == 1
+    assert B.relay_workspace_bytes(_d()) == 0
+
+
+def test_packed_weight_bytes_and_channel_alignment():
+    assert B.relay_packed_weight_bytes(_d()) == 64 * 576 * 2                 # 576 is a whole number of 128-byte groups
+    assert B.relay_packed_weight_bytes(_d(c=8)) == 64 * 128 * 2             # 72 halves -> 128 (two 128-byte groups)
+    assert B.relay_packed_weight_bytes(_d(dtype=B.RELAY_I8, c=16)) == 64 * 256
+    assert B.relay_packed_weight_bytes(_d(dtype=B.RELAY_F32, layout=B.RELAY_NCHW, c=3)) == 64 * 27 * 4
+    assert B.relay_packed_weight_bytes(_d(c=3, r=7, s=7, pad=3, layout=B.RELAY_NHWC4_PADDED)) == 64 * 256 * 2
+    for kw, status in [(dict(c=3), 5), (dict(dtype=B.RELAY_I8, c=8), 5), (dict(layout=B.RELAY_NCHW), 4),
+                       (dict(dtype=B.RELAY_F32), 4), (dict(c=5, layout=B.RELAY_NHWC4_PADDED), 2),
+                       (dict(c=3, r=9, s=9, pad=4, layout=B.RELAY_NHWC4_PADDED), 4)]:
+        with pytest.raises(B.RelayError) as e:
+            B.relay_packed_weight_bytes(_d(**kw))
+        assert e.value.status == status, kw
+    hp, wp = B.relay_nhwc4_padded_shape(_d(c=3, h=224, w=224, r=7, s=7, pad=3, stride=2, layout=B.RELAY_NHWC4_PADDED))
+    assert (hp, wp) == (230, 232)
+
+
+def _conv(d, x=FAKE, w=FAKE, bias=None, sc=None, sf=None, res=None, y=FAKE + 4096):
+    return _status("relay_fused_conv2d_bias_bn_relu", C.byref(d), x, w, bias, sc, sf, res, y, None, 0, None)
+
+
+def test_conv_argument_checks_fail_before_any_launch():
+    assert _conv(_d(), x=None) == 1
+    assert _conv(_d(), y=None) == 1
+    assert _conv(_d(flags=B.HAS_BIAS)) == 1                       # flag set, pointer NULL
+    assert _conv(_d(), bias=FAKE) == 1                            # pointer given, flag clear
+    assert _conv(_d(flags=B.HAS_BN), sc=FAKE) == 1                # shift missing
+    assert _conv(_d(flags=B.HAS_RESIDUAL)) == 1
+    assert _conv(_d(dtype=B.RELAY_I8)) == 3                       # int8 has its own entry point
+    assert _conv(_d(), y=FAKE) == 4                               # output aliases input
+    assert _conv(_d(), x=FAKE + 2) == 5                           # misaligned
+    assert _conv(_d(c=12)) == 5
+    assert _conv(_d(layout=B.RELAY_NCHW)) == 4
+    assert _conv(_d(dtype=B.RELAY_F32, layout=B.RELAY_NHWC)) == 4
+    assert b"" != B.lib().relay_last_error()
+
+
+def _q(d, x=FAKE, w=FAKE, bias=None, res=None, l=0, s=8, y=FAKE + 4096):
+    return _status("relay_qconv2d_requant", C.byref(d), x, w, bias, res, l, s, y, None, 0, None)
+
+
+def test_qconv_argument_checks():
+    q = dict(dtype=B.RELAY_I8)
+    assert _q(_d()) == 3                                          # not an int8 descriptor
+    assert _q(_d(**q), s=-1) == 4 and _q(_d(**q), s=32) == 4
+    assert _q(_d(**q), l=-1) == 4 and _q(_d(**q), l=24) == 4
+    assert _q(_d(flags=B.HAS_BN, **q)) == 4
+    assert _q(_d(flags=B.HAS_RESIDUAL, **q)) == 1
+    assert _q(_d(**q), res=FAKE) == 1
+    assert _q(_d(c=24, **q)) == 5
+    assert _q(_d(**q), y=FAKE + 4) == 5
+    assert _q(_d(**q), x=None) == 1
+
+
+def test_dwconv_dense_and_glue_checks():
+    dw = _status
+    d = _d(c=32, k=32)
+    assert dw("relay_fused_dwconv_bias_relu", C.byref(d), None, FAKE, None, None, None, FAKE + 4096, None) == 1
+    assert dw("relay_fused_dwconv_bias_relu", C.byref(_d(c=32, k=64)), FAKE, FAKE, None, None, None, FAKE + 4096, None) == 2
+    assert dw("relay_fused_dwconv_bias_relu", C.byref(_d(c=36, k=36)), FAKE, FAKE, None, None, None, FAKE + 4096, None) == 5
+    assert dw("relay_fused_dwconv_bias_relu", C.byref(_d(c=32, k=32, r=5, s=5, pad=2)), FAKE, FAKE, None, None, None, FAKE + 4096, None) == 4
+    assert dw("relay_fused_dwconv_bias_relu", C.byref(_d(c=32, k=32, stride=3)), FAKE, FAKE, None, None, None, FAKE + 4096, None) == 4
+    assert dw("relay_fused_dwconv_bias_relu", C.byref(_d(c=32, k=32, dtype=B.RELAY_I8)), FAKE, FAKE, None, None, None, FAKE + 4096, None) == 3
+    assert dw("relay_prepack_dwconv_weights", C.byref(d), None, FAKE, None) == 1
+    de = "relay_fused_dense_bias_act"
+    assert _status(de, 0, 10, 16, B.RELAY_F16, FAKE, FAKE, None, 0, FAKE + 4096, None) == 2
+    assert _status(de, 1, 10, 12, B.RELAY_F16, FAKE, FAKE, None, 0, FAKE + 4096, None) == 5
+    assert _status(de, 1, 10, 16, B.RELAY_I8, FAKE, FAKE, None, 0, FAKE + 4096, None) == 3
+    assert _status(de, 1, 10, 16, B.RELAY_F16, FAKE, FAKE, None, 2, FAKE + 4096, None) == 4
+    assert _status(de, 1, 10, 16, B.RELAY_F16, None, FAKE, None, 0, FAKE + 4096, None) == 1
+    assert _status("relay_maxpool2d", B.RELAY_F16, 1, 12, 8, 8, 3, 2, 1, FAKE, FAKE + 4096, None) == 5
+    assert _status("relay_maxpool2d", B.RELAY_F32, 1, 16, 8, 8, 3, 2, 1, FAKE, FAKE + 4096, None) == 3
+    assert _status("relay_maxpool2d", B.RELAY_F16, 1, 16, 8, 8, 3, 2, 3, FAKE, FAKE + 4096, None) == 2
+    assert _status("relay_global_avgpool", B.RELAY_I8, 1, 16, 4, FAKE, FAKE + 4096, None) == 3
+    assert _status("relay_nchw_to_nhwc", B.RELAY_F16, 1, 3, 8, 8, 2, FAKE, FAKE + 4096, None) == 2
+    assert _status("relay_nchw_to_nhwc", B.RELAY_F16, 1, 3, 8, 8, 8, FAKE, FAKE, None) == 4
+    assert _status("relay_pack_input_nhwc4", C.byref(_d(c=3)), None, FAKE, None) == 1
+    assert _status("relay_pack_input_nhwc4", C.byref(_d(c=8)), FAKE, FAKE + 4096, None) == 2
+    assert _status("relay_set_conv_tile", 99) == 4
+    assert _status("relay_set_conv_tile", -1) == 0
+    buf = C.create_string_buffer(128)
+    assert _status("relay_conv2d_kernel_name", C.byref(_d()), None, 0) == 1
+    assert _status("relay_conv2d_kernel_name", C.byref(_d(n=32, h=56, w=56)), buf, 128) == 0
+    assert buf.value.decode().startswith("igemm_dma_kernel<false")
+    assert _status("relay_conv2d_kernel_name", C.byref(_d(c=24)), buf, 128) == 0
+    assert buf.value.decode().startswith("igemm_conv_kernel<false")
+
+
+def test_product_path_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_1904_08368_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".cpp", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower(), f"{f} mentions the oracle"
+    for f in ("oracle/__init__.py", "oracle/stack.py", "oracle/oracle.c"):
+        text = open(os.path.join(ROOT, f)).read()
+        assert "paper_1904_08368_amd" not in text and "relay_fused" not in text
