@@ -313,6 +313,8 @@ static relay_status check_dw(const relay_conv2d_desc* d, int* ho, int* wo) {
   if (d->stride_h != d->stride_w || (d->stride_h != 1 && d->stride_h != 2))
     return fail(RELAY_ERR_UNSUPPORTED, "depthwise stride must be 1 or 2");
   if (d->flags & RELAY_HAS_RESIDUAL) return fail(RELAY_ERR_UNSUPPORTED, "depthwise conv2d has no residual input");
+  if ((long)d->n * d->h * d->w * d->c * 2 > 0x7fffffffL)  // 32-bit buffer offsets, 2^31 marks "out of range"
+    return fail(RELAY_ERR_SHAPE, "depthwise input exceeds 2^31-1 bytes");
   return RELAY_OK;
 }
 
