@@ -93,7 +93,17 @@ relay::ConvArgs make_args(const relay_conv2d_desc* d, int ho, int wo) {
   }
   a.Kred = a.R * a.S * a.C;
   a.Kp = relay::packed_pitch(a.Kred, esize_of(d->dtype));
+  a.rcp_wo = 1.0f / (float)wo;
+  a.rcp_ho = 1.0f / (float)ho;
+  if (a.R * a.S <= 32)
+    for (int r = 0; r < a.R; ++r) a.tap_spread |= 1u << (r * a.S);
   return a;
+}
+
+// after the operand pointers are in place
+void finish_args(relay::ConvArgs& a) {
+  const bool al = aligned(a.bias, 16) && aligned(a.scale, 16) && aligned(a.shift, 16) && aligned(a.qbias, 16);
+  a.param_vec = (al && (a.K & 7) == 0) ? 1 : 0;
 }
 
 relay_status device_status(hipError_t e, const char* what) {
@@ -262,6 +272,7 @@ relay_status relay_fused_conv2d_bias_bn_relu(const relay_conv2d_desc* d, const v
   if (y == x || y == residual) return fail(RELAY_ERR_UNSUPPORTED, "output must not alias an input");
   relay::ConvArgs a = make_args(d, ho, wo);
   a.x = x; a.w = w_packed; a.y = y; a.res = residual; a.bias = bias; a.scale = bn_scale; a.shift = bn_shift;
+  finish_args(a);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   if (d->dtype == RELAY_F32) {
     if (d->layout != RELAY_NCHW) return fail(RELAY_ERR_UNSUPPORTED, "fp32 conv2d is NCHW only");
@@ -299,6 +310,7 @@ relay_status relay_qconv2d_requant(const relay_conv2d_desc* d, const int8_t* x, 
   relay::ConvArgs a = make_args(d, ho, wo);
   a.x = x; a.w = w_packed; a.y = y; a.res = residual; a.qbias = bias;
   a.lshift = residual_lshift; a.rshift = out_rshift;
+  finish_args(a);
   return device_status(launch_igemm(a, true, static_cast<hipStream_t>(hip_stream)), "qconv2d launch");
 }
 

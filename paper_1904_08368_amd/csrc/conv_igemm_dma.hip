@@ -123,17 +123,52 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N,
   const int ech = n0 + wn * WTN + (lane % CG) * 8;
   float emul[8], eadd[8];
   int ebias[8];
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const int c = ech + e < a.K ? ech + e : a.K - 1;
+  if (a.param_vec) {  // two 16-byte loads per array
+    const int c8 = ech < a.K ? ech : a.K - 8;
     if constexpr (IS_I8) {
-      ebias[e] = (a.flags & F_BIAS) ? a.qbias[c] : 0;
+      int4 b0 = make_int4(0, 0, 0, 0), b1 = b0;
+      if (a.flags & F_BIAS) {
+        b0 = *reinterpret_cast<const int4*>(a.qbias + c8);
+        b1 = *reinterpret_cast<const int4*>(a.qbias + c8 + 4);
+      }
+      const int t[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ebias[e] = t[e];
     } else {
-      const float sc = (a.flags & F_BN) ? a.scale[c] : 1.f;
-      const float sf = (a.flags & F_BN) ? a.shift[c] : 0.f;
-      const float b = (a.flags & F_BIAS) ? a.bias[c] : 0.f;
-      emul[e] = sc;
-      eadd[e] = b * sc + sf;  // (acc + b)*sc + sf
+      float4 s0 = make_float4(1.f, 1.f, 1.f, 1.f), s1 = s0;
+      float4 f0 = make_float4(0.f, 0.f, 0.f, 0.f), f1 = f0, b0 = f0, b1 = f0;
+      if (a.flags & F_BN) {
+        s0 = *reinterpret_cast<const float4*>(a.scale + c8);
+        s1 = *reinterpret_cast<const float4*>(a.scale + c8 + 4);
+        f0 = *reinterpret_cast<const float4*>(a.shift + c8);
+        f1 = *reinterpret_cast<const float4*>(a.shift + c8 + 4);
+      }
+      if (a.flags & F_BIAS) {
+        b0 = *reinterpret_cast<const float4*>(a.bias + c8);
+        b1 = *reinterpret_cast<const float4*>(a.bias + c8 + 4);
+      }
+      const float sc[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+      const float sf[8] = {f0.x, f0.y, f0.z, f0.w, f1.x, f1.y, f1.z, f1.w};
+      const float bb[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        emul[e] = sc[e];
+        eadd[e] = bb[e] * sc[e] + sf[e];  // (acc + b)*sc + sf
+      }
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int c = ech + e < a.K ? ech + e : a.K - 1;
+      if constexpr (IS_I8) {
+        ebias[e] = (a.flags & F_BIAS) ? a.qbias[c] : 0;
+      } else {
+        const float sc = (a.flags & F_BN) ? a.scale[c] : 1.f;
+        const float sf = (a.flags & F_BN) ? a.shift[c] : 0.f;
+        const float b = (a.flags & F_BIAS) ? a.bias[c] : 0.f;
+        emul[e] = sc;
+        eadd[e] = b * sc + sf;  // (acc + b)*sc + sf
+      }
     }
   }
 
@@ -145,7 +180,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N,
   const int rem_0 = m0 - n_0 * HoWo;
   const int p_0 = rem_0 / a.Wo;
   const int q_0 = rem_0 - p_0 * a.Wo;
-  const float rcp_wo = 1.0f / (float)a.Wo, rcp_ho = 1.0f / (float)a.Ho;
   int x_off[XL];        // byte offset of tap (0,0), channel 0 of the row's k-vector
   unsigned x_taps[XL];  // bit t set: tap t of this row lies inside the image
 #pragma unroll
@@ -153,16 +187,18 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N,
     const int row = (wave * XL + j) * 16 + srow;
     const int kvl = sphys ^ ((row >> 1) & (BKV - 1));
     int dp, q, dn, p;
-    small_divmod(q_0 + row, a.Wo, rcp_wo, dp, q);
-    small_divmod(p_0 + dp, a.Ho, rcp_ho, dn, p);
+    small_divmod(q_0 + row, a.Wo, a.rcp_wo, dp, q);
+    small_divmod(p_0 + dp, a.Ho, a.rcp_ho, dn, p);
     const int n = n_0 + dn;
     const int ih0 = p * a.sh - a.ph, iw0 = q * a.sw - a.pw;
-    unsigned rowbits = 0, colbits = 0;
-    for (int r = 0; r < a.R; ++r) rowbits |= ((unsigned)(ih0 + r) < (unsigned)a.H ? 1u : 0u) << r;
-    for (int s = 0; s < a.S; ++s) colbits |= ((unsigned)(iw0 + s) < (unsigned)a.W ? 1u : 0u) << s;
-    unsigned taps = 0;
-    for (int r = 0; r < a.R; ++r)
-      if ((rowbits >> r) & 1u) taps |= colbits << (r * a.S);
+    // filter rows [rlo, rhi) and columns [clo, chi) fall inside the image: the tap mask is the
+    // column run replicated at every valid row (a product, the runs do not overlap)
+    const int rlo = max(0, -ih0), rhi = min(a.R, a.H - ih0);
+    const int clo = max(0, -iw0), chi = min(a.S, a.W - iw0);
+    const unsigned colbits = (unsigned)((1ull << max(chi, 0)) - 1ull) & ~(unsigned)((1ull << clo) - 1ull);
+    const unsigned rows = a.tap_spread & (unsigned)((1ull << (max(rhi, 0) * a.S)) - 1ull) &
+                          ~(unsigned)((1ull << (rlo * a.S)) - 1ull);
+    const unsigned taps = (rhi > rlo && chi > clo) ? colbits * rows : 0u;
     x_taps[j] = (m0 + row < a.M) ? taps : 0u;
     x_off[j] = (n * a.xs_n + ih0 * a.xs_h + iw0 * a.xs_w + kvl * VE) * ES;
   }

@@ -24,6 +24,10 @@ struct ConvArgs {
   // stem path views a [.., Wp, 4] tensor as 32- or 64-"channel" pixels that overlap: then
   // xs_w = 4 while C is the chunk length.
   int xs_n, xs_h, xs_w;
+  // host-computed constants of the implicit-GEMM prologue
+  float rcp_wo, rcp_ho;   // 1/Wo, 1/Ho
+  unsigned tap_spread;    // bit r*S set for every filter row r (R*S <= 32)
+  int param_vec;          // per-channel constants are 16-byte aligned and K % 8 == 0: vector loads
   int M;        // N*Ho*Wo  (rows of the implicit GEMM)
   int Kred;     // R*S*C    (reduction length)
   int Kp;       // row pitch of the packed filters, elements
