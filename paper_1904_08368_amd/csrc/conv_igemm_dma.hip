@@ -116,62 +116,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N,
   const int tile_n = tile % tiles_n, tile_m = tile / tiles_n;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
-  // ---- epilogue constants of this lane: after the transposition it owns channels
-  //      [ech, ech + 8) of whichever pixels it handles.  Fetched first so that the latency
-  //      hides under the main loop (older than every ring load, so vmcnt accounting holds).
-  constexpr int CG = WTN / 8;  // lanes per pixel row in the epilogue
-  const int ech = n0 + wn * WTN + (lane % CG) * 8;
-  float emul[8], eadd[8];
-  int ebias[8];
-  if (a.param_vec) {  // two 16-byte loads per array
-    const int c8 = ech < a.K ? ech : a.K - 8;
-    if constexpr (IS_I8) {
-      int4 b0 = make_int4(0, 0, 0, 0), b1 = b0;
-      if (a.flags & F_BIAS) {
-        b0 = *reinterpret_cast<const int4*>(a.qbias + c8);
-        b1 = *reinterpret_cast<const int4*>(a.qbias + c8 + 4);
-      }
-      const int t[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
-#pragma unroll
-      for (int e = 0; e < 8; ++e) ebias[e] = t[e];
-    } else {
-      float4 s0 = make_float4(1.f, 1.f, 1.f, 1.f), s1 = s0;
-      float4 f0 = make_float4(0.f, 0.f, 0.f, 0.f), f1 = f0, b0 = f0, b1 = f0;
-      if (a.flags & F_BN) {
-        s0 = *reinterpret_cast<const float4*>(a.scale + c8);
-        s1 = *reinterpret_cast<const float4*>(a.scale + c8 + 4);
-        f0 = *reinterpret_cast<const float4*>(a.shift + c8);
-        f1 = *reinterpret_cast<const float4*>(a.shift + c8 + 4);
-      }
-      if (a.flags & F_BIAS) {
-        b0 = *reinterpret_cast<const float4*>(a.bias + c8);
-        b1 = *reinterpret_cast<const float4*>(a.bias + c8 + 4);
-      }
-      const float sc[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
-      const float sf[8] = {f0.x, f0.y, f0.z, f0.w, f1.x, f1.y, f1.z, f1.w};
-      const float bb[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        emul[e] = sc[e];
-        eadd[e] = bb[e] * sc[e] + sf[e];  // (acc + b)*sc + sf
-      }
-    }
-  } else {
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int c = ech + e < a.K ? ech + e : a.K - 1;
-      if constexpr (IS_I8) {
-        ebias[e] = (a.flags & F_BIAS) ? a.qbias[c] : 0;
-      } else {
-        const float sc = (a.flags & F_BN) ? a.scale[c] : 1.f;
-        const float sf = (a.flags & F_BN) ? a.shift[c] : 0.f;
-        const float b = (a.flags & F_BIAS) ? a.bias[c] : 0.f;
-        emul[e] = sc;
-        eadd[e] = b * sc + sf;  // (acc + b)*sc + sf
-      }
-    }
-  }
-
   // ---- staging role of this lane inside a 16-row block: row srow, physical slot sphys.
   //      The tile's first pixel is decoded once (uniform); rows are small offsets from it.
   const int srow = lane >> 2, sphys = lane & 3;
@@ -262,6 +206,65 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N,
 #pragma unroll
     for (int i = 0; i < LPC; ++i) issue_one(i);
     next_chunk(s + 1 == NS ? 0 : s + 1);
+  }
+
+  // ---- epilogue constants of this lane: after the transposition it owns channels
+  //      [ech, ech + 8) of whichever pixels it handles.  Fetched here, behind the first ring
+  //      loads (which are on the critical path) and ahead of the main loop that hides the
+  //      latency.  vmcnt counts these loads too: being younger than the prologue chunks they
+  //      only make the first waits stricter than needed, and every later ring load is younger
+  //      than they are.
+  constexpr int CG = WTN / 8;  // lanes per pixel row in the epilogue
+  const int ech = n0 + wn * WTN + (lane % CG) * 8;
+  float emul[8], eadd[8];
+  int ebias[8];
+  if (a.param_vec) {  // two 16-byte loads per array
+    const int c8 = ech < a.K ? ech : a.K - 8;
+    if constexpr (IS_I8) {
+      int4 b0 = make_int4(0, 0, 0, 0), b1 = b0;
+      if (a.flags & F_BIAS) {
+        b0 = *reinterpret_cast<const int4*>(a.qbias + c8);
+        b1 = *reinterpret_cast<const int4*>(a.qbias + c8 + 4);
+      }
+      const int t[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ebias[e] = t[e];
+    } else {
+      float4 s0 = make_float4(1.f, 1.f, 1.f, 1.f), s1 = s0;
+      float4 f0 = make_float4(0.f, 0.f, 0.f, 0.f), f1 = f0, b0 = f0, b1 = f0;
+      if (a.flags & F_BN) {
+        s0 = *reinterpret_cast<const float4*>(a.scale + c8);
+        s1 = *reinterpret_cast<const float4*>(a.scale + c8 + 4);
+        f0 = *reinterpret_cast<const float4*>(a.shift + c8);
+        f1 = *reinterpret_cast<const float4*>(a.shift + c8 + 4);
+      }
+      if (a.flags & F_BIAS) {
+        b0 = *reinterpret_cast<const float4*>(a.bias + c8);
+        b1 = *reinterpret_cast<const float4*>(a.bias + c8 + 4);
+      }
+      const float sc[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+      const float sf[8] = {f0.x, f0.y, f0.z, f0.w, f1.x, f1.y, f1.z, f1.w};
+      const float bb[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        emul[e] = sc[e];
+        eadd[e] = bb[e] * sc[e] + sf[e];  // (acc + b)*sc + sf
+      }
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int c = ech + e < a.K ? ech + e : a.K - 1;
+      if constexpr (IS_I8) {
+        ebias[e] = (a.flags & F_BIAS) ? a.qbias[c] : 0;
+      } else {
+        const float sc = (a.flags & F_BN) ? a.scale[c] : 1.f;
+        const float sf = (a.flags & F_BN) ? a.shift[c] : 0.f;
+        const float b = (a.flags & F_BIAS) ? a.bias[c] : 0.f;
+        emul[e] = sc;
+        eadd[e] = b * sc + sf;  // (acc + b)*sc + sf
+      }
+    }
   }
 
   const int lrow = lane & 31, lhalf = lane >> 5;

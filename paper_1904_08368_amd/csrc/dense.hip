@@ -70,11 +70,17 @@ __global__ __launch_bounds__(256) void dense_kernel(int M, int N, int K, const v
 
 hipError_t launch_dense(int m, int n, int k, bool is_f16, const void* x, const void* w, const float* bias, int act,
                         void* y, hipStream_t st) {
+  // a wave keeps MB rows of x against one weight row: 32 when the batch has that many, so the
+  // weights are read once and one round of loads covers the whole reduction of a typical layer
   dim3 block(256), grid((unsigned)((n + 3) / 4));
-  if (is_f16)
-    hipLaunchKernelGGL((dense_kernel<true, 8>), grid, block, 0, st, m, n, k, x, w, bias, act, y);
-  else
+  if (is_f16) {
+    if (m > 8)
+      hipLaunchKernelGGL((dense_kernel<true, 32>), grid, block, 0, st, m, n, k, x, w, bias, act, y);
+    else
+      hipLaunchKernelGGL((dense_kernel<true, 8>), grid, block, 0, st, m, n, k, x, w, bias, act, y);
+  } else {
     hipLaunchKernelGGL((dense_kernel<false, 8>), grid, block, 0, st, m, n, k, x, w, bias, act, y);
+  }
   return hipGetLastError();
 }
 

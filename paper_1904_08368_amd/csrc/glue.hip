@@ -128,22 +128,36 @@ __global__ __launch_bounds__(256) void maxpool_kernel(const V* x, V* y, int N, i
   y[idx] = best;
 }
 
-// global average pool, NHWC fp16 -> [N][C] fp16, fp32 sum.
-__global__ __launch_bounds__(256) void avgpool_f16_kernel(const half8* x, half8* y, int N, int CV, int HW) {
-  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= N * CV) return;
-  const int cv = idx % CV, n = idx / CV;
+// global average pool, NHWC fp16 -> [N][C] fp16, fp32 sum.  One workgroup per (image, group
+// of up to 256 channel vectors); the HW positions are split over 256/CVB thread groups whose
+// partial sums meet in LDS.
+__global__ __launch_bounds__(256) void avgpool_f16_kernel(const half8* x, half8* y, int N, int CV, int HW, int CVB) {
+  __shared__ float part[256 * 8];
+  const int groups = (CV + CVB - 1) / CVB;
+  const int n = blockIdx.x / groups, g = blockIdx.x % groups;
+  const int parts = 256 / CVB;
+  const int cvl = threadIdx.x % CVB, pi = threadIdx.x / CVB;
+  const int cv = g * CVB + cvl;
   float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  for (int i = 0; i < HW; ++i) {
-    const half8 v = x[((long)n * HW + i) * CV + cv];
+  if (cv < CV && pi < parts)
+    for (int i = pi; i < HW; i += parts) {
+      const half8 v = x[((long)n * HW + i) * CV + cv];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) acc[e] += (float)v[e];
+      for (int e = 0; e < 8; ++e) acc[e] += (float)v[e];
+    }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) part[threadIdx.x * 8 + e] = acc[e];
+  __syncthreads();
+  if (pi == 0 && cv < CV) {
+    for (int p = 1; p < parts; ++p)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] += part[(p * CVB + cvl) * 8 + e];
+    half8 o;
+    const float inv = 1.0f / (float)HW;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = (_Float16)(acc[e] * inv);
+    y[(long)n * CV + cv] = o;
   }
-  half8 o;
-  const float inv = 1.0f / (float)HW;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) o[e] = (_Float16)(acc[e] * inv);
-  y[idx] = o;
 }
 
 inline unsigned blocks_for(long total) { return (unsigned)((total + 255) / 256); }
@@ -188,8 +202,11 @@ hipError_t launch_maxpool(bool is_i8, int N, int C, int H, int W, int R, int str
 
 hipError_t launch_avgpool_f16(int N, int C, int HW, const void* x, void* y, hipStream_t st) {
   const int cv = C / 8;
-  hipLaunchKernelGGL(avgpool_f16_kernel, dim3(blocks_for((long)N * cv)), dim3(256), 0, st, (const half8*)x, (half8*)y,
-                     N, cv, HW);
+  int cvb = 256;  // channel vectors per workgroup: the largest power of two that leaves >= 4 position groups
+  while (cvb > 1 && (cvb > cv || 256 / cvb < 4)) cvb >>= 1;
+  const int groups = (cv + cvb - 1) / cvb;
+  hipLaunchKernelGGL(avgpool_f16_kernel, dim3((unsigned)(N * groups)), dim3(256), 0, st, (const half8*)x, (half8*)y,
+                     N, cv, HW, cvb);
   return hipGetLastError();
 }
 

@@ -25,7 +25,8 @@ class FusedNet:
     ``shifts[i] = {'s': out_rshift, 'l': residual_lshift}`` per conv."""
 
     def __init__(self, ops, params: List[dict], batch: int, h: int, w: int, mode: str = "f16",
-                 shifts: Optional[List[dict]] = None, in_channels: int = 3, device: str = "cuda:0"):
+                 shifts: Optional[List[dict]] = None, in_channels: int = 3, device: str = "cuda:0",
+                 overlap_shortcuts: bool = True):
         assert mode in ("f16", "i8")
         self.ops, self.mode, self.batch = ops, mode, batch
         self.dev = torch.device(device)
@@ -117,6 +118,21 @@ class FusedNet:
                 self.bufs[op.dst], self.shape[op.dst] = y, (op.cout, 1, 1)
             else:
                 raise ValueError(op.kind)
+        # calls that may run beside their predecessor: a conv that reads the same tensor as the
+        # conv before it and whose output is first needed as a residual
+        self.side_calls, self.join_before = set(), set()
+        self.side = None
+        if overlap_shortcuts:
+            idx_of = {name: i for i, name in enumerate(self.call_names)}
+            for j in range(1, len(ops)):
+                a0, a1 = ops[j - 1], ops[j]
+                if a0.kind == "conv" and a1.kind == "conv" and a0.src == a1.src and not a1.res and not a0.res:
+                    users = [o for o in ops if o.src == a1.dst or o.res == a1.dst]
+                    if len(users) == 1 and users[0].res == a1.dst:
+                        self.side_calls.add(idx_of[a1.name])
+                        self.join_before.add(idx_of[users[0].name])
+            if self.side_calls:
+                self.side = torch.cuda.Stream(device=self.dev)
         torch.cuda.synchronize(self.dev)
         self.graph = None
 
@@ -135,9 +151,33 @@ class FusedNet:
         self.x_nchw.copy_(torch.from_numpy(np.ascontiguousarray(x_nchw)).to(self.dev))
 
     def run(self) -> None:
-        """Enqueue the whole network on the current stream (layout conversion included)."""
-        for fn, args in self.calls:
+        """Enqueue the whole network on the current stream (layout conversion included).
+
+        A conv whose output is only used as a later residual (the 1x1 shortcut of a ResNet
+        block) is launched on a side stream between two events, so that it overlaps the block's
+        first conv: both read the block input, neither reads the other."""
+        if not self.side_calls:
+            for fn, args in self.calls:
+                fn(*args)
+            return
+        main = torch.cuda.current_stream()
+        pending = None
+        for i, (fn, args) in enumerate(self.calls):
+            if i in self.side_calls:
+                fork = torch.cuda.Event()
+                fork.record(main)
+                self.side.wait_event(fork)
+                with torch.cuda.stream(self.side):
+                    fn(*args)
+                    pending = torch.cuda.Event()
+                    pending.record(self.side)
+                continue
+            if pending is not None and i in self.join_before:
+                main.wait_event(pending)
+                pending = None
             fn(*args)
+        if pending is not None:
+            main.wait_event(pending)
 
     def capture(self) -> None:
         """Record run() into a HIP graph (kernel launches only; nothing in it clears memory)."""
