@@ -94,6 +94,9 @@ def main() -> int:
     ap.add_argument("--no-extra", action="store_true", help="skip the int8 / MobileNet / batch-1 sections")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--layer-reps", type=int, default=20)
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run a 256 MiB device-to-device copy 10 times: a kernel of known HBM traffic that "
+                         "scales FETCH_SIZE / WRITE_SIZE counter readings of the same profiler run")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU; the path shards over the batch axis with no "
@@ -213,6 +216,13 @@ def main() -> int:
                                "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
                                "sample": f"all {nimg} images of the batch, mean of {passes} passes of the full stack, fp64 loops",
                                "seconds": round(dt, 2)}
+    if a.copy_probe:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        extra["copy_probe_bytes_each_way"] = 256 << 20
     out["extra"] = extra
     print(json.dumps(out))
     return 0

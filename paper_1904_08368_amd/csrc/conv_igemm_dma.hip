@@ -81,12 +81,17 @@ __device__ __forceinline__ void small_divmod(int t, int d, float rcp_d, int& q, 
 // KP = 64-byte planes per ring chunk (a chunk covers KP*64 bytes of reduction; each plane is
 // a [rows][64 B] sub-tile with its own swizzle, because 128-byte LDS rows cannot be read
 // conflict-free).  More planes = fewer barriers and fewer exposed LDS latencies per MFMA.
-template <bool IS_I8, int WAVES_M, int WAVES_N, int TM, int TN, int NS, int KP>
-__global__ __launch_bounds__(64 * WAVES_M * WAVES_N,
+// SK = waves that share one accumulator tile and split the k-steps of every chunk between
+// them (their partial sums meet in LDS before the epilogue).  A wave then owns a SK times
+// larger tile for the same workgroup tile, which cuts the LDS operand reads per MFMA -- the
+// resource the small tiles are bound by.
+template <bool IS_I8, int WAVES_M, int WAVES_N, int TM, int TN, int NS, int KP, int SK>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
                              // two workgroups per CU where their LDS rings fit side by side
                              (NS * KP * (WAVES_M * TM + WAVES_N * TN) * 32 * 64 <= 80 * 1024 ? 2 : 1))
     void igemm_dma_kernel(const ConvArgs a) {
-  constexpr int NW = WAVES_M * WAVES_N;
+  constexpr int NW = WAVES_M * WAVES_N * SK;
+  static_assert(SK == 1 || (SK == 2 && KP == 2 && TM % 2 == 0), "k-split pairs take one 64-byte plane each");
   constexpr int VE = IS_I8 ? 16 : 8;
   constexpr int ES = IS_I8 ? 1 : 2;
   constexpr int CK = KP * BKV * VE;
@@ -100,9 +105,11 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N,
   constexpr int STAGE = KP * PLANE;            // ... per ring stage
   constexpr int KSTEPS = KP * (BKV / 2);       // MFMA k-steps per chunk
   static_assert((NS - 1) * LPC <= 63, "vmcnt is a 6-bit counter");
-  static_assert(LPC <= TM * TN * KSTEPS, "one load is issued behind each MFMA of a chunk");
+  constexpr int KSW = KSTEPS / SK;             // ... of which this wave runs KSW
+  static_assert(LPC <= TM * TN * KSW, "one load is issued behind each MFMA of a chunk");
   constexpr int EP = WTN / 4 + 1;  // epilogue staging pitch (16-byte slots) of one pixel row, padded
-  static_assert(NW * 32 * EP <= NS * STAGE, "epilogue staging reuses the ring");
+  constexpr int XCH = SK == 2 ? (TM / 2) * TN * 4 * 64 : 0;  // slots a wave hands to its k-split partner
+  static_assert(NW * (32 * EP + XCH) <= NS * STAGE, "epilogue staging reuses the ring");
   typedef typename Mma<IS_I8>::acc_t acc_t;
 
   __shared__ uint4 ring[NS * STAGE];
@@ -110,7 +117,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N,
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave % WAVES_M, wn = wave / WAVES_M;
+  const int wk = wave / (WAVES_M * WAVES_N), wsub = wave % (WAVES_M * WAVES_N);
+  const int wm = wsub % WAVES_M, wn = wsub / WAVES_M;
   const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.K + BN - 1) / BN;
   const int tile = xcd_remap(blockIdx.x, tiles_m * tiles_n);
   const int tile_n = tile % tiles_n, tile_m = tile / tiles_n;
@@ -301,12 +309,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N,
     };
     // operands of k-step k+1 are fetched while the MFMAs of k-step k run (two register sets)
     uint4 wfa[TN], xfa[TM], wfb[TN], xfb[TM];
-    fetch(0, wfa, xfa);
+    const int k0 = wk * KSW;  // first k-step of this wave
+    fetch(k0, wfa, xfa);
 #pragma unroll
-    for (int k = 0; k < KSTEPS; k += 2) {
-      fetch(k + 1, wfb, xfb);
+    for (int k = 0; k < KSW; k += 2) {
+      fetch(k0 + k + 1, wfb, xfb);
       mma_step(k, wfa, xfa);
-      if (k + 2 < KSTEPS) fetch(k + 2, wfa, xfa);
+      if (k + 2 < KSW) fetch(k0 + k + 2, wfa, xfa);
       mma_step(k + 1, wfb, xfb);
     }
     fill = fill + 1 == NS ? 0 : fill + 1;
@@ -318,21 +327,72 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N,
   //      of pixel lane%32.  Each wave transposes its blocks through a private LDS region.
   wait_loads<0>();               // the trailing out-of-range loads still write zeros into the ring
   __builtin_amdgcn_s_barrier();  // every wave is done reading the ring
-  uint4* stg = ring + wave * (32 * EP);
+  constexpr int TM_E = SK == 2 ? TM / 2 : TM;  // accumulator block rows this wave finishes
+  const int tm_lo = SK == 2 ? wk * TM_E : 0;
+  if constexpr (SK == 2) {
+    // the pair splits the tile: each wave hands the partner the half it does not finish
+    uint4* give = ring + wave * XCH;
+    const uint4* take = ring + (wave ^ (WAVES_M * WAVES_N)) * XCH;
+#pragma unroll
+    for (int t = 0; t < TM_E; ++t)
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int tm = (1 - wk) * TM_E + t;  // a block of the partner's half
+          uint4 v;
+          v.x = as_u32(wk ? acc[tn][t][4 * g] : acc[tn][TM_E + t][4 * g]);
+          v.y = as_u32(wk ? acc[tn][t][4 * g + 1] : acc[tn][TM_E + t][4 * g + 1]);
+          v.z = as_u32(wk ? acc[tn][t][4 * g + 2] : acc[tn][TM_E + t][4 * g + 2]);
+          v.w = as_u32(wk ? acc[tn][t][4 * g + 3] : acc[tn][TM_E + t][4 * g + 3]);
+          (void)tm;
+          give[((t * TN + tn) * 4 + g) * 64 + lane] = v;
+        }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the LDS writes are done
+    __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (int t = 0; t < TM_E; ++t)
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const uint4 v = take[((t * TN + tn) * 4 + g) * 64 + lane];
+          const unsigned r[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            if constexpr (IS_I8) {
+              if (wk) acc[tn][TM_E + t][4 * g + e] += (int)r[e];
+              else acc[tn][t][4 * g + e] += (int)r[e];
+            } else {
+              if (wk) acc[tn][TM_E + t][4 * g + e] += __builtin_bit_cast(float, r[e]);
+              else acc[tn][t][4 * g + e] += __builtin_bit_cast(float, r[e]);
+            }
+          }
+        }
+  }
+  uint4* stg = ring + NW * XCH + wave * (32 * EP);
   constexpr int PPI = 64 / CG;  // pixels per pass of 64 lanes
   const int epix = lane / CG, ecg = lane % CG;
   const bool vec_ok = (a.K & 7) == 0;
 #pragma unroll
-  for (int tm = 0; tm < TM; ++tm) {
+  for (int te = 0; te < TM_E; ++te) {
+    const int tm = tm_lo + te;  // block row in the workgroup tile
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         uint4 v;
-        v.x = as_u32(acc[tn][tm][4 * g]);
-        v.y = as_u32(acc[tn][tm][4 * g + 1]);
-        v.z = as_u32(acc[tn][tm][4 * g + 2]);
-        v.w = as_u32(acc[tn][tm][4 * g + 3]);
+        if (SK == 2 && wk) {  // (wave-uniform) the upper half of the accumulator blocks
+          v.x = as_u32(acc[tn][TM - TM_E + te][4 * g]);
+          v.y = as_u32(acc[tn][TM - TM_E + te][4 * g + 1]);
+          v.z = as_u32(acc[tn][TM - TM_E + te][4 * g + 2]);
+          v.w = as_u32(acc[tn][TM - TM_E + te][4 * g + 3]);
+        } else {
+          v.x = as_u32(acc[tn][te][4 * g]);
+          v.y = as_u32(acc[tn][te][4 * g + 1]);
+          v.z = as_u32(acc[tn][te][4 * g + 2]);
+          v.w = as_u32(acc[tn][te][4 * g + 3]);
+        }
         stg[lrow * EP + tn * 8 + 2 * g + lhalf] = v;
       }
     // same wave wrote what it now reads: LDS operations of a wave execute in order
@@ -417,34 +477,37 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N,
 }
 
 struct DmaTile {
-  int waves_m, waves_n, tm, tn, ns, kp;
+  int waves_m, waves_n, tm, tn, ns, kp, sk;
   constexpr int bm() const { return waves_m * tm * 32; }
   constexpr int bn() const { return waves_n * tn * 32; }
 };
 // largest first; must match launch_typed
 constexpr DmaTile kTiles[] = {
-    {2, 2, 4, 2, 3, 1},  // 256 x 128
-    {4, 1, 4, 2, 3, 1},  // 512 x 64
-    {2, 1, 4, 2, 3, 1},  // 256 x 64, two waves
-    {2, 2, 2, 2, 3, 1},  // 128 x 128
-    {2, 2, 2, 1, 4, 1},  // 128 x 64
-    {2, 2, 1, 1, 4, 1},  // 64 x 64
+    {2, 2, 4, 2, 3, 1, 1},  // 256 x 128
+    {4, 1, 4, 2, 3, 1, 1},  // 512 x 64
+    {2, 1, 4, 2, 3, 1, 1},  // 256 x 64, two waves
+    {2, 2, 2, 2, 3, 1, 1},  // 128 x 128
+    {2, 2, 2, 1, 4, 1, 1},  // 128 x 64
+    {2, 2, 1, 1, 4, 1, 1},  // 64 x 64
     // 128-byte chunks (need C % 64 == 0 for fp16, C % 128 == 0 for int8)
-    {2, 2, 4, 2, 3, 2},  // 256 x 128
-    {2, 2, 4, 2, 2, 2},  // 256 x 128, two stages
-    {2, 2, 2, 2, 3, 2},  // 128 x 128
-    {2, 2, 2, 1, 3, 2},  // 128 x 64
-    {2, 2, 1, 1, 3, 2},  // 64 x 64
-    {2, 1, 4, 2, 3, 2},  // 256 x 64, two waves
+    {2, 2, 4, 2, 3, 2, 1},  // 256 x 128
+    {2, 2, 4, 2, 2, 2, 1},  // 256 x 128, two stages
+    {2, 2, 2, 2, 3, 2, 1},  // 128 x 128
+    {2, 2, 2, 1, 3, 2, 1},  // 128 x 64
+    {2, 2, 1, 1, 3, 2, 1},  // 64 x 64
+    {2, 1, 4, 2, 3, 2, 1},  // 256 x 64, two waves
+    // k-split wave pairs
+    {2, 1, 2, 2, 3, 2, 2},  // 128 x 64, four waves of 64 x 64
+    {1, 1, 2, 2, 3, 2, 2},  // 64 x 64, two waves of 64 x 64
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
-template <bool IS_I8, int WAVES_M, int WAVES_N, int TM, int TN, int NS, int KP>
+template <bool IS_I8, int WAVES_M, int WAVES_N, int TM, int TN, int NS, int KP, int SK = 1>
 hipError_t launch_one(const ConvArgs& a, hipStream_t st) {
   constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
   const int tiles = ((a.M + BM - 1) / BM) * ((a.K + BN - 1) / BN);
-  hipLaunchKernelGGL((igemm_dma_kernel<IS_I8, WAVES_M, WAVES_N, TM, TN, NS, KP>), dim3(tiles),
-                     dim3(64 * WAVES_M * WAVES_N), 0, st, a);
+  hipLaunchKernelGGL((igemm_dma_kernel<IS_I8, WAVES_M, WAVES_N, TM, TN, NS, KP, SK>), dim3(tiles),
+                     dim3(64 * WAVES_M * WAVES_N * SK), 0, st, a);
   return hipGetLastError();
 }
 
@@ -462,7 +525,9 @@ hipError_t launch_typed(const ConvArgs& a, int tile, hipStream_t st) {
     case 8: return launch_one<IS_I8, 2, 2, 2, 2, 3, 2>(a, st);
     case 9: return launch_one<IS_I8, 2, 2, 2, 1, 3, 2>(a, st);
     case 10: return launch_one<IS_I8, 2, 2, 1, 1, 3, 2>(a, st);
-    default: return launch_one<IS_I8, 2, 1, 4, 2, 3, 2>(a, st);
+    case 11: return launch_one<IS_I8, 2, 1, 4, 2, 3, 2>(a, st);
+    case 12: return launch_one<IS_I8, 2, 1, 2, 2, 3, 2, 2>(a, st);
+    default: return launch_one<IS_I8, 1, 1, 2, 2, 3, 2, 2>(a, st);
   }
 }
 
@@ -505,8 +570,8 @@ int igemm_dma_tile_count() { return kNumTiles; }
 
 void igemm_dma_kernel_name(const ConvArgs& a, bool is_i8, int tile, char* buf, size_t len) {
   const DmaTile& t = kTiles[resolve_tile(a, is_i8, tile)];
-  snprintf(buf, len, "igemm_dma_kernel<%s, %d, %d, %d, %d, %d, %d>", is_i8 ? "true" : "false", t.waves_m, t.waves_n,
-           t.tm, t.tn, t.ns, t.kp);
+  snprintf(buf, len, "igemm_dma_kernel<%s, %d, %d, %d, %d, %d, %d, %d>", is_i8 ? "true" : "false", t.waves_m,
+           t.waves_n, t.tm, t.tn, t.ns, t.kp, t.sk);
 }
 
 hipError_t launch_conv_igemm_dma(const ConvArgs& a, bool is_i8, int tile, hipStream_t st) {

@@ -103,7 +103,7 @@ def test_fp16_conv_full_epilogue(G, case):
 
 
 @pytest.mark.parametrize("c", [64, 24])          # 64: direct-to-LDS kernel; 24: register-staged kernel
-@pytest.mark.parametrize("tile", list(range(12)))
+@pytest.mark.parametrize("tile", list(range(14)))
 def test_fp16_conv_every_tile_shape(G, tile, c):
     g = _rng(50)
     n, h, w, k = 2, 23, 27, 192
@@ -192,7 +192,7 @@ def test_int8_qconv_bit_exact(G, case):
 
 
 @pytest.mark.parametrize("c", [64, 48])
-@pytest.mark.parametrize("tile", list(range(12)))
+@pytest.mark.parametrize("tile", list(range(14)))
 def test_int8_every_tile_shape_and_repeatable(G, tile, c):
     g = _rng(150)
     x = g.integers(-127, 128, (2, c, 23, 27)).astype(np.int8)
