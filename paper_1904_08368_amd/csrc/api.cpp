@@ -104,6 +104,9 @@ relay::ConvArgs make_args(const relay_conv2d_desc* d, int ho, int wo) {
 void finish_args(relay::ConvArgs& a) {
   const bool al = aligned(a.bias, 16) && aligned(a.scale, 16) && aligned(a.shift, 16) && aligned(a.qbias, 16);
   a.param_vec = (al && (a.K & 7) == 0) ? 1 : 0;
+  // an XCD works through a run of consecutive tiles: let the run share whichever operand is
+  // larger, so that the XCD's L2 only has to hold a slab of it
+  a.n_major = (size_t)a.K * a.Kred > (size_t)a.N * a.H * a.W * a.C ? 1 : 0;
 }
 
 relay_status device_status(hipError_t e, const char* what) {

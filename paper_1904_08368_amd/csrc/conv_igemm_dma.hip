@@ -121,7 +121,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
   const int wm = wsub % WAVES_M, wn = wsub / WAVES_M;
   const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.K + BN - 1) / BN;
   const int tile = xcd_remap(blockIdx.x, tiles_m * tiles_n);
-  const int tile_n = tile % tiles_n, tile_m = tile / tiles_n;
+  const int tile_n = a.n_major ? tile / tiles_m : tile % tiles_n;
+  const int tile_m = a.n_major ? tile % tiles_m : tile / tiles_n;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
   // ---- staging role of this lane inside a 16-row block: row srow, physical slot sphys.
@@ -137,7 +138,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
 #pragma unroll
   for (int j = 0; j < XL; ++j) {
     const int row = (wave * XL + j) * 16 + srow;
-    const int kvl = sphys ^ ((row >> 1) & (BKV - 1));
+    const int kvl = sphys ^ lds_swizzle(row);
     int dp, q, dn, p;
     small_divmod(q_0 + row, a.Wo, a.rcp_wo, dp, q);
     small_divmod(p_0 + dp, a.Ho, a.rcp_ho, dn, p);
@@ -158,7 +159,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
 #pragma unroll
   for (int j = 0; j < WL; ++j) {
     const int row = (wave * WL + j) * 16 + srow;
-    const int kvl = sphys ^ ((row >> 1) & (BKV - 1));
+    const int kvl = sphys ^ lds_swizzle(row);
     const int ch = n0 + row;
     w_off[j] = ch < a.K ? (unsigned)((ch * a.Kp + kvl * VE) * ES) : kOob;
   }
@@ -307,16 +308,18 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
           }
         }
     };
-    // operands of k-step k+1 are fetched while the MFMAs of k-step k run (two register sets)
-    uint4 wfa[TN], xfa[TM], wfb[TN], xfb[TM];
+    // operands of k-step k+PD are fetched before the MFMAs of k-step k run (PD+1 register sets):
+    // small wave tiles have too few MFMAs per k-step to cover the LDS latency one step ahead,
+    // so they fetch the whole chunk right behind the barrier
+    constexpr int PD = (TM + TN <= 4 && KSW > 1) ? KSW - 1 : 1;
+    uint4 wf[PD + 1][TN], xf[PD + 1][TM];
     const int k0 = wk * KSW;  // first k-step of this wave
-    fetch(k0, wfa, xfa);
 #pragma unroll
-    for (int k = 0; k < KSW; k += 2) {
-      fetch(k0 + k + 1, wfb, xfb);
-      mma_step(k, wfa, xfa);
-      if (k + 2 < KSW) fetch(k0 + k + 2, wfa, xfa);
-      mma_step(k + 1, wfb, xfb);
+    for (int k = 0; k < PD && k < KSW; ++k) fetch(k0 + k, wf[k], xf[k]);
+#pragma unroll
+    for (int k = 0; k < KSW; ++k) {
+      if (k + PD < KSW) fetch(k0 + k + PD, wf[(k + PD) % (PD + 1)], xf[(k + PD) % (PD + 1)]);
+      mma_step(k, wf[k % (PD + 1)], xf[k % (PD + 1)]);
     }
     fill = fill + 1 == NS ? 0 : fill + 1;
     next_chunk(fill);

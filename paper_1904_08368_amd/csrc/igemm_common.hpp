@@ -13,10 +13,12 @@ typedef int intx16 __attribute__((ext_vector_type(16)));
 
 constexpr int BKV = 4;  // 16-byte k-vectors per tile row per chunk: 64 bytes of reduction
 
-// LDS slot (in 16-byte units) of k-vector kv of a tile row.  The XOR spreads the 32 rows
-// that one MFMA operand read touches over all banks: measured 122 B/clk/CU of the 128 B/clk
-// LDS read peak, against 31 B/clk unswizzled.
-__device__ __forceinline__ int lds_slot(int row, int kv) { return row * BKV + (kv ^ ((row >> 1) & (BKV - 1))); }
+// LDS slot (in 16-byte units) of k-vector kv of a tile row.  The XOR spreads the 32 rows that
+// one MFMA operand read (ds_read_b128: lanes 0-31 one k-vector of 32 rows, lanes 32-63 the
+// next) touches over all banks: measured 126 B/clk/CU of the 128 B/clk LDS read peak, against
+// 61 B/clk unswizzled and 111 B/clk with the row pair (row >> 1) as the key.
+__device__ __forceinline__ int lds_swizzle(int row) { return (row >> 2) & (BKV - 1); }
+__device__ __forceinline__ int lds_slot(int row, int kv) { return row * BKV + (kv ^ lds_swizzle(row)); }
 
 template <bool IS_I8>
 struct Mma;

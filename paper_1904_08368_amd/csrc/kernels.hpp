@@ -28,6 +28,7 @@ struct ConvArgs {
   float rcp_wo, rcp_ho;   // 1/Wo, 1/Ho
   unsigned tap_spread;    // bit r*S set for every filter row r (R*S <= 32)
   int param_vec;          // per-channel constants are 16-byte aligned and K % 8 == 0: vector loads
+  int n_major;            // tile order: consecutive workgroups share an output-channel tile (else a pixel tile)
   int M;        // N*Ho*Wo  (rows of the implicit GEMM)
   int Kred;     // R*S*C    (reduction length)
   int Kp;       // row pitch of the packed filters, elements

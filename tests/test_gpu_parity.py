@@ -104,9 +104,10 @@ def test_fp16_conv_full_epilogue(G, case):
 
 @pytest.mark.parametrize("c", [64, 24])          # 64: direct-to-LDS kernel; 24: register-staged kernel
 @pytest.mark.parametrize("tile", list(range(14)))
-def test_fp16_conv_every_tile_shape(G, tile, c):
+@pytest.mark.parametrize("n", [2, 5])            # filters larger than the activations, and the reverse: both tile orders
+def test_fp16_conv_every_tile_shape(G, tile, c, n):
     g = _rng(50)
-    n, h, w, k = 2, 23, 27, 192
+    h, w, k = 23, 27, 192
     x = _h(g.standard_normal((n, c, h, w)))
     wt = _h(g.standard_normal((k, c, 3, 3)) * np.sqrt(2.0 / (c * 9)))
     sc = (1 + g.standard_normal(k) * 0.1).astype(np.float32)
