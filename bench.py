@@ -29,8 +29,8 @@ HBM_PEAK_GBS = 8000.0
 
 
 def _layer_table(net, ops, batch, reps, trials):
-    """Per-launch duration of every call of the network: `reps` back-to-back launches
-    between two events on the launch stream, median of `trials`."""
+    """Per-launch duration of every call of the network: `reps` back-to-back launches (one
+    graph replay) between two events on the launch stream, median of `trials`."""
     import torch
     from paper_1904_08368_amd import binding as B
     rows = []
@@ -38,15 +38,23 @@ def _layer_table(net, ops, batch, reps, trials):
     for (fn, args), name in zip(net.calls, net.call_names):
         for _ in range(3):
             fn(*args)
+        torch.cuda.synchronize()
+        # the launches are replayed from a HIP graph so that their spacing is set by the GPU,
+        # not by the Python call overhead (which exceeds the duration of the small layers)
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for _ in range(reps):
+                fn(*args)
+        g.replay()
         ts = []
         for _ in range(trials):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
-            for _ in range(reps):
-                fn(*args)
+            g.replay()
             e1.record()
             e1.synchronize()
             ts.append(e0.elapsed_time(e1) * 1e3 / reps)      # us per launch
+        del g
         row = {"name": name, "us": statistics.median(ts)}
         d = args[0]
         if fn in (B.relay_fused_conv2d_bias_bn_relu, B.relay_qconv2d_requant, B.relay_fused_dwconv_bias_relu):
@@ -69,6 +77,39 @@ def _layer_table(net, ops, batch, reps, trials):
             row["gbs"] = row["mbytes"] / row["us"] * 1e3              # MB/us = 1000 GB/s
         rows.append(row)
     return rows
+
+
+KERNEL_SOURCES = ("conv_igemm_dma.hip", "igemm_common.hpp", "kernels.hpp")
+
+
+def _kernel_source_digest():
+    """sha256 over the sources the implicit-GEMM kernel is compiled from."""
+    import hashlib
+    h = hashlib.sha256()
+    for f in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_1904_08368_amd", "csrc", f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()
+
+
+def _hbm_traffic(kernel_name):
+    """HBM bytes per launch of `kernel_name` from the stored rocprofv3 counter summary
+    (FETCH_SIZE and WRITE_SIZE passes, each scaled by the reading of a copy of known size).
+    None when there is no summary for this kernel or the kernel sources have changed since."""
+    path = os.path.join(ROOT, "profiles", "igemm_dma_kernel_resnet18_fp16_b32_hbm_traffic.md")
+    if not os.path.exists(path):
+        return None
+    kv = {}
+    with open(path) as fh:
+        for line in fh:
+            if line.startswith("    ") and ":" in line:
+                k, v = line.strip().split(":", 1)
+                kv[k.strip()] = v.strip()
+    if kv.get("kernel") != kernel_name or kv.get("source_sha256") != _kernel_source_digest():
+        return None
+    fetch = float(kv["fetch_size_kib_per_launch"]) * float(kv["fetch_scale"])
+    write = float(kv["write_size_kib_per_launch"]) * float(kv["write_scale"])
+    return round((fetch + write) * 1024.0)
 
 
 def _time_steps(net, steps, warmup, use_graph):
@@ -135,7 +176,7 @@ def main() -> int:
     dom_name, dom = max(by_kernel.items(), key=lambda kv: kv[1]["us"])
     achieved = dom["gflop"] / dom["us"] * 1e3          # TFLOP/s
     roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK["f16"], "unit": "TFLOP/s",
-                "frac": round(achieved / PEAK["f16"], 4), "traffic": None, "kernel": dom_name,
+                "frac": round(achieved / PEAK["f16"], 4), "traffic": _hbm_traffic(dom_name), "kernel": dom_name,
                 "launches_per_step": dom["launches"], "avg_launch_us": round(dom["us"] / dom["launches"], 2),
                 "gflop_per_launch": round(dom["gflop"] / dom["launches"], 3), "layers": dom["layers"]}
     conv_us = sum(r["us"] for r in rows if r.get("kernel", "").startswith("igemm"))

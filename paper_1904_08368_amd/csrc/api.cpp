@@ -375,6 +375,22 @@ relay_status relay_fused_dense_bias_act(int32_t m, int32_t n, int32_t k, int32_t
   if (!aligned(x, 16) || !aligned(w, 16) || !aligned(y, dtype == RELAY_F16 ? 2 : 4))
     return fail(RELAY_ERR_ALIGN, "x and w must be 16-byte aligned");
   if (y == x || y == w) return fail(RELAY_ERR_UNSUPPORTED, "output must not alias an input");
+  if (dtype == RELAY_F16 && m >= 16 && k % 64 == 0) {
+    // With a batch, dense is a 1x1 convolution over m one-pixel images; a weight row of whole
+    // 128-byte groups is already the packed filter layout, so the MFMA kernel takes it as is.
+    relay_conv2d_desc d;
+    memset(&d, 0, sizeof(d));
+    d.n = m; d.c = k; d.h = 1; d.w = 1; d.k = n; d.r = 1; d.s = 1;
+    d.stride_h = d.stride_w = 1;
+    d.dtype = RELAY_F16; d.layout = RELAY_NHWC;
+    d.flags = (bias ? RELAY_HAS_BIAS : 0u) | (act == 1 ? RELAY_RELU : 0u);
+    relay::ConvArgs a = make_args(&d, 1, 1);
+    a.x = x; a.w = w; a.y = y; a.bias = bias;
+    finish_args(a);
+    if (relay::igemm_dma_supported(a, false))
+      return device_status(relay::launch_conv_igemm_dma(a, false, -1, static_cast<hipStream_t>(hip_stream)),
+                           "dense launch");
+  }
   return device_status(relay::launch_dense(m, n, k, dtype == RELAY_F16, x, w, bias, act, y, static_cast<hipStream_t>(hip_stream)),
                        "dense launch");
 }

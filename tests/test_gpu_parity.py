@@ -237,7 +237,7 @@ def test_dwconv_f16(G, case):
 
 
 # ------------------------------------------------------------------------------ dense
-@pytest.mark.parametrize("m,n,k", [(1, 1000, 512), (32, 1000, 1024), (5, 37, 24), (9, 130, 2048)])
+@pytest.mark.parametrize("m,n,k", [(1, 1000, 512), (32, 1000, 1024), (5, 37, 24), (9, 130, 2048), (32, 1000, 512), (17, 37, 192), (70, 136, 64)])
 def test_dense(G, m, n, k):
     from paper_1904_08368_amd import binding as B
     g = _rng(300 + m)
