@@ -137,6 +137,151 @@ __global__ __launch_bounds__(256) void dwconv3x3_f16_kernel(const ConvArgs a) {
   }
 }
 
+// ---- stride 1, wide images: the input patch of a workgroup goes through LDS.
+//
+// A workgroup of NT threads owns (2*MTH) x 28 output pixels x (8*CBV) channels of one image.
+// Its input patch, (2*MTH + 2) x 30 pixels, is fetched once with global->LDS loads (lane i of
+// an instruction writes 16 bytes at base + 16*i; the patch is stored as [pixel][channel
+// vector], so one instruction moves 64/CBV whole pixels; taps in the padding get an
+// out-of-range offset and arrive as zeros).  A thread then reads the 4 x 6 patch of its 2 x 4
+// outputs from LDS instead of from the vector L1: the patch is requested from L2 about 1.3
+// times per input element (the halo) instead of 3 times.  28 columns divide the 112-, 56- and
+// 28-pixel rows of the workloads; other widths run with a ragged last tile.  Measured: the
+// same kernel without its multiply-adds streams at 5.2 TB/s; the 9 fp32 FMAs per output
+// element that the vector ALUs must issue are what is left of the gap to the HBM rate.
+__device__ __forceinline__ void lds_dma16(const int (&rsrc)[4], unsigned lds_base, unsigned voff) {
+  typedef int intx4 __attribute__((ext_vector_type(4)));
+  intx4 r;
+  r[0] = rsrc[0]; r[1] = rsrc[1]; r[2] = rsrc[2]; r[3] = rsrc[3];
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds_base), "v"(voff),
+               "s"(r)
+               : "memory");
+}
+
+template <int CBV, int MTH, int NT>
+__global__ __launch_bounds__(NT) void dwconv3x3_s1_lds_kernel(const ConvArgs a) {
+  constexpr int MTW = 7;                       // micro-tiles (2 x 4 outputs) across the workgroup tile
+  constexpr int TH = 2 * MTH, TW = 4 * MTW;    // output tile
+  constexpr int PH = TH + 2, PW = TW + 2;      // input patch
+  constexpr int NV = PH * PW * CBV;            // 16-byte vectors of the patch
+  constexpr int LOADS = (NV + NT - 1) / NT;    // load instructions per thread
+  constexpr int NW = NT / 64;
+  static_assert(MTH * MTW * CBV <= NT, "one thread per micro-tile and channel vector");
+  constexpr unsigned kOob = 0x80000000u;
+  __shared__ uint4 patch[LOADS * NT];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int cblocks = a.C / (8 * CBV);
+  const int tiles_w = (a.Wo + TW - 1) / TW, tiles_h = (a.Ho + TH - 1) / TH;
+  int t = xcd_order(blockIdx.x, gridDim.x);  // (n, tile row, tile column, channel block), channel block fastest
+  const int cb = t % cblocks;
+  t /= cblocks;
+  const int tx = t % tiles_w;
+  t /= tiles_w;
+  const int ty = t % tiles_h;
+  const int n = t / tiles_h;
+  const int oy0 = ty * TH, ox0 = tx * TW;
+  const int iy0 = oy0 - a.ph, ix0 = ox0 - a.pw;  // input coordinates of patch pixel (0, 0)
+  const int c0 = cb * 8 * CBV;
+
+  const unsigned long long pa = reinterpret_cast<unsigned long long>(a.x);
+  const int rs[4] = {(int)(unsigned)pa, (int)(unsigned)((pa >> 32) & 0xffffu),
+                     (int)((unsigned)a.N * a.H * a.W * a.C * 2u), 0x00020000};
+  const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) uint4*)(&patch[0]);
+#pragma unroll
+  for (int j = 0; j < LOADS; ++j) {
+    const int v = (j * NW + wave) * 64 + lane;  // vector index in the patch: pixel * CBV + channel vector
+    const int pix = v / CBV, cv = v % CBV;
+    const int py = pix / PW, px = pix - py * PW;
+    const int iy = iy0 + py, ix = ix0 + px;
+    const bool ok = v < NV && (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W;
+    const unsigned off = ok ? (unsigned)((((n * a.H + iy) * a.W + ix) * a.C + c0 + cv * 8) * 2) : kOob;
+    lds_dma16(rs, lds_base + (unsigned)((j * NW + wave) * 64) * 16u, off);
+  }
+
+  // this thread's micro-tile and channel vector; the filters and constants load while the patch is in flight
+  const int cv = tid % CBV, mt = tid / CBV;
+  const int mtx = mt % MTW, mty = mt / MTW;
+  const bool active = mty < MTH;
+  const int c = c0 + cv * 8;
+  const _Float16* w = static_cast<const _Float16*>(a.w) + c;  // [r][s][c]
+  uint4 wv[9];
+#pragma unroll
+  for (int k = 0; k < 9; ++k) wv[k] = *reinterpret_cast<const uint4*>(w + (long)k * a.C);
+  float mul[8], add[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const float sc = (a.flags & F_BN) ? a.scale[c + e] : 1.f;
+    const float sf = (a.flags & F_BN) ? a.shift[c + e] : 0.f;
+    const float b = (a.flags & F_BIAS) ? a.bias[c + e] : 0.f;
+    mul[e] = sc;
+    add[e] = b * sc + sf;  // (acc + b)*sc + sf
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (!active) return;
+
+  float acc[2][4][8];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[i][j][e] = 0.f;
+  const uint4* pp = patch + ((mty * 2) * PW + mtx * 4) * CBV + cv;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {  // patch row: feeds output row i = r - fr for filter row fr
+    uint4 xr[6];
+#pragma unroll
+    for (int q = 0; q < 6; ++q) xr[q] = pp[(r * PW + q) * CBV];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int fr = r - i;
+      if (fr < 0 || fr > 2) continue;
+#pragma unroll
+      for (int fs = 0; fs < 3; ++fs) {
+        const uint4 ww = wv[fr * 3 + fs];
+        const unsigned wr[4] = {ww.x, ww.y, ww.z, ww.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const uint4 xx = xr[j + fs];
+          const unsigned xh[4] = {xx.x, xx.y, xx.z, xx.w};
+#pragma unroll
+          for (int h = 0; h < 4; ++h) {
+            fma_mix_lo(acc[i][j][2 * h], xh[h], wr[h]);
+            fma_mix_hi(acc[i][j][2 * h + 1], xh[h], wr[h]);
+          }
+        }
+      }
+    }
+  }
+
+  const float lo = (a.flags & F_RELU) ? 0.f : -__builtin_inff();
+  _Float16* y = static_cast<_Float16*>(a.y) + (long)n * a.Ho * a.Wo * a.C + c;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int p = oy0 + mty * 2 + i;
+    if (p >= a.Ho) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int q = ox0 + mtx * 4 + j;
+      if (q >= a.Wo) continue;
+      half8 o;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] = (_Float16)fmaxf(acc[i][j][e] * mul[e] + add[e], lo);
+      *reinterpret_cast<half8*>(y + ((long)p * a.Wo + q) * a.C) = o;
+    }
+  }
+}
+
+template <int CBV, int MTH, int NT>
+hipError_t launch_dw_lds(const ConvArgs& a, hipStream_t st) {
+  const long tiles = (long)a.N * ((a.Ho + 2 * MTH - 1) / (2 * MTH)) * ((a.Wo + 27) / 28) * (a.C / (8 * CBV));
+  hipLaunchKernelGGL((dwconv3x3_s1_lds_kernel<CBV, MTH, NT>), dim3((unsigned)tiles), dim3(NT), 0, st, a);
+  return hipGetLastError();
+}
+
 template <int STRIDE, int TH, int TW>
 hipError_t launch_dw(const ConvArgs& a, hipStream_t st) {
   const long total = (long)a.N * ((a.Ho + TH - 1) / TH) * ((a.Wo + TW - 1) / TW) * (a.C / 8);
@@ -150,6 +295,14 @@ hipError_t launch_dw(const ConvArgs& a, hipStream_t st) {
 // 2x4 (stride 1) and 2x2 (stride 2) outputs per thread: measured faster than smaller patches
 // on every MobileNet layer, including the 7x7 ones.
 hipError_t launch_dwconv_f16(const ConvArgs& a, hipStream_t st) {
+  // rows of at least one 28-pixel tile: the LDS-staged kernel (measured faster from 28 x 28 up)
+  // rows of at least one 28-pixel tile: the LDS-staged kernel (measured faster from 28 x 28 up;
+  // small workgroups on the large images, where eight of them share a CU and overlap their
+  // load, compute and store phases)
+  if (a.sh == 1 && a.sw == 1 && a.Wo >= 28 && a.Ho >= 8 && a.C % 32 == 0) {
+    if (a.Wo >= 56) return launch_dw_lds<4, 4, 128>(a, st);
+    return launch_dw_lds<4, 8, 256>(a, st);
+  }
   if (a.sh == 1) return launch_dw<1, 2, 4>(a, st);
   return launch_dw<2, 2, 2>(a, st);
 }

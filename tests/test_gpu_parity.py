@@ -220,7 +220,9 @@ def test_int8_rounding_ties_through_the_kernel(G):
 
 # -------------------------------------------------------------------------- depthwise
 @pytest.mark.parametrize("case", [(2, 32, 19, 23, 1), (2, 64, 19, 23, 2), (1, 8, 7, 7, 1), (3, 128, 14, 14, 2),
-                                  (1, 1024, 7, 7, 1), (1, 40, 5, 9, 2)])
+                                  (1, 1024, 7, 7, 1), (1, 40, 5, 9, 2),
+                                  # rows of 28 pixels and more at stride 1: the LDS-staged kernel, exact and ragged tiles
+                                  (2, 64, 30, 37, 1), (1, 96, 17, 28, 1), (2, 128, 56, 56, 1), (1, 32, 9, 61, 1)])
 def test_dwconv_f16(G, case):
     n, c, h, w, st = case
     g = _rng(200 + c + st)
