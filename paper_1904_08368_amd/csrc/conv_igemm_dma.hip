@@ -502,6 +502,8 @@ constexpr DmaTile kTiles[] = {
     // k-split wave pairs
     {2, 1, 2, 2, 3, 2, 2},  // 128 x 64, four waves of 64 x 64
     {1, 1, 2, 2, 3, 2, 2},  // 64 x 64, two waves of 64 x 64
+    // tall tiles for layers with few output channels
+    {4, 1, 2, 2, 3, 1, 1},  // 256 x 64, four waves of 64 x 64
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
@@ -530,7 +532,8 @@ hipError_t launch_typed(const ConvArgs& a, int tile, hipStream_t st) {
     case 10: return launch_one<IS_I8, 2, 2, 1, 1, 3, 2>(a, st);
     case 11: return launch_one<IS_I8, 2, 1, 4, 2, 3, 2>(a, st);
     case 12: return launch_one<IS_I8, 2, 1, 2, 2, 3, 2, 2>(a, st);
-    default: return launch_one<IS_I8, 1, 1, 2, 2, 3, 2, 2>(a, st);
+    case 13: return launch_one<IS_I8, 1, 1, 2, 2, 3, 2, 2>(a, st);
+    default: return launch_one<IS_I8, 4, 1, 2, 2, 3, 1, 1>(a, st);
   }
 }
 
@@ -548,6 +551,8 @@ bool tile_fits(const ConvArgs& a, bool is_i8, int t) {
 // the workgroup count more than the per-tile intensity); 128-byte chunks where C allows.
 int pick_tile(const ConvArgs& a, bool is_i8) {
   const bool kp2 = a.C % (2 * BKV * (is_i8 ? 16 : 8)) == 0;
+  // 64 output channels over very many pixels (the stem, int8 layer 1): tall tiles of 64 x 64 per wave
+  if (a.K <= 64 && (is_i8 || a.xs_w != a.C) && tiles_of(a, kTiles[14]) >= 384) return 14;
   if (a.K > 64 && tiles_of(a, kTiles[0]) >= 512) return 0;
   const int mid = kp2 ? 9 : 4;
   if (tiles_of(a, kTiles[mid]) >= 190) return mid;

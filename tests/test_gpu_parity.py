@@ -103,7 +103,7 @@ def test_fp16_conv_full_epilogue(G, case):
 
 
 @pytest.mark.parametrize("c", [64, 24])          # 64: direct-to-LDS kernel; 24: register-staged kernel
-@pytest.mark.parametrize("tile", list(range(14)))
+@pytest.mark.parametrize("tile", list(range(15)))
 @pytest.mark.parametrize("n", [2, 5])            # filters larger than the activations, and the reverse: both tile orders
 def test_fp16_conv_every_tile_shape(G, tile, c, n):
     g = _rng(50)
@@ -193,7 +193,7 @@ def test_int8_qconv_bit_exact(G, case):
 
 
 @pytest.mark.parametrize("c", [64, 48])
-@pytest.mark.parametrize("tile", list(range(14)))
+@pytest.mark.parametrize("tile", list(range(15)))
 def test_int8_every_tile_shape_and_repeatable(G, tile, c):
     g = _rng(150)
     x = g.integers(-127, 128, (2, c, 23, 27)).astype(np.int8)
