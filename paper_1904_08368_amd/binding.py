@@ -9,7 +9,7 @@ from __future__ import annotations
 
 import ctypes as C
 import os
-from typing import Optional, Tuple
+from typing import Sequence, Optional, Tuple
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "librelayfused.so")
@@ -54,6 +54,7 @@ SIGNATURES = {
     "relay_nchw_to_nhwc": [_I, _I, _I, _I, _I, _I, _P, _P, _P],
     "relay_nhwc4_padded_shape": [_DP, C.POINTER(_I), C.POINTER(_I)],
     "relay_pack_input_nhwc4": [_DP, _P, _P, _P],
+    "relay_fuse_extract": [_I, _P, _P, _P, _P, _P],
     "relay_set_conv_tile": [_I],
     "relay_conv2d_kernel_name": [_DP, C.c_char_p, _SZ],
 }
@@ -173,6 +174,17 @@ def relay_nhwc4_padded_shape(d: ConvDesc) -> Tuple[int, int]:
 
 def relay_pack_input_nhwc4(d: ConvDesc, x_nchw, y) -> None:
     _check(lib().relay_pack_input_nhwc4(C.byref(d), _ptr(x_nchw), _ptr(y), _stream()))
+
+
+def relay_fuse_extract(pattern: Sequence[int], in_offsets: Sequence[int], in_nodes: Sequence[int]):
+    """Host-side call: returns (ipdom, group) as lists, one entry per operator."""
+    n = len(pattern)
+    arr = lambda v: (C.c_int32 * max(len(v), 1))(*v)
+    pat, offs, ins = arr(pattern), arr(in_offsets), arr(in_nodes)
+    ipdom, group = (C.c_int32 * n)(), (C.c_int32 * n)()
+    _check(lib().relay_fuse_extract(n, C.cast(pat, _P), C.cast(offs, _P), C.cast(ins, _P) if len(in_nodes) else None,
+                                    C.cast(ipdom, _P), C.cast(group, _P)))
+    return list(ipdom), list(group)
 
 
 def relay_conv2d_kernel_name(d: ConvDesc) -> str:

@@ -6,6 +6,8 @@
 #include <cstring>
 
 #include "../../include/relay_fused.h"
+#include "../../include/relay_fusion.h"
+#include "fusion.hpp"
 #include "kernels.hpp"
 
 namespace {
@@ -393,6 +395,30 @@ relay_status relay_fused_dense_bias_act(int32_t m, int32_t n, int32_t k, int32_t
   }
   return device_status(relay::launch_dense(m, n, k, dtype == RELAY_F16, x, w, bias, act, y, static_cast<hipStream_t>(hip_stream)),
                        "dense launch");
+}
+
+relay_status relay_fuse_extract(int32_t n_ops, const int32_t* pattern, const int32_t* in_offsets,
+                                const int32_t* in_nodes, int32_t* ipdom, int32_t* group) {
+  if (!pattern || !in_offsets || !group) return fail(RELAY_ERR_NULL, "pattern, in_offsets and group are required");
+  if (n_ops < 1 || n_ops > (1 << 20)) return fail(RELAY_ERR_SHAPE, "n_ops=%d outside 1..2^20", n_ops);
+  if (in_offsets[0] != 0) return fail(RELAY_ERR_SHAPE, "in_offsets[0] must be 0");
+  for (int32_t i = 0; i < n_ops; ++i) {
+    if (pattern[i] < RELAY_PATTERN_OPAQUE || pattern[i] > RELAY_PATTERN_CONTRACTION)
+      return fail(RELAY_ERR_UNSUPPORTED, "operator %d has unknown pattern %d", i, pattern[i]);
+    if (in_offsets[i + 1] < in_offsets[i]) return fail(RELAY_ERR_SHAPE, "in_offsets decreases at operator %d", i);
+  }
+  if (in_offsets[n_ops] > 0 && !in_nodes) return fail(RELAY_ERR_NULL, "in_nodes is NULL");
+  for (int32_t i = 0; i < n_ops; ++i)
+    for (int32_t e = in_offsets[i]; e < in_offsets[i + 1]; ++e)
+      if (in_nodes[e] < 0 || in_nodes[e] >= i)
+        return fail(RELAY_ERR_SHAPE, "operator %d reads operator %d: inputs must be earlier operators", i, in_nodes[e]);
+  std::vector<int32_t> ip, gr;
+  relay::fuse_extract(n_ops, pattern, in_offsets, in_nodes, ip, gr);
+  for (int32_t i = 0; i < n_ops; ++i) {
+    if (ipdom) ipdom[i] = ip[i];
+    group[i] = gr[i];
+  }
+  return RELAY_OK;
 }
 
 relay_status relay_maxpool2d(int32_t dtype, int32_t n, int32_t c, int32_t h, int32_t w, int32_t r, int32_t stride,

@@ -1,0 +1,95 @@
+"""Operator fusion front half: dataflow graph -> fusion groups -> sequence of fused primitive
+functions (paper Section 4.1).  The grouping itself is the library's relay_fuse_extract; this
+module marshals the graph and turns every group into the record `FusedNet` launches.
+
+A group that holds a contraction must have the shape the kernels fuse (paper Section 4.1,
+"Lowering": the fused function is compiled as one operator): contraction, then optionally
+bias add, scale/shift, add of one outside tensor, relu, each reading the one before, in that
+order.  Anything else raises: there is no unfused fallback.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Dict, List, Optional, Sequence
+
+from . import binding as B
+
+KIND_OF = {"conv2d": "conv", "dwconv2d": "dwconv", "dense": "dense", "maxpool": "maxpool", "avgpool": "avgpool"}
+EPILOGUE_ORDER = ("bias_add", "scale_shift", "add", "relu")
+
+
+@dataclass(frozen=True)
+class FusedOp:
+    """One primitive function: the fields FusedNet reads."""
+    kind: str
+    name: str
+    src: str
+    dst: str
+    cin: int = 0
+    cout: int = 0
+    r: int = 1
+    stride: int = 1
+    pad: int = 0
+    bias: bool = False
+    bn: bool = False
+    relu: bool = False
+    res: Optional[str] = None
+
+
+def extract_groups(graph) -> List[List[int]]:
+    """Fusion groups of `graph` (nodes with .kind, .inputs; graph.patterns(), graph.csr()), each a
+    sorted list of node indices, in execution order (by the group's last node)."""
+    offs, flat = graph.csr()
+    _, group = B.relay_fuse_extract(graph.patterns(), offs, flat)
+    members: Dict[int, List[int]] = {}
+    for i, g in enumerate(group):
+        members.setdefault(g, []).append(i)
+    return sorted(members.values(), key=lambda ms: ms[-1])
+
+
+def lower(graph, groups: Sequence[Sequence[int]]) -> List[FusedOp]:
+    """One FusedOp per group (graph inputs produce none).  The tensor a group writes carries
+    the name of the group's last node."""
+    nodes = graph.nodes
+    out_name: Dict[int, str] = {}          # node index -> name of the tensor holding its value
+    ops: List[FusedOp] = []
+    for ms in groups:
+        first, last = nodes[ms[0]], nodes[ms[-1]]
+        if first.kind == "input":
+            assert len(ms) == 1
+            out_name[ms[0]] = first.name
+            continue
+        inside = set(ms)
+        if first.kind not in KIND_OF:
+            raise ValueError(f"group {[nodes[m].name for m in ms]} does not start with a contraction or a pool")
+        a = first.attrs
+        fields = dict(kind=KIND_OF[first.kind], name=first.name, src=out_name[first.inputs[0]], dst=last.name,
+                      cin=a.get("cin", 0), cout=a.get("cout", 0), r=a.get("r", 1), stride=a.get("stride", 1),
+                      pad=a.get("pad", 0))
+        stage, prev = -1, ms[0]
+        for m in ms[1:]:
+            n = nodes[m]
+            if n.kind not in EPILOGUE_ORDER or EPILOGUE_ORDER.index(n.kind) <= stage or prev not in n.inputs:
+                raise ValueError(f"no fused kernel for operator {n.name} in group {[nodes[k].name for k in ms]}")
+            stage = EPILOGUE_ORDER.index(n.kind)
+            if n.kind == "bias_add":
+                fields["bias"] = True
+            elif n.kind == "scale_shift":
+                fields["bn"] = True
+            elif n.kind == "relu":
+                fields["relu"] = True
+            else:
+                others = [i for i in n.inputs if i != prev]
+                if len(others) != 1 or others[0] in inside:
+                    raise ValueError(f"add {n.name} must take exactly one tensor from outside its group")
+                fields["res"] = out_name[others[0]]
+            prev = m
+        if fields["kind"] in ("maxpool", "avgpool") and len(ms) != 1:
+            raise ValueError("pooling operators are not fused")
+        ops.append(FusedOp(**fields))
+        out_name[ms[-1]] = last.name
+    return ops
+
+
+def fuse(graph) -> List[FusedOp]:
+    return lower(graph, extract_groups(graph))
