@@ -6,7 +6,7 @@ import pytest
 from oracle import fusion as OF
 from paper_1904_08368_amd import binding as B
 from paper_1904_08368_amd import fusion as PF
-from test_fusion_oracle import golden_cases
+from tests.test_fusion_oracle import golden_cases
 from workloads import graphs, nets
 
 
