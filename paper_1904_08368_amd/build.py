@@ -38,7 +38,10 @@ def build(verbose: bool = False) -> str:
             print(f"[build] {src}:\n{out}")
     if failed:
         raise RuntimeError("hipcc failed")
-    subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], check=True)
+    # link beside the target and rename: a process that has the old library mapped keeps a valid file
+    tmp = LIB + ".tmp"
+    subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs], check=True)
+    os.replace(tmp, LIB)
     return LIB
 
 

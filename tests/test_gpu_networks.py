@@ -46,6 +46,50 @@ def test_config2_basic_block_fp16(G):
     assert net.tensor("blk.out").min() >= 0
 
 
+def test_networks_built_by_the_fusion_pass(G):
+    """The operator graph of a network, run through the library's fusion extraction and lowered to
+    fused primitive functions, computes what the oracle computes on the hand-written layer table
+    (fp16 block and int8 ResNet-18), and bit for bit what the table-built network computes."""
+    from paper_1904_08368_amd import fusion
+    from workloads import graphs
+    # config 2 block, fp16
+    ops = fusion.fuse(graphs.single_block(64))
+    table = nets.basic_block(64)
+    params = inputs.net_params(table, 2, "f16")
+    x = inputs.image(2, 1, 64, 56, 56, "f16")
+    ref = run_float(table, params, x, "f16")
+    net = _net(ops, params, 1, 56, "f16", cin=64)
+    net.load_input(x)
+    net.run()
+    torch.cuda.synchronize()
+    assert O.max_rel_err(net.tensor(ops[-1].dst), ref["blk.out"]) <= TOL_F16
+    # whole ResNet-18, fp16, batch 2: same bits as the table-built stack
+    ops = fusion.fuse(graphs.resnet18())
+    table = nets.resnet18()
+    params = inputs.net_params(table, 3, "f16")
+    x = inputs.image(3, 2, 3, 224, 224, "f16")
+    outs = []
+    for o in (ops, table):
+        net = _net(o, params, 2, 224, "f16")
+        net.load_input(x)
+        net.run()
+        torch.cuda.synchronize()
+        outs.append(net.tensor(o[-1].dst))
+    assert np.array_equal(outs[0], outs[1])
+    # int8 ResNet-18 conv stack, batch 1: bit-exact against the oracle
+    ops = fusion.fuse(graphs.resnet18(with_dense=False))
+    table = nets.resnet18(with_dense=False)
+    params = inputs.net_params(table, 4, "i8")
+    shifts = inputs.chain_shifts(table)
+    xq = inputs.image(4, 1, 3, 224, 224, "i8")
+    ref = run_quantized(table, params, shifts, xq)
+    net = _net(ops, params, 1, 224, "i8", shifts=shifts)
+    net.load_input(xq)
+    net.run()
+    torch.cuda.synchronize()
+    assert np.array_equal(net.tensor(ops[-1].dst), ref[table[-1].dst])
+
+
 def _per_layer_float(G, ops, params, ref, batch_note=""):
     """Each conv / dwconv / dense of a float net on the oracle's input for that layer."""
     from paper_1904_08368_amd import binding as B
