@@ -113,6 +113,44 @@ relay_status relay_qconv2d_requant(const relay_conv2d_desc* d, const int8_t* x, 
                                    int32_t out_rshift, int8_t* y, void* workspace, size_t workspace_bytes,
                                    void* hip_stream);
 
+/* Rounding strategies of the quantization flow (paper Section 4.2 names nearest, floor, ceiling
+ * and stochastic rounding as choices of a quantization scheme). */
+typedef enum {
+  RELAY_ROUND_NEAREST = 0,    /* ties toward +infinity: floor(t + 1/2) */
+  RELAY_ROUND_FLOOR = 1,
+  RELAY_ROUND_CEIL = 2,
+  RELAY_ROUND_STOCHASTIC = 3  /* up with probability frac(t) */
+} relay_round_mode;
+
+/* relay_qconv2d_requant with a rounding strategy for acc / 2^out_rshift:
+ *   nearest: (acc + 2^(s-1)) >> s;  floor: acc >> s;  ceiling: (acc + 2^s - 1) >> s;
+ *   stochastic: (acc + u) >> s with u = the low s bits of the element's random word.
+ * Random words come from Philox-4x32-10 (Salmon et al., SC'11), a counter-based generator:
+ * output element e = ((n*ho + p)*wo + q)*k + channel (its NHWC position) takes word e mod 4 of
+ * the block with counter (e div 4 low word, high word, 0, 0) and key (seed low word, seed high
+ * word), so a result depends on (seed, position) only, not on the launch shape.
+ * Precondition: |acc| + 2^out_rshift < 2^31.  Everything else as relay_qconv2d_requant, which
+ * is this call with RELAY_ROUND_NEAREST. */
+relay_status relay_qconv2d_requant_rounding(const relay_conv2d_desc* d, const int8_t* x, const int8_t* w_packed,
+                                            const int32_t* bias, const int8_t* residual, int32_t residual_lshift,
+                                            int32_t out_rshift, int32_t round_mode, uint64_t seed, int8_t* y,
+                                            void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* The quantization operators themselves (paper Section 4.2), elementwise over n_elems values:
+ *   code = clip(round(x / rho * 2^(beta - sigma)), +-(2^(beta-1) - 1))
+ *   relay_quantize       ("Realize", Q):    y_i8  = (int8) code          x: F32 or F16, 2 <= beta <= 8
+ *   relay_sim_quantize   ("Annotate", simQ): y_f32 = code * rho / 2^(beta - sigma)   x: F32, 2 <= beta <= 24
+ * beta = bits of the target type, sigma = bits that carry no magnitude (1 for a signed type),
+ * rho > 0 = the range mapped onto full scale (this library's reading of the three parameters).
+ * The code is decided in fp32 in the order written: IEEE division, exact scaling by the power of
+ * two, then the rounding rule (nearest = floor(t + 0.5f); stochastic = floor(t + w * 2^-24) with
+ * w the top 24 bits of the element's random word, element index = position in x).
+ * x and y 16-byte aligned (relay_quantize: y 8-byte); y must not alias x. */
+relay_status relay_quantize(int64_t n_elems, int32_t src_dtype, const void* x, float rho, int32_t beta,
+                            int32_t sigma, int32_t round_mode, uint64_t seed, int8_t* y, void* hip_stream);
+relay_status relay_sim_quantize(int64_t n_elems, const float* x, float rho, int32_t beta, int32_t sigma,
+                                int32_t round_mode, uint64_t seed, float* y, void* hip_stream);
+
 /* Depthwise conv2d (k == c) -> [+bias] -> [*scale + shift] -> [relu] -> cast.  F16 NHWC,
  * c % 8 == 0, fp32 accumulation.  w_rsc: filters repacked [r][s][c] by
  * relay_prepack_dwconv_weights from [c][r][s]. */

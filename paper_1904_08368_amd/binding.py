@@ -55,6 +55,9 @@ SIGNATURES = {
     "relay_nhwc4_padded_shape": [_DP, C.POINTER(_I), C.POINTER(_I)],
     "relay_pack_input_nhwc4": [_DP, _P, _P, _P],
     "relay_fuse_extract": [_I, _P, _P, _P, _P, _P],
+    "relay_qconv2d_requant_rounding": [_DP, _P, _P, _P, _P, _I, _I, _I, C.c_uint64, _P, _P, _SZ, _P],
+    "relay_quantize": [C.c_int64, _I, _P, C.c_float, _I, _I, _I, C.c_uint64, _P, _P],
+    "relay_sim_quantize": [C.c_int64, _P, C.c_float, _I, _I, _I, C.c_uint64, _P, _P],
     "relay_set_conv_tile": [_I],
     "relay_conv2d_kernel_name": [_DP, C.c_char_p, _SZ],
 }
@@ -174,6 +177,25 @@ def relay_nhwc4_padded_shape(d: ConvDesc) -> Tuple[int, int]:
 
 def relay_pack_input_nhwc4(d: ConvDesc, x_nchw, y) -> None:
     _check(lib().relay_pack_input_nhwc4(C.byref(d), _ptr(x_nchw), _ptr(y), _stream()))
+
+
+ROUND_NEAREST, ROUND_FLOOR, ROUND_CEIL, ROUND_STOCHASTIC = 0, 1, 2, 3
+
+
+def relay_qconv2d_requant_rounding(d: ConvDesc, x, w_packed, bias, residual, residual_lshift: int, out_rshift: int,
+                                   round_mode: int, seed: int, y, workspace=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().relay_qconv2d_requant_rounding(C.byref(d), _ptr(x), _ptr(w_packed), _ptr(bias), _ptr(residual),
+                                                residual_lshift, out_rshift, round_mode, seed, _ptr(y), _ptr(workspace),
+                                                ws_bytes, _stream()))
+
+
+def relay_quantize(n_elems: int, src_dtype: int, x, rho: float, beta: int, sigma: int, round_mode: int, seed: int, y) -> None:
+    _check(lib().relay_quantize(n_elems, src_dtype, _ptr(x), rho, beta, sigma, round_mode, seed, _ptr(y), _stream()))
+
+
+def relay_sim_quantize(n_elems: int, x, rho: float, beta: int, sigma: int, round_mode: int, seed: int, y) -> None:
+    _check(lib().relay_sim_quantize(n_elems, _ptr(x), rho, beta, sigma, round_mode, seed, _ptr(y), _stream()))
 
 
 def relay_fuse_extract(pattern: Sequence[int], in_offsets: Sequence[int], in_nodes: Sequence[int]):

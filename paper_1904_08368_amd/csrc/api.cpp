@@ -294,6 +294,14 @@ relay_status relay_qconv2d_requant(const relay_conv2d_desc* d, const int8_t* x, 
                                    const int32_t* bias, const int8_t* residual, int32_t residual_lshift,
                                    int32_t out_rshift, int8_t* y, void* workspace, size_t workspace_bytes,
                                    void* hip_stream) {
+  return relay_qconv2d_requant_rounding(d, x, w_packed, bias, residual, residual_lshift, out_rshift,
+                                        RELAY_ROUND_NEAREST, 0, y, workspace, workspace_bytes, hip_stream);
+}
+
+relay_status relay_qconv2d_requant_rounding(const relay_conv2d_desc* d, const int8_t* x, const int8_t* w_packed,
+                                            const int32_t* bias, const int8_t* residual, int32_t residual_lshift,
+                                            int32_t out_rshift, int32_t round_mode, uint64_t seed, int8_t* y,
+                                            void* workspace, size_t workspace_bytes, void* hip_stream) {
   (void)workspace;
   (void)workspace_bytes;
   int ho, wo;
@@ -307,6 +315,8 @@ relay_status relay_qconv2d_requant(const relay_conv2d_desc* d, const int8_t* x, 
   if (out_rshift < 0 || out_rshift > 31) return fail(RELAY_ERR_UNSUPPORTED, "out_rshift=%d outside 0..31", out_rshift);
   if (residual_lshift < 0 || residual_lshift > 23)
     return fail(RELAY_ERR_UNSUPPORTED, "residual_lshift=%d outside 0..23", residual_lshift);
+  if (round_mode < RELAY_ROUND_NEAREST || round_mode > RELAY_ROUND_STOCHASTIC)
+    return fail(RELAY_ERR_UNSUPPORTED, "round_mode=%d is not a relay_round_mode", round_mode);
   if (y == x || y == residual) return fail(RELAY_ERR_UNSUPPORTED, "output must not alias an input");
   if ((st = check_igemm_support(d)) != RELAY_OK) return st;
   if (!aligned(x, 16) || !aligned(w_packed, 16) || !aligned(y, 8) || (residual && !aligned(residual, 8)) ||
@@ -315,6 +325,10 @@ relay_status relay_qconv2d_requant(const relay_conv2d_desc* d, const int8_t* x, 
   relay::ConvArgs a = make_args(d, ho, wo);
   a.x = x; a.w = w_packed; a.y = y; a.res = residual; a.qbias = bias;
   a.lshift = residual_lshift; a.rshift = out_rshift;
+  a.round_mode = round_mode; a.seed_lo = (unsigned)seed; a.seed_hi = (unsigned)(seed >> 32);
+  a.round_add = out_rshift == 0 ? 0
+                : round_mode == RELAY_ROUND_NEAREST ? 1 << (out_rshift - 1)
+                : round_mode == RELAY_ROUND_CEIL ? (int)((1u << out_rshift) - 1u) : 0;
   finish_args(a);
   return device_status(launch_igemm(a, true, static_cast<hipStream_t>(hip_stream)), "qconv2d launch");
 }
@@ -395,6 +409,41 @@ relay_status relay_fused_dense_bias_act(int32_t m, int32_t n, int32_t k, int32_t
   }
   return device_status(relay::launch_dense(m, n, k, dtype == RELAY_F16, x, w, bias, act, y, static_cast<hipStream_t>(hip_stream)),
                        "dense launch");
+}
+
+static relay_status check_quantize(int64_t n, const void* x, const void* y, float rho, int beta, int max_beta, int sigma,
+                                   int round_mode) {
+  if (n <= 0 || n > ((int64_t)1 << 40)) return fail(RELAY_ERR_SHAPE, "n_elems=%lld outside 1..2^40", (long long)n);
+  if (!x || !y) return fail(RELAY_ERR_NULL, "x and y are required");
+  if (!(rho > 0.f) || rho > 3.0e38f) return fail(RELAY_ERR_SHAPE, "rho must be positive and finite");
+  if (beta < 2 || beta > max_beta) return fail(RELAY_ERR_UNSUPPORTED, "beta=%d outside 2..%d", beta, max_beta);
+  if (sigma < 0 || sigma > beta) return fail(RELAY_ERR_UNSUPPORTED, "sigma=%d outside 0..beta", sigma);
+  if (round_mode < RELAY_ROUND_NEAREST || round_mode > RELAY_ROUND_STOCHASTIC)
+    return fail(RELAY_ERR_UNSUPPORTED, "round_mode=%d is not a relay_round_mode", round_mode);
+  if (x == y) return fail(RELAY_ERR_UNSUPPORTED, "output must not alias the input");
+  return RELAY_OK;
+}
+
+relay_status relay_quantize(int64_t n_elems, int32_t src_dtype, const void* x, float rho, int32_t beta, int32_t sigma,
+                            int32_t round_mode, uint64_t seed, int8_t* y, void* hip_stream) {
+  if (src_dtype != RELAY_F32 && src_dtype != RELAY_F16) return fail(RELAY_ERR_DTYPE, "quantize takes F32 or F16 input");
+  relay_status st = check_quantize(n_elems, x, y, rho, beta, 8, sigma, round_mode);
+  if (st != RELAY_OK) return st;
+  if (!aligned(x, 16) || !aligned(y, 8)) return fail(RELAY_ERR_ALIGN, "x must be 16-byte and y 8-byte aligned");
+  return device_status(relay::launch_quantize(src_dtype == RELAY_F16, n_elems, x, rho, beta, sigma, round_mode,
+                                              (unsigned)seed, (unsigned)(seed >> 32), y,
+                                              static_cast<hipStream_t>(hip_stream)),
+                       "quantize launch");
+}
+
+relay_status relay_sim_quantize(int64_t n_elems, const float* x, float rho, int32_t beta, int32_t sigma,
+                                int32_t round_mode, uint64_t seed, float* y, void* hip_stream) {
+  relay_status st = check_quantize(n_elems, x, y, rho, beta, 24, sigma, round_mode);
+  if (st != RELAY_OK) return st;
+  if (!aligned(x, 16) || !aligned(y, 16)) return fail(RELAY_ERR_ALIGN, "x and y must be 16-byte aligned");
+  return device_status(relay::launch_sim_quantize(n_elems, x, rho, beta, sigma, round_mode, (unsigned)seed,
+                                                  (unsigned)(seed >> 32), y, static_cast<hipStream_t>(hip_stream)),
+                       "sim_quantize launch");
 }
 
 relay_status relay_fuse_extract(int32_t n_ops, const int32_t* pattern, const int32_t* in_offsets,

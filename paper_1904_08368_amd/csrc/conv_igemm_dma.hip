@@ -85,7 +85,9 @@ __device__ __forceinline__ void small_divmod(int t, int d, float rcp_d, int& q, 
 // them (their partial sums meet in LDS before the epilogue).  A wave then owns a SK times
 // larger tile for the same workgroup tile, which cuts the LDS operand reads per MFMA -- the
 // resource the small tiles are bound by.
-template <bool IS_I8, int WAVES_M, int WAVES_N, int TM, int TN, int NS, int KP, int SK>
+// STOCH: the stochastic rounding of the quantized epilogue (its generator costs registers, so it is an
+// instantiation of its own; the deterministic rules are one host-computed addend).
+template <bool IS_I8, int WAVES_M, int WAVES_N, int TM, int TN, int NS, int KP, int SK, bool STOCH>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
                              // two workgroups per CU where their LDS rings fit side by side
                              (NS * KP * (WAVES_M * TM + WAVES_N * TN) * 32 * 64 <= 80 * 1024 ? 2 : 1))
@@ -457,10 +459,12 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
           }
         }
         unsigned pk[2] = {0u, 0u};
+        WordStream rng{a.seed_lo, a.seed_hi};
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          int q = t[e];
-          if (a.rshift > 0) q = (q + (1 << (a.rshift - 1))) >> a.rshift;  // arithmetic shift: floor
+          int q;
+          if constexpr (STOCH) q = requant_shift(t[e], a.rshift, ROUND_STOCHASTIC, rng, o + e);
+          else q = (t[e] + a.round_add) >> a.rshift;  // arithmetic shift: floor
           q = q < -127 ? -127 : (q > 127 ? 127 : q);
           if (a.flags & F_RELU) q = q > 0 ? q : 0;
           t[e] = q;
@@ -507,33 +511,33 @@ constexpr DmaTile kTiles[] = {
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
-template <bool IS_I8, int WAVES_M, int WAVES_N, int TM, int TN, int NS, int KP, int SK = 1>
+template <bool IS_I8, bool STOCH, int WAVES_M, int WAVES_N, int TM, int TN, int NS, int KP, int SK = 1>
 hipError_t launch_one(const ConvArgs& a, hipStream_t st) {
   constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
   const int tiles = ((a.M + BM - 1) / BM) * ((a.K + BN - 1) / BN);
-  hipLaunchKernelGGL((igemm_dma_kernel<IS_I8, WAVES_M, WAVES_N, TM, TN, NS, KP, SK>), dim3(tiles),
+  hipLaunchKernelGGL((igemm_dma_kernel<IS_I8, WAVES_M, WAVES_N, TM, TN, NS, KP, SK, STOCH>), dim3(tiles),
                      dim3(64 * WAVES_M * WAVES_N * SK), 0, st, a);
   return hipGetLastError();
 }
 
-template <bool IS_I8>
+template <bool IS_I8, bool STOCH>
 hipError_t launch_typed(const ConvArgs& a, int tile, hipStream_t st) {
   switch (tile) {
-    case 0: return launch_one<IS_I8, 2, 2, 4, 2, 3, 1>(a, st);
-    case 1: return launch_one<IS_I8, 4, 1, 4, 2, 3, 1>(a, st);
-    case 2: return launch_one<IS_I8, 2, 1, 4, 2, 3, 1>(a, st);
-    case 3: return launch_one<IS_I8, 2, 2, 2, 2, 3, 1>(a, st);
-    case 4: return launch_one<IS_I8, 2, 2, 2, 1, 4, 1>(a, st);
-    case 5: return launch_one<IS_I8, 2, 2, 1, 1, 4, 1>(a, st);
-    case 6: return launch_one<IS_I8, 2, 2, 4, 2, 3, 2>(a, st);
-    case 7: return launch_one<IS_I8, 2, 2, 4, 2, 2, 2>(a, st);
-    case 8: return launch_one<IS_I8, 2, 2, 2, 2, 3, 2>(a, st);
-    case 9: return launch_one<IS_I8, 2, 2, 2, 1, 3, 2>(a, st);
-    case 10: return launch_one<IS_I8, 2, 2, 1, 1, 3, 2>(a, st);
-    case 11: return launch_one<IS_I8, 2, 1, 4, 2, 3, 2>(a, st);
-    case 12: return launch_one<IS_I8, 2, 1, 2, 2, 3, 2, 2>(a, st);
-    case 13: return launch_one<IS_I8, 1, 1, 2, 2, 3, 2, 2>(a, st);
-    default: return launch_one<IS_I8, 4, 1, 2, 2, 3, 1, 1>(a, st);
+    case 0: return launch_one<IS_I8, STOCH, 2, 2, 4, 2, 3, 1>(a, st);
+    case 1: return launch_one<IS_I8, STOCH, 4, 1, 4, 2, 3, 1>(a, st);
+    case 2: return launch_one<IS_I8, STOCH, 2, 1, 4, 2, 3, 1>(a, st);
+    case 3: return launch_one<IS_I8, STOCH, 2, 2, 2, 2, 3, 1>(a, st);
+    case 4: return launch_one<IS_I8, STOCH, 2, 2, 2, 1, 4, 1>(a, st);
+    case 5: return launch_one<IS_I8, STOCH, 2, 2, 1, 1, 4, 1>(a, st);
+    case 6: return launch_one<IS_I8, STOCH, 2, 2, 4, 2, 3, 2>(a, st);
+    case 7: return launch_one<IS_I8, STOCH, 2, 2, 4, 2, 2, 2>(a, st);
+    case 8: return launch_one<IS_I8, STOCH, 2, 2, 2, 2, 3, 2>(a, st);
+    case 9: return launch_one<IS_I8, STOCH, 2, 2, 2, 1, 3, 2>(a, st);
+    case 10: return launch_one<IS_I8, STOCH, 2, 2, 1, 1, 3, 2>(a, st);
+    case 11: return launch_one<IS_I8, STOCH, 2, 1, 4, 2, 3, 2>(a, st);
+    case 12: return launch_one<IS_I8, STOCH, 2, 1, 2, 2, 3, 2, 2>(a, st);
+    case 13: return launch_one<IS_I8, STOCH, 1, 1, 2, 2, 3, 2, 2>(a, st);
+    default: return launch_one<IS_I8, STOCH, 4, 1, 2, 2, 3, 1, 1>(a, st);
   }
 }
 
@@ -578,13 +582,14 @@ int igemm_dma_tile_count() { return kNumTiles; }
 
 void igemm_dma_kernel_name(const ConvArgs& a, bool is_i8, int tile, char* buf, size_t len) {
   const DmaTile& t = kTiles[resolve_tile(a, is_i8, tile)];
-  snprintf(buf, len, "igemm_dma_kernel<%s, %d, %d, %d, %d, %d, %d, %d>", is_i8 ? "true" : "false", t.waves_m,
-           t.waves_n, t.tm, t.tn, t.ns, t.kp, t.sk);
+  snprintf(buf, len, "igemm_dma_kernel<%s, %d, %d, %d, %d, %d, %d, %d, %s>", is_i8 ? "true" : "false", t.waves_m,
+           t.waves_n, t.tm, t.tn, t.ns, t.kp, t.sk, is_i8 && a.round_mode == ROUND_STOCHASTIC ? "true" : "false");
 }
 
 hipError_t launch_conv_igemm_dma(const ConvArgs& a, bool is_i8, int tile, hipStream_t st) {
   tile = resolve_tile(a, is_i8, tile);
-  return is_i8 ? launch_typed<true>(a, tile, st) : launch_typed<false>(a, tile, st);
+  if (!is_i8) return launch_typed<false, false>(a, tile, st);
+  return a.round_mode == ROUND_STOCHASTIC ? launch_typed<true, true>(a, tile, st) : launch_typed<true, false>(a, tile, st);
 }
 
 }  // namespace relay

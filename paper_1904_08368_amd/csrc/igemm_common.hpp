@@ -2,6 +2,7 @@
 // the fused epilogues (float: paper Section 4.1; quantized: Section 4.2, "Realize").
 #pragma once
 #include "kernels.hpp"
+#include "rounding.hpp"
 
 namespace relay {
 
@@ -118,10 +119,11 @@ __device__ __forceinline__ void epilogue_store4(const ConvArgs& a, const S (&v)[
       }
     }
     int q[4];
+    WordStream rng{a.seed_lo, a.seed_hi};
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       int t = v[e] + p.ibias[e] + rs[e] * (1 << a.lshift);
-      if (a.rshift > 0) t = (t + (1 << (a.rshift - 1))) >> a.rshift;  // arithmetic shift: floor
+      t = requant_shift(t, a.rshift, a.round_mode, rng, o + e);
       t = t < -127 ? -127 : (t > 127 ? 127 : t);
       if (a.flags & F_RELU) t = t > 0 ? t : 0;
       q[e] = t;

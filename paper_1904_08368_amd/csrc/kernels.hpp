@@ -8,6 +8,7 @@
 namespace relay {
 
 enum : unsigned { F_BIAS = 1, F_BN = 2, F_RES = 4, F_RELU = 8 };
+enum : int { ROUND_NEAREST = 0, ROUND_FLOOR = 1, ROUND_CEIL = 2, ROUND_STOCHASTIC = 3 };
 
 // Geometry and operands of one conv-like primitive function.
 struct ConvArgs {
@@ -33,6 +34,9 @@ struct ConvArgs {
   int Kred;     // R*S*C    (reduction length)
   int Kp;       // row pitch of the packed filters, elements
   int lshift, rshift;
+  int round_mode;          // ROUND_* rule of the requantization acc / 2^rshift
+  int round_add;           // what the deterministic rules add before the shift (0 when rshift == 0)
+  unsigned seed_lo, seed_hi;  // key of the stochastic rounding draws
   unsigned flags;
 };
 
@@ -69,6 +73,11 @@ hipError_t launch_nchw_to_nhwc(int esize, int N, int C, int H, int W, int Cpad, 
 hipError_t launch_pack_input_nhwc4(int esize, int N, int C, int H, int W, int ph, int pw, int Wp, const void* x,
                                    void* y, hipStream_t st);
 // OIHW [K][Csrc<=4][R][S] -> [K][Kp] with reduction index r*ck + s*4 + c, zero elsewhere
+// Q and simQ of the quantization flow (paper Section 4.2) on n elements; src_f16: x is fp16, else fp32
+hipError_t launch_quantize(bool src_f16, long n, const void* x, float rho, int beta, int sigma, int mode,
+                           unsigned seed_lo, unsigned seed_hi, int8_t* y, hipStream_t st);
+hipError_t launch_sim_quantize(long n, const float* x, float rho, int beta, int sigma, int mode, unsigned seed_lo,
+                               unsigned seed_hi, float* y, hipStream_t st);
 hipError_t launch_pack_filters_rows(const void* w_oihw, void* w_packed, int K, int Csrc, int R, int S, int ck,
                                     int Kp, int esize, hipStream_t st);
 

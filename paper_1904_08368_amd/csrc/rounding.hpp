@@ -1,0 +1,59 @@
+// Rounding strategies of the quantization flow (paper Section 4.2: nearest, floor, ceiling,
+// stochastic) and the counter-based generator behind the stochastic one.
+#pragma once
+#include "kernels.hpp"
+
+namespace relay {
+
+// Philox-4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): ten rounds of two 32x32->64 multiplies
+// and a key schedule of two Weyl sequences.
+__device__ __forceinline__ void philox4x32_10(unsigned c0, unsigned c1, unsigned c2, unsigned c3, unsigned k0,
+                                              unsigned k1, unsigned (&out)[4]) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const unsigned hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+    const unsigned hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+    const unsigned n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+    c0 = n0;
+    c1 = lo1;
+    c2 = n2;
+    c3 = lo0;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  out[0] = c0;
+  out[1] = c1;
+  out[2] = c2;
+  out[3] = c3;
+}
+
+// The random word of tensor element `index`: word index%4 of the block with counter
+// (index/4, 0, 0, 0).  `cache` holds the last block computed, so that the consecutive elements a
+// lane finishes cost one block per four.
+struct WordStream {
+  unsigned k0, k1;
+  unsigned long long block = ~0ull;
+  unsigned w[4];
+  __device__ __forceinline__ unsigned word(unsigned long long index) {
+    const unsigned long long b = index >> 2;
+    if (b != block) {
+      block = b;
+      philox4x32_10((unsigned)b, (unsigned)(b >> 32), 0u, 0u, k0, k1, w);
+    }
+    const unsigned j = (unsigned)index & 3u;
+    return j == 0 ? w[0] : j == 1 ? w[1] : j == 2 ? w[2] : w[3];
+  }
+};
+
+// acc / 2^s rounded by `mode` (arithmetic shift = floor division): what is added before the shift.
+__device__ __forceinline__ int requant_shift(int acc, int s, int mode, WordStream& rng, unsigned long long index) {
+  if (s == 0) return acc;
+  int addend;
+  if (mode == ROUND_NEAREST) addend = 1 << (s - 1);  // ties toward +infinity
+  else if (mode == ROUND_FLOOR) addend = 0;
+  else if (mode == ROUND_CEIL) addend = (int)((1u << s) - 1u);
+  else addend = (int)(rng.word(index) & ((1u << s) - 1u));  // up with probability frac(acc / 2^s)
+  return (acc + addend) >> s;
+}
+
+}  // namespace relay

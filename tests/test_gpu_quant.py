@@ -1,0 +1,114 @@
+"""GPU parity of the quantization variants (paper Section 4.2): rounding strategies of the fused
+requantization and the Q / simQ operators, bit for bit against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+from oracle import quant as OQ
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def G():
+    from paper_1904_08368_amd import binding as B
+    B.lib()
+    assert torch.cuda.is_available()
+    from tests import gpu_util
+    return gpu_util
+
+
+def _qconv_mode(G, x, w, stride, pad, *, bias=None, residual=None, lshift=0, rshift=0, relu=False, mode=0, seed=0):
+    from paper_1904_08368_amd import binding as B
+    n, c, h, ww = x.shape
+    k, _, r, s = w.shape
+    flags = B.flags_of(bias, None, residual, relu)
+    d, xd = G._input(x, k, r, s, stride, pad, B.RELAY_I8, 16, flags, False)
+    ho, wo = B.relay_conv2d_out_shape(d)
+    wp = torch.empty(B.relay_packed_weight_bytes(d), dtype=torch.uint8, device=G.DEV)
+    B.relay_prepack_conv2d_weights(d, G.up(w), c, wp)
+    y = torch.full((n, ho, wo, k), -128, dtype=torch.int8, device=G.DEV)
+    res = G.to_nhwc(residual, k, B.RELAY_I8) if residual is not None else None
+    B.relay_qconv2d_requant_rounding(d, xd, wp, G.up(bias) if bias is not None else None, res, lshift, rshift, mode, seed, y)
+    torch.cuda.synchronize()
+    return G.from_nhwc(y, k)
+
+
+@pytest.mark.parametrize("mode", [OQ.NEAREST, OQ.FLOOR, OQ.CEIL, OQ.STOCHASTIC])
+@pytest.mark.parametrize("shape", [(2, 64, 13, 17, 192), (1, 48, 9, 11, 37), (2, 128, 7, 7, 64)])
+def test_qconv_rounding_modes_bit_exact(G, mode, shape):
+    n, c, h, w, k = shape
+    rng = np.random.default_rng(700 + c + mode)
+    x = rng.integers(-127, 128, (n, c, h, w)).astype(np.int8)
+    wt = rng.integers(-127, 128, (k, c, 3, 3)).astype(np.int8)
+    res = rng.integers(-127, 128, (n, k, h, w)).astype(np.int8)
+    b = rng.integers(-5000, 5000, k).astype(np.int32)
+    for seed, s in ((0x1234_5678_9ABC_DEF0, 13), (7, 1), (99, 0)):
+        ref = OQ.qconv2d_requant_mode(x, wt, stride=(1, 1), pad=(1, 1), bias=b, residual=res, residual_lshift=s,
+                                      out_rshift=s, relu_flag=False, mode=mode, seed=seed)
+        got = _qconv_mode(G, x, wt, 1, 1, bias=b, residual=res, lshift=s, rshift=s, mode=mode, seed=seed)
+        assert np.array_equal(got, ref), (mode, s)
+    # nearest through the new entry point is the old entry point
+    if mode == OQ.NEAREST:
+        assert np.array_equal(_qconv_mode(G, x, wt, 1, 1, rshift=12, relu=True), G.run_qconv(x, wt, 1, 1, rshift=12, relu=True))
+
+
+def test_qconv_stochastic_depends_on_seed_and_position_only(G):
+    """The same layer with a different tile shape, and as two half-batches, draws the same words."""
+    from paper_1904_08368_amd import binding as B
+    rng = np.random.default_rng(720)
+    x = rng.integers(-127, 128, (2, 64, 12, 12)).astype(np.int8)
+    wt = rng.integers(-127, 128, (64, 64, 3, 3)).astype(np.int8)
+    ref = OQ.qconv2d_requant_mode(x, wt, stride=(1, 1), pad=(1, 1), out_rshift=14, mode=OQ.STOCHASTIC, seed=5)
+    for tile in (4, 5, 0):
+        B.relay_set_conv_tile(tile)
+        try:
+            got = _qconv_mode(G, x, wt, 1, 1, rshift=14, mode=OQ.STOCHASTIC, seed=5)
+        finally:
+            B.relay_set_conv_tile(-1)
+        assert np.array_equal(got, ref), tile
+    assert not np.array_equal(_qconv_mode(G, x, wt, 1, 1, rshift=14, mode=OQ.STOCHASTIC, seed=6), ref)
+
+
+@pytest.mark.parametrize("mode", [OQ.NEAREST, OQ.FLOOR, OQ.CEIL, OQ.STOCHASTIC])
+@pytest.mark.parametrize("src", ["f32", "f16"])
+def test_quantize_and_sim_quantize_bit_exact(G, mode, src):
+    from paper_1904_08368_amd import binding as B
+    rng = np.random.default_rng(740 + mode)
+    n = 2048 * 3 + 5                                     # whole blocks and a ragged tail
+    x = (rng.standard_normal(n) * 3).astype(np.float32)
+    x[:8] = [0.0, -0.0, 2.5 / 64, -2.5 / 64, 1e9, -1e9, 0.5 / 64, -0.5 / 64]   # ties and far out of range
+    if src == "f16":
+        x[4:6] = [60000, -60000]
+        x = x.astype(np.float16)
+    xd = G.up(x)
+    for rho, beta, sigma in ((2.0, 8, 1), (6.5, 8, 1), (0.75, 4, 1), (16.0, 8, 0)):
+        y = torch.full((n,), -128, dtype=torch.int8, device=G.DEV)
+        B.relay_quantize(n, B.RELAY_F16 if src == "f16" else B.RELAY_F32, xd, rho, beta, sigma, mode, 42, y)
+        torch.cuda.synchronize()
+        ref = OQ.Q(x, rho, beta, sigma, mode, 42)
+        assert np.array_equal(y.cpu().numpy(), ref), (rho, beta)
+        if src == "f32":
+            ys = torch.full((n,), float("nan"), dtype=torch.float32, device=G.DEV)
+            B.relay_sim_quantize(n, xd, rho, beta, sigma, mode, 42, ys)
+            torch.cuda.synchronize()
+            refs = OQ.simQ(x, beta, sigma, rho, mode, 42)
+            assert np.array_equal(ys.cpu().numpy().view(np.uint32), refs.view(np.uint32)), (rho, beta)
+
+
+def test_quantized_input_feeds_the_int8_stack(G):
+    """Q as the first operator of a realized network: fp16 image -> int8 codes -> int8 conv, the
+    whole chain bit-exact against the oracle chain."""
+    from paper_1904_08368_amd import binding as B
+    rng = np.random.default_rng(760)
+    img = (rng.standard_normal((2, 16, 10, 10))).astype(np.float16)
+    wt = rng.integers(-127, 128, (32, 16, 3, 3)).astype(np.int8)
+    codes_ref = OQ.Q(img, 4.0, 8, 1)
+    ref = O.qconv2d_requant(codes_ref, wt, stride=(1, 1), pad=(1, 1), out_rshift=9, relu_flag=True)
+    xq = torch.empty(img.size, dtype=torch.int8, device=G.DEV)
+    B.relay_quantize(img.size, B.RELAY_F16, G.up(img), 4.0, 8, 1, B.ROUND_NEAREST, 0, xq)
+    torch.cuda.synchronize()
+    codes = xq.cpu().numpy().reshape(img.shape)
+    assert np.array_equal(codes, codes_ref)
+    assert np.array_equal(G.run_qconv(codes, wt, 1, 1, rshift=9, relu=True), ref)
