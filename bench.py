@@ -207,6 +207,17 @@ def main() -> int:
              "layers": [{k: (round(v, 3) if isinstance(v, float) else v) for k, v in r.items()} for r in rows]}
 
     if not a.no_extra:
+        # ---- the same stack with operator fusion switched off (the paper's fusion ablation, Section 5.2):
+        #      contraction, bias add, scale/shift, residual add and relu as separate launches and tensors
+        un = FusedNet(ops, params, a.batch, 224, 224, "f16", fused=False)
+        un.load_input(inputs.image(3, a.batch, 3, 224, 224, "f16"))
+        if use_graph:
+            un.capture()
+        usec = _time_steps(un, max(10, a.steps // 2), a.warmup, use_graph)
+        extra["fusion_ablation"] = {"unfused_ms_per_step": round(usec * 1e3, 4), "fused_ms_per_step": round(sec * 1e3, 4),
+                                    "launches_unfused": len(un.calls), "launches_fused": len(net.calls),
+                                    "speedup_from_fusion": round(usec / sec, 3)}
+        del un
         # ---- batch 1 latency of the same stack
         n1 = FusedNet(ops, params, 1, 224, 224, "f16")
         n1.load_input(inputs.image(3, 1, 3, 224, 224, "f16"))

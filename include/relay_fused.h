@@ -173,6 +173,20 @@ relay_status relay_maxpool2d(int32_t dtype, int32_t n, int32_t c, int32_t h, int
                              int32_t stride, int32_t pad, const void* x, void* y, void* hip_stream);
 relay_status relay_global_avgpool(int32_t dtype, int32_t n, int32_t c, int32_t hw, const void* x, void* y,
                                   void* hip_stream);
+
+/* One UNFUSED elementwise operator on an fp16 NHWC tensor [n_pixels, c] (c % 8 == 0): what runs
+ * behind a convolution when operator fusion is switched off.  The paper measures fusion against
+ * such a pipeline (Section 5.2); this entry point exists for that comparison and for checking
+ * that the fused operators equal the unfused sequence.  Reads x, writes y (fp16, round to
+ * nearest even); y may alias x.
+ *   RELAY_EW_BIAS_ADD     y = x + p0[channel]
+ *   RELAY_EW_SCALE_SHIFT  y = x * p0[channel] + p1[channel]
+ *   RELAY_EW_ADD          y = x + other            (other: fp16, same shape)
+ *   RELAY_EW_RELU         y = max(x, 0)
+ * Operands an operator does not use must be NULL.  Tensors 16-byte aligned. */
+typedef enum { RELAY_EW_BIAS_ADD = 0, RELAY_EW_SCALE_SHIFT = 1, RELAY_EW_ADD = 2, RELAY_EW_RELU = 3 } relay_elementwise_op;
+relay_status relay_elementwise_f16(int32_t op, int64_t n_pixels, int32_t c, const void* x, const float* p0,
+                                   const float* p1, const void* other, void* y, void* hip_stream);
 /* [n,c,h,w] -> [n,h,w,c_pad], channels c..c_pad-1 zero.  Any dtype; c_pad >= c. */
 relay_status relay_nchw_to_nhwc(int32_t dtype, int32_t n, int32_t c, int32_t h, int32_t w, int32_t c_pad,
                                 const void* x, void* y, void* hip_stream);

@@ -56,3 +56,37 @@ def run_quantized(ops, params: List[dict], shifts: List[dict], x: np.ndarray) ->
         else:
             raise ValueError(op.kind)
     return t
+
+
+def run_float_unfused(ops, params: List[dict], x: np.ndarray) -> Dict[str, np.ndarray]:
+    """The same network with operator fusion switched off: every elementwise operator behind a
+    contraction is an operator call of its own whose result is stored in fp16 before the next one
+    reads it (paper Section 5.2 compares fusion against such a pipeline)."""
+    import oracle as O
+    h = O.cast_f16
+    t: Dict[str, np.ndarray] = {"x": x}
+    for op, p in zip(ops, params):
+        src = t[op.src]
+        if op.kind in ("conv", "dwconv", "dense"):
+            if op.kind == "conv":
+                y = h(O.conv2d(src, p["w"], (op.stride, op.stride), (op.pad, op.pad)))
+            elif op.kind == "dwconv":
+                y = h(O.dwconv2d(src, p["w"], (op.stride, op.stride), (op.pad, op.pad)))
+            else:
+                y = h(O.dense(src.reshape(src.shape[0], -1), p["w"]))
+            if p.get("bias") is not None:
+                y = h(O.bias_add(y.astype(np.float64), p["bias"]))
+            if p.get("scale") is not None:
+                y = h(O.scale_shift(y.astype(np.float64), p["scale"], p["shift"]))
+            if op.res:
+                y = h(O.add(y.astype(np.float64), t[op.res]))
+            if op.relu:
+                y = h(O.relu(y.astype(np.float64)))
+            t[op.dst] = y
+        elif op.kind == "maxpool":
+            t[op.dst] = _narrow(maxpool2d(src, op.r, op.stride, op.pad), "f16")
+        elif op.kind == "avgpool":
+            t[op.dst] = _narrow(global_avgpool(src), "f16")
+        else:
+            raise ValueError(op.kind)
+    return t

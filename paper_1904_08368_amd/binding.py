@@ -54,6 +54,7 @@ SIGNATURES = {
     "relay_nchw_to_nhwc": [_I, _I, _I, _I, _I, _I, _P, _P, _P],
     "relay_nhwc4_padded_shape": [_DP, C.POINTER(_I), C.POINTER(_I)],
     "relay_pack_input_nhwc4": [_DP, _P, _P, _P],
+    "relay_elementwise_f16": [_I, C.c_int64, _I, _P, _P, _P, _P, _P, _P],
     "relay_fuse_extract": [_I, _P, _P, _P, _P, _P],
     "relay_qconv2d_requant_rounding": [_DP, _P, _P, _P, _P, _I, _I, _I, C.c_uint64, _P, _P, _SZ, _P],
     "relay_quantize": [C.c_int64, _I, _P, C.c_float, _I, _I, _I, C.c_uint64, _P, _P],
@@ -180,6 +181,12 @@ def relay_pack_input_nhwc4(d: ConvDesc, x_nchw, y) -> None:
 
 
 ROUND_NEAREST, ROUND_FLOOR, ROUND_CEIL, ROUND_STOCHASTIC = 0, 1, 2, 3
+EW_BIAS_ADD, EW_SCALE_SHIFT, EW_ADD, EW_RELU = 0, 1, 2, 3
+
+
+def relay_elementwise_f16(op: int, n_pixels: int, c: int, x, p0, p1, other, y) -> None:
+    _check(lib().relay_elementwise_f16(op, n_pixels, c, _ptr(x), _ptr(p0), _ptr(p1), _ptr(other), _ptr(y), _stream()))
+
 
 
 def relay_qconv2d_requant_rounding(d: ConvDesc, x, w_packed, bias, residual, residual_lshift: int, out_rshift: int,

@@ -411,6 +411,23 @@ relay_status relay_fused_dense_bias_act(int32_t m, int32_t n, int32_t k, int32_t
                        "dense launch");
 }
 
+relay_status relay_elementwise_f16(int32_t op, int64_t n_pixels, int32_t c, const void* x, const float* p0,
+                                   const float* p1, const void* other, void* y, void* hip_stream) {
+  if (op < RELAY_EW_BIAS_ADD || op > RELAY_EW_RELU) return fail(RELAY_ERR_UNSUPPORTED, "op=%d is not a relay_elementwise_op", op);
+  if (n_pixels <= 0 || c <= 0 || n_pixels * c > kMaxElems) return fail(RELAY_ERR_SHAPE, "bad extent (n_pixels=%lld c=%d)", (long long)n_pixels, c);
+  if (c % 8) return fail(RELAY_ERR_ALIGN, "c=%d must be a multiple of 8", c);
+  if (!x || !y) return fail(RELAY_ERR_NULL, "x and y are required");
+  const bool need_p0 = op == RELAY_EW_BIAS_ADD || op == RELAY_EW_SCALE_SHIFT, need_p1 = op == RELAY_EW_SCALE_SHIFT,
+             need_other = op == RELAY_EW_ADD;
+  if ((p0 != nullptr) != need_p0 || (p1 != nullptr) != need_p1 || (other != nullptr) != need_other)
+    return fail(RELAY_ERR_NULL, "operands of op %d: p0 %s, p1 %s, other %s", op, need_p0 ? "required" : "must be NULL",
+                need_p1 ? "required" : "must be NULL", need_other ? "required" : "must be NULL");
+  if (!aligned(x, 16) || !aligned(y, 16) || (other && !aligned(other, 16)))
+    return fail(RELAY_ERR_ALIGN, "fp16 tensors must be 16-byte aligned");
+  return device_status(relay::launch_elementwise_f16(op, n_pixels, c, x, p0, p1, other, y, static_cast<hipStream_t>(hip_stream)),
+                       "elementwise launch");
+}
+
 static relay_status check_quantize(int64_t n, const void* x, const void* y, float rho, int beta, int max_beta, int sigma,
                                    int round_mode) {
   if (n <= 0 || n > ((int64_t)1 << 40)) return fail(RELAY_ERR_SHAPE, "n_elems=%lld outside 1..2^40", (long long)n);

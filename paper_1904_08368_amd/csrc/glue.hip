@@ -186,6 +186,56 @@ hipError_t launch_pack_dw_filters(const void* w, void* out, int C, int RS, hipSt
   return hipGetLastError();
 }
 
+namespace {
+typedef _Float16 half8v __attribute__((ext_vector_type(8)));
+
+// One unfused elementwise operator over an fp16 NHWC tensor: what a framework without operator
+// fusion launches behind a convolution (paper Section 5.2 measures fusion against exactly this).
+// Every operator reads its input tensor and writes a new one, rounded to fp16.
+//   OP 0 bias add: x + p0[c];  1 scale/shift: x*p0[c] + p1[c];  2 add: x + other;  3 relu
+template <int OP>
+__global__ __launch_bounds__(256) void elementwise_f16_kernel(long nvec, int cvecs, const half8v* x, const float* p0,
+                                                              const float* p1, const half8v* other, half8v* y) {
+  const long i = (long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= nvec) return;
+  const int c = (int)(i % cvecs) * 8;
+  const half8v v = x[i];
+  half8v o;
+  if constexpr (OP == 2) {
+    const half8v r = other[i];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = (_Float16)((float)v[e] + (float)r[e]);
+  } else {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float t = (float)v[e];
+      float u;
+      if constexpr (OP == 0) u = t + p0[c + e];
+      else if constexpr (OP == 1) u = t * p0[c + e] + p1[c + e];
+      else u = t > 0.f ? t : 0.f;
+      o[e] = (_Float16)u;
+    }
+  }
+  y[i] = o;
+}
+}  // namespace
+
+hipError_t launch_elementwise_f16(int op, long npix, int c, const void* x, const float* p0, const float* p1,
+                                  const void* other, void* y, hipStream_t st) {
+  const long nvec = npix * (c / 8);
+  const dim3 grid((unsigned)((nvec + 255) / 256)), block(256);
+  const half8v* xv = static_cast<const half8v*>(x);
+  const half8v* ov = static_cast<const half8v*>(other);
+  half8v* yv = static_cast<half8v*>(y);
+  switch (op) {
+    case 0: hipLaunchKernelGGL((elementwise_f16_kernel<0>), grid, block, 0, st, nvec, c / 8, xv, p0, p1, ov, yv); break;
+    case 1: hipLaunchKernelGGL((elementwise_f16_kernel<1>), grid, block, 0, st, nvec, c / 8, xv, p0, p1, ov, yv); break;
+    case 2: hipLaunchKernelGGL((elementwise_f16_kernel<2>), grid, block, 0, st, nvec, c / 8, xv, p0, p1, ov, yv); break;
+    default: hipLaunchKernelGGL((elementwise_f16_kernel<3>), grid, block, 0, st, nvec, c / 8, xv, p0, p1, ov, yv); break;
+  }
+  return hipGetLastError();
+}
+
 hipError_t launch_maxpool(bool is_i8, int N, int C, int H, int W, int R, int stride, int pad, int Ho, int Wo,
                           const void* x, void* y, hipStream_t st) {
   if (is_i8) {

@@ -66,6 +66,9 @@ hipError_t launch_pack_filters(const void* w_oihw, void* w_packed, int K, int Cs
 hipError_t launch_pack_dw_filters(const void* w_crs, void* w_rsc, int C, int RS, hipStream_t st);
 hipError_t launch_maxpool(bool is_i8, int N, int C, int H, int W, int R, int stride, int pad, int Ho, int Wo,
                           const void* x, void* y, hipStream_t st);
+// one unfused elementwise operator on an fp16 NHWC tensor of npix pixels x c channels (c % 8 == 0)
+hipError_t launch_elementwise_f16(int op, long npix, int c, const void* x, const float* p0, const float* p1,
+                                  const void* other, void* y, hipStream_t st);
 hipError_t launch_avgpool_f16(int N, int C, int HW, const void* x, void* y, hipStream_t st);
 hipError_t launch_nchw_to_nhwc(int esize, int N, int C, int H, int W, int Cpad, const void* x, void* y,
                                hipStream_t st);

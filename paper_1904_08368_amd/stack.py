@@ -26,8 +26,13 @@ class FusedNet:
 
     def __init__(self, ops, params: List[dict], batch: int, h: int, w: int, mode: str = "f16",
                  shifts: Optional[List[dict]] = None, in_channels: int = 3, device: str = "cuda:0",
-                 overlap_shortcuts: bool = True):
+                 overlap_shortcuts: bool = True, fused: bool = True):
         assert mode in ("f16", "i8")
+        assert fused or mode == "f16"
+        # fused=False launches every elementwise operator behind a contraction as a kernel of its
+        # own on a tensor of its own: the pipeline of a framework without operator fusion, kept
+        # for the fusion ablation (paper Section 5.2)
+        self.fused = fused
         self.ops, self.mode, self.batch = ops, mode, batch
         self.dev = torch.device(device)
         self.dtype = B.RELAY_F16 if mode == "f16" else B.RELAY_I8
@@ -76,7 +81,13 @@ class FusedNet:
                 B.relay_prepack_conv2d_weights(d, wsrc, cin_l, wp)
                 y = torch.empty((batch, ho, wo, op.cout), dtype=self.tdtype, device=self.dev)
                 res = self.bufs[op.res] if op.res else None
-                if mode == "f16":
+                if mode == "f16" and not fused and flags:
+                    d0 = B.conv_desc(d.n, d.c, d.h, d.w, d.k, d.r, d.s, d.stride_h, d.pad_h, self.dtype, d.layout, 0)
+                    raw = torch.empty_like(y)
+                    self._add(op.name, B.relay_fused_conv2d_bias_bn_relu, (d0, src, wp, None, None, None, None, raw))
+                    self.keep.append(d0)
+                    y = self._unfused_tail(op, p, raw, batch * ho * wo, op.cout, res)
+                elif mode == "f16":
                     bias, sc, sf = (self._f32(p.get(k)) for k in ("bias", "scale", "shift"))
                     self._add(op.name, B.relay_fused_conv2d_bias_bn_relu, (d, src, wp, bias, sc, sf, res, y))
                 else:
@@ -94,8 +105,15 @@ class FusedNet:
                 wp = torch.empty((op.r * op.r, cin_p), dtype=self.tdtype, device=self.dev)
                 B.relay_prepack_dwconv_weights(d, wsrc, wp)
                 y = torch.empty((batch, ho, wo, cin_p), dtype=self.tdtype, device=self.dev)
-                bias, sc, sf = (self._f32(p.get(k)) for k in ("bias", "scale", "shift"))
-                self._add(op.name, B.relay_fused_dwconv_bias_relu, (d, src, wp, bias, sc, sf, y))
+                if not fused and flags:
+                    d0 = B.conv_desc(d.n, d.c, d.h, d.w, d.k, d.r, d.s, d.stride_h, d.pad_h, self.dtype, d.layout, 0)
+                    raw = torch.empty_like(y)
+                    self._add(op.name, B.relay_fused_dwconv_bias_relu, (d0, src, wp, None, None, None, raw))
+                    self.keep.append(d0)
+                    y = self._unfused_tail(op, p, raw, batch * ho * wo, cin_p, None)
+                else:
+                    bias, sc, sf = (self._f32(p.get(k)) for k in ("bias", "scale", "shift"))
+                    self._add(op.name, B.relay_fused_dwconv_bias_relu, (d, src, wp, bias, sc, sf, y))
                 self.keep += [wp, d]
                 self.bufs[op.dst], self.shape[op.dst] = y, (op.cout, ho, wo)
             elif op.kind == "maxpool":
@@ -112,8 +130,14 @@ class FusedNet:
                 wd = torch.from_numpy(np.ascontiguousarray(p["w"])).to(self.dev)
                 bias = self._f32(p.get("bias"))
                 y = torch.empty((batch, 1, 1, op.cout), dtype=self.tdtype, device=self.dev)
-                self._add(op.name, B.relay_fused_dense_bias_act,
-                          (batch, op.cout, op.cin, self.dtype, src, wd, bias, 1 if op.relu else 0, y))
+                if not fused and mode == "f16" and (bias is not None or op.relu) and op.cout % 8 == 0:
+                    raw = torch.empty_like(y)
+                    self._add(op.name, B.relay_fused_dense_bias_act,
+                              (batch, op.cout, op.cin, self.dtype, src, wd, None, 0, raw))
+                    y = self._unfused_tail(op, p, raw, batch, op.cout, None)
+                else:
+                    self._add(op.name, B.relay_fused_dense_bias_act,
+                              (batch, op.cout, op.cin, self.dtype, src, wd, bias, 1 if op.relu else 0, y))
                 self.keep += [wd]
                 self.bufs[op.dst], self.shape[op.dst] = y, (op.cout, 1, 1)
             else:
@@ -122,7 +146,7 @@ class FusedNet:
         # conv before it and whose output is first needed as a residual
         self.side_calls, self.join_before = set(), set()
         self.side = None
-        if overlap_shortcuts:
+        if overlap_shortcuts and fused:   # (the unfused tails would have to follow their conv onto the side stream)
             idx_of = {name: i for i, name in enumerate(self.call_names)}
             for j in range(1, len(ops)):
                 a0, a1 = ops[j - 1], ops[j]
@@ -142,6 +166,23 @@ class FusedNet:
         t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(self.dev)
         self.keep.append(t)
         return t
+
+    def _unfused_tail(self, op, p, cur, npix, c, res):
+        """bias add, scale/shift, residual add, relu as separate launches, each into a new tensor."""
+        def step(tag, ew, p0, p1, other):
+            nonlocal cur
+            nxt = torch.empty_like(cur)
+            self._add(f"{op.name}.{tag}", B.relay_elementwise_f16, (ew, npix, c, cur, p0, p1, other, nxt))
+            cur = nxt
+        if p.get("bias") is not None:
+            step("bias_add", B.EW_BIAS_ADD, self._f32(p["bias"]), None, None)
+        if p.get("scale") is not None:
+            step("scale_shift", B.EW_SCALE_SHIFT, self._f32(p["scale"]), self._f32(p["shift"]), None)
+        if res is not None:
+            step("add", B.EW_ADD, None, None, res)
+        if op.relu:
+            step("relu", B.EW_RELU, None, None, None)
+        return cur
 
     def _add(self, name, fn, args):
         self.calls.append((fn, args))

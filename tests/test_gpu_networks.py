@@ -90,6 +90,32 @@ def test_networks_built_by_the_fusion_pass(G):
     assert np.array_equal(net.tensor(ops[-1].dst), ref[table[-1].dst])
 
 
+def test_unfused_pipeline_against_the_unfused_oracle(G):
+    """Fusion switched off (every elementwise operator a launch and an fp16 tensor of its own): the
+    GPU pipeline equals the oracle's unfused operator sequence, and both stay close to the fused
+    result, which skips the intermediate fp16 roundings."""
+    from oracle.stack import run_float_unfused
+    from paper_1904_08368_amd.stack import FusedNet
+    for ops, cfg, cin, hw, mk in ((nets.basic_block(64), 2, 64, 56, None), (nets.resnet18(), 3, 3, 224, None),
+                                  (nets.mobilenet_v1(), 5, 3, 224, None)):
+        params = inputs.net_params(ops, cfg, "f16")
+        x = inputs.image(cfg, 1, cin, hw, hw, "f16")
+        ref_u = run_float_unfused(ops, params, x)
+        ref_f = run_float(ops, params, x, "f16")
+        net = FusedNet(ops, params, 1, hw, hw, "f16", in_channels=cin, fused=False)
+        assert len(net.calls) > len(ops) + 1                 # the elementwise operators really are launches
+        net.load_input(x)
+        net.run()
+        torch.cuda.synchronize()
+        last = ops[-1].dst
+        got = net.tensor(last)
+        tol = TOL_F16_CHAIN if len(ops) <= 23 else 2 * TOL_F16_CHAIN
+        assert O.max_rel_err(got, ref_u[last]) <= tol, ops[0].name
+        assert O.max_rel_err(got, ref_f[last]) <= 2 * tol, ops[0].name
+        first = ops[0].dst                                    # one layer deep both sides saw the same input bits
+        assert O.max_rel_err(net.tensor(first), ref_u[first]) <= TOL_F16
+
+
 def _per_layer_float(G, ops, params, ref, batch_note=""):
     """Each conv / dwconv / dense of a float net on the oracle's input for that layer."""
     from paper_1904_08368_amd import binding as B
