@@ -47,7 +47,7 @@ def run_quantized(ops, params: List[dict], shifts: List[dict], x: np.ndarray) ->
         src = t[op.src]
         if op.kind == "conv":
             t[op.dst] = qconv2d_requant(src, p["w"], stride=(op.stride, op.stride), pad=(op.pad, op.pad),
-                                        residual=t[op.res] if op.res else None,
+                                        bias=p.get("bias"), residual=t[op.res] if op.res else None,
                                         residual_lshift=sh.get("l", 0), out_rshift=sh["s"],
                                         relu_flag=op.relu)
         elif op.kind == "maxpool":
