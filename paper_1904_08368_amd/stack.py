@@ -92,8 +92,12 @@ class FusedNet:
                     self._add(op.name, B.relay_fused_conv2d_bias_bn_relu, (d, src, wp, bias, sc, sf, res, y))
                 else:
                     sh = shifts[i]
+                    qb = None
+                    if p.get("bias") is not None:
+                        qb = torch.from_numpy(np.ascontiguousarray(p["bias"], dtype=np.int32)).to(self.dev)
+                        self.keep.append(qb)
                     self._add(op.name, B.relay_qconv2d_requant,
-                              (d, src, wp, None, res, int(sh.get("l", 0)), int(sh["s"]), y))
+                              (d, src, wp, qb, res, int(sh.get("l", 0)), int(sh["s"]), y))
                 self.keep += [wp, d]
                 self.bufs[op.dst], self.shape[op.dst] = y, (op.cout, ho, wo)
             elif op.kind == "dwconv":

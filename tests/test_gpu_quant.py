@@ -112,3 +112,43 @@ def test_quantized_input_feeds_the_int8_stack(G):
     codes = xq.cpu().numpy().reshape(img.shape)
     assert np.array_equal(codes, codes_ref)
     assert np.array_equal(G.run_qconv(codes, wt, 1, 1, rshift=9, relu=True), ref)
+
+
+def test_calibrate_realize_flow_on_resnet18(G):
+    """fp16 ResNet-18 conv stack -> calibrated power-of-two ranges -> scale folded into the filters ->
+    realized int8 network: ranges, filters, biases and shifts equal the oracle's; the realized network
+    runs bit-exactly; its dequantized output follows the float network."""
+    from oracle import realize as R
+    from oracle.stack import run_float, run_quantized
+    from paper_1904_08368_amd import quantize as PQ
+    from paper_1904_08368_amd.stack import FusedNet
+    from workloads import inputs, nets
+    ops = nets.resnet18(with_dense=False)
+    params = inputs.net_params(ops, 3, "f16")
+    x = inputs.image(3, 2, 3, 224, 224, "f16")
+    t = run_float(ops, params, x, "f16")
+    rho_ref = R.calibrate(ops, t)
+    rho = PQ.calibrate(ops, params, x)
+    # the two float runs differ in the last bits: a maximum sitting on a power of two could flip a range
+    assert sum(1 for k in rho_ref if rho[k] != rho_ref[k]) == 0, {k: (rho[k], rho_ref[k]) for k in rho if rho[k] != rho_ref[k]}
+    qp_ref, sh_ref = R.realize(ops, params, rho_ref)
+    qp, sh = PQ.realize(ops, params, rho)
+    assert sh == sh_ref
+    for a, b, op in zip(qp, qp_ref, ops):
+        assert a.keys() == b.keys(), op.name
+        for k in a:
+            assert np.array_equal(a[k], b[k]), (op.name, k)
+    xq = PQ.quantize_input(x, rho["x"])
+    assert np.array_equal(xq, OQ.Q(x, rho_ref["x"], 8, 1))
+    ref_q = run_quantized(ops, qp_ref, sh_ref, xq)
+    net = FusedNet(ops, qp, 2, 224, 224, "i8", shifts=sh)
+    net.load_input(xq)
+    net.run()
+    torch.cuda.synchronize()
+    for op in ops:
+        assert np.array_equal(net.tensor(op.dst), ref_q[op.dst]), op.name
+    last = ops[-1].dst
+    ref = t[last].astype(np.float64)
+    deq = R.dequantize(net.tensor(last), rho[last])
+    sqnr = 10 * np.log10((ref ** 2).sum() / ((deq - ref) ** 2).sum())
+    assert sqnr > 20, sqnr
