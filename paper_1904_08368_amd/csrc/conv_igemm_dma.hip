@@ -313,7 +313,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
     // operands of k-step k+PD are fetched before the MFMAs of k-step k run (PD+1 register sets):
     // small wave tiles have too few MFMAs per k-step to cover the LDS latency one step ahead,
     // so they fetch the whole chunk right behind the barrier
-    constexpr int PD = (TM + TN <= 4 && KSW > 1) ? KSW - 1 : 1;
+    constexpr int PD = (TM + TN <= 4 && KSW > 1) ? (KSW - 1 < 7 ? KSW - 1 : 7) : 1;
     uint4 wf[PD + 1][TN], xf[PD + 1][TM];
     const int k0 = wk * KSW;  // first k-step of this wave
 #pragma unroll
@@ -508,6 +508,8 @@ constexpr DmaTile kTiles[] = {
     {1, 1, 2, 2, 3, 2, 2},  // 64 x 64, two waves of 64 x 64
     // tall tiles for layers with few output channels
     {4, 1, 2, 2, 3, 1, 1},  // 256 x 64, four waves of 64 x 64
+    // 256-byte chunks: half as many barriers for the long reductions of the 512-channel layers
+    {2, 2, 1, 1, 3, 4, 1},  // 64 x 64
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
@@ -537,7 +539,8 @@ hipError_t launch_typed(const ConvArgs& a, int tile, hipStream_t st) {
     case 11: return launch_one<IS_I8, STOCH, 2, 1, 4, 2, 3, 2>(a, st);
     case 12: return launch_one<IS_I8, STOCH, 2, 1, 2, 2, 3, 2, 2>(a, st);
     case 13: return launch_one<IS_I8, STOCH, 1, 1, 2, 2, 3, 2, 2>(a, st);
-    default: return launch_one<IS_I8, STOCH, 4, 1, 2, 2, 3, 1, 1>(a, st);
+    case 14: return launch_one<IS_I8, STOCH, 4, 1, 2, 2, 3, 1, 1>(a, st);
+    default: return launch_one<IS_I8, STOCH, 2, 2, 1, 1, 3, 4, 1>(a, st);
   }
 }
 
@@ -552,7 +555,7 @@ bool tile_fits(const ConvArgs& a, bool is_i8, int t) {
 
 // Tile choice from measured sweeps over the ResNet / MobileNet layer shapes: the 256x128
 // tile once it gives every CU two workgroups, else 128x64, else 64x64 (small-M layers need
-// the workgroup count more than the per-tile intensity); 128-byte chunks where C allows.
+// the workgroup count more than the per-tile intensity); the longest chunks C and LDS allow.
 int pick_tile(const ConvArgs& a, bool is_i8) {
   const bool kp2 = a.C % (2 * BKV * (is_i8 ? 16 : 8)) == 0;
   // 64 output channels over very many pixels (the stem, int8 layer 1): tall tiles of 64 x 64 per wave
@@ -560,6 +563,8 @@ int pick_tile(const ConvArgs& a, bool is_i8) {
   if (a.K > 64 && tiles_of(a, kTiles[0]) >= 512) return 0;
   const int mid = kp2 ? 9 : 4;
   if (tiles_of(a, kTiles[mid]) >= 190) return mid;
+  // a layer that gives each CU at most one 64 x 64 workgroup can afford the 96 KiB ring of 256-byte chunks
+  if (a.C % (4 * BKV * (is_i8 ? 16 : 8)) == 0 && tiles_of(a, kTiles[15]) <= 256) return 15;
   return kp2 ? 10 : 5;
 }
 
