@@ -175,3 +175,37 @@ def test_product_path_does_not_import_the_oracle():
     for f in ("oracle/__init__.py", "oracle/stack.py", "oracle/oracle.c"):
         text = open(os.path.join(ROOT, f)).read()
         assert "paper_1904_08368_amd" not in text and "relay_fused" not in text
+
+
+def test_quantize_and_elementwise_arguments_are_checked_on_the_host():
+    """Every refusal below happens before any HIP call (FAKE is never dereferenced)."""
+    lib = B.lib()
+    q = lambda **kw: lib.relay_quantize(*[{**dict(n=64, src=B.RELAY_F32, x=FAKE, rho=2.0, beta=8, sigma=1, mode=0, seed=0,
+                                                  y=FAKE + 4096, st=None), **kw}[k]
+                                          for k in ("n", "src", "x", "rho", "beta", "sigma", "mode", "seed", "y", "st")])
+    assert q(n=0) == 2 and q(x=None) == 1 and q(y=None) == 1
+    assert q(src=B.RELAY_I8) == 3
+    assert q(rho=0.0) == 2 and q(rho=-1.0) == 2 and q(rho=float("inf")) == 2 and q(rho=float("nan")) == 2
+    assert q(beta=9) == 4 and q(beta=1) == 4 and q(sigma=9) == 4 and q(mode=4) == 4 and q(mode=-1) == 4
+    assert q(x=FAKE + 4) == 5 and q(y=FAKE + 4096 + 4) == 5
+    assert q(y=FAKE) == 4                                     # output aliases the input
+    s = lambda **kw: lib.relay_sim_quantize(*[{**dict(n=64, x=FAKE, rho=2.0, beta=8, sigma=1, mode=0, seed=0, y=FAKE + 4096,
+                                                      st=None), **kw}[k]
+                                              for k in ("n", "x", "rho", "beta", "sigma", "mode", "seed", "y", "st")])
+    assert s(beta=25) == 4 and s(beta=24, y=FAKE + 4096 + 8) == 5 and s(x=None) == 1 and s(n=-5) == 2
+    e = lambda **kw: lib.relay_elementwise_f16(*[{**dict(op=B.EW_RELU, n=10, c=64, x=FAKE, p0=None, p1=None, other=None,
+                                                         y=FAKE + 4096, st=None), **kw}[k]
+                                                 for k in ("op", "n", "c", "x", "p0", "p1", "other", "y", "st")])
+    assert e(op=7) == 4 and e(n=0) == 2 and e(c=12) == 5 and e(x=None) == 1
+    assert e(p0=FAKE) == 1                                    # relu takes no parameters
+    assert e(op=B.EW_BIAS_ADD) == 1 and e(op=B.EW_SCALE_SHIFT, p0=FAKE) == 1 and e(op=B.EW_ADD) == 1
+    assert e(op=B.EW_ADD, other=FAKE + 2) == 5
+    assert b"op" in lib.relay_last_error() or lib.relay_last_error()
+
+
+def test_rounding_entry_point_checks_mode_and_shifts():
+    lib = B.lib()
+    d = _d(dtype=B.RELAY_I8, c=64)
+    call = lambda mode=0, s=5, l=0: lib.relay_qconv2d_requant_rounding(C.byref(d), FAKE, FAKE + 4096, None, None, l, s, mode, 1,
+                                                                       FAKE + 8192, None, 0, None)
+    assert call(mode=4) == 4 and call(mode=-1) == 4 and call(s=32) == 4 and call(s=-1) == 4 and call(l=24) == 4
