@@ -510,6 +510,8 @@ constexpr DmaTile kTiles[] = {
     {4, 1, 2, 2, 3, 1, 1},  // 256 x 64, four waves of 64 x 64
     // 256-byte chunks: half as many barriers for the long reductions of the 512-channel layers
     {2, 2, 1, 1, 3, 4, 1},  // 64 x 64
+    // short reductions over very many pixels (the first layer): a small ring, four workgroups per CU
+    {2, 2, 2, 1, 3, 1, 1},  // 128 x 64
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
@@ -540,7 +542,8 @@ hipError_t launch_typed(const ConvArgs& a, int tile, hipStream_t st) {
     case 12: return launch_one<IS_I8, STOCH, 2, 1, 2, 2, 3, 2, 2>(a, st);
     case 13: return launch_one<IS_I8, STOCH, 1, 1, 2, 2, 3, 2, 2>(a, st);
     case 14: return launch_one<IS_I8, STOCH, 4, 1, 2, 2, 3, 1, 1>(a, st);
-    default: return launch_one<IS_I8, STOCH, 2, 2, 1, 1, 3, 4, 1>(a, st);
+    case 15: return launch_one<IS_I8, STOCH, 2, 2, 1, 1, 3, 4, 1>(a, st);
+    default: return launch_one<IS_I8, STOCH, 2, 2, 2, 1, 3, 1, 1>(a, st);
   }
 }
 
@@ -558,8 +561,11 @@ bool tile_fits(const ConvArgs& a, bool is_i8, int t) {
 // the workgroup count more than the per-tile intensity); the longest chunks C and LDS allow.
 int pick_tile(const ConvArgs& a, bool is_i8) {
   const bool kp2 = a.C % (2 * BKV * (is_i8 ? 16 : 8)) == 0;
-  // 64 output channels over very many pixels (the stem, int8 layer 1): tall tiles of 64 x 64 per wave
-  if (a.K <= 64 && (is_i8 || a.xs_w != a.C) && tiles_of(a, kTiles[14]) >= 384) return 14;
+  // the row-packed first layer: a handful of chunks per tile, so the tile's life is mostly the latency of
+  // its first loads and its stores; many small-ring workgroups per CU overlap those
+  if (a.xs_w != a.C && a.Kred <= 8 * BKV * (is_i8 ? 16 : 8) && tiles_of(a, kTiles[16]) >= 1024) return 16;
+  // 64 output channels over very many pixels in int8 (layer 1): tall tiles of 64 x 64 per wave
+  if (a.K <= 64 && is_i8 && tiles_of(a, kTiles[14]) >= 384) return 14;
   if (a.K > 64 && tiles_of(a, kTiles[0]) >= 512) return 0;
   const int mid = kp2 ? 9 : 4;
   if (tiles_of(a, kTiles[mid]) >= 190) return mid;
