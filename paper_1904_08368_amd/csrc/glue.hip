@@ -128,6 +128,47 @@ __global__ __launch_bounds__(256) void maxpool_kernel(const V* x, V* y, int N, i
   y[idx] = best;
 }
 
+// The same for a compile-time window R x R: every tap is loaded, with its coordinates clamped
+// into the image.  A clamped tap repeats an element that the window already holds (the window
+// of a valid output overlaps the image in both directions), so the maximum is unchanged, and
+// with no branches all R*R loads are in flight at once.  Workgroups are renumbered so that an
+// XCD works through a contiguous range of output rows: rows that two windows share are then
+// fetched into one L2.
+template <typename V, int VE, int R>
+__global__ __launch_bounds__(256) void maxpool_fixed_kernel(const V* x, V* y, int N, int CV, int H, int W, int stride,
+                                                            int pad, int Ho, int Wo) {
+  const long total = (long)N * Ho * Wo * CV;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int per = gridDim.x >> 3, rem = gridDim.x & 7;
+  const long bid = xcd < rem ? (long)xcd * (per + 1) + slot : (long)rem * (per + 1) + (long)(xcd - rem) * per + slot;
+  const long idx = bid * 256 + threadIdx.x;
+  if (idx >= total) return;
+  const int cv = (int)(idx % CV);
+  long t = idx / CV;
+  const int q = (int)(t % Wo);
+  t /= Wo;
+  const int p = (int)(t % Ho);
+  const int n = (int)(t / Ho);
+  V v[R][R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int ih = min(max(p * stride - pad + r, 0), H - 1);
+#pragma unroll
+    for (int s = 0; s < R; ++s) {
+      const int iw = min(max(q * stride - pad + s, 0), W - 1);
+      v[r][s] = x[(((long)n * H + ih) * W + iw) * CV + cv];
+    }
+  }
+  V best = v[0][0];
+#pragma unroll
+  for (int r = 0; r < R; ++r)
+#pragma unroll
+    for (int s = 0; s < R; ++s)
+#pragma unroll
+      for (int e = 0; e < VE; ++e) best[e] = v[r][s][e] > best[e] ? v[r][s][e] : best[e];
+  y[idx] = best;
+}
+
 // global average pool, NHWC fp16 -> [N][C] fp16, fp32 sum.  One workgroup per (image, group
 // of up to 256 channel vectors); the HW positions are split over 256/CVB thread groups whose
 // partial sums meet in LDS.
@@ -238,7 +279,15 @@ hipError_t launch_elementwise_f16(int op, long npix, int c, const void* x, const
 
 hipError_t launch_maxpool(bool is_i8, int N, int C, int H, int W, int R, int stride, int pad, int Ho, int Wo,
                           const void* x, void* y, hipStream_t st) {
-  if (is_i8) {
+  if (R == 3 && !is_i8) {
+    const int cv = C / 8;
+    hipLaunchKernelGGL((maxpool_fixed_kernel<half8, 8, 3>), dim3(blocks_for((long)N * Ho * Wo * cv)), dim3(256), 0, st,
+                       (const half8*)x, (half8*)y, N, cv, H, W, stride, pad, Ho, Wo);
+  } else if (R == 3) {
+    const int cv = C / 16;
+    hipLaunchKernelGGL((maxpool_fixed_kernel<char16, 16, 3>), dim3(blocks_for((long)N * Ho * Wo * cv)), dim3(256), 0, st,
+                       (const char16*)x, (char16*)y, N, cv, H, W, stride, pad, Ho, Wo);
+  } else if (is_i8) {
     const int cv = C / 16;
     hipLaunchKernelGGL((maxpool_kernel<char16, 16>), dim3(blocks_for((long)N * Ho * Wo * cv)), dim3(256), 0, st,
                        (const char16*)x, (char16*)y, N, cv, H, W, R, stride, pad, Ho, Wo);

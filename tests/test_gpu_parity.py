@@ -278,3 +278,19 @@ def test_pools_and_layout(G):
     B.relay_maxpool2d(B.RELAY_I8, 2, 16, 9, 9, 3, 2, 1, G.to_nhwc(xi, 16, B.RELAY_I8), yi)
     torch.cuda.synchronize()
     assert np.array_equal(G.from_nhwc(yi, 16), O.maxpool2d(xi, 3, 2, 1).astype(np.int8))
+
+
+@pytest.mark.parametrize("geom", [(3, 1, 1), (3, 2, 0), (3, 3, 2), (3, 2, 2), (2, 2, 0), (2, 1, 1), (5, 2, 2)])
+def test_maxpool_window_stride_and_padding(G, geom):
+    """Negative inputs next to the border: padding must never win the maximum, whichever kernel runs
+    (3x3 windows: the branch-free one; other sizes: the general one)."""
+    from paper_1904_08368_amd import binding as B
+    r, st, pd = geom
+    g = _rng(410 + r + st)
+    n, c, h, w = 3, 24, 11, 14
+    x = _h(g.standard_normal((n, c, h, w)) - 3.0)              # mostly negative
+    ho, wo = (h + 2 * pd - r) // st + 1, (w + 2 * pd - r) // st + 1
+    y = torch.empty((n, ho, wo, c), dtype=torch.float16, device=G.DEV)
+    B.relay_maxpool2d(B.RELAY_F16, n, c, h, w, r, st, pd, G.to_nhwc(x, c, B.RELAY_F16), y)
+    torch.cuda.synchronize()
+    assert np.array_equal(G.from_nhwc(y, c), O.maxpool2d(x, r, st, pd).astype(np.float16))
