@@ -141,7 +141,7 @@ def main() -> int:
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU; the path shards over the batch axis with no "
-              "collective (see DESIGN.md) but nothing here launches more than one rank.", file=sys.stderr)
+              "collective, but nothing here launches more than one rank.", file=sys.stderr)
         return 2
 
     import torch

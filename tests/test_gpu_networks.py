@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 TOL_F16 = 1e-2
 # A chained fp16 network re-rounds every layer's output; one-ulp differences (2^-11
 # relative) between the two sides re-enter the next layer and add up like a random walk
-# over the 20 layers.  Bound for the end-to-end comparison, derived in the design doc.
+# over the 20 layers: about sqrt(20) * 2^-11 * (a few) = 5e-3.  Bound for the end-to-end comparison:
 TOL_F16_CHAIN = 2e-2
 
 
