@@ -29,54 +29,10 @@
 // go to the register-staged kernel in conv_igemm.hip.
 #include <cstdio>
 
-#include "igemm_common.hpp"
+#include "dma_common.hpp"
 
 namespace relay {
 namespace {
-
-__device__ __forceinline__ void lds_dma16(intx4 rsrc, unsigned lds_base, unsigned voff) {
-  // m0 = wave-uniform LDS byte address; lane i lands at m0 + 16*i
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds_base), "v"(voff),
-               "s"(rsrc)
-               : "memory");
-}
-
-// Wait until at most N of this wave's global->LDS loads are pending and all of its LDS reads
-// have returned (so that the stage they read may be refilled after the barrier).
-template <int N>
-__device__ __forceinline__ void wait_loads() {
-  asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(N) : "memory");
-}
-
-__device__ __forceinline__ intx4 make_rsrc(const void* p, unsigned bytes) {
-  const unsigned long long pa = reinterpret_cast<unsigned long long>(p);
-  intx4 r;
-  r[0] = (int)(unsigned)pa;
-  r[1] = (int)(unsigned)((pa >> 32) & 0xffffu);  // stride 0: raw buffer
-  r[2] = (int)bytes;                            // num_records
-  r[3] = 0x00020000;                            // 32-bit data format, no swizzle
-  return r;
-}
-
-// 32-bit pattern of an accumulator element (taken by value: a bit cast applied directly to a
-// vector-element lvalue is not reliable)
-__device__ __forceinline__ unsigned as_u32(float f) { return __builtin_bit_cast(unsigned, f); }
-__device__ __forceinline__ unsigned as_u32(int i) { return (unsigned)i; }
-
-constexpr unsigned kOob = 0x80000000u;  // beyond any num_records this library accepts
-
-// floor(t / d) and remainder for 0 <= t < 2^22, d > 0: float reciprocal plus one fix-up step.
-__device__ __forceinline__ void small_divmod(int t, int d, float rcp_d, int& q, int& r) {
-  q = (int)((float)t * rcp_d);
-  r = t - q * d;
-  if (r < 0) {
-    r += d;
-    --q;
-  } else if (r >= d) {
-    r -= d;
-    ++q;
-  }
-}
 
 // KP = 64-byte planes per ring chunk (a chunk covers KP*64 bytes of reduction; each plane is
 // a [rows][64 B] sub-tile with its own swizzle, because 128-byte LDS rows cannot be read
@@ -227,56 +183,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
   //      than they are.
   constexpr int CG = WTN / 8;  // lanes per pixel row in the epilogue
   const int ech = n0 + wn * WTN + (lane % CG) * 8;
-  float emul[8], eadd[8];
-  int ebias[8];
-  if (a.param_vec) {  // two 16-byte loads per array
-    const int c8 = ech < a.K ? ech : a.K - 8;
-    if constexpr (IS_I8) {
-      int4 b0 = make_int4(0, 0, 0, 0), b1 = b0;
-      if (a.flags & F_BIAS) {
-        b0 = *reinterpret_cast<const int4*>(a.qbias + c8);
-        b1 = *reinterpret_cast<const int4*>(a.qbias + c8 + 4);
-      }
-      const int t[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
-#pragma unroll
-      for (int e = 0; e < 8; ++e) ebias[e] = t[e];
-    } else {
-      float4 s0 = make_float4(1.f, 1.f, 1.f, 1.f), s1 = s0;
-      float4 f0 = make_float4(0.f, 0.f, 0.f, 0.f), f1 = f0, b0 = f0, b1 = f0;
-      if (a.flags & F_BN) {
-        s0 = *reinterpret_cast<const float4*>(a.scale + c8);
-        s1 = *reinterpret_cast<const float4*>(a.scale + c8 + 4);
-        f0 = *reinterpret_cast<const float4*>(a.shift + c8);
-        f1 = *reinterpret_cast<const float4*>(a.shift + c8 + 4);
-      }
-      if (a.flags & F_BIAS) {
-        b0 = *reinterpret_cast<const float4*>(a.bias + c8);
-        b1 = *reinterpret_cast<const float4*>(a.bias + c8 + 4);
-      }
-      const float sc[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
-      const float sf[8] = {f0.x, f0.y, f0.z, f0.w, f1.x, f1.y, f1.z, f1.w};
-      const float bb[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        emul[e] = sc[e];
-        eadd[e] = bb[e] * sc[e] + sf[e];  // (acc + b)*sc + sf
-      }
-    }
-  } else {
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int c = ech + e < a.K ? ech + e : a.K - 1;
-      if constexpr (IS_I8) {
-        ebias[e] = (a.flags & F_BIAS) ? a.qbias[c] : 0;
-      } else {
-        const float sc = (a.flags & F_BN) ? a.scale[c] : 1.f;
-        const float sf = (a.flags & F_BN) ? a.shift[c] : 0.f;
-        const float b = (a.flags & F_BIAS) ? a.bias[c] : 0.f;
-        emul[e] = sc;
-        eadd[e] = b * sc + sf;  // (acc + b)*sc + sf
-      }
-    }
-  }
+  LaneParams lp;
+  load_lane_params<IS_I8>(a, ech, lp);
 
   const int lrow = lane & 31, lhalf = lane >> 5;
   int stage = 0;      // ring stage of chunk kc
@@ -408,77 +316,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
       const unsigned raw[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
       const int m = m0 + wm * WTM + tm * 32 + pix;
       if (m >= a.M || ech >= a.K) continue;
-      const size_t o = (size_t)m * a.K + ech;
-      if constexpr (!IS_I8) {
-        float t[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) t[e] = __builtin_bit_cast(float, raw[e]) * emul[e] + eadd[e];
-        if (a.flags & F_RES) {
-          const _Float16* rp = static_cast<const _Float16*>(a.res) + o;
-          if (vec_ok) {
-            const half8 rv = *reinterpret_cast<const half8*>(rp);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) t[e] += (float)rv[e];
-          } else {
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-              if (ech + e < a.K) t[e] += (float)rp[e];
-          }
-        }
-        half8 hv;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          if (a.flags & F_RELU) t[e] = t[e] > 0.f ? t[e] : 0.f;
-          hv[e] = (_Float16)t[e];
-        }
-        _Float16* yp = static_cast<_Float16*>(a.y) + o;
-        if (vec_ok) {
-          *reinterpret_cast<half8*>(yp) = hv;
-        } else {
-#pragma unroll
-          for (int e = 0; e < 8; ++e)
-            if (ech + e < a.K) yp[e] = hv[e];
-        }
-      } else {
-        int t[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) t[e] = (int)raw[e] + ebias[e];
-        if (a.flags & F_RES) {
-          const int8_t* rp = static_cast<const int8_t*>(a.res) + o;
-          if (vec_ok) {
-            const uint2 rv = *reinterpret_cast<const uint2*>(rp);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              t[e] += (int)(int8_t)(rv.x >> (8 * e)) * (1 << a.lshift);
-              t[4 + e] += (int)(int8_t)(rv.y >> (8 * e)) * (1 << a.lshift);
-            }
-          } else {
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-              if (ech + e < a.K) t[e] += (int)rp[e] * (1 << a.lshift);
-          }
-        }
-        unsigned pk[2] = {0u, 0u};
-        WordStream rng{a.seed_lo, a.seed_hi};
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          int q;
-          if constexpr (STOCH) q = requant_shift(t[e], a.rshift, ROUND_STOCHASTIC, rng, o + e);
-          else q = (t[e] + a.round_add) >> a.rshift;  // arithmetic shift: floor
-          q = q < -127 ? -127 : (q > 127 ? 127 : q);
-          if (a.flags & F_RELU) q = q > 0 ? q : 0;
-          t[e] = q;
-          pk[e >> 2] |= (unsigned)(q & 0xff) << (8 * (e & 3));
-        }
-        int8_t* yp = static_cast<int8_t*>(a.y) + o;
-        if (vec_ok) {
-          *reinterpret_cast<uint2*>(yp) = make_uint2(pk[0], pk[1]);
-        } else {
-#pragma unroll
-          for (int e = 0; e < 8; ++e)
-            if (ech + e < a.K) yp[e] = (int8_t)t[e];
-        }
-      }
+      finish_store8<IS_I8, STOCH>(a, raw, m, ech, lp, vec_ok);
     }
   }
 }
