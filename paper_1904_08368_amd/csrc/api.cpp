@@ -228,15 +228,28 @@ relay_status relay_prepack_conv2d_weights(const relay_conv2d_desc* d, const void
                        "filter packing");
 }
 
+// g_force_tile: -1 heuristics; -2 heuristics without the halo kernel; 0.. a tile of the implicit-GEMM
+// kernels; kHaloBase + v the halo kernel's variant v (where it applies)
+constexpr int kHaloBase = 100;
+
 relay_status relay_set_conv_tile(int32_t tile) {
   const int most = relay::igemm_dma_tile_count() > relay::igemm_tile_count() ? relay::igemm_dma_tile_count()
                                                                              : relay::igemm_tile_count();
-  if (tile >= most) return fail(RELAY_ERR_UNSUPPORTED, "no tile %d", tile);
-  g_force_tile = tile < 0 ? -1 : tile;
+  const bool halo = tile >= kHaloBase && tile < kHaloBase + relay::conv_halo_variant_count();
+  if (tile >= most && !halo) return fail(RELAY_ERR_UNSUPPORTED, "no tile %d", tile);
+  g_force_tile = tile < -1 ? -2 : tile;
   return RELAY_OK;
 }
 
+// which halo variant runs this layer, or -1
+static int halo_choice(const relay::ConvArgs& a, bool is_i8) {
+  if (g_force_tile >= kHaloBase) return relay::conv_halo_supported(a, is_i8, g_force_tile - kHaloBase) ? g_force_tile - kHaloBase : -1;
+  return g_force_tile == -1 ? relay::conv_halo_pick(a, is_i8) : -1;
+}
+
 static hipError_t launch_igemm(const relay::ConvArgs& a, bool is_i8, hipStream_t s) {
+  const int hv = halo_choice(a, is_i8);
+  if (hv >= 0) return relay::launch_conv_halo(a, is_i8, hv, s);
   if (relay::igemm_dma_supported(a, is_i8)) return relay::launch_conv_igemm_dma(a, is_i8, g_force_tile, s);
   if (a.xs_w != a.C) return hipErrorInvalidValue;  // the register-staged kernel reads plain NHWC only
   return relay::launch_conv_igemm(a, is_i8, g_force_tile, s);
@@ -251,7 +264,9 @@ relay_status relay_conv2d_kernel_name(const relay_conv2d_desc* d, char* buf, siz
   if ((st = check_igemm_support(d)) != RELAY_OK) return st;
   relay::ConvArgs a = make_args(d, ho, wo);
   const bool i8 = d->dtype == RELAY_I8;
-  if (relay::igemm_dma_supported(a, i8))
+  if (halo_choice(a, i8) >= 0)
+    relay::conv_halo_kernel_name(a, i8, halo_choice(a, i8), buf, len);
+  else if (relay::igemm_dma_supported(a, i8))
     relay::igemm_dma_kernel_name(a, i8, g_force_tile, buf, len);
   else
     relay::igemm_kernel_name(a, i8, g_force_tile, buf, len);

@@ -1,0 +1,338 @@
+// 3x3 / stride 1 / pad 1 conv2d for gfx950 that stages the activations ONCE per channel chunk
+// (paper Section 4.1 / 4.2: same fused primitive function as conv_igemm_dma.hip, other schedule).
+//
+// The implicit-GEMM kernel re-fetches the activation tile for each of the nine filter taps: its
+// L2->LDS traffic is what bounds the 3x3 layers of the workloads.  Here the pixels are numbered in
+// a "padded-flat" coordinate in which a filter tap is a constant shift:
+//     o = n*F + p*P + q,   P = W + 1,  F = (H + 1)*P
+// (one shared zero column between image rows, one shared zero row between images: the left
+// padding of a row is the right padding of the row before it).  Output position o reads input
+// position o + r*P + s for tap (r, s), where input position g holds pixel (row - 1, col - 1) of
+// image g / F with (row, col) = divmod(g % F, P), and zero when row == 0 or col == 0.  A
+// workgroup owns BM consecutive positions (positions with q == W or p == H are computed and
+// dropped: 3-15 % of the work on these images) x BN channels.  Per chunk of CK input channels it
+// needs the BM + 2P + 2 input positions from its first one on -- the halo -- which it loads once
+// into LDS with global->LDS loads (zero fill by out-of-range offset, as in the other kernel);
+// the nine taps then read the same buffer at row offsets r*P + s.  The LDS swizzle is keyed on
+// row >> 2 and any 16 consecutive rows cover all banks, so the shifted reads stay conflict-free.
+// Filters go through a 3-stage ring, one tap x chunk per stage, exactly as before.
+//
+// Pipeline: a "step" is one (chunk, tap).  Behind the MFMAs of step i a wave issues the filter
+// loads of step i+2 and its share of the NEXT chunk's halo (spread over the first 8 taps, so the
+// halo has landed two steps before its chunk starts).  Every step issues the same number of
+// loads (missing ones go, out of range, to a dump block), so one compile-time vmcnt wait per
+// step orders everything; nine steps per chunk and three ring stages make the stage of a step a
+// compile-time constant of the unrolled tap loop.
+#include <cstdio>
+
+#include "dma_common.hpp"
+
+namespace relay {
+namespace {
+
+struct HaloGeom {
+  int P, F;           // row pitch W + 1 and image pitch (H + 1) * P of the flat coordinate
+  int Mflat;          // N * F flat output positions
+  float rcp_p, rcp_f;
+  int xblk;           // 16-row blocks per plane of a halo buffer
+  int nxbuf;          // halo buffers: 2 when there are several channel chunks, else 1
+  int ncc;            // channel chunks, C / CK
+};
+
+constexpr int NSW = 3;         // filter ring stages (9 taps per chunk keep step % NSW compile-time)
+constexpr int XS = 11 - NSW;   // taps of a chunk behind which the next chunk's halo is loaded
+
+template <bool IS_I8, int WAVES_M, int WAVES_N, int TM, int TN, int KP>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_halo_kernel(const ConvArgs a, const HaloGeom g) {
+  constexpr int NW = WAVES_M * WAVES_N;
+  constexpr int VE = IS_I8 ? 16 : 8;
+  constexpr int ES = IS_I8 ? 1 : 2;
+  constexpr int CK = KP * BKV * VE;
+  constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
+  constexpr int WTM = TM * 32, WTN = TN * 32;
+  static_assert((BN / 16) % NW == 0, "filter staging blocks must divide over the waves");
+  constexpr int WLP = BN / 16 / NW;      // filter blocks per plane per wave
+  constexpr int LW = KP * WLP;           // filter loads per step per wave
+  constexpr int L = LW + 1;              // loads per step per wave: filters + one halo block
+  constexpr int KSTEPS = KP * (BKV / 2);
+  static_assert(L <= TM * TN * KSTEPS, "one load is issued behind each MFMA of a step");
+  static_assert(XS + (NSW - 1) * L + 8 <= 63, "vmcnt is a 6-bit counter");
+  constexpr int WPLANE = BN * BKV;       // 16-byte slots of one filter plane
+  constexpr int WSTAGE = KP * WPLANE;
+  constexpr int EP = WTN / 4 + 1;
+  typedef typename Mma<IS_I8>::acc_t acc_t;
+
+  extern __shared__ uint4 lds[];
+  const int xplane = g.xblk * 64;                   // slots of one halo plane
+  const int xbuf_slots = KP * xplane;
+  const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) uint4*)(&lds[0]);
+  const unsigned wring_base = lds_base + (unsigned)(g.nxbuf * xbuf_slots) * 16u;
+  const unsigned dump_base = wring_base + (unsigned)(NSW * WSTAGE) * 16u;
+  const uint4* wring = lds + g.nxbuf * xbuf_slots;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave % WAVES_M, wn = wave / WAVES_M;
+  const int tiles_m = (g.Mflat + BM - 1) / BM, tiles_n = (a.K + BN - 1) / BN;
+  const int tile = xcd_remap(blockIdx.x, tiles_m * tiles_n);
+  const int tile_n = a.n_major ? tile / tiles_m : tile % tiles_n;
+  const int tile_m = a.n_major ? tile % tiles_m : tile / tiles_n;
+  const int o0 = tile_m * BM, n0 = tile_n * BN;
+  const int n_0 = o0 / g.F;            // (uniform) image and in-image position of the tile's first position
+  const int rem_0 = o0 - n_0 * g.F;
+
+  // ---- this lane's part of a halo: block (t * NW + wave) of the KP * xblk blocks, for t < XS
+  const int srow = lane >> 2, sphys = lane & 3;
+  unsigned x_off[XS];    // byte offset of the 16 bytes this lane fetches (chunk 0), or out of range
+  unsigned x_dst[XS];    // LDS byte offset inside a halo buffer
+  unsigned x_live = 0;   // bit t: the block exists (else the load goes to the dump block)
+#pragma unroll
+  for (int t = 0; t < XS; ++t) {
+    const int b = t * NW + wave;
+    const int plane = b / g.xblk, blk = b - plane * g.xblk;
+    const bool live = plane < KP;
+    const int row = blk * 16 + srow;
+    const int kvl = sphys ^ lds_swizzle(row);
+    int dn, r1, rowi, coli;
+    small_divmod(rem_0 + row, g.F, g.rcp_f, dn, r1);
+    small_divmod(r1, g.P, g.rcp_p, rowi, coli);
+    const int n = n_0 + dn;
+    const bool pixel = live && n < a.N && rowi >= 1 && coli >= 1;
+    x_off[t] = pixel ? (unsigned)((((n * a.H + rowi - 1) * a.W + coli - 1) * a.C + plane * (BKV * VE) + kvl * VE) * ES) : kOob;
+    x_dst[t] = (unsigned)((plane * g.xblk + blk) * 64) * 16u;
+    if (live) x_live |= 1u << t;
+  }
+  unsigned w_off[WLP];
+#pragma unroll
+  for (int j = 0; j < WLP; ++j) {
+    const int row = (wave * WLP + j) * 16 + srow;
+    const int kvl = sphys ^ lds_swizzle(row);
+    const int ch = n0 + row;
+    w_off[j] = ch < a.K ? (unsigned)((ch * a.Kp + kvl * VE) * ES) : kOob;
+  }
+  const intx4 rs_x = make_rsrc(a.x, (unsigned)((size_t)a.N * a.xs_n * ES));
+  const intx4 rs_w = make_rsrc(a.w, (unsigned)((size_t)a.K * a.Kp * ES));
+
+  // the i-th load of the issue slot behind step (cc, t): filters of step (cc, t) + NSW - 1, then
+  // block t of the halo of chunk cc + 1
+  auto issue_one = [&](int cc, int t, int i) {
+    if (i < LW) {
+      const int tw = (t + NSW - 1) % 9, ccw = cc + (t + NSW - 1) / 9;  // tap and chunk of the step being fetched
+      const int plane = i / WLP, j = i % WLP;
+      const bool live = ccw < g.ncc;
+      const unsigned voff = live ? w_off[j] + (unsigned)((tw * a.C + ccw * CK + plane * (BKV * VE)) * ES) : kOob;
+      lds_dma16(rs_w, wring_base + (unsigned)(((t + NSW - 1) % NSW) * WSTAGE + plane * WPLANE + (wave * WLP + j) * 64) * 16u, voff);
+    } else {
+      const bool live = t < XS && ((x_live >> (t < XS ? t : 0)) & 1u) && cc + 1 < g.ncc;
+      const unsigned voff = (live && x_off[t < XS ? t : 0] != kOob) ? x_off[t < XS ? t : 0] + (unsigned)((cc + 1) * CK * ES) : kOob;
+      const unsigned dst = live ? lds_base + (unsigned)((((cc + 1) & 1) * (g.nxbuf - 1)) * xbuf_slots) * 16u + x_dst[t < XS ? t : 0] : dump_base;
+      lds_dma16(rs_x, dst, voff);
+    }
+  };
+
+  acc_t acc[TN][TM];
+#pragma unroll
+  for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[tn][tm][v] = 0;
+
+  // ---- prologue: the whole halo of chunk 0, then the filters of the first NSW - 1 steps, each
+  //      with a dump load so that every issue slot, here and in the loop, holds L loads
+#pragma unroll
+  for (int t = 0; t < XS; ++t) {
+    const bool live = (x_live >> t) & 1u;
+    lds_dma16(rs_x, live ? lds_base + x_dst[t] : dump_base, live ? x_off[t] : kOob);
+  }
+#pragma unroll
+  for (int s = 0; s < NSW - 1; ++s) {
+#pragma unroll
+    for (int i = 0; i < LW; ++i) {
+      const int plane = i / WLP, j = i % WLP;
+      lds_dma16(rs_w, wring_base + (unsigned)(s * WSTAGE + plane * WPLANE + (wave * WLP + j) * 64) * 16u,
+                w_off[j] == kOob ? kOob : w_off[j] + (unsigned)((s * a.C + plane * (BKV * VE)) * ES));
+    }
+    lds_dma16(rs_x, dump_base, kOob);
+  }
+
+  constexpr int CG = WTN / 8;  // lanes per pixel row in the epilogue
+  const int ech = n0 + wn * WTN + (lane % CG) * 8;
+  LaneParams lp;
+  load_lane_params<IS_I8>(a, ech, lp);
+
+  const int lrow = lane & 31, lhalf = lane >> 5;
+  const int xrow0 = wm * WTM + lrow;  // halo row of this lane's first pixel at tap (0, 0)
+  for (int cc = 0; cc < g.ncc; ++cc) {
+    const uint4* xb = lds + ((cc & 1) * (g.nxbuf - 1)) * xbuf_slots;
+#pragma unroll
+    for (int t = 0; t < 9; ++t) {
+      // step (cc, t) has landed once only the loads of the NSW - 2 issue slots after its own are pending
+      wait_loads<(NSW - 2) * L>();
+      __builtin_amdgcn_s_barrier();
+      const uint4* ws = wring + (t % NSW) * WSTAGE;
+      const int xrow = xrow0 + (t / 3) * g.P + (t % 3);  // the tap is a shift of the halo rows
+      const int xs = lds_swizzle(xrow);                  // unchanged by the + 32 of the next block
+      uint4 wf[KSTEPS][TN], xf[KSTEPS][TM];
+#pragma unroll
+      for (int k = 0; k < KSTEPS; ++k) {
+        const int kq = 2 * (k & 1) + lhalf;
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) wf[k][tn] = ws[(k >> 1) * WPLANE + lds_slot(wn * WTN + tn * 32 + lrow, kq)];
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) xf[k][tm] = xb[(k >> 1) * xplane + (xrow + tm * 32) * BKV + (kq ^ xs)];
+      }
+#pragma unroll
+      for (int k = 0; k < KSTEPS; ++k)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+          for (int tm = 0; tm < TM; ++tm) {
+            acc[tn][tm] = Mma<IS_I8>::mma(wf[k][tn], xf[k][tm], acc[tn][tm]);
+            const int i = (k * TN + tn) * TM + tm;  // one load rides behind each MFMA
+            if (i < L) {
+              __builtin_amdgcn_sched_barrier(0);
+              issue_one(cc, t, i);
+              __builtin_amdgcn_sched_barrier(0);
+            }
+          }
+    }
+  }
+
+  // ---- epilogue: as in the implicit-GEMM kernel, with the flat position decoded back to a pixel
+  wait_loads<0>();               // the trailing out-of-range loads still write zeros
+  __builtin_amdgcn_s_barrier();  // every wave is done reading
+  uint4* stg = lds + wave * (32 * EP);
+  constexpr int PPI = 64 / CG;
+  const int epix = lane / CG, ecg = lane % CG;
+  const bool vec_ok = (a.K & 7) == 0;
+#pragma unroll
+  for (int tm = 0; tm < TM; ++tm) {
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        uint4 v;
+        v.x = as_u32(acc[tn][tm][4 * q4]);
+        v.y = as_u32(acc[tn][tm][4 * q4 + 1]);
+        v.z = as_u32(acc[tn][tm][4 * q4 + 2]);
+        v.w = as_u32(acc[tn][tm][4 * q4 + 3]);
+        stg[lrow * EP + tn * 8 + 2 * q4 + lhalf] = v;
+      }
+    // same wave wrote what it now reads: LDS operations of a wave execute in order
+#pragma unroll
+    for (int it = 0; it < 32 / PPI; ++it) {
+      const int pix = it * PPI + epix;
+      const uint4 lo = stg[pix * EP + ecg * 2], hi = stg[pix * EP + ecg * 2 + 1];
+      const unsigned raw[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+      int dn, r1, p, q;
+      small_divmod(rem_0 + wm * WTM + tm * 32 + pix, g.F, g.rcp_f, dn, r1);
+      small_divmod(r1, g.P, g.rcp_p, p, q);
+      const int n = n_0 + dn;
+      if (n >= a.N || p >= a.H || q >= a.W || ech >= a.K) continue;  // not a pixel, or past Cout
+      finish_store8<IS_I8, false>(a, raw, (n * a.H + p) * a.W + q, ech, lp, vec_ok);
+    }
+  }
+}
+
+struct HaloTile {
+  int waves_m, waves_n, tm, tn;
+  constexpr int bm() const { return waves_m * tm * 32; }
+  constexpr int bn() const { return waves_n * tn * 32; }
+};
+constexpr HaloTile kHalo[] = {{2, 2, 2, 1}, {2, 2, 1, 1}};  // 128 x 64, 64 x 64
+constexpr int kNumHalo = 2;
+
+int chunk_planes(const ConvArgs& a, bool is_i8) {
+  const int ve = is_i8 ? 16 : 8;
+  return a.C % (2 * BKV * ve) == 0 ? 2 : 1;
+}
+
+bool make_geom(const ConvArgs& a, bool is_i8, int v, HaloGeom& g, size_t& lds_bytes) {
+  const int kp = chunk_planes(a, is_i8), ve = is_i8 ? 16 : 8;
+  g.P = a.W + 1;
+  g.F = (a.H + 1) * g.P;
+  if ((long)a.N * g.F > 0x3fffffffL || g.F >= (1 << 21)) return false;
+  g.Mflat = a.N * g.F;
+  g.rcp_p = 1.0f / (float)g.P;
+  g.rcp_f = 1.0f / (float)g.F;
+  const int rows = kHalo[v].bm() + 2 * g.P + 2;
+  g.xblk = (rows + 15) / 16;
+  g.ncc = a.C / (kp * BKV * ve);
+  g.nxbuf = g.ncc > 1 ? 2 : 1;
+  if (kp * g.xblk > XS * 4) return false;  // a halo must fit the load slots of XS steps x 4 waves
+  const int nw = kHalo[v].waves_m * kHalo[v].waves_n;
+  const size_t ring = (size_t)g.nxbuf * kp * g.xblk * 64 + (size_t)NSW * kp * kHalo[v].bn() * BKV + 64;
+  const size_t epi = (size_t)nw * 32 * (kHalo[v].tn * 32 / 4 + 1);
+  lds_bytes = (ring > epi ? ring : epi) * 16;
+  return lds_bytes <= 160 * 1024;
+}
+
+template <bool IS_I8, int WM, int WN, int TM, int TN, int KP>
+hipError_t launch_halo_one(const ConvArgs& a, const HaloGeom& g, size_t lds_bytes, hipStream_t st) {
+  auto kern = conv3x3_halo_kernel<IS_I8, WM, WN, TM, TN, KP>;
+  static bool raised = false;  // dynamic LDS above the default limit has to be asked for once per kernel
+  if (!raised) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                             160 * 1024);
+    if (e != hipSuccess) return e;
+    raised = true;
+  }
+  constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+  const int tiles = ((g.Mflat + BM - 1) / BM) * ((a.K + BN - 1) / BN);
+  hipLaunchKernelGGL(kern, dim3(tiles), dim3(64 * WM * WN), lds_bytes, st, a, g);
+  return hipGetLastError();
+}
+
+template <bool IS_I8>
+hipError_t launch_halo_typed(const ConvArgs& a, const HaloGeom& g, size_t lds_bytes, int v, int kp, hipStream_t st) {
+  if (v == 0) return kp == 2 ? launch_halo_one<IS_I8, 2, 2, 2, 1, 2>(a, g, lds_bytes, st)
+                             : launch_halo_one<IS_I8, 2, 2, 2, 1, 1>(a, g, lds_bytes, st);
+  return kp == 2 ? launch_halo_one<IS_I8, 2, 2, 1, 1, 2>(a, g, lds_bytes, st)
+                 : launch_halo_one<IS_I8, 2, 2, 1, 1, 1>(a, g, lds_bytes, st);
+}
+
+}  // namespace
+
+int conv_halo_variant_count() { return kNumHalo; }
+
+// 3x3, stride 1, pad 1, plain NHWC, whole chunks of channels, deterministic rounding.
+bool conv_halo_supported(const ConvArgs& a, bool is_i8, int v) {
+  if (v < 0 || v >= kNumHalo) return false;
+  const int es = is_i8 ? 1 : 2, ve = is_i8 ? 16 : 8;
+  if (a.R != 3 || a.S != 3 || a.sh != 1 || a.sw != 1 || a.ph != 1 || a.pw != 1) return false;
+  if (a.xs_w != a.C || a.xs_h != a.W * a.C || a.xs_n != a.H * a.W * a.C) return false;
+  if (a.C % (BKV * ve) != 0 || a.round_mode == ROUND_STOCHASTIC) return false;
+  if ((size_t)a.N * a.xs_n * es > 0x7fffffffu || (size_t)a.K * a.Kp * es > 0x7fffffffu) return false;
+  HaloGeom g;
+  size_t lds_bytes;
+  return make_geom(a, is_i8, v, g, lds_bytes);
+}
+
+// The variant the heuristic takes, or -1 to leave the layer to the implicit-GEMM kernel.  Measured on
+// the ResNet shapes at batch 32: cutting the activation loads by 2-4x pays only where they are the
+// larger part of a tile's traffic and both kernels get two workgroups per CU -- the 256-channel
+// 14 x 14 layers (14.8 against 16.6 us); at 56 x 56 the two halo buffers cost the second workgroup,
+// at 7 x 7 a quarter of the flat positions are not pixels, and the int8 layers are even.
+int conv_halo_pick(const ConvArgs& a, bool is_i8) {
+  if (is_i8 || a.C < 256 || a.W > 16 || !conv_halo_supported(a, is_i8, 0)) return -1;
+  const long flat = (long)a.N * (a.H + 1) * (a.W + 1);
+  const long t128 = ((flat + 127) / 128) * ((a.K + 63) / 64);
+  return t128 >= 190 && t128 <= 512 ? 0 : -1;
+}
+
+void conv_halo_kernel_name(const ConvArgs& a, bool is_i8, int v, char* buf, size_t len) {
+  snprintf(buf, len, "conv3x3_halo_kernel<%s, %d, %d, %d, %d, %d>", is_i8 ? "true" : "false", kHalo[v].waves_m,
+           kHalo[v].waves_n, kHalo[v].tm, kHalo[v].tn, chunk_planes(a, is_i8));
+}
+
+hipError_t launch_conv_halo(const ConvArgs& a, bool is_i8, int v, hipStream_t st) {
+  HaloGeom g;
+  size_t lds_bytes;
+  if (!make_geom(a, is_i8, v, g, lds_bytes)) return hipErrorInvalidValue;
+  const int kp = chunk_planes(a, is_i8);
+  return is_i8 ? launch_halo_typed<true>(a, g, lds_bytes, v, kp, st) : launch_halo_typed<false>(a, g, lds_bytes, v, kp, st);
+}
+
+}  // namespace relay

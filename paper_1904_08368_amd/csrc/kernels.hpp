@@ -58,6 +58,12 @@ bool igemm_dma_supported(const ConvArgs& a, bool is_i8);
 hipError_t launch_conv_igemm_dma(const ConvArgs& a, bool is_i8, int tile, hipStream_t st);
 int igemm_dma_tile_count();
 void igemm_dma_kernel_name(const ConvArgs& a, bool is_i8, int tile, char* buf, size_t len);
+// The 3x3 / stride 1 / pad 1 kernel that stages the activations once per channel chunk (conv_halo.hip).
+bool conv_halo_supported(const ConvArgs& a, bool is_i8, int variant);
+int conv_halo_pick(const ConvArgs& a, bool is_i8);  // variant, or -1: leave the layer to the implicit-GEMM kernel
+int conv_halo_variant_count();
+hipError_t launch_conv_halo(const ConvArgs& a, bool is_i8, int variant, hipStream_t st);
+void conv_halo_kernel_name(const ConvArgs& a, bool is_i8, int variant, char* buf, size_t len);
 hipError_t launch_dwconv_f16(const ConvArgs& a, hipStream_t st);
 hipError_t launch_dense(int m, int n, int k, bool is_f16, const void* x, const void* w, const float* bias,
                         int act, void* y, hipStream_t st);

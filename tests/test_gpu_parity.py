@@ -294,3 +294,51 @@ def test_maxpool_window_stride_and_padding(G, geom):
     B.relay_maxpool2d(B.RELAY_F16, n, c, h, w, r, st, pd, G.to_nhwc(x, c, B.RELAY_F16), y)
     torch.cuda.synchronize()
     assert np.array_equal(G.from_nhwc(y, c), O.maxpool2d(x, r, st, pd).astype(np.float16))
+
+
+# ------------------------------------------------------------- 3x3 kernel with one-time staging
+HALO_SHAPES = [  # n, c, h, w, k
+    (2, 64, 23, 27, 192), (1, 32, 9, 11, 37), (3, 128, 14, 14, 128), (1, 256, 7, 7, 64), (2, 64, 56, 56, 64),
+    (5, 96, 5, 6, 72), (1, 64, 1, 1, 64), (2, 64, 2, 40, 24),
+]
+
+
+@pytest.mark.parametrize("variant", [0, 1])
+@pytest.mark.parametrize("shape", HALO_SHAPES)
+def test_fp16_halo_kernel(G, shape, variant):
+    from paper_1904_08368_amd import binding as B
+    n, c, h, w, k = shape
+    g = _rng(900 + c + h)
+    x = _h(g.standard_normal((n, c, h, w)))
+    wt = _h(g.standard_normal((k, c, 3, 3)) * np.sqrt(2.0 / (c * 9)))
+    sc = (1 + g.standard_normal(k) * 0.1).astype(np.float32)
+    sf = (g.standard_normal(k) * 0.1).astype(np.float32)
+    res = _h(g.standard_normal((n, k, h, w)))
+    d = B.conv_desc(n, c, h, w, k, 3, 3, 1, 1, B.RELAY_F16, B.RELAY_NHWC, 0)
+    B.relay_set_conv_tile(100 + variant)
+    try:
+        assert "halo" in B.relay_conv2d_kernel_name(d), "the forced variant does not take this shape"
+    finally:
+        B.relay_set_conv_tile(-1)
+    ref = O.fused_conv2d(x, wt, stride=(1, 1), pad=(1, 1), scale=sc, shift=sf, residual=res, relu_flag=True)
+    got = G.run_conv_f16(x, wt, 1, 1, scale=sc, shift=sf, residual=res, relu=True, tile=100 + variant)
+    assert got.shape == ref.shape and not np.isnan(got).any()
+    assert O.max_rel_err(got, ref) <= TOL_F16
+    ref0 = O.fused_conv2d(x, wt, stride=(1, 1), pad=(1, 1))
+    assert O.max_rel_err(G.run_conv_f16(x, wt, 1, 1, tile=100 + variant), ref0) <= TOL_F16
+
+
+@pytest.mark.parametrize("variant", [0, 1])
+@pytest.mark.parametrize("shape", [(2, 64, 23, 27, 192), (1, 128, 9, 11, 40), (2, 256, 14, 14, 64), (1, 64, 56, 56, 64)])
+def test_int8_halo_kernel_bit_exact(G, shape, variant):
+    n, c, h, w, k = shape
+    g = _rng(950 + c + h)
+    x = g.integers(-127, 128, (n, c, h, w)).astype(np.int8)
+    wt = g.integers(-127, 128, (k, c, 3, 3)).astype(np.int8)
+    res = g.integers(-127, 128, (n, k, h, w)).astype(np.int8)
+    b = g.integers(-3000, 3000, k).astype(np.int32)
+    ref = O.qconv2d_requant(x, wt, stride=(1, 1), pad=(1, 1), bias=b, residual=res, residual_lshift=12, out_rshift=12,
+                            relu_flag=True)
+    for _ in range(2):
+        got = G.run_qconv(x, wt, 1, 1, bias=b, residual=res, lshift=12, rshift=12, relu=True, tile=100 + variant)
+        assert np.array_equal(got, ref)
