@@ -399,9 +399,10 @@ bool tile_fits(const ConvArgs& a, bool is_i8, int t) {
 // the workgroup count more than the per-tile intensity); the longest chunks C and LDS allow.
 int pick_tile(const ConvArgs& a, bool is_i8) {
   const bool kp2 = a.C % (2 * BKV * (is_i8 ? 16 : 8)) == 0;
-  // the row-packed first layer: a handful of chunks per tile, so the tile's life is mostly the latency of
-  // its first loads and its stores; many small-ring workgroups per CU overlap those
-  if (a.xs_w != a.C && a.Kred <= 8 * BKV * (is_i8 ? 16 : 8) && tiles_of(a, kTiles[16]) >= 1024) return 16;
+  // short reductions over many pixels (the row-packed first layer, the early pointwise layers): a tile
+  // lives for a handful of chunks, mostly the latency of its first loads and its stores; many
+  // small-ring workgroups per CU overlap those
+  if (a.Kred <= 8 * BKV * (is_i8 ? 16 : 8) && tiles_of(a, kTiles[16]) >= 512) return 16;
   // 64 output channels over very many pixels in int8 (layer 1): tall tiles of 64 x 64 per wave
   if (a.K <= 64 && is_i8 && tiles_of(a, kTiles[14]) >= 384) return 14;
   if (a.K > 64 && tiles_of(a, kTiles[0]) >= 512) return 0;
