@@ -342,3 +342,62 @@ def test_int8_halo_kernel_bit_exact(G, shape, variant):
     for _ in range(2):
         got = G.run_qconv(x, wt, 1, 1, bias=b, residual=res, lshift=12, rshift=12, relu=True, tile=100 + variant)
         assert np.array_equal(got, ref)
+
+
+# -------------------------------------------------------------------------- maximum sizes
+def _pattern(shape, dtype):
+    """A cheap deterministic tensor (no generator can fill 2 GB in seconds): small signed values that
+    depend on every coordinate."""
+    n, c, h, w = shape
+    v = (np.arange(n, dtype=np.int16).reshape(n, 1, 1, 1) * 7 + np.arange(c, dtype=np.int16).reshape(1, c, 1, 1) * 17 +
+         np.arange(h, dtype=np.int16).reshape(1, 1, h, 1) * 131 + np.arange(w, dtype=np.int16).reshape(1, 1, 1, w) * 71)
+    v = (v % 13 - 6).astype(np.int8)
+    return v if dtype == np.int8 else (v.astype(np.float16) / np.float16(8))
+
+
+@pytest.mark.parametrize("mode", ["f16", "i8"])
+def test_conv_input_at_the_2_31_byte_limit(G, mode):
+    """The largest input the 32-bit buffer offsets admit (2^31 - 1 bytes): outputs sampled near the
+    far end of the tensor, where an offset that wrapped or lost its top bit would read elsewhere."""
+    if mode == "f16":
+        n, c, h, w, k = 3, 64, 2364, 2364, 16
+        assert n * c * h * w * 2 <= 2 ** 31 - 1 < n * c * (h + 1) * (w + 1) * 2
+    else:
+        n, c, h, w, k = 2, 64, 4096, 4095, 16
+        assert n * c * h * w <= 2 ** 31 - 1
+    g = _rng(990)
+    x = _pattern((n, c, h, w), np.int8 if mode == "i8" else np.float16)
+    pts = [(n - 1, int(g.integers(0, k)), int(g.integers(h - 40, h)), int(g.integers(0, w))) for _ in range(120)]
+    pts += [(n - 1, k - 1, h - 1, w - 1), (n - 1, 0, h - 1, 0), (0, 0, 0, 0), (n - 1, 3, h - 2, w - 1)]
+    if mode == "f16":
+        wt = _h(g.standard_normal((k, c, 3, 3)) * np.sqrt(2.0 / (c * 9)))
+        got = G.run_conv_f16(x, wt, 1, 1, relu=True)
+        acc = O.conv2d_points(x, wt, pts, (1, 1), (1, 1))
+        want = O.cast_f16(np.maximum(acc, 0.0)).astype(np.float64)
+        gv = np.array([got[t] for t in pts], dtype=np.float64)
+        assert np.max(np.abs(gv - want) / np.maximum(np.abs(want), 0.05)) <= TOL_F16
+        assert np.any(want > 0)
+    else:
+        wt = g.integers(-127, 128, (k, c, 3, 3)).astype(np.int8)
+        got = G.run_qconv(x, wt, 1, 1, rshift=9)
+        acc = O.conv2d_points(x, wt, pts, (1, 1), (1, 1), integer=True)
+        want = O.requant_points(acc, out_rshift=9)
+        assert np.array_equal(np.array([got[t] for t in pts]), want)
+
+
+@pytest.mark.parametrize("stride", [1, 2])
+def test_dwconv_input_at_the_2_31_byte_limit(G, stride):
+    n, c, h, w = 1, 32, 5793, 5792
+    assert n * c * h * w * 2 <= 2 ** 31 - 1 < n * c * (h + 1) * w * 2
+    g = _rng(991 + stride)
+    x = _pattern((n, c, h, w), np.float16)
+    wt = _h(g.standard_normal((c, 3, 3)) * np.sqrt(2.0 / 9))
+    got = G.run_dwconv_f16(x, wt, stride, 1, relu=True)
+    ho, wo = got.shape[2], got.shape[3]
+    pts = [(0, int(g.integers(0, c)), int(g.integers(ho - 30, ho)), int(g.integers(0, wo))) for _ in range(120)]
+    pts += [(0, c - 1, ho - 1, wo - 1), (0, 0, ho - 1, 0), (0, 0, 0, 0), (0, 5, ho - 1, wo - 2)]
+    acc = O.dwconv2d_points(x, wt, pts, (stride, stride), (1, 1))
+    want = O.cast_f16(np.maximum(acc, 0.0)).astype(np.float64)
+    gv = np.array([got[t] for t in pts], dtype=np.float64)
+    assert np.max(np.abs(gv - want) / np.maximum(np.abs(want), 0.05)) <= TOL_F16
+    assert np.any(want > 0)
