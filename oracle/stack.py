@@ -35,6 +35,8 @@ def run_float(ops, params: List[dict], x: np.ndarray, out_dtype: str = "f16") ->
             t[op.dst] = _narrow(global_avgpool(src), out_dtype)
         elif op.kind == "dense":
             t[op.dst] = fused_dense(src, p["w"], bias=p.get("bias"), relu_flag=op.relu, out_dtype=out_dtype)
+        elif op.kind == "concat":
+            t[op.dst] = np.concatenate([t[s] for s in op.srcs], axis=1)   # channel axis of NCHW
         else:
             raise ValueError(op.kind)
     return t

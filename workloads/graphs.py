@@ -10,11 +10,11 @@ from __future__ import annotations
 from dataclasses import dataclass, field
 from typing import Dict, List, Tuple
 
-from .nets import MOBILENET_V1_BLOCKS
+from .nets import INCEPTION_WIDTHS, MOBILENET_V1_BLOCKS
 
 CONTRACTIONS = ("conv2d", "dwconv2d", "dense")
 ELEMENTWISE = ("bias_add", "scale_shift", "add", "relu")
-OPAQUE = ("input", "maxpool", "avgpool")
+OPAQUE = ("input", "maxpool", "avgpool", "concat")
 
 
 @dataclass(frozen=True)
@@ -102,6 +102,22 @@ def single_block(cin: int = 64) -> Graph:
     g = Graph()
     x = g.add("input", "x")
     basic_block(g, "blk", x, cin, cin, 1)
+    return g
+
+
+def inception_block(widths=INCEPTION_WIDTHS) -> Graph:
+    """Four branches over one input, joined by a channel concatenation."""
+    cin, c1, c3r, c3, c5r, c5, cp = widths
+    g = Graph()
+    x = g.add("input", "x")
+    b1 = _conv_bn_relu(g, "b1", x, cin, c1, 1, 1, 0)
+    t = _conv_bn_relu(g, "b3r", x, cin, c3r, 1, 1, 0)
+    b3 = _conv_bn_relu(g, "b3", t, c3r, c3, 3, 1, 1)
+    t = _conv_bn_relu(g, "b5r", x, cin, c5r, 1, 1, 0)
+    b5 = _conv_bn_relu(g, "b5", t, c5r, c5, 5, 1, 2)
+    p = g.add("maxpool", "pool", (x,), r=3, stride=1, pad=1, cin=cin, cout=cin)
+    bp = _conv_bn_relu(g, "bp", p, cin, cp, 1, 1, 0)
+    g.add("concat", "cat", (b1, b3, b5, bp), cout=c1 + c3 + c5 + cp)
     return g
 
 

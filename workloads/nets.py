@@ -17,7 +17,7 @@ from typing import List, Optional
 
 @dataclass(frozen=True)
 class Op:
-    kind: str                 # "conv" | "dwconv" | "dense" | "maxpool" | "avgpool"
+    kind: str                 # "conv" | "dwconv" | "dense" | "maxpool" | "avgpool" | "concat"
     name: str
     src: str                  # input tensor name
     dst: str                  # output tensor name
@@ -30,6 +30,7 @@ class Op:
     bn: bool = False
     relu: bool = False
     res: Optional[str] = None  # tensor added before relu (residual), or None
+    srcs: tuple = ()          # concat only: the tensors joined along the channel axis, in order (src = srcs[0])
 
 
 def conv(name, src, dst, cin, cout, r, stride, pad, *, bn=True, relu=True, res=None, bias=False):
@@ -94,6 +95,29 @@ def basic_block(c: int = 64) -> List[Op]:
     ]
 
 
+# Width table of one Inception block: input channels, 1x1 branch, 3x3 reduce -> 3x3, 5x5 reduce -> 5x5,
+# pool projection.  (256, 128, 128, 192, 32, 96, 64) are the published widths of GoogLeNet's second
+# block at 28x28, chosen because every reduction length is a multiple of 32 channels.
+INCEPTION_WIDTHS = (256, 128, 128, 192, 32, 96, 64)
+
+
+def inception_block(widths=INCEPTION_WIDTHS) -> List[Op]:
+    """Four branches reading the same tensor, joined along the channel axis: the pattern the
+    paper's parallel convolution combination was written for (Section 4.4).  conv + folded BN +
+    relu throughout."""
+    cin, c1, c3r, c3, c5r, c5, cp = widths
+    return [
+        conv("b1", "x", "b1.out", cin, c1, 1, 1, 0),
+        conv("b3r", "x", "b3r.out", cin, c3r, 1, 1, 0),
+        conv("b3", "b3r.out", "b3.out", c3r, c3, 3, 1, 1),
+        conv("b5r", "x", "b5r.out", cin, c5r, 1, 1, 0),
+        conv("b5", "b5r.out", "b5.out", c5r, c5, 5, 1, 2),
+        Op("maxpool", "pool", "x", "pool.out", cin, cin, 3, 1, 1),
+        conv("bp", "pool.out", "bp.out", cin, cp, 1, 1, 0),
+        Op("concat", "cat", "b1.out", "cat", 0, c1 + c3 + c5 + cp, srcs=("b1.out", "b3.out", "b5.out", "bp.out")),
+    ]
+
+
 def out_hw(h: int, r: int, stride: int, pad: int) -> int:
     return (h + 2 * pad - r) // stride + 1
 
@@ -109,6 +133,8 @@ def trace_shapes(ops: List[Op], h: int, w: int, c: int = 3):
             shp[op.dst] = (ci, 1, 1)
         elif op.kind == "dense":
             shp[op.dst] = (op.cout, 1, 1)
+        elif op.kind == "concat":
+            shp[op.dst] = (sum(shp[s][0] for s in op.srcs), hi, wi)
         else:
             raise ValueError(op.kind)
     return shp
