@@ -187,6 +187,46 @@ relay_status relay_global_avgpool(int32_t dtype, int32_t n, int32_t c, int32_t h
 typedef enum { RELAY_EW_BIAS_ADD = 0, RELAY_EW_SCALE_SHIFT = 1, RELAY_EW_ADD = 2, RELAY_EW_RELU = 3 } relay_elementwise_op;
 relay_status relay_elementwise_f16(int32_t op, int64_t n_pixels, int32_t c, const void* x, const float* p0,
                                    const float* p1, const void* other, void* y, void* hip_stream);
+/* Parallel convolution combination (paper Section 4.4, "Parallel convolution combination"):
+ * several convolutions that read the same tensor with the same window, stride and padding and
+ * carry the same elementwise tail run as ONE launch over their filters stacked along the
+ * output-channel axis.  Each member's result is a channel range ("segment") of that launch and
+ * is stored straight into the member's own tensor -- which may itself be a channel range of a
+ * wider NHWC tensor, so a later concatenation along channels costs nothing -- and the input may
+ * likewise be a channel range of a wider tensor.
+ *   d            NHWC, F16; c = channels read per pixel, k = channels of all segments together;
+ *                flags as for relay_fused_conv2d_bias_bn_relu, without RELAY_HAS_RESIDUAL
+ *   x, x_ld      first channel read of pixel (0,0,0) (device); pixel p of the input starts at
+ *                x + p*x_ld elements.  x_ld >= c, multiple of 8
+ *   w_packed     the members' packed filters one after another (packing is row-per-output-channel,
+ *                so the members' relay_prepack_conv2d_weights results are simply concatenated)
+ *   bias, bn_scale, bn_shift   [k], the members' constants one after another; NULL iff flag clear
+ *   nseg         1..4 segments; seg_channels[i] > 0, multiple of 8, summing to k (host array)
+ *   seg_y[i]     where channel 0 of segment i of output pixel 0 goes (device pointers, host array);
+ *   seg_ld[i]    output pixel m of segment i starts at seg_y[i] + m*seg_ld[i] elements;
+ *                seg_ld[i] >= seg_channels[i], multiple of 8 (host array)
+ * Output ranges must not overlap each other or the input (not checked beyond pointer equality).
+ * RELAY_ERR_UNSUPPORTED for shapes outside the direct-to-LDS kernels (c % 32 != 0, r*s > 32).
+ * All pointers 16-byte aligned.  Nothing is allocated; the call only enqueues on hip_stream. */
+relay_status relay_fused_conv2d_combined(const relay_conv2d_desc* d, const void* x, int32_t x_ld,
+                                         const void* w_packed, const float* bias, const float* bn_scale,
+                                         const float* bn_shift, int32_t nseg, const int32_t* seg_channels,
+                                         void* const* seg_y, const int32_t* seg_ld, void* hip_stream);
+
+/* Axis scale folding (paper Section 4.4, "Axis scale folding"): a multiplication by a
+ * per-channel constant before or after a convolution is moved into the convolution's constant
+ * filters ahead of time, leaving no multiplication in the operator's tail.
+ *   relay_fold_scale_axis: w_out[k][c][r][s] = w[k][c][r][s] * scale[axis == RELAY_FOLD_OUT ? k : c]
+ *     on OIHW filters (device, F16 or F32; rs = r*s), scale [k] resp. [c] fp32 (device).  The
+ *     product is formed exactly (fp64) and rounded once to the filter type.  w_out may equal w.
+ *   relay_fold_bias: out[k] = bias[k]*scale[k] + shift[k] (bias NULL: 0), fp64 arithmetic rounded
+ *     to fp32 -- the bias that replaces "add bias, scale, shift" once scale sits in the filters. */
+typedef enum { RELAY_FOLD_OUT = 0, RELAY_FOLD_IN = 1 } relay_fold_axis;
+relay_status relay_fold_scale_axis(int32_t dtype, int32_t k, int32_t c, int32_t rs, int32_t axis, const void* w,
+                                   const float* scale, void* w_out, void* hip_stream);
+relay_status relay_fold_bias(int32_t k, const float* bias, const float* scale, const float* shift, float* out,
+                             void* hip_stream);
+
 /* [n,c,h,w] -> [n,h,w,c_pad], channels c..c_pad-1 zero.  Any dtype; c_pad >= c. */
 relay_status relay_nchw_to_nhwc(int32_t dtype, int32_t n, int32_t c, int32_t h, int32_t w, int32_t c_pad,
                                 const void* x, void* y, void* hip_stream);

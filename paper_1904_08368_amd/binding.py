@@ -59,6 +59,9 @@ SIGNATURES = {
     "relay_qconv2d_requant_rounding": [_DP, _P, _P, _P, _P, _I, _I, _I, C.c_uint64, _P, _P, _SZ, _P],
     "relay_quantize": [C.c_int64, _I, _P, C.c_float, _I, _I, _I, C.c_uint64, _P, _P],
     "relay_sim_quantize": [C.c_int64, _P, C.c_float, _I, _I, _I, C.c_uint64, _P, _P],
+    "relay_fused_conv2d_combined": [_DP, _P, _I, _P, _P, _P, _P, _I, _P, _P, _P, _P],
+    "relay_fold_scale_axis": [_I, _I, _I, _I, _I, _P, _P, _P, _P],
+    "relay_fold_bias": [_I, _P, _P, _P, _P, _P],
     "relay_set_conv_tile": [_I],
     "relay_conv2d_kernel_name": [_DP, C.c_char_p, _SZ],
 }
@@ -203,6 +206,30 @@ def relay_quantize(n_elems: int, src_dtype: int, x, rho: float, beta: int, sigma
 
 def relay_sim_quantize(n_elems: int, x, rho: float, beta: int, sigma: int, round_mode: int, seed: int, y) -> None:
     _check(lib().relay_sim_quantize(n_elems, _ptr(x), rho, beta, sigma, round_mode, seed, _ptr(y), _stream()))
+
+
+FOLD_OUT, FOLD_IN = 0, 1
+
+
+def relay_fused_conv2d_combined(d: ConvDesc, x, x_ld: int, w_packed, bias, bn_scale, bn_shift,
+                                seg_channels: Sequence[int], seg_y: Sequence, seg_ld: Sequence[int]) -> None:
+    """seg_y: one tensor per segment whose data_ptr() is channel 0 of pixel 0 of that segment
+    (a channel slice of a wider NHWC tensor is fine: its data_ptr() already carries the offset)."""
+    n = len(seg_y)
+    ch = (C.c_int32 * max(n, 1))(*seg_channels)
+    ld = (C.c_int32 * max(n, 1))(*seg_ld)
+    ys = (C.c_void_p * max(n, 1))(*[_ptr(t) for t in seg_y])
+    _check(lib().relay_fused_conv2d_combined(C.byref(d), _ptr(x), x_ld, _ptr(w_packed), _ptr(bias), _ptr(bn_scale),
+                                             _ptr(bn_shift), n, C.cast(ch, _P), C.cast(ys, _P), C.cast(ld, _P),
+                                             _stream()))
+
+
+def relay_fold_scale_axis(dtype: int, k: int, c: int, rs: int, axis: int, w, scale, w_out) -> None:
+    _check(lib().relay_fold_scale_axis(dtype, k, c, rs, axis, _ptr(w), _ptr(scale), _ptr(w_out), _stream()))
+
+
+def relay_fold_bias(k: int, bias, scale, shift, out) -> None:
+    _check(lib().relay_fold_bias(k, _ptr(bias), _ptr(scale), _ptr(shift), _ptr(out), _stream()))
 
 
 def relay_fuse_extract(pattern: Sequence[int], in_offsets: Sequence[int], in_nodes: Sequence[int]):

@@ -305,6 +305,81 @@ relay_status relay_fused_conv2d_bias_bn_relu(const relay_conv2d_desc* d, const v
   return device_status(launch_igemm(a, false, s), "conv2d fp16 launch");
 }
 
+relay_status relay_fused_conv2d_combined(const relay_conv2d_desc* d, const void* x, int32_t x_ld,
+                                         const void* w_packed, const float* bias, const float* bn_scale,
+                                         const float* bn_shift, int32_t nseg, const int32_t* seg_channels,
+                                         void* const* seg_y, const int32_t* seg_ld, void* hip_stream) {
+  int ho, wo;
+  relay_status st = check_geometry(d, &ho, &wo);
+  if (st != RELAY_OK) return st;
+  if (d->dtype != RELAY_F16) return fail(RELAY_ERR_DTYPE, "the combined conv2d takes F16");
+  if (d->layout != RELAY_NHWC) return fail(RELAY_ERR_UNSUPPORTED, "the combined conv2d takes NHWC");
+  if (d->flags & RELAY_HAS_RESIDUAL) return fail(RELAY_ERR_UNSUPPORTED, "the combined conv2d has no residual operand");
+  if (!x || !w_packed || !seg_channels || !seg_y || !seg_ld)
+    return fail(RELAY_ERR_NULL, "x, w_packed and the segment arrays are required");
+  if ((st = check_optional(bias, d->flags & RELAY_HAS_BIAS, "bias")) != RELAY_OK) return st;
+  if ((st = check_optional(bn_scale, d->flags & RELAY_HAS_BN, "bn_scale")) != RELAY_OK) return st;
+  if ((st = check_optional(bn_shift, d->flags & RELAY_HAS_BN, "bn_shift")) != RELAY_OK) return st;
+  if (nseg < 1 || nseg > 4) return fail(RELAY_ERR_SHAPE, "nseg=%d outside 1..4", nseg);
+  if (x_ld < d->c || x_ld % 8) return fail(RELAY_ERR_SHAPE, "x_ld=%d must be a multiple of 8 and at least c=%d", x_ld, d->c);
+  if ((long)d->n * d->h * d->w * x_ld > kMaxElems) return fail(RELAY_ERR_SHAPE, "input view exceeds 2^31-1 elements");
+  relay::ConvArgs a = make_args(d, ho, wo);
+  long total = 0;
+  for (int i = 0; i < nseg; ++i) {
+    if (seg_channels[i] <= 0 || seg_channels[i] % 8)
+      return fail(RELAY_ERR_SHAPE, "segment %d has %d channels: must be a positive multiple of 8", i, seg_channels[i]);
+    if (seg_ld[i] < seg_channels[i] || seg_ld[i] % 8)
+      return fail(RELAY_ERR_SHAPE, "seg_ld[%d]=%d must be a multiple of 8 and at least %d", i, seg_ld[i], seg_channels[i]);
+    if (!seg_y[i]) return fail(RELAY_ERR_NULL, "seg_y[%d] is NULL", i);
+    if (!aligned(seg_y[i], 16)) return fail(RELAY_ERR_ALIGN, "seg_y[%d] must be 16-byte aligned", i);
+    if (seg_y[i] == x) return fail(RELAY_ERR_UNSUPPORTED, "output must not alias an input");
+    for (int j = 0; j < i; ++j)
+      if (seg_y[j] == seg_y[i]) return fail(RELAY_ERR_UNSUPPORTED, "segments %d and %d share an address", j, i);
+    if ((long)a.M * seg_ld[i] > kMaxElems) return fail(RELAY_ERR_SHAPE, "output view %d exceeds 2^31-1 elements", i);
+    total += seg_channels[i];
+    a.seg_end[i] = (int)total;
+    a.seg_ld[i] = seg_ld[i];
+    a.seg_y[i] = seg_y[i];
+  }
+  if (total != d->k) return fail(RELAY_ERR_SHAPE, "segments hold %ld channels, the descriptor k=%d", total, d->k);
+  if ((st = check_igemm_support(d)) != RELAY_OK) return st;
+  if (!aligned(x, 16) || !aligned(w_packed, 16)) return fail(RELAY_ERR_ALIGN, "fp16 tensors must be 16-byte aligned");
+  a.nseg = nseg;
+  a.xs_w = x_ld;
+  a.xs_h = d->w * x_ld;
+  a.xs_n = d->h * d->w * x_ld;
+  a.x = x; a.w = w_packed; a.y = seg_y[0]; a.bias = bias; a.scale = bn_scale; a.shift = bn_shift;
+  finish_args(a);
+  if (!relay::igemm_dma_supported(a, false))
+    return fail(RELAY_ERR_UNSUPPORTED, "the combined conv2d needs c %% 32 == 0 and r*s <= 32 (c=%d, r=%d, s=%d)", d->c,
+                d->r, d->s);
+  return device_status(launch_igemm(a, false, static_cast<hipStream_t>(hip_stream)), "combined conv2d launch");
+}
+
+relay_status relay_fold_scale_axis(int32_t dtype, int32_t k, int32_t c, int32_t rs, int32_t axis, const void* w,
+                                   const float* scale, void* w_out, void* hip_stream) {
+  if (dtype != RELAY_F16 && dtype != RELAY_F32) return fail(RELAY_ERR_DTYPE, "scale folding takes F16 or F32 filters");
+  if (k <= 0 || c <= 0 || rs <= 0) return fail(RELAY_ERR_SHAPE, "non-positive extent (k=%d c=%d rs=%d)", k, c, rs);
+  if ((long)k * c * rs > kMaxElems) return fail(RELAY_ERR_SHAPE, "filters exceed 2^31-1 elements");
+  if (axis != RELAY_FOLD_OUT && axis != RELAY_FOLD_IN) return fail(RELAY_ERR_UNSUPPORTED, "unknown axis %d", axis);
+  if (!w || !scale || !w_out) return fail(RELAY_ERR_NULL, "w, scale and w_out are required");
+  if (!aligned(w, esize_of(dtype)) || !aligned(w_out, esize_of(dtype)) || !aligned(scale, 4))
+    return fail(RELAY_ERR_ALIGN, "pointers must be aligned to their element size");
+  return device_status(relay::launch_fold_scale_axis(dtype == RELAY_F16, k, c, rs, axis == RELAY_FOLD_IN, w, scale,
+                                                     w_out, static_cast<hipStream_t>(hip_stream)),
+                       "scale folding");
+}
+
+relay_status relay_fold_bias(int32_t k, const float* bias, const float* scale, const float* shift, float* out,
+                             void* hip_stream) {
+  if (k <= 0) return fail(RELAY_ERR_SHAPE, "k=%d must be positive", k);
+  if (!scale || !shift || !out) return fail(RELAY_ERR_NULL, "scale, shift and out are required");
+  if (!aligned(scale, 4) || !aligned(shift, 4) || !aligned(out, 4) || !aligned(bias, 4))
+    return fail(RELAY_ERR_ALIGN, "pointers must be 4-byte aligned");
+  return device_status(relay::launch_fold_bias(k, bias, scale, shift, out, static_cast<hipStream_t>(hip_stream)),
+                       "bias folding");
+}
+
 relay_status relay_qconv2d_requant(const relay_conv2d_desc* d, const int8_t* x, const int8_t* w_packed,
                                    const int32_t* bias, const int8_t* residual, int32_t residual_lshift,
                                    int32_t out_rshift, int8_t* y, void* workspace, size_t workspace_bytes,

@@ -207,6 +207,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_halo_kernel
   constexpr int PPI = 64 / CG;
   const int epix = lane / CG, ecg = lane % CG;
   const bool vec_ok = (a.K & 7) == 0;
+  const OutLoc ol = locate_output(a, ech);
 #pragma unroll
   for (int tm = 0; tm < TM; ++tm) {
 #pragma unroll
@@ -231,7 +232,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_halo_kernel
       small_divmod(r1, g.P, g.rcp_p, p, q);
       const int n = n_0 + dn;
       if (n >= a.N || p >= a.H || q >= a.W || ech >= a.K) continue;  // not a pixel, or past Cout
-      finish_store8<IS_I8, false>(a, raw, (n * a.H + p) * a.W + q, ech, lp, vec_ok);
+      finish_store8<IS_I8, false>(a, raw, (n * a.H + p) * a.W + q, ech, lp, ol, vec_ok);
     }
   }
 }

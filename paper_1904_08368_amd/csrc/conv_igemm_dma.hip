@@ -287,6 +287,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
   constexpr int PPI = 64 / CG;  // pixels per pass of 64 lanes
   const int epix = lane / CG, ecg = lane % CG;
   const bool vec_ok = (a.K & 7) == 0;
+  const OutLoc ol = locate_output(a, ech);
 #pragma unroll
   for (int te = 0; te < TM_E; ++te) {
     const int tm = tm_lo + te;  // block row in the workgroup tile
@@ -316,7 +317,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
       const unsigned raw[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
       const int m = m0 + wm * WTM + tm * 32 + pix;
       if (m >= a.M || ech >= a.K) continue;
-      finish_store8<IS_I8, STOCH>(a, raw, m, ech, lp, vec_ok);
+      finish_store8<IS_I8, STOCH>(a, raw, m, ech, lp, ol, vec_ok);
     }
   }
 }

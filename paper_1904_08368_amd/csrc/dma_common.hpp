@@ -57,6 +57,33 @@ struct LaneParams {
   int ibias[8];
 };
 
+// Where a lane's 8 channels [ech, ech + 8) are stored: the tensor, its pixel pitch (elements) and
+// the position of channel ech inside a pixel of it.  Worked out after the main loop, so that it
+// occupies no registers there.
+struct OutLoc {
+  void* y;
+  int ldy;
+  int cho;
+};
+
+__device__ __forceinline__ OutLoc locate_output(const ConvArgs& a, int ech) {
+  OutLoc ol{nullptr, 0, 0};  // unused for the plain tensor: finish_store8 addresses that from the arguments
+  if (a.nseg) {  // (uniform) which output segment holds the lane's channels
+    int begin = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (i < a.nseg) {
+        if (ech >= begin && ech < a.seg_end[i]) {
+          ol.y = a.seg_y[i];
+          ol.ldy = a.seg_ld[i];
+          ol.cho = ech - begin;
+        }
+        begin = a.seg_end[i];
+      }
+  }
+  return ol;
+}
+
 template <bool IS_I8>
 __device__ __forceinline__ void load_lane_params(const ConvArgs& a, int ech, LaneParams& lp) {
   float(&emul)[8] = lp.mul;
@@ -112,12 +139,13 @@ __device__ __forceinline__ void load_lane_params(const ConvArgs& a, int ech, Lan
   }
 }
 
-// Finish the 8 consecutive channels [ech, ech + 8) of output pixel m (its index in the NHWC output)
+// Finish the 8 consecutive channels [ech, ech + 8) of output pixel m (its index in the NHWC output;
+// residual and random draws are addressed in the plain [M][K] tensor, the store goes where ol says)
 // from the raw accumulator bits and store them (bias, scale/shift, residual, relu, cast -- or the
 // quantized epilogue, with STOCH the stochastic rounding).
 template <bool IS_I8, bool STOCH>
 __device__ __forceinline__ void finish_store8(const ConvArgs& a, const unsigned (&raw)[8], int m, int ech,
-                                              const LaneParams& lp, bool vec_ok) {
+                                              const LaneParams& lp, const OutLoc& ol, bool vec_ok) {
   const float(&emul)[8] = lp.mul;
   const float(&eadd)[8] = lp.add;
   const int(&ebias)[8] = lp.ibias;
@@ -144,7 +172,7 @@ __device__ __forceinline__ void finish_store8(const ConvArgs& a, const unsigned 
       if (a.flags & F_RELU) t[e] = t[e] > 0.f ? t[e] : 0.f;
       hv[e] = (_Float16)t[e];
     }
-    _Float16* yp = static_cast<_Float16*>(a.y) + o;
+    _Float16* yp = a.nseg ? static_cast<_Float16*>(ol.y) + ((size_t)m * ol.ldy + ol.cho) : static_cast<_Float16*>(a.y) + o;
     if (vec_ok) {
       *reinterpret_cast<half8*>(yp) = hv;
     } else {
@@ -183,7 +211,7 @@ __device__ __forceinline__ void finish_store8(const ConvArgs& a, const unsigned 
       t[e] = q;
       pk[e >> 2] |= (unsigned)(q & 0xff) << (8 * (e & 3));
     }
-    int8_t* yp = static_cast<int8_t*>(a.y) + o;
+    int8_t* yp = a.nseg ? static_cast<int8_t*>(ol.y) + ((size_t)m * ol.ldy + ol.cho) : static_cast<int8_t*>(a.y) + o;
     if (vec_ok) {
       *reinterpret_cast<uint2*>(yp) = make_uint2(pk[0], pk[1]);
     } else {

@@ -277,6 +277,47 @@ hipError_t launch_elementwise_f16(int op, long npix, int c, const void* x, const
   return hipGetLastError();
 }
 
+namespace {
+// Axis scale folding (paper Section 4.4): the per-channel factor next to a convolution is
+// multiplied into the OIHW filters once, ahead of time.  The product of a filter value and an
+// fp32 factor is exact in fp64, so the result is rounded exactly once, to the filter type.
+template <typename T>
+__global__ __launch_bounds__(256) void fold_scale_axis_kernel(long n, int C, int RS, bool axis_in, const T* w,
+                                                              const float* scale, T* out) {
+  const long i = (long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  const long kc = i / RS;  // k*C + c
+  const int ch = axis_in ? (int)(kc % C) : (int)(kc / C);
+  out[i] = (T)((double)w[i] * (double)scale[ch]);
+}
+
+__global__ __launch_bounds__(256) void fold_bias_kernel(int K, const float* bias, const float* scale,
+                                                        const float* shift, float* out) {
+  const int k = blockIdx.x * 256 + threadIdx.x;
+  if (k >= K) return;
+  const double b = bias ? (double)bias[k] : 0.0;
+  out[k] = (float)__dadd_rn(__dmul_rn(b, (double)scale[k]), (double)shift[k]);  // product rounded, then the sum: no fma
+}
+}  // namespace
+
+hipError_t launch_fold_scale_axis(bool is_f16, int K, int C, int RS, bool axis_in, const void* w, const float* scale,
+                                  void* w_out, hipStream_t st) {
+  const long n = (long)K * C * RS;
+  if (is_f16)
+    hipLaunchKernelGGL((fold_scale_axis_kernel<_Float16>), dim3(blocks_for(n)), dim3(256), 0, st, n, C, RS, axis_in,
+                       (const _Float16*)w, scale, (_Float16*)w_out);
+  else
+    hipLaunchKernelGGL((fold_scale_axis_kernel<float>), dim3(blocks_for(n)), dim3(256), 0, st, n, C, RS, axis_in,
+                       (const float*)w, scale, (float*)w_out);
+  return hipGetLastError();
+}
+
+hipError_t launch_fold_bias(int K, const float* bias, const float* scale, const float* shift, float* out,
+                            hipStream_t st) {
+  hipLaunchKernelGGL(fold_bias_kernel, dim3(blocks_for(K)), dim3(256), 0, st, K, bias, scale, shift, out);
+  return hipGetLastError();
+}
+
 hipError_t launch_maxpool(bool is_i8, int N, int C, int H, int W, int R, int stride, int pad, int Ho, int Wo,
                           const void* x, void* y, hipStream_t st) {
   if (R == 3 && !is_i8) {

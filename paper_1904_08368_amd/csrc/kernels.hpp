@@ -38,6 +38,14 @@ struct ConvArgs {
   int round_add;           // what the deterministic rules add before the shift (0 when rshift == 0)
   unsigned seed_lo, seed_hi;  // key of the stochastic rounding draws
   unsigned flags;
+  // Output channel segments (parallel convolution combination and concatenation views, paper
+  // Section 4.4): channel ch in [seg_end[i-1], seg_end[i]) of output pixel m is stored at
+  // seg_y[i] + m*seg_ld[i] + (ch - seg_end[i-1]) elements; boundaries are multiples of 8.
+  // nseg == 0: the plain tensor y with pixel pitch K.  Only the direct-to-LDS kernels read these.
+  int nseg;
+  int seg_end[4];
+  int seg_ld[4];
+  void* seg_y[4];
 };
 
 // Row pitch (elements) of packed filters for a reduction of kred elements of esize bytes:
@@ -75,6 +83,12 @@ hipError_t launch_maxpool(bool is_i8, int N, int C, int H, int W, int R, int str
 // one unfused elementwise operator on an fp16 NHWC tensor of npix pixels x c channels (c % 8 == 0)
 hipError_t launch_elementwise_f16(int op, long npix, int c, const void* x, const float* p0, const float* p1,
                                   const void* other, void* y, hipStream_t st);
+// w_out[k][c][i] = w[k][c][i] * scale[axis_in ? c : k] for i < rs, product in fp64, one rounding to the filter type
+hipError_t launch_fold_scale_axis(bool is_f16, int K, int C, int RS, bool axis_in, const void* w, const float* scale,
+                                  void* w_out, hipStream_t st);
+// out[k] = bias[k]*scale[k] + shift[k] (bias may be NULL: 0), fp64 arithmetic, fp32 result
+hipError_t launch_fold_bias(int K, const float* bias, const float* scale, const float* shift, float* out,
+                            hipStream_t st);
 hipError_t launch_avgpool_f16(int N, int C, int HW, const void* x, void* y, hipStream_t st);
 hipError_t launch_nchw_to_nhwc(int esize, int N, int C, int H, int W, int Cpad, const void* x, void* y,
                                hipStream_t st);

@@ -14,7 +14,8 @@ from typing import Dict, List, Optional, Sequence
 
 from . import binding as B
 
-KIND_OF = {"conv2d": "conv", "dwconv2d": "dwconv", "dense": "dense", "maxpool": "maxpool", "avgpool": "avgpool"}
+KIND_OF = {"conv2d": "conv", "dwconv2d": "dwconv", "dense": "dense", "maxpool": "maxpool", "avgpool": "avgpool",
+           "concat": "concat"}
 EPILOGUE_ORDER = ("bias_add", "scale_shift", "add", "relu")
 
 
@@ -34,6 +35,7 @@ class FusedOp:
     bn: bool = False
     relu: bool = False
     res: Optional[str] = None
+    srcs: tuple = ()      # concat: the tensors joined along the channel axis (src = srcs[0])
 
 
 def extract_groups(graph) -> List[List[int]]:
@@ -84,8 +86,10 @@ def lower(graph, groups: Sequence[Sequence[int]]) -> List[FusedOp]:
                     raise ValueError(f"add {n.name} must take exactly one tensor from outside its group")
                 fields["res"] = out_name[others[0]]
             prev = m
-        if fields["kind"] in ("maxpool", "avgpool") and len(ms) != 1:
-            raise ValueError("pooling operators are not fused")
+        if fields["kind"] in ("maxpool", "avgpool", "concat") and len(ms) != 1:
+            raise ValueError("pooling and concatenation are not fused")
+        if fields["kind"] == "concat":
+            fields["srcs"] = tuple(out_name[i] for i in first.inputs)
         ops.append(FusedOp(**fields))
         out_name[ms[-1]] = last.name
     return ops
@@ -93,3 +97,15 @@ def lower(graph, groups: Sequence[Sequence[int]]) -> List[FusedOp]:
 
 def fuse(graph) -> List[FusedOp]:
     return lower(graph, extract_groups(graph))
+
+
+def combine_parallel(ops: Sequence[FusedOp]) -> List[List[int]]:
+    """Parallel convolution combination (paper Section 4.4): indices of the fused convs that can
+    run as one launch -- same input tensor, same window, stride and padding, same elementwise
+    tail, no residual operand (its tail would read a second tensor).  One list per combined
+    conv, at least two members each, in program order."""
+    by_key: Dict[tuple, List[int]] = {}
+    for i, op in enumerate(ops):
+        if op.kind == "conv" and op.res is None:
+            by_key.setdefault((op.src, op.cin, op.r, op.stride, op.pad, op.bias, op.bn, op.relu), []).append(i)
+    return [g for g in by_key.values() if len(g) > 1]

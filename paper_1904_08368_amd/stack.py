@@ -26,9 +26,14 @@ class FusedNet:
 
     def __init__(self, ops, params: List[dict], batch: int, h: int, w: int, mode: str = "f16",
                  shifts: Optional[List[dict]] = None, in_channels: int = 3, device: str = "cuda:0",
-                 overlap_shortcuts: bool = True, fused: bool = True):
+                 overlap_shortcuts: bool = True, fused: bool = True, combine: bool = False,
+                 fold_scale: bool = False):
         assert mode in ("f16", "i8")
         assert fused or mode == "f16"
+        # combine: convs that share input, window and tail run as one launch; fold_scale: the
+        # batch-norm scale is multiplied into the filters ahead of time (paper Section 4.4, both)
+        assert not (combine or fold_scale) or (mode == "f16" and fused)
+        self.fold_scale = fold_scale
         # fused=False launches every elementwise operator behind a contraction as a kernel of its
         # own on a tensor of its own: the pipeline of a framework without operator fusion, kept
         # for the fusion ablation (paper Section 5.2)
@@ -63,11 +68,25 @@ class FusedNet:
             self._add("nchw_to_nhwc", B.relay_nchw_to_nhwc,
                       (self.dtype, batch, in_channels, h, w, cpad, self.x_nchw, self.bufs["x"]))
 
+        from .fusion import combine_parallel
+        group_of = {g[0]: g for g in (combine_parallel(ops) if combine else [])}
+        absorbed = {j for g in group_of.values() for j in g[1:]}
+        self._plan_concats(ops, batch, h, w, in_channels, cpad)
+
         for i, (op, p) in enumerate(zip(ops, params)):
+            if i in absorbed:
+                continue
             cin_l, hi, wi = self.shape[op.src]
             src = self.bufs[op.src]
             cin_p = src.shape[-1]
-            if op.kind == "conv":
+            if op.kind == "concat":
+                # nothing to launch: every producer has already written its channel range
+                assert all(self.view_of.get(s_, (None,))[0] == op.dst for s_ in op.srcs)
+                self.shape[op.dst] = (self.bufs[op.dst].shape[-1], hi, wi)
+            elif op.kind == "conv" and (i in group_of or op.dst in self.view_of or not src.is_contiguous()):
+                idxs = group_of.get(i, [i])
+                self._emit_conv_views([ops[j] for j in idxs], [params[j] for j in idxs], batch)
+            elif op.kind == "conv":
                 flags = B.flags_of(p.get("bias"), p.get("scale"), op.res, op.relu)
                 if i == 0 and self.stem_nhwc4:
                     d = B.conv_desc(batch, cin_l, hi, wi, op.cout, op.r, op.r, op.stride, op.pad, self.dtype,
@@ -87,6 +106,14 @@ class FusedNet:
                     self._add(op.name, B.relay_fused_conv2d_bias_bn_relu, (d0, src, wp, None, None, None, None, raw))
                     self.keep.append(d0)
                     y = self._unfused_tail(op, p, raw, batch * ho * wo, op.cout, res)
+                elif mode == "f16" and fold_scale and p.get("scale") is not None:
+                    # the filters were packed unscaled above: pack the folded ones over them
+                    bias = self._fold(op, p, wsrc, cin_l)
+                    B.relay_prepack_conv2d_weights(d, wsrc, cin_l, wp)
+                    d1 = B.conv_desc(d.n, d.c, d.h, d.w, d.k, d.r, d.s, d.stride_h, d.pad_h, self.dtype, d.layout,
+                                     B.flags_of(True, None, op.res, op.relu))
+                    self._add(op.name, B.relay_fused_conv2d_bias_bn_relu, (d1, src, wp, bias, None, None, res, y))
+                    self.keep.append(d1)
                 elif mode == "f16":
                     bias, sc, sf = (self._f32(p.get(k)) for k in ("bias", "scale", "shift"))
                     self._add(op.name, B.relay_fused_conv2d_bias_bn_relu, (d, src, wp, bias, sc, sf, res, y))
@@ -156,13 +183,101 @@ class FusedNet:
                 a0, a1 = ops[j - 1], ops[j]
                 if a0.kind == "conv" and a1.kind == "conv" and a0.src == a1.src and not a1.res and not a0.res:
                     users = [o for o in ops if o.src == a1.dst or o.res == a1.dst]
-                    if len(users) == 1 and users[0].res == a1.dst:
+                    if len(users) == 1 and users[0].res == a1.dst and a1.name in idx_of and users[0].name in idx_of:
                         self.side_calls.add(idx_of[a1.name])
                         self.join_before.add(idx_of[users[0].name])
             if self.side_calls:
                 self.side = torch.cuda.Stream(device=self.dev)
         torch.cuda.synchronize(self.dev)
         self.graph = None
+
+    def _plan_concats(self, ops, batch, h, w, in_channels, cpad):
+        """A channel concatenation is free when every tensor it joins is written by a conv: the
+        conv stores straight into its channel range of the joined tensor.  Allocates those joined
+        tensors and records view_of[name] = (joined tensor, first channel)."""
+        self.view_of: Dict[str, tuple] = {}
+        if not any(o.kind == "concat" for o in ops):
+            return
+        if self.mode != "f16" or not self.fused:
+            raise ValueError("concatenation needs the fp16 fused pipeline")
+        phys, hw = {"x": cpad}, {"x": (h, w)}      # physical channels and spatial size of every tensor
+        producer = {}
+        for o in ops:
+            hi, wi = hw[o.src]
+            out = lambda e: (e + 2 * o.pad - o.r) // o.stride + 1
+            if o.kind in ("conv", "dwconv", "maxpool"):
+                phys[o.dst] = o.cout if o.kind == "conv" else phys[o.src]
+                hw[o.dst] = (out(hi), out(wi))
+            elif o.kind in ("avgpool", "dense"):
+                phys[o.dst], hw[o.dst] = (phys[o.src] if o.kind == "avgpool" else o.cout), (1, 1)
+            elif o.kind == "concat":
+                phys[o.dst], hw[o.dst] = sum(phys[s_] for s_ in o.srcs), hw[o.srcs[0]]
+                off = 0
+                for s_ in o.srcs:
+                    if producer.get(s_) != "conv" or s_ in self.view_of or phys[s_] % 8 or hw[s_] != hw[o.dst]:
+                        raise ValueError(f"concat {o.name}: {s_} must be a conv output of the same size, used in one "
+                                         "concatenation, with a multiple of 8 channels")
+                    self.view_of[s_] = (o.dst, off)
+                    off += phys[s_]
+                self.bufs[o.dst] = torch.empty((batch, *hw[o.dst], off), dtype=self.tdtype, device=self.dev)
+            producer[o.dst] = o.kind
+
+    def _emit_conv_views(self, members, mparams, batch):
+        """One launch for one or more fp16 convs over the same input (a channel range of a wider
+        tensor or a plain one), each storing into its own tensor or channel range."""
+        op0 = members[0]
+        cin_l, hi, wi = self.shape[op0.src]
+        src = self.bufs[op0.src]
+        cin_p = src.shape[-1]
+        if any(m.res for m in members):
+            raise ValueError(f"{op0.name}: a conv with a residual operand cannot store into a view")
+        has_bias = mparams[0].get("bias") is not None
+        has_bn = mparams[0].get("scale") is not None
+        fold = self.fold_scale and has_bn
+        flags = B.flags_of(True if (has_bias or fold) else None, None if fold or not has_bn else True, None, op0.relu)
+        ktot = sum(m.cout for m in members)
+        d = B.conv_desc(batch, cin_p, hi, wi, ktot, op0.r, op0.r, op0.stride, op0.pad, self.dtype, B.RELAY_NHWC, flags)
+        ho, wo = B.relay_conv2d_out_shape(d)
+        wp = torch.empty(B.relay_packed_weight_bytes(d), dtype=torch.uint8, device=self.dev)
+        consts = {k: [] for k in ("bias", "scale", "shift")}
+        ys, off = [], 0
+        for m, p in zip(members, mparams):
+            dm = B.conv_desc(batch, cin_p, hi, wi, m.cout, m.r, m.r, m.stride, m.pad, self.dtype, B.RELAY_NHWC, flags)
+            nbytes = B.relay_packed_weight_bytes(dm)
+            wsrc = torch.from_numpy(np.ascontiguousarray(p["w"])).to(self.dev)
+            if fold:
+                consts["bias"].append(self._fold(m, p, wsrc, cin_l))
+            else:
+                consts["bias"].append(self._f32(p.get("bias")))
+                consts["scale"].append(self._f32(p.get("scale")))
+                consts["shift"].append(self._f32(p.get("shift")))
+            B.relay_prepack_conv2d_weights(dm, wsrc, cin_l, wp[off:off + nbytes])
+            off += nbytes
+            if m.dst in self.view_of:
+                cat, c0 = self.view_of[m.dst]
+                y = self.bufs[cat][..., c0:c0 + m.cout]
+            else:
+                y = torch.empty((batch, ho, wo, m.cout), dtype=self.tdtype, device=self.dev)
+            assert tuple(y.shape) == (batch, ho, wo, m.cout)
+            ys.append(y)
+            self.bufs[m.dst], self.shape[m.dst] = y, (m.cout, ho, wo)
+            self.keep.append(dm)
+        joined = {k: (torch.cat(v) if v and v[0] is not None else None) for k, v in consts.items()}
+        name = "+".join(m.name for m in members)
+        self._add(name, B.relay_fused_conv2d_combined,
+                  (d, src, src.stride(2), wp, joined["bias"], joined["scale"], joined["shift"],
+                   [m.cout for m in members], ys, [y.stride(2) for y in ys]))
+        self.keep += [wp, d, joined]
+
+    def _fold(self, op, p, wsrc, cin_l):
+        """Axis scale folding: multiplies the OIHW filters on the device by the conv's batch-norm
+        scale, in place, and returns the bias that replaces "add bias, scale, shift"."""
+        sc, sf = self._f32(p["scale"]), self._f32(p["shift"])
+        B.relay_fold_scale_axis(self.dtype, op.cout, cin_l, op.r * op.r, B.FOLD_OUT, wsrc, sc, wsrc)
+        folded = torch.empty(op.cout, dtype=torch.float32, device=self.dev)
+        B.relay_fold_bias(op.cout, self._f32(p.get("bias")), sc, sf, folded)
+        self.keep.append(folded)
+        return folded
 
     def _f32(self, a):
         if a is None:

@@ -209,3 +209,52 @@ def test_rounding_entry_point_checks_mode_and_shifts():
     call = lambda mode=0, s=5, l=0: lib.relay_qconv2d_requant_rounding(C.byref(d), FAKE, FAKE + 4096, None, None, l, s, mode, 1,
                                                                        FAKE + 8192, None, 0, None)
     assert call(mode=4) == 4 and call(mode=-1) == 4 and call(s=32) == 4 and call(s=-1) == 4 and call(l=24) == 4
+
+
+def _comb(d, x=FAKE, x_ld=None, w=FAKE, bias=None, sc=None, sf=None, ch=(32, 32), ys=(FAKE + 4096, FAKE + 8192),
+          ld=None, arrays=True):
+    n = len(ch)
+    cha = (C.c_int32 * max(n, 1))(*ch)
+    lda = (C.c_int32 * max(n, 1))(*(ld if ld is not None else ch))
+    ya = (C.c_void_p * max(n, len(ys), 1))(*ys)
+    P = C.c_void_p
+    return _status("relay_fused_conv2d_combined", C.byref(d), x, d.c if x_ld is None else x_ld, w, bias, sc, sf, n,
+                   C.cast(cha, P) if arrays else None, C.cast(ya, P), C.cast(lda, P), None)
+
+
+def test_combined_conv_argument_checks():
+    """Every case fails validation on the host; nothing is launched."""
+    assert _comb(_d(), x=None) == 1
+    assert _comb(_d(), arrays=False) == 1
+    assert _comb(_d(), ys=(FAKE + 4096, None)) == 1
+    assert _comb(_d(flags=B.HAS_BIAS)) == 1                                   # flag set, pointer NULL
+    assert _comb(_d(), sc=FAKE) == 1                                          # pointer given, flag clear
+    assert _comb(_d(dtype=B.RELAY_I8)) == 3
+    assert _comb(_d(layout=B.RELAY_NCHW)) == 4
+    assert _comb(_d(flags=B.HAS_RESIDUAL)) == 4
+    assert _comb(_d(), ch=()) == 2                                            # nseg outside 1..4
+    assert _comb(_d(), ch=(16,) * 5, ys=(FAKE + 4096,) * 5) == 2
+    assert _comb(_d(), ch=(32, 24)) == 2                                      # segments do not add up to k
+    assert _comb(_d(), ch=(60, 4)) == 2                                       # not multiples of 8
+    assert _comb(_d(), ld=(32, 24)) == 2                                      # pitch below the segment
+    assert _comb(_d(), ld=(32, 36)) == 2                                      # pitch not a multiple of 8
+    assert _comb(_d(), x_ld=56) == 2 and _comb(_d(), x_ld=68) == 2            # below c / not a multiple of 8
+    assert _comb(_d(), ys=(FAKE + 4096, FAKE + 4096)) == 4                    # two segments at one address
+    assert _comb(_d(), ys=(FAKE, FAKE + 4096)) == 4                           # output aliases the input
+    assert _comb(_d(), ys=(FAKE + 4096, FAKE + 8200)) == 5                    # misaligned
+    assert _comb(_d(c=48, k=64)) == 4                                         # c % 32: no direct-to-LDS kernel
+    assert _comb(_d(n=4096, h=64, w=64, c=64), x_ld=256) == 2                 # view beyond 2^31-1 elements
+
+
+def test_scale_folding_argument_checks():
+    f = lambda *a: _status("relay_fold_scale_axis", *a)
+    assert f(B.RELAY_I8, 8, 8, 9, 0, FAKE, FAKE, FAKE, None) == 3
+    assert f(B.RELAY_F16, 0, 8, 9, 0, FAKE, FAKE, FAKE, None) == 2
+    assert f(B.RELAY_F16, 1 << 16, 1 << 16, 9, 0, FAKE, FAKE, FAKE, None) == 2
+    assert f(B.RELAY_F16, 8, 8, 9, 2, FAKE, FAKE, FAKE, None) == 4
+    assert f(B.RELAY_F16, 8, 8, 9, 0, None, FAKE, FAKE, None) == 1
+    assert f(B.RELAY_F32, 8, 8, 9, 1, FAKE + 2, FAKE, FAKE, None) == 5
+    g = lambda *a: _status("relay_fold_bias", *a)
+    assert g(0, None, FAKE, FAKE, FAKE, None) == 2
+    assert g(8, None, None, FAKE, FAKE, None) == 1
+    assert g(8, FAKE + 1, FAKE, FAKE, FAKE, None) == 5

@@ -1,0 +1,215 @@
+"""GPU parity of the paper's Section 4.4 rewrites: axis scale folding (bit-exact against the
+oracle's fp64 product rounded once) and parallel convolution combination (one launch whose
+channel segments equal the members' own fused convs of the oracle), through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+from oracle import combine as OC
+from oracle.stack import run_float
+from workloads import inputs, nets
+
+pytestmark = pytest.mark.gpu
+TOL_F16 = 1e-2
+
+
+@pytest.fixture(scope="module")
+def G():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from tests import gpu_util
+    return gpu_util
+
+
+# ------------------------------------------------------------------------------ scale folding
+@pytest.mark.parametrize("dt", ["f16", "f32"])
+@pytest.mark.parametrize("axis", ["out", "in"])
+def test_fold_scale_axis_is_bit_exact(G, dt, axis):
+    from paper_1904_08368_amd import binding as B
+    rng = np.random.default_rng(11)
+    k, c, r = 37, 21, 3
+    w = rng.standard_normal((k, c, r, r)).astype(np.float16 if dt == "f16" else np.float32)
+    w[0, 0, 0, 0] = 1.0 + 2.0 ** -10            # products that land near fp16 rounding boundaries
+    w[1, 1] = 6.1e-5                            # around the fp16 subnormal threshold
+    s = (1.0 + 0.1 * rng.standard_normal(c if axis == "in" else k)).astype(np.float32)
+    s[0] = np.float32(1.0 + 2.0 ** -11 + 2.0 ** -23)
+    wd, sd = G.up(w), G.up(s)
+    out = torch.empty_like(wd)
+    B.relay_fold_scale_axis(B.RELAY_F16 if dt == "f16" else B.RELAY_F32, k, c, r * r,
+                            B.FOLD_IN if axis == "in" else B.FOLD_OUT, wd, sd, out)
+    torch.cuda.synchronize()
+    want = OC.fold_scale_axis(w, s, axis, dt)
+    got = out.cpu().numpy()
+    assert got.dtype == want.dtype and np.array_equal(got.view(np.uint16 if dt == "f16" else np.uint32),
+                                                      want.view(np.uint16 if dt == "f16" else np.uint32))
+    # in place
+    B.relay_fold_scale_axis(B.RELAY_F16 if dt == "f16" else B.RELAY_F32, k, c, r * r,
+                            B.FOLD_IN if axis == "in" else B.FOLD_OUT, wd, sd, wd)
+    torch.cuda.synchronize()
+    assert np.array_equal(wd.cpu().numpy(), want)
+
+
+def test_fold_bias_is_bit_exact(G):
+    from paper_1904_08368_amd import binding as B
+    rng = np.random.default_rng(12)
+    k = 300
+    b, sc, sf = (rng.standard_normal(k).astype(np.float32) for _ in range(3))
+    out = torch.empty(k, dtype=torch.float32, device=G.DEV)
+    for bias in (b, None):
+        B.relay_fold_bias(k, G.up(bias), G.up(sc), G.up(sf), out)
+        torch.cuda.synchronize()
+        p = {"w": np.zeros((k, 1, 1, 1), np.float32), "scale": sc, "shift": sf}
+        if bias is not None:
+            p["bias"] = bias
+        want = OC.fold_bn_into_conv(p, "f32")["bias"]
+        assert np.array_equal(out.cpu().numpy().view(np.uint32), want.view(np.uint32))
+
+
+# ------------------------------------------------------------------------ parallel combination
+def _members(cin, couts, r, seed, bias=False):
+    ops = [nets.conv(f"m{j}", "x", f"m{j}", cin, k, r, 1, r // 2, bias=bias) for j, k in enumerate(couts)]
+    return ops, [inputs.layer_params(op, 21, 10 * seed + j, "f16") for j, op in enumerate(ops)]
+
+
+def _run_combined(G, x, ops, params, stride, pad, relu, x_wide=0, x_off=0, out_plan=None, tile=-1):
+    """x [N,C,H,W] fp16 -> list of member outputs (NCHW numpy) plus the raw output tensors.
+    x_wide > 0: the input is channels [x_off, x_off + C) of an NHWC tensor of x_wide channels.
+    out_plan[i] = (buffer index, first channel, buffer channels) places segment i; default: own tensors."""
+    from paper_1904_08368_amd import binding as B
+    n, c, h, w = x.shape
+    r = ops[0].r
+    couts = [o.cout for o in ops]
+    flags = B.flags_of(params[0].get("bias"), params[0].get("scale"), None, relu)
+    d = B.conv_desc(n, c, h, w, sum(couts), r, r, stride, pad, B.RELAY_F16, B.RELAY_NHWC, flags)
+    ho, wo = B.relay_conv2d_out_shape(d)
+    xd = G.to_nhwc(x, c, B.RELAY_F16)
+    if x_wide:
+        wide = torch.full((n, h, w, x_wide), 99.0, dtype=torch.float16, device=G.DEV)
+        wide[..., x_off:x_off + c] = xd
+        xd = wide[..., x_off:x_off + c]
+    wp = torch.empty(B.relay_packed_weight_bytes(d), dtype=torch.uint8, device=G.DEV)
+    off = 0
+    for o, p in zip(ops, params):
+        dm = B.conv_desc(n, c, h, w, o.cout, r, r, stride, pad, B.RELAY_F16, B.RELAY_NHWC, flags)
+        nb = B.relay_packed_weight_bytes(dm)
+        B.relay_prepack_conv2d_weights(dm, G.up(p["w"]), c, wp[off:off + nb])
+        off += nb
+    cat = lambda key: None if params[0].get(key) is None else G.up(np.concatenate([p[key] for p in params]))
+    bufs = {}
+    ys = []
+    for i, k in enumerate(couts):
+        bi, c0, cw = out_plan[i] if out_plan else (i, 0, k)
+        if bi not in bufs:
+            bufs[bi] = torch.full((n, ho, wo, cw), -77.0, dtype=torch.float16, device=G.DEV)
+        ys.append(bufs[bi][..., c0:c0 + k])
+    B.relay_set_conv_tile(tile)
+    try:
+        B.relay_fused_conv2d_combined(d, xd, xd.stride(2), wp, cat("bias"), cat("scale"), cat("shift"), couts, ys,
+                                      [y.stride(2) for y in ys])
+    finally:
+        B.relay_set_conv_tile(-1)
+    torch.cuda.synchronize()
+    return [G.from_nhwc(y, k) for y, k in zip(ys, couts)], bufs
+
+
+def _check_members(x, ops, params, outs, stride, pad, relu):
+    for o, p, got in zip(ops, params, outs):
+        want = O.fused_conv2d(x, p["w"], stride=(stride, stride), pad=(pad, pad), bias=p.get("bias"),
+                              scale=p.get("scale"), shift=p.get("shift"), relu_flag=relu, out_dtype="f16")
+        assert got.shape == want.shape
+        assert O.max_rel_err(got, want) <= TOL_F16, o.name
+
+
+def test_inception_1x1_members_into_their_own_tensors(G):
+    ops, params = _members(256, (128, 128, 32), 1, 0)
+    x = inputs.activation(21, 0, (2, 256, 28, 28), "f16")
+    outs, _ = _run_combined(G, x, ops, params, 1, 0, True)
+    _check_members(x, ops, params, outs, 1, 0, True)
+    assert all(o.min() >= 0 for o in outs)
+
+
+@pytest.mark.parametrize("tile", [-1, 3, 4, 5, 9, 10, 16])
+def test_ragged_segments_views_on_both_sides(G, tile):
+    """Segment boundaries off the wave tiles (8, 24, 40 channels), a pixel count that is no multiple of
+    any tile, the input a channel range of a wider tensor, two segments inside one wider output tensor
+    whose other channels must stay untouched."""
+    ops, params = _members(64, (8, 24, 40), 3, 1, bias=True)
+    x = inputs.activation(21, 1, (3, 64, 9, 7), "f16")
+    plan = [(0, 16, 64), (1, 0, 24), (0, 24, 64)]        # segment 0 -> buf0[16:24], 2 -> buf0[24:64]
+    outs, bufs = _run_combined(G, x, ops, params, 1, 1, True, x_wide=96, x_off=32, out_plan=plan, tile=tile)
+    _check_members(x, ops, params, outs, 1, 1, True)
+    assert torch.all(bufs[0][..., :16] == -77.0)
+
+
+def test_strided_conv_and_no_tail(G):
+    ops, params = _members(32, (16, 48), 3, 2)
+    for p in params:
+        p.pop("scale"), p.pop("shift")
+    x = inputs.activation(21, 2, (2, 32, 11, 13), "f16")
+    outs, _ = _run_combined(G, x, ops, params, 2, 1, False)
+    _check_members(x, ops, params, outs, 2, 1, False)
+    assert min(o.min() for o in outs) < 0
+
+
+def test_one_segment_equals_the_plain_entry_point(G):
+    ops, params = _members(128, (96,), 3, 3)
+    x = inputs.activation(21, 3, (2, 128, 14, 14), "f16")
+    outs, _ = _run_combined(G, x, ops, params, 1, 1, True)
+    p = params[0]
+    plain = G.run_conv_f16(x, p["w"], 1, 1, scale=p["scale"], shift=p["shift"], relu=True)
+    assert np.array_equal(outs[0], plain)
+
+
+# ------------------------------------------------------------------------------ whole blocks
+def _block(G, combine, fold_scale=False, batch=2, hw=28):
+    from paper_1904_08368_amd import fusion
+    from paper_1904_08368_amd.stack import FusedNet
+    from workloads import graphs
+    ops = fusion.fuse(graphs.inception_block())
+    table = nets.inception_block()
+    params = inputs.net_params(table, 22, "f16")
+    x = inputs.image(22, batch, 256, hw, hw, "f16")
+    net = FusedNet(ops, params, batch, hw, hw, "f16", in_channels=256, combine=combine, fold_scale=fold_scale)
+    net.load_input(x)
+    net.run()
+    torch.cuda.synchronize()
+    return net, ops, table, params, x
+
+
+@pytest.mark.parametrize("combine", [False, True])
+def test_inception_block_from_its_graph(G, combine):
+    net, ops, table, params, x = _block(G, combine)
+    ref = run_float(table, params, x, "f16")
+    for a, b in zip(ops, table):
+        assert O.max_rel_err(net.tensor(a.dst), ref[b.dst]) <= TOL_F16, a.name
+    assert net.tensor("cat").shape == ref["cat"].shape == (2, 480, 28, 28)
+    convs = [n for n in net.call_names if n not in ("nchw_to_nhwc", "pool")]
+    assert len(convs) == (4 if combine else 6) and ("b1+b3r+b5r" in convs) == combine
+
+
+def test_combined_and_separate_blocks_agree_bit_for_bit(G):
+    a = _block(G, False)[0].tensor("cat")
+    b = _block(G, True)[0].tensor("cat")
+    assert np.array_equal(a, b)
+
+
+def test_scale_folding_on_networks(G):
+    """Folded networks against the oracle run on folded parameters (the same rewrite done in fp64)."""
+    net, ops, table, params, x = _block(G, True, fold_scale=True)
+    folded = [OC.fold_bn_into_conv(p, "f16") if p else p for p in params]
+    ref = run_float(table, folded, x, "f16")
+    assert O.max_rel_err(net.tensor("cat"), ref["cat"]) <= TOL_F16
+    # and within fp16 rounding of the unfolded network
+    assert O.max_rel_err(net.tensor("cat"), run_float(table, params, x, "f16")["cat"]) <= 2e-2
+    # ResNet basic block: the residual conv takes the folded form through the plain entry point
+    from paper_1904_08368_amd.stack import FusedNet
+    table = nets.basic_block(64)
+    params = inputs.net_params(table, 2, "f16")
+    x = inputs.image(2, 1, 64, 56, 56, "f16")
+    net = FusedNet(table, params, 1, 56, 56, "f16", in_channels=64, fold_scale=True)
+    net.load_input(x)
+    net.run()
+    torch.cuda.synchronize()
+    ref = run_float(table, [OC.fold_bn_into_conv(p, "f16") for p in params], x, "f16")
+    assert O.max_rel_err(net.tensor("blk.out"), ref["blk.out"]) <= TOL_F16
