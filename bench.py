@@ -261,6 +261,22 @@ def main() -> int:
             "pointwise_tflops": round(sum(r["gflop"] for r in pw) / sum(r["us"] for r in pw) * 1e3, 2),
             "layers": [{k: (round(v, 3) if isinstance(v, float) else v) for k, v in r.items()} for r in mrows]}
         del mn
+        # ---- parallel convolution combination (paper Section 4.4) on an Inception-shaped block, batch 32:
+        #      the three 1x1 convs that read the block input as one launch instead of three
+        iops = fusion.fuse(graphs.inception_block())
+        ip = inputs.net_params(iops, 22, "f16")
+        res = {}
+        for tag, kw in (("separate", {}), ("combined", {"combine": True}),
+                        ("combined_scale_folded", {"combine": True, "fold_scale": True})):
+            inet = FusedNet(iops, ip, 32, 28, 28, "f16", in_channels=256, **kw)
+            inet.load_input(inputs.image(22, 32, 256, 28, 28, "f16"))
+            if use_graph:
+                inet.capture()
+            res[tag + "_ms"] = round(_time_steps(inet, a.steps, a.warmup, use_graph) * 1e3, 4)
+            res[tag + "_launches"] = len(inet.calls)
+            del inet
+        res["speedup_from_combination"] = round(res["separate_ms"] / res["combined_ms"], 3)
+        extra["parallel_conv_combination_inception_block_b32"] = res
 
     if not a.no_cpu:
         # ---- the CPU oracle on this host: 4 of the 32 images, one pass of the same stack
