@@ -69,7 +69,19 @@ typedef struct {
 /* Ho = floor((h + 2*pad_h - r)/stride_h) + 1, Wo likewise.  Validates the geometry. */
 relay_status relay_conv2d_out_shape(const relay_conv2d_desc* d, int32_t* ho, int32_t* wo);
 
-/* Bytes of device scratch the conv entry points need for this descriptor (may be 0). */
+/* Bytes of device scratch the conv entry points (relay_fused_conv2d_bias_bn_relu, relay_qconv2d_requant*)
+ * can use for this descriptor; 0 for most layers.  A layer with few output tiles and a long reduction
+ * (the deep layers at small batch) is split along the reduction over several workgroups per tile, which
+ * leave partial sums and a per-tile arrival count in the workspace; the last to arrive adds the partials
+ * in a fixed order (results do not depend on timing; int8 stays bit-exact) and runs the fused tail.
+ * Workspace contract of those entry points:
+ *   workspace == NULL            the layer runs unsplit (always valid, slower for such layers)
+ *   workspace != NULL            device memory, 256-byte aligned, workspace_bytes >= this size, else
+ *                                RELAY_ERR_ALIGN / RELAY_ERR_WORKSPACE; its first bytes (the counts) must
+ *                                be ZERO before the first call that uses it -- zero the whole buffer once;
+ *                                every call leaves them zero again, so the buffer can be reused by later
+ *                                calls in the same stream (or replayed from a graph) without clearing.
+ * Calls that may overlap in time (different streams) need workspaces of their own. */
 relay_status relay_workspace_bytes(const relay_conv2d_desc* d, size_t* bytes);
 
 /* Size of the packed filter tensor, and the packing itself -- compile-time work in the
@@ -235,6 +247,10 @@ relay_status relay_nchw_to_nhwc(int32_t dtype, int32_t n, int32_t c, int32_t h, 
  * by this process (0 .. count-1, largest first; negative = choose by layer shape, the
  * default).  Results do not depend on the tile (int8: bit for bit). */
 relay_status relay_set_conv_tile(int32_t tile);
+/* Tuning aid: workgroups per output tile of later conv calls that are given a workspace
+ * (0 = choose by layer shape, the default; 1 = never split; n <= 64, clamped to the number of
+ * reduction chunks).  relay_workspace_bytes follows the setting. */
+relay_status relay_set_conv_split(int32_t split);
 
 /* Profiling aid: the name, as a kernel trace prints it, of the implicit-GEMM kernel variant
  * a fp16 / int8 descriptor runs on (template arguments give the workgroup's wave grid and

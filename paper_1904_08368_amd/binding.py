@@ -63,6 +63,7 @@ SIGNATURES = {
     "relay_fold_scale_axis": [_I, _I, _I, _I, _I, _P, _P, _P, _P],
     "relay_fold_bias": [_I, _P, _P, _P, _P, _P],
     "relay_set_conv_tile": [_I],
+    "relay_set_conv_split": [_I],
     "relay_conv2d_kernel_name": [_DP, C.c_char_p, _SZ],
 }
 
@@ -251,3 +252,7 @@ def relay_conv2d_kernel_name(d: ConvDesc) -> str:
 
 def relay_set_conv_tile(tile: int) -> None:
     _check(lib().relay_set_conv_tile(tile))
+
+
+def relay_set_conv_split(split: int) -> None:
+    _check(lib().relay_set_conv_split(split))

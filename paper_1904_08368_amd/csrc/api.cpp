@@ -117,6 +117,7 @@ relay_status device_status(hipError_t e, const char* what) {
 }
 
 int g_force_tile = -1;
+int g_force_split = 0;  // 0: by layer shape; n >= 1: n workgroups per tile where the kernel can split
 
 // implicit-GEMM paths: which (dtype, layout, channel count) combinations have a kernel
 relay_status check_igemm_support(const relay_conv2d_desc* d) {
@@ -151,12 +152,21 @@ relay_status relay_conv2d_out_shape(const relay_conv2d_desc* d, int32_t* ho, int
   return RELAY_OK;
 }
 
+// Split of the reduction over workgroups for this layer (1: none) and the workspace it takes.
+// Only the direct-to-LDS implicit GEMM splits; a layer that goes to another kernel gets 1.
+static int plan_split(const relay::ConvArgs& a, bool is_i8, size_t* counter_bytes, size_t* total_bytes);
+
 relay_status relay_workspace_bytes(const relay_conv2d_desc* d, size_t* bytes) {
   if (!bytes) return fail(RELAY_ERR_NULL, "bytes is NULL");
   int oh, ow;
   relay_status st = check_geometry(d, &oh, &ow);
   if (st != RELAY_OK) return st;
-  *bytes = 0;  // every kernel keeps its partial sums in registers
+  *bytes = 0;  // most layers keep their partial sums in registers
+  if ((d->dtype == RELAY_F16 || d->dtype == RELAY_I8) && check_igemm_support(d) == RELAY_OK) {
+    const relay::ConvArgs a = make_args(d, oh, ow);
+    size_t cb = 0;
+    plan_split(a, d->dtype == RELAY_I8, &cb, bytes);
+  }
   return RELAY_OK;
 }
 
@@ -247,6 +257,34 @@ static int halo_choice(const relay::ConvArgs& a, bool is_i8) {
   return g_force_tile == -1 ? relay::conv_halo_pick(a, is_i8) : -1;
 }
 
+static int plan_split(const relay::ConvArgs& a, bool is_i8, size_t* counter_bytes, size_t* total_bytes) {
+  *counter_bytes = *total_bytes = 0;
+  if (halo_choice(a, is_i8) >= 0 || !relay::igemm_dma_supported(a, is_i8)) return 1;
+  return relay::igemm_dma_plan_split(a, is_i8, g_force_tile, g_force_split, counter_bytes, total_bytes);
+}
+
+relay_status relay_set_conv_split(int32_t split) {
+  if (split < 0 || split > 64) return fail(RELAY_ERR_UNSUPPORTED, "split=%d outside 0..64", split);
+  g_force_split = split;
+  return RELAY_OK;
+}
+
+// Takes the caller's workspace into the arguments if this layer splits its reduction.
+static relay_status use_workspace(relay::ConvArgs& a, bool is_i8, void* workspace, size_t workspace_bytes) {
+  a.split = 1;
+  if (!workspace) return RELAY_OK;  // without a workspace every tile is reduced by one workgroup
+  size_t cb = 0, need = 0;
+  const int split = plan_split(a, is_i8, &cb, &need);
+  if (split <= 1) return RELAY_OK;
+  if (!aligned(workspace, 256)) return fail(RELAY_ERR_ALIGN, "workspace must be 256-byte aligned");
+  if (workspace_bytes < need)
+    return fail(RELAY_ERR_WORKSPACE, "workspace has %zu bytes, relay_workspace_bytes asks for %zu", workspace_bytes, need);
+  a.split = split;
+  a.ws_cnt = static_cast<unsigned*>(workspace);
+  a.ws_part = reinterpret_cast<unsigned*>(static_cast<char*>(workspace) + cb);
+  return RELAY_OK;
+}
+
 static hipError_t launch_igemm(const relay::ConvArgs& a, bool is_i8, hipStream_t s) {
   const int hv = halo_choice(a, is_i8);
   if (hv >= 0) return relay::launch_conv_halo(a, is_i8, hv, s);
@@ -277,8 +315,6 @@ relay_status relay_fused_conv2d_bias_bn_relu(const relay_conv2d_desc* d, const v
                                              const float* bias, const float* bn_scale, const float* bn_shift,
                                              const void* residual, void* y, void* workspace,
                                              size_t workspace_bytes, void* hip_stream) {
-  (void)workspace;
-  (void)workspace_bytes;
   int ho, wo;
   relay_status st = check_geometry(d, &ho, &wo);
   if (st != RELAY_OK) return st;
@@ -302,6 +338,7 @@ relay_status relay_fused_conv2d_bias_bn_relu(const relay_conv2d_desc* d, const v
   if ((st = check_igemm_support(d)) != RELAY_OK) return st;
   if (!aligned(x, 16) || !aligned(w_packed, 16) || !aligned(y, 16) || (residual && !aligned(residual, 16)))
     return fail(RELAY_ERR_ALIGN, "fp16 tensors must be 16-byte aligned");
+  if ((st = use_workspace(a, false, workspace, workspace_bytes)) != RELAY_OK) return st;
   return device_status(launch_igemm(a, false, s), "conv2d fp16 launch");
 }
 
@@ -392,8 +429,6 @@ relay_status relay_qconv2d_requant_rounding(const relay_conv2d_desc* d, const in
                                             const int32_t* bias, const int8_t* residual, int32_t residual_lshift,
                                             int32_t out_rshift, int32_t round_mode, uint64_t seed, int8_t* y,
                                             void* workspace, size_t workspace_bytes, void* hip_stream) {
-  (void)workspace;
-  (void)workspace_bytes;
   int ho, wo;
   relay_status st = check_geometry(d, &ho, &wo);
   if (st != RELAY_OK) return st;
@@ -420,6 +455,7 @@ relay_status relay_qconv2d_requant_rounding(const relay_conv2d_desc* d, const in
                 : round_mode == RELAY_ROUND_NEAREST ? 1 << (out_rshift - 1)
                 : round_mode == RELAY_ROUND_CEIL ? (int)((1u << out_rshift) - 1u) : 0;
   finish_args(a);
+  if ((st = use_workspace(a, true, workspace, workspace_bytes)) != RELAY_OK) return st;
   return device_status(launch_igemm(a, true, static_cast<hipStream_t>(hip_stream)), "qconv2d launch");
 }
 

@@ -207,7 +207,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_halo_kernel
   constexpr int PPI = 64 / CG;
   const int epix = lane / CG, ecg = lane % CG;
   const bool vec_ok = (a.K & 7) == 0;
-  const OutLoc ol = locate_output(a, ech);
+  const OutLoc ol{nullptr, 0, 0};  // this kernel stores plain tensors only
 #pragma unroll
   for (int tm = 0; tm < TM; ++tm) {
 #pragma unroll
@@ -304,7 +304,7 @@ bool conv_halo_supported(const ConvArgs& a, bool is_i8, int v) {
   const int es = is_i8 ? 1 : 2, ve = is_i8 ? 16 : 8;
   if (a.R != 3 || a.S != 3 || a.sh != 1 || a.sw != 1 || a.ph != 1 || a.pw != 1) return false;
   if (a.xs_w != a.C || a.xs_h != a.W * a.C || a.xs_n != a.H * a.W * a.C) return false;
-  if (a.C % (BKV * ve) != 0 || a.round_mode == ROUND_STOCHASTIC) return false;
+  if (a.C % (BKV * ve) != 0 || a.round_mode == ROUND_STOCHASTIC || a.nseg) return false;
   if ((size_t)a.N * a.xs_n * es > 0x7fffffffu || (size_t)a.K * a.Kp * es > 0x7fffffffu) return false;
   HaloGeom g;
   size_t lds_bytes;

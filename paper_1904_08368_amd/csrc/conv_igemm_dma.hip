@@ -28,6 +28,7 @@
 // Needs C to be a whole number of chunks (32 halves / 64 int8) and R*S <= 32; other shapes
 // go to the register-staged kernel in conv_igemm.hip.
 #include <cstdio>
+#include <type_traits>
 
 #include "dma_common.hpp"
 
@@ -43,7 +44,17 @@ namespace {
 // resource the small tiles are bound by.
 // STOCH: the stochastic rounding of the quantized epilogue (its generator costs registers, so it is an
 // instantiation of its own; the deterministic rules are one host-computed addend).
-template <bool IS_I8, int WAVES_M, int WAVES_N, int TM, int TN, int NS, int KP, int SK, bool STOCH>
+// Arrival counters of different tiles sit 256 bytes apart: device-scope atomics on one line
+// are served one after another.
+constexpr int kCntStride = 64;
+
+template <bool IS_I8>
+using acc_t_scalar = typename std::conditional<IS_I8, int, float>::type;
+
+// EXT: the instantiation that can split a tile's reduction over workgroups and store output
+// channel segments.  Both are rare; kept out of the plain kernel because even as untaken uniform
+// branches they cost it about 1 % each (registers held across the main loop, code size).
+template <bool IS_I8, int WAVES_M, int WAVES_N, int TM, int TN, int NS, int KP, int SK, bool STOCH, bool EXT>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
                              // two workgroups per CU where their LDS rings fit side by side
                              (NS * KP * (WAVES_M * TM + WAVES_N * TN) * 32 * 64 <= 80 * 1024 ? 2 : 1))
@@ -78,7 +89,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
   const int wk = wave / (WAVES_M * WAVES_N), wsub = wave % (WAVES_M * WAVES_N);
   const int wm = wsub % WAVES_M, wn = wsub / WAVES_M;
   const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.K + BN - 1) / BN;
-  const int tile = xcd_remap(blockIdx.x, tiles_m * tiles_n);
+  // with a split reduction consecutive workgroups (same XCD) share a tile
+  const int nsplit = (EXT && a.split > 1) ? a.split : 1;
+  const int wg = xcd_remap(blockIdx.x, tiles_m * tiles_n * nsplit);
+  const int tile = wg / nsplit, ks = wg - tile * nsplit;
   const int tile_n = a.n_major ? tile / tiles_m : tile % tiles_n;
   const int tile_m = a.n_major ? tile % tiles_m : tile / tiles_n;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
@@ -125,12 +139,23 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
   const intx4 rs_w = make_rsrc(a.w, (unsigned)((size_t)a.K * a.Kp * ES));
   const unsigned ring_base = (unsigned)(size_t)(__attribute__((address_space(3))) uint4*)(&ring[0]);
 
-  const int nchunks = a.Kred / CK;
+  // this workgroup reduces chunks [kbeg, nchunks) of the layer's Kred / CK
+  const int all_chunks = a.Kred / CK;
+  const int per_split = (all_chunks + nsplit - 1) / nsplit;
+  const int kbeg = ks * per_split;
+  const int nchunks = min(all_chunks, kbeg + per_split);
   // reduction position of the chunk being issued (wave-uniform); chunks past the end are
   // issued as all-out-of-range loads into a free stage so that every iteration looks alike
-  int is_tap = 0, is_r = 0, is_s = 0, is_c = 0, is_kc = 0;
-  unsigned is_delta = 0, is_sbase = ring_base;
-  bool is_live = nchunks > 0;
+  int is_tap = 0, is_r = 0, is_s = 0, is_c = 0, is_kc = kbeg;
+  if (kbeg) {  // (uniform) position of the first chunk
+    const int per_tap = a.C / CK;
+    is_tap = kbeg / per_tap;
+    is_c = (kbeg - is_tap * per_tap) * CK;
+    is_r = is_tap / a.S;
+    is_s = is_tap - is_r * a.S;
+  }
+  unsigned is_delta = (unsigned)((is_r * a.xs_h + is_s * a.xs_w + is_c) * ES), is_sbase = ring_base;
+  bool is_live = is_kc < nchunks;
   auto issue_one = [&](int idx) {  // idx-th load of the chunk: per plane XL activation blocks, then WL filter blocks
     const int plane = idx / (XL + WL), i = idx % (XL + WL);
     const unsigned pbase = is_sbase + (unsigned)(plane * PLANE) * 16u;
@@ -189,7 +214,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
   const int lrow = lane & 31, lhalf = lane >> 5;
   int stage = 0;      // ring stage of chunk kc
   int fill = NS - 1;  // ring stage the chunk issued during this iteration lands in (set by next_chunk above)
-  for (int kc = 0; kc < nchunks; ++kc) {
+  for (int kc = kbeg; kc < nchunks; ++kc) {
     // chunk kc has landed once only the loads of the NS-2 chunks issued after it are pending
     wait_loads<(NS - 2) * LPC>();
     __builtin_amdgcn_s_barrier();  // everyone's part of chunk kc is in LDS; stage `fill` is free again
@@ -287,7 +312,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
   constexpr int PPI = 64 / CG;  // pixels per pass of 64 lanes
   const int epix = lane / CG, ecg = lane % CG;
   const bool vec_ok = (a.K & 7) == 0;
-  const OutLoc ol = locate_output(a, ech);
+  const OutLoc ol = EXT ? locate_output(a, ech) : OutLoc{nullptr, 0, 0};
 #pragma unroll
   for (int te = 0; te < TM_E; ++te) {
     const int tm = tm_lo + te;  // block row in the workgroup tile
@@ -317,7 +342,76 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
       const unsigned raw[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
       const int m = m0 + wm * WTM + tm * 32 + pix;
       if (m >= a.M || ech >= a.K) continue;
-      finish_store8<IS_I8, STOCH>(a, raw, m, ech, lp, ol, vec_ok);
+      if (EXT && nsplit > 1) {  // (uniform) leave the raw partial sums for the workgroup that finishes the tile
+        uint4* pp = reinterpret_cast<uint4*>(
+            a.ws_part + ((size_t)(tile * nsplit + ks) * BM + (wm * WTM + tm * 32 + pix)) * BN + (ech - n0));
+        pp[0] = lo;
+        pp[1] = hi;
+      } else {
+        finish_store8<IS_I8, STOCH, EXT>(a, raw, m, ech, lp, ol, vec_ok);
+      }
+    }
+  }
+  if (EXT && nsplit > 1) {
+    // The workgroup that counts itself last owns the tile.  The XCDs' L2s are not coherent with
+    // each other, so the partial tiles are released to device scope before the count (an L2
+    // write-back) and acquired after it (an L2 invalidate).  One wave does that for the whole
+    // workgroup, behind a barrier that has every wave's stores in L2: these fences act on the whole
+    // L2, one per wave measured ~0.1 us per workgroup, serialised.  (Device-scope atomic stores and
+    // loads for the partial sums themselves were far slower still.)  The winner leaves the counter
+    // at zero for the next launch.  Nobody waits for anybody: the other workgroups are done once
+    // they have counted.
+    __shared__ int s_last;
+    __syncthreads();
+    if (tid == 0) {
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+      const unsigned old = atomicAdd(a.ws_cnt + tile * kCntStride, 1u);
+      s_last = old == (unsigned)(nsplit - 1);
+      if (s_last) {
+        atomicExch(a.ws_cnt + tile * kCntStride, 0u);
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+      }
+    }
+    __syncthreads();
+    if (!s_last) return;
+    // A lane finishes NPOS positions of 1 pixel x 8 channels, one after another (this code must not
+    // cost the main loop registers).  The partial tiles are added in split order, so the result does
+    // not depend on who arrived when; JB of them are in flight at a time, because every load is a
+    // round trip to memory (other XCDs wrote them).
+    constexpr int NIT = 32 / PPI, NPOS = TM_E * NIT, JB = 8;
+    typedef acc_t_scalar<IS_I8> sum_t;
+    const unsigned* tile_part = a.ws_part + (size_t)tile * nsplit * BM * BN;
+#pragma unroll 1
+    for (int pos = 0; pos < NPOS; ++pos) {
+      const int tm = tm_lo + pos / NIT, pix = (pos % NIT) * PPI + epix;
+      const int m = m0 + wm * WTM + tm * 32 + pix;
+      if (m >= a.M || ech >= a.K) continue;
+      const unsigned* at = tile_part + (unsigned)((wm * WTM + tm * 32 + pix) * BN + (ech - n0));
+      sum_t sum[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) sum[e] = 0;
+#pragma unroll 1
+      for (int j = 0; j < nsplit; j += JB) {
+        uint4 lo[JB], hi[JB];
+#pragma unroll
+        for (int u = 0; u < JB; ++u) {
+          const int jj = j + u < nsplit ? j + u : nsplit - 1;  // (uniform) past the end: a repeat that is not added
+          const uint4* pp = reinterpret_cast<const uint4*>(at + (size_t)jj * BM * BN);
+          lo[u] = pp[0];
+          hi[u] = pp[1];
+        }
+#pragma unroll
+        for (int u = 0; u < JB; ++u)
+          if (j + u < nsplit) {
+            const unsigned r[8] = {lo[u].x, lo[u].y, lo[u].z, lo[u].w, hi[u].x, hi[u].y, hi[u].z, hi[u].w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sum[e] += __builtin_bit_cast(sum_t, r[e]);
+          }
+      }
+      unsigned raw[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) raw[e] = as_u32(sum[e]);
+      finish_store8<IS_I8, STOCH, EXT>(a, raw, m, ech, lp, ol, vec_ok);
     }
   }
 }
@@ -357,9 +451,13 @@ constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 template <bool IS_I8, bool STOCH, int WAVES_M, int WAVES_N, int TM, int TN, int NS, int KP, int SK = 1>
 hipError_t launch_one(const ConvArgs& a, hipStream_t st) {
   constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
-  const int tiles = ((a.M + BM - 1) / BM) * ((a.K + BN - 1) / BN);
-  hipLaunchKernelGGL((igemm_dma_kernel<IS_I8, WAVES_M, WAVES_N, TM, TN, NS, KP, SK, STOCH>), dim3(tiles),
-                     dim3(64 * WAVES_M * WAVES_N * SK), 0, st, a);
+  const int tiles = ((a.M + BM - 1) / BM) * ((a.K + BN - 1) / BN) * (a.split > 1 ? a.split : 1);
+  if (STOCH || a.nseg || a.split > 1)
+    hipLaunchKernelGGL((igemm_dma_kernel<IS_I8, WAVES_M, WAVES_N, TM, TN, NS, KP, SK, STOCH, true>), dim3(tiles),
+                       dim3(64 * WAVES_M * WAVES_N * SK), 0, st, a);
+  else
+    hipLaunchKernelGGL((igemm_dma_kernel<IS_I8, WAVES_M, WAVES_N, TM, TN, NS, KP, SK, false, false>), dim3(tiles),
+                       dim3(64 * WAVES_M * WAVES_N * SK), 0, st, a);
   return hipGetLastError();
 }
 
@@ -431,10 +529,40 @@ bool igemm_dma_supported(const ConvArgs& a, bool is_i8) {
 
 int igemm_dma_tile_count() { return kNumTiles; }
 
+int igemm_dma_plan_split(const ConvArgs& a, bool is_i8, int tile, int want, size_t* counter_bytes,
+                         size_t* total_bytes) {
+  const DmaTile& t = kTiles[resolve_tile(a, is_i8, tile)];
+  const int tiles = (int)tiles_of(a, t);
+  const int chunks = a.Kred / (t.kp * BKV * (is_i8 ? 16 : 8));
+  int split = want;
+  if (split <= 0) {
+    // Few tiles and a long reduction (the deep layers at small batch): the reduction is what can
+    // still be spread over the idle CUs.  Handing a tile over costs about as much as six chunks of
+    // the main loop and grows with the number of workgroups (measured on 7x7 and 14x14 layers of
+    // 256 and 512 channels at batch 1 to 16): at least six chunks per workgroup, at most 128
+    // workgroups, and only layers of at most 32 tiles.
+    split = 1;
+    if (tiles <= 32 && chunks >= 12) {
+      split = 128 / tiles;
+      if (split > chunks / 6) split = chunks / 6;
+      if (split > 16) split = 16;
+    }
+  }
+  if (split > chunks) split = chunks;
+  if (split < 1) split = 1;
+  const int per = (chunks + split - 1) / split;
+  split = (chunks + per - 1) / per;  // every workgroup gets at least one chunk
+  *counter_bytes = (size_t)tiles * kCntStride * sizeof(unsigned);
+  *total_bytes = split > 1 ? *counter_bytes + (size_t)tiles * split * t.bm() * t.bn() * 4 : 0;
+  return split;
+}
+
 void igemm_dma_kernel_name(const ConvArgs& a, bool is_i8, int tile, char* buf, size_t len) {
   const DmaTile& t = kTiles[resolve_tile(a, is_i8, tile)];
-  snprintf(buf, len, "igemm_dma_kernel<%s, %d, %d, %d, %d, %d, %d, %d, %s>", is_i8 ? "true" : "false", t.waves_m,
-           t.waves_n, t.tm, t.tn, t.ns, t.kp, t.sk, is_i8 && a.round_mode == ROUND_STOCHASTIC ? "true" : "false");
+  const bool stoch = is_i8 && a.round_mode == ROUND_STOCHASTIC;
+  snprintf(buf, len, "igemm_dma_kernel<%s, %d, %d, %d, %d, %d, %d, %d, %s, %s>", is_i8 ? "true" : "false", t.waves_m,
+           t.waves_n, t.tm, t.tn, t.ns, t.kp, t.sk, stoch ? "true" : "false",
+           (stoch || a.nseg || a.split > 1) ? "true" : "false");
 }
 
 hipError_t launch_conv_igemm_dma(const ConvArgs& a, bool is_i8, int tile, hipStream_t st) {

@@ -139,11 +139,12 @@ __device__ __forceinline__ void load_lane_params(const ConvArgs& a, int ech, Lan
   }
 }
 
+// EXT: the instantiation that knows about output segments (the plain one ignores ol).
 // Finish the 8 consecutive channels [ech, ech + 8) of output pixel m (its index in the NHWC output;
 // residual and random draws are addressed in the plain [M][K] tensor, the store goes where ol says)
 // from the raw accumulator bits and store them (bias, scale/shift, residual, relu, cast -- or the
 // quantized epilogue, with STOCH the stochastic rounding).
-template <bool IS_I8, bool STOCH>
+template <bool IS_I8, bool STOCH, bool EXT = false>
 __device__ __forceinline__ void finish_store8(const ConvArgs& a, const unsigned (&raw)[8], int m, int ech,
                                               const LaneParams& lp, const OutLoc& ol, bool vec_ok) {
   const float(&emul)[8] = lp.mul;
@@ -172,7 +173,9 @@ __device__ __forceinline__ void finish_store8(const ConvArgs& a, const unsigned 
       if (a.flags & F_RELU) t[e] = t[e] > 0.f ? t[e] : 0.f;
       hv[e] = (_Float16)t[e];
     }
-    _Float16* yp = a.nseg ? static_cast<_Float16*>(ol.y) + ((size_t)m * ol.ldy + ol.cho) : static_cast<_Float16*>(a.y) + o;
+    _Float16* yp = static_cast<_Float16*>(a.y) + o;
+    if constexpr (EXT)
+      if (a.nseg) yp = static_cast<_Float16*>(ol.y) + ((size_t)m * ol.ldy + ol.cho);
     if (vec_ok) {
       *reinterpret_cast<half8*>(yp) = hv;
     } else {
@@ -211,7 +214,9 @@ __device__ __forceinline__ void finish_store8(const ConvArgs& a, const unsigned 
       t[e] = q;
       pk[e >> 2] |= (unsigned)(q & 0xff) << (8 * (e & 3));
     }
-    int8_t* yp = a.nseg ? static_cast<int8_t*>(ol.y) + ((size_t)m * ol.ldy + ol.cho) : static_cast<int8_t*>(a.y) + o;
+    int8_t* yp = static_cast<int8_t*>(a.y) + o;
+    if constexpr (EXT)
+      if (a.nseg) yp = static_cast<int8_t*>(ol.y) + ((size_t)m * ol.ldy + ol.cho);
     if (vec_ok) {
       *reinterpret_cast<uint2*>(yp) = make_uint2(pk[0], pk[1]);
     } else {

@@ -42,6 +42,14 @@ struct ConvArgs {
   // Section 4.4): channel ch in [seg_end[i-1], seg_end[i]) of output pixel m is stored at
   // seg_y[i] + m*seg_ld[i] + (ch - seg_end[i-1]) elements; boundaries are multiples of 8.
   // nseg == 0: the plain tensor y with pixel pitch K.  Only the direct-to-LDS kernels read these.
+  // Reduction split over workgroups (direct-to-LDS implicit GEMM only): `split` workgroups share one
+  // output tile, each reducing a contiguous run of chunks; they leave raw partial tiles in ws_part
+  // ([tile][split][BM][BN] accumulator words) and count themselves in ws_cnt[tile]; the workgroup
+  // that arrives last adds the partials in split order and runs the epilogue, then puts the
+  // counter back to zero.  split <= 1: one workgroup per tile, nothing of this is touched.
+  int split;
+  unsigned* ws_part;
+  unsigned* ws_cnt;
   int nseg;
   int seg_end[4];
   int seg_ld[4];
@@ -64,6 +72,10 @@ void igemm_kernel_name(const ConvArgs& a, bool is_i8, int tile, char* buf, size_
 // The direct-to-LDS variant (conv_igemm_dma.hip) and the shapes it takes.
 bool igemm_dma_supported(const ConvArgs& a, bool is_i8);
 hipError_t launch_conv_igemm_dma(const ConvArgs& a, bool is_i8, int tile, hipStream_t st);
+// How many workgroups should share a tile's reduction for this layer (1: none; `want` > 0 forces a
+// count, clamped to the number of chunks) and the bytes of zero-initialised device memory that takes:
+// counters first (counter_bytes, a multiple of 256), then the partial tiles.
+int igemm_dma_plan_split(const ConvArgs& a, bool is_i8, int tile, int want, size_t* counter_bytes, size_t* total_bytes);
 int igemm_dma_tile_count();
 void igemm_dma_kernel_name(const ConvArgs& a, bool is_i8, int tile, char* buf, size_t len);
 // The 3x3 / stride 1 / pad 1 kernel that stages the activations once per channel chunk (conv_halo.hip).

@@ -100,6 +100,7 @@ class FusedNet:
                 B.relay_prepack_conv2d_weights(d, wsrc, cin_l, wp)
                 y = torch.empty((batch, ho, wo, op.cout), dtype=self.tdtype, device=self.dev)
                 res = self.bufs[op.res] if op.res else None
+                ws = self._workspace(d)     # None for most layers
                 if mode == "f16" and not fused and flags:
                     d0 = B.conv_desc(d.n, d.c, d.h, d.w, d.k, d.r, d.s, d.stride_h, d.pad_h, self.dtype, d.layout, 0)
                     raw = torch.empty_like(y)
@@ -112,11 +113,11 @@ class FusedNet:
                     B.relay_prepack_conv2d_weights(d, wsrc, cin_l, wp)
                     d1 = B.conv_desc(d.n, d.c, d.h, d.w, d.k, d.r, d.s, d.stride_h, d.pad_h, self.dtype, d.layout,
                                      B.flags_of(True, None, op.res, op.relu))
-                    self._add(op.name, B.relay_fused_conv2d_bias_bn_relu, (d1, src, wp, bias, None, None, res, y))
+                    self._add(op.name, B.relay_fused_conv2d_bias_bn_relu, (d1, src, wp, bias, None, None, res, y, ws))
                     self.keep.append(d1)
                 elif mode == "f16":
                     bias, sc, sf = (self._f32(p.get(k)) for k in ("bias", "scale", "shift"))
-                    self._add(op.name, B.relay_fused_conv2d_bias_bn_relu, (d, src, wp, bias, sc, sf, res, y))
+                    self._add(op.name, B.relay_fused_conv2d_bias_bn_relu, (d, src, wp, bias, sc, sf, res, y, ws))
                 else:
                     sh = shifts[i]
                     qb = None
@@ -124,7 +125,7 @@ class FusedNet:
                         qb = torch.from_numpy(np.ascontiguousarray(p["bias"], dtype=np.int32)).to(self.dev)
                         self.keep.append(qb)
                     self._add(op.name, B.relay_qconv2d_requant,
-                              (d, src, wp, qb, res, int(sh.get("l", 0)), int(sh["s"]), y))
+                              (d, src, wp, qb, res, int(sh.get("l", 0)), int(sh["s"]), y, ws))
                 self.keep += [wp, d]
                 self.bufs[op.dst], self.shape[op.dst] = y, (op.cout, ho, wo)
             elif op.kind == "dwconv":
@@ -268,6 +269,16 @@ class FusedNet:
                   (d, src, src.stride(2), wp, joined["bias"], joined["scale"], joined["shift"],
                    [m.cout for m in members], ys, [y.stride(2) for y in ys]))
         self.keep += [wp, d, joined]
+
+    def _workspace(self, d):
+        """Zeroed scratch of a conv whose reduction the library splits over workgroups (the deep
+        layers at small batch), one buffer per conv so that convs on forked streams cannot share one."""
+        need = B.relay_workspace_bytes(d)
+        if need == 0:
+            return None
+        ws = torch.zeros(need, dtype=torch.uint8, device=self.dev)
+        self.keep.append(ws)
+        return ws
 
     def _fold(self, op, p, wsrc, cin_l):
         """Axis scale folding: multiplies the OIHW filters on the device by the conv's batch-norm

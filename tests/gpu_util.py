@@ -45,8 +45,22 @@ def _input(x, k, r, s, stride, pad, dtype, ve, flags, nhwc4):
     return d, to_nhwc(x, cp, dtype)
 
 
+def workspace_for(d, split, state=None):
+    """Zeroed workspace of the size the library asks for under a forced split (None if it asks for none).
+    state: a dict that keeps one buffer across calls, to exercise reuse without clearing."""
+    B.relay_set_conv_split(split)
+    need = B.relay_workspace_bytes(d)
+    if need == 0:
+        return None
+    if state is not None:
+        if state.get("ws") is None or state["ws"].numel() < need:
+            state["ws"] = torch.zeros(need, dtype=torch.uint8, device=DEV)
+        return state["ws"]
+    return torch.zeros(need, dtype=torch.uint8, device=DEV)
+
+
 def run_conv_f16(x, w, stride, pad, bias=None, scale=None, shift=None, residual=None, relu=False, tile=-1,
-                 nhwc4=True):
+                 nhwc4=True, split=None, ws_state=None):
     """x [N,C,H,W] fp16, w [K,C,R,S] fp16 (numpy) -> y NCHW fp16 (numpy), via the C ABI."""
     n, c, h, wd = x.shape
     k, _, r, s = w.shape
@@ -59,14 +73,17 @@ def run_conv_f16(x, w, stride, pad, bias=None, scale=None, shift=None, residual=
     y = torch.full((n, ho, wo, k), float("nan"), dtype=torch.float16, device=DEV)
     B.relay_set_conv_tile(tile)
     try:
-        B.relay_fused_conv2d_bias_bn_relu(d, xd, wp, up(bias), up(scale), up(shift), rd, y)
+        ws = None if split is None else workspace_for(d, split, ws_state)
+        B.relay_fused_conv2d_bias_bn_relu(d, xd, wp, up(bias), up(scale), up(shift), rd, y, ws)
     finally:
         B.relay_set_conv_tile(-1)
+        B.relay_set_conv_split(0)
     torch.cuda.synchronize()
     return from_nhwc(y, k)
 
 
-def run_qconv(x, w, stride, pad, bias=None, residual=None, lshift=0, rshift=0, relu=False, tile=-1, nhwc4=True):
+def run_qconv(x, w, stride, pad, bias=None, residual=None, lshift=0, rshift=0, relu=False, tile=-1, nhwc4=True,
+              split=None, ws_state=None, round_mode=None, seed=0):
     n, c, h, wd = x.shape
     k, _, r, s = w.shape
     flags = B.flags_of(bias, None, residual, relu)
@@ -79,9 +96,14 @@ def run_qconv(x, w, stride, pad, bias=None, residual=None, lshift=0, rshift=0, r
     bd = None if bias is None else up(np.asarray(bias, dtype=np.int32))
     B.relay_set_conv_tile(tile)
     try:
-        B.relay_qconv2d_requant(d, xd, wp, bd, rd, lshift, rshift, y)
+        ws = None if split is None else workspace_for(d, split, ws_state)
+        if round_mode is None:
+            B.relay_qconv2d_requant(d, xd, wp, bd, rd, lshift, rshift, y, ws)
+        else:
+            B.relay_qconv2d_requant_rounding(d, xd, wp, bd, rd, lshift, rshift, round_mode, seed, y, ws)
     finally:
         B.relay_set_conv_tile(-1)
+        B.relay_set_conv_split(0)
     torch.cuda.synchronize()
     return from_nhwc(y, k)
 

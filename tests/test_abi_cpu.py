@@ -75,7 +75,45 @@ def test_null_descriptor_and_outputs():
     assert _status("relay_conv2d_out_shape", None, C.byref(i), C.byref(i)) == 1
     assert _status("relay_conv2d_out_shape", C.byref(_d()), None, C.byref(i)) == 1
     assert _status("relay_workspace_bytes", C.byref(_d()), None) == 1
+    # a layer with many output tiles, or a short reduction, keeps its sums in registers; a deep layer at
+    # batch 1 is split along its reduction: 36 chunks over 6 workgroups for each of the 8 tiles of 64 x 64,
+    # behind one 256-byte counter line per tile
+    assert B.relay_workspace_bytes(_d(n=32, h=56, w=56)) == 0
     assert B.relay_workspace_bytes(_d()) == 0
+    deep = _d(c=512, k=512, h=7, w=7)
+    assert B.relay_workspace_bytes(deep) == 8 * 256 + 8 * 6 * 64 * 64 * 4
+    B.relay_set_conv_split(1)
+    try:
+        assert B.relay_workspace_bytes(deep) == 0
+    finally:
+        B.relay_set_conv_split(0)
+    B.relay_set_conv_split(3)
+    try:
+        assert B.relay_workspace_bytes(_d()) == 256 + 3 * 64 * 64 * 4
+    finally:
+        B.relay_set_conv_split(0)
+    with pytest.raises(B.RelayError):
+        B.relay_set_conv_split(65)
+
+
+def test_workspace_is_checked_before_any_launch():
+    B.relay_set_conv_split(3)
+    try:
+        _workspace_checks()
+    finally:
+        B.relay_set_conv_split(0)
+
+
+def _workspace_checks():
+    need = B.relay_workspace_bytes(_d())
+    assert need > 0
+    ws = FAKE + (1 << 20)
+    assert _status("relay_fused_conv2d_bias_bn_relu", C.byref(_d()), FAKE, FAKE, None, None, None, None, FAKE + 4096,
+                   ws + 16, need, None) == 5                                   # not 256-byte aligned
+    assert _status("relay_fused_conv2d_bias_bn_relu", C.byref(_d()), FAKE, FAKE, None, None, None, None, FAKE + 4096,
+                   ws, need - 1, None) == 6                                    # too small
+    assert _status("relay_qconv2d_requant", C.byref(_d(dtype=B.RELAY_I8)), FAKE, FAKE, None, None, 0, 8, FAKE + 4096,
+                   ws, 16, None) == 6
 
 
 def test_packed_weight_bytes_and_channel_alignment():
