@@ -504,7 +504,7 @@ int pick_tile(const ConvArgs& a, bool is_i8) {
   if (a.Kred <= 8 * BKV * (is_i8 ? 16 : 8) && tiles_of(a, kTiles[16]) >= 512) return 16;
   // 64 output channels over very many pixels in int8 (layer 1): tall tiles of 64 x 64 per wave
   if (a.K <= 64 && is_i8 && tiles_of(a, kTiles[14]) >= 384) return 14;
-  if (a.K > 64 && tiles_of(a, kTiles[0]) >= 512) return 0;
+  if (a.K > 64 && tiles_of(a, kTiles[0]) >= 384) return 0;  // (measured down to 392 tiles: 737 vs 613 TFLOP/s on 512 -> 512 at 28 x 28)
   const int mid = kp2 ? 9 : 4;
   if (tiles_of(a, kTiles[mid]) >= 190) return mid;
   // a layer that gives each CU at most one 64 x 64 workgroup can afford the 96 KiB ring of 256-byte chunks

@@ -306,3 +306,25 @@ def test_config5_mobilenet_batch32_sampled(G):
         rms = float(np.sqrt(np.mean(got.astype(np.float64) ** 2)))
         err = np.max(np.abs(gv - want.astype(np.float64)) / np.maximum(np.abs(want.astype(np.float64)), rms))
         assert err <= TOL_F16, f"{op.name}: {err}"
+
+
+# ------------------------------------------------- a second large vision model: the VGG-16 conv stack
+def test_vgg16_conv_stack_fp16_batch1(G):
+    """13 conv + bias + relu layers at their real sizes (up to 224 x 224 x 64 and 512 -> 512 channels),
+    built from the operator graph: every layer on the oracle's input, then the chain."""
+    from paper_1904_08368_amd import fusion
+    from workloads import graphs
+    table = nets.vgg16_convs()
+    ops = fusion.fuse(graphs.vgg16_convs())
+    params = inputs.net_params(table, 6, "f16")
+    x = inputs.image(6, 1, 3, 224, 224, "f16")
+    ref = run_float(table, params, x, "f16")
+    _per_layer_float(G, table, params, ref)
+    net = _net(ops, params, 1, 224, "f16")
+    net.load_input(x)
+    net.run()
+    torch.cuda.synchronize()
+    for a, b in zip(ops, table):
+        if b.name in ("conv1_1", "pool1", "conv3_3", "pool5"):
+            tol = TOL_F16 if b.name == "conv1_1" else TOL_F16_CHAIN
+            assert O.max_rel_err(net.tensor(a.dst), ref[b.dst]) <= tol, b.name

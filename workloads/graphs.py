@@ -10,7 +10,7 @@ from __future__ import annotations
 from dataclasses import dataclass, field
 from typing import Dict, List, Tuple
 
-from .nets import INCEPTION_WIDTHS, MOBILENET_V1_BLOCKS
+from .nets import INCEPTION_WIDTHS, MOBILENET_V1_BLOCKS, VGG16_CONV
 
 CONTRACTIONS = ("conv2d", "dwconv2d", "dense")
 ELEMENTWISE = ("bias_add", "scale_shift", "add", "relu")
@@ -102,6 +102,21 @@ def single_block(cin: int = 64) -> Graph:
     g = Graph()
     x = g.add("input", "x")
     basic_block(g, "blk", x, cin, cin, 1)
+    return g
+
+
+def vgg16_convs() -> Graph:
+    g = Graph()
+    cur, cin, blk, j = g.add("input", "x"), 3, 1, 1
+    for v in VGG16_CONV:
+        if v == "M":
+            cur = g.add("maxpool", f"pool{blk}", (cur,), r=2, stride=2, pad=0, cin=cin, cout=cin)
+            blk, j = blk + 1, 1
+        else:
+            c = g.add("conv2d", f"conv{blk}_{j}", (cur,), cin=cin, cout=v, r=3, stride=1, pad=1)
+            b = g.add("bias_add", f"conv{blk}_{j}.bias", (c,))
+            cur = g.add("relu", f"conv{blk}_{j}.relu", (b,))
+            cin, j = v, j + 1
     return g
 
 

@@ -95,6 +95,24 @@ def basic_block(c: int = 64) -> List[Op]:
     ]
 
 
+# VGG-16 (configuration D of its paper): 3x3 convs with bias and relu, no batch norm; "M" = 2x2 / stride 2 max pool
+VGG16_CONV = (64, 64, "M", 128, 128, "M", 256, 256, 256, "M", 512, 512, 512, "M", 512, 512, 512, "M")
+
+
+def vgg16_convs() -> List[Op]:
+    """The 13 fused conv + bias + relu layers and 5 pools of VGG-16 (the paper's second large vision
+    model, Section 5); the three dense layers behind them are left out."""
+    ops, cur, cin, blk, j = [], "x", 3, 1, 1
+    for v in VGG16_CONV:
+        if v == "M":
+            ops.append(Op("maxpool", f"pool{blk}", cur, f"p{blk}", cin=cin, cout=cin, r=2, stride=2, pad=0))
+            cur, blk, j = f"p{blk}", blk + 1, 1
+        else:
+            ops.append(conv(f"conv{blk}_{j}", cur, f"c{blk}_{j}", cin, v, 3, 1, 1, bn=False, bias=True))
+            cur, cin, j = f"c{blk}_{j}", v, j + 1
+    return ops
+
+
 # Width table of one Inception block: input channels, 1x1 branch, 3x3 reduce -> 3x3, 5x5 reduce -> 5x5,
 # pool projection.  (256, 128, 128, 192, 32, 96, 64) are the published widths of GoogLeNet's second
 # block at 28x28, chosen because every reduction length is a multiple of 32 channels.
