@@ -214,6 +214,16 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
   const int lrow = lane & 31, lhalf = lane >> 5;
   int stage = 0;      // ring stage of chunk kc
   int fill = NS - 1;  // ring stage the chunk issued during this iteration lands in (set by next_chunk above)
+  // Small wave tiles have too few MFMAs per k-step to cover the LDS latency of the next k-step's
+  // operands, and right behind the barrier there is nothing to cover the first fetch at all.  So
+  // they carry the second half of every chunk's MFMAs (operands already in registers) across the
+  // barrier: those run while the first operands of the new chunk come in.  Order of the sums per
+  // accumulator is unchanged.
+  constexpr bool DEFER = TM + TN <= 4 && KP >= 4 && SK == 1;  // (measured: a gain with 8 k-steps per chunk, none with 4)
+  constexpr int HK = DEFER ? KSW / 2 : 0;              // k-steps run in their own iteration
+  constexpr int DK = DEFER ? KSW - HK : 1;             // k-steps carried into the next one
+  uint4 wfd[DK][TN], xfd[DK][TM];
+  bool carried = false;
   for (int kc = kbeg; kc < nchunks; ++kc) {
     // chunk kc has landed once only the loads of the NS-2 chunks issued after it are pending
     wait_loads<(NS - 2) * LPC>();
@@ -229,13 +239,15 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
 #pragma unroll
       for (int tm = 0; tm < TM; ++tm) xf[tm] = xs[lds_slot(wm * WTM + tm * 32 + lrow, kq)];
     };
-    auto mma_step = [&](int k, const uint4(&wf)[TN], const uint4(&xf)[TM]) {
+    // the MFMAs of one k-step; `slot` is the k-step's place in this iteration's MFMA sequence: one
+    // ring load rides behind each of the first LPC MFMAs of an iteration
+    auto mma_step = [&](int slot, const uint4(&wf)[TN], const uint4(&xf)[TM]) {
 #pragma unroll
       for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm) {
           acc[tn][tm] = Mma<IS_I8>::mma(wf[tn], xf[tm], acc[tn][tm]);
-          const int i = (k * TN + tn) * TM + tm;  // one ring load rides behind each MFMA
+          const int i = (slot * TN + tn) * TM + tm;
           if (i < LPC) {
             __builtin_amdgcn_sched_barrier(0);  // keep the load behind this MFMA, not hoisted above all of them
             issue_one(i);
@@ -243,22 +255,49 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
           }
         }
     };
-    // operands of k-step k+PD are fetched before the MFMAs of k-step k run (PD+1 register sets):
-    // small wave tiles have too few MFMAs per k-step to cover the LDS latency one step ahead,
-    // so they fetch the whole chunk right behind the barrier
-    constexpr int PD = (TM + TN <= 4 && KSW > 1) ? (KSW - 1 < 7 ? KSW - 1 : 7) : 1;
-    uint4 wf[PD + 1][TN], xf[PD + 1][TM];
     const int k0 = wk * KSW;  // first k-step of this wave
+    if constexpr (DEFER) {
+      uint4 wf[HK][TN], xf[HK][TM];
 #pragma unroll
-    for (int k = 0; k < PD && k < KSW; ++k) fetch(k0 + k, wf[k], xf[k]);
+      for (int k = 0; k < HK; ++k) fetch(k, wf[k], xf[k]);
+      if (carried) {
 #pragma unroll
-    for (int k = 0; k < KSW; ++k) {
-      if (k + PD < KSW) fetch(k0 + k + PD, wf[(k + PD) % (PD + 1)], xf[(k + PD) % (PD + 1)]);
-      mma_step(k, wf[k % (PD + 1)], xf[k % (PD + 1)]);
+        for (int k = 0; k < DK; ++k) mma_step(k, wfd[k], xfd[k]);
+      } else {  // (first chunk) nothing carried: the loads of those slots go out in one go
+#pragma unroll
+        for (int i = 0; i < DK * TN * TM && i < LPC; ++i) issue_one(i);
+      }
+#pragma unroll
+      for (int k = 0; k < DK; ++k) fetch(HK + k, wfd[k], xfd[k]);
+#pragma unroll
+      for (int k = 0; k < HK; ++k) mma_step(DK + k, wf[k], xf[k]);
+      carried = true;
+    } else {
+      // operands of k-step k+PD are fetched before the MFMAs of k-step k run (PD+1 register sets);
+      // the other small wave tiles fetch the whole chunk right behind the barrier
+      constexpr int PD = (TM + TN <= 4 && KSW > 1) ? (KSW - 1 < 7 ? KSW - 1 : 7) : 1;
+      uint4 wf[PD + 1][TN], xf[PD + 1][TM];
+#pragma unroll
+      for (int k = 0; k < PD && k < KSW; ++k) fetch(k0 + k, wf[k], xf[k]);
+#pragma unroll
+      for (int k = 0; k < KSW; ++k) {
+        if (k + PD < KSW) fetch(k0 + k + PD, wf[(k + PD) % (PD + 1)], xf[(k + PD) % (PD + 1)]);
+        mma_step(k, wf[k % (PD + 1)], xf[k % (PD + 1)]);
+      }
     }
     fill = fill + 1 == NS ? 0 : fill + 1;
     next_chunk(fill);
     stage = stage + 1 == NS ? 0 : stage + 1;
+  }
+  if constexpr (DEFER) {
+    if (carried) {  // the last chunk's second half
+#pragma unroll
+      for (int k = 0; k < DK; ++k)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+          for (int tm = 0; tm < TM; ++tm) acc[tn][tm] = Mma<IS_I8>::mma(wfd[k][tn], xfd[k][tm], acc[tn][tm]);
+    }
   }
 
   // ---- epilogue.  Element v of a 32x32 accumulator block is channel 8*(v/4) + 4*(lane/32) + v%4
