@@ -213,3 +213,27 @@ def test_scale_folding_on_networks(G):
     torch.cuda.synchronize()
     ref = run_float(table, [OC.fold_bn_into_conv(p, "f16") for p in params], x, "f16")
     assert O.max_rel_err(net.tensor("blk.out"), ref["blk.out"]) <= TOL_F16
+
+
+def test_inception_block_batch32_sampled(G):
+    """The configuration the benchmark times: batch 32, combined launch, concatenation by views.  The
+    block input is the oracle's input too (first layer deep), so sampled outputs of every conv that
+    reads it are recomputed one by one; the deeper convs are checked through the whole-block test."""
+    net, ops, table, params, x = _block(G, True, batch=32)
+    g = np.random.default_rng(2204)
+    cat = net.tensor("cat")
+    assert cat.shape == (32, 480, 28, 28) and not np.isnan(cat).any() and cat.min() >= 0
+    for a, b, p in zip(ops, table, params):
+        if b.kind != "conv" or b.src != "x":
+            continue
+        got = net.tensor(a.dst)
+        pts = [(int(g.integers(32)), int(g.integers(b.cout)), int(g.integers(28)), int(g.integers(28))) for _ in range(120)]
+        pts += [(0, 0, 0, 0), (31, b.cout - 1, 27, 27)]
+        acc = O.conv2d_points(x, p["w"], pts, (1, 1), (0, 0))
+        want = O.cast_f16(O.float_epilogue_points(acc, [t[1] for t in pts], scale=p["scale"], shift=p["shift"], relu_flag=True))
+        gv = np.array([got[t] for t in pts]).astype(np.float64)
+        rms = float(np.sqrt(np.mean(got.astype(np.float64) ** 2)))
+        err = np.max(np.abs(gv - want.astype(np.float64)) / np.maximum(np.abs(want.astype(np.float64)), rms))
+        assert err <= TOL_F16, b.name
+    # the 1x1 member that goes straight into the concatenation sits in its channel range
+    assert np.array_equal(cat[:, :128], net.tensor(ops[0].dst))

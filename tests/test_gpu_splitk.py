@@ -104,3 +104,40 @@ def test_library_splits_the_deep_layers_at_batch_1_only(G):
     want = O.fused_conv2d(x, wt, stride=(1, 1), pad=(1, 1), scale=sc, shift=sf, relu_flag=True, out_dtype="f16")
     got = G.run_conv_f16(x, wt, 1, 1, scale=sc, shift=sf, relu=True, split=0)
     assert O.max_rel_err(got, want) <= TOL_F16
+
+
+def test_resnet18_batch1_with_split_layers_matches_the_oracle(G):
+    """Batch 1 is where the network driver hands workspaces to the deep layers: the chain against the
+    oracle, eager and replayed from a HIP graph three times (the counters must come back to zero
+    every time), fp16 and int8."""
+    from oracle.stack import run_float, run_quantized
+    from paper_1904_08368_amd.stack import FusedNet
+    from workloads import nets
+    ops = nets.resnet18()
+    params = inputs.net_params(ops, 3, "f16")
+    x = inputs.image(3, 1, 3, 224, 224, "f16")
+    ref = run_float(ops, params, x, "f16")
+    net = FusedNet(ops, params, 1, 224, 224, "f16")
+    assert sum(1 for _, args in net.calls if len(args) == 9 and args[-1] is not None) >= 4     # layers given a workspace
+    net.load_input(x)
+    net.run()
+    torch.cuda.synchronize()
+    logits = net.tensor("logits").reshape(1, 1000)
+    assert O.max_rel_err(logits, ref["logits"]) <= 2e-2
+    assert O.max_rel_err(net.tensor("l4.b1.out"), ref["l4.b1.out"]) <= 2e-2
+    net.capture()
+    for _ in range(3):
+        net.bufs["logits"].zero_()
+        net.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(net.tensor("logits").reshape(1, 1000), logits)
+    qops = nets.resnet18(with_dense=False)
+    qp = inputs.net_params(qops, 4, "i8")
+    sh = inputs.chain_shifts(qops)
+    xq = inputs.image(4, 1, 3, 224, 224, "i8")
+    qnet = FusedNet(qops, qp, 1, 224, 224, "i8", shifts=sh)
+    qnet.load_input(xq)
+    qnet.run()
+    torch.cuda.synchronize()
+    refq = run_quantized(qops, qp, sh, xq)
+    assert np.array_equal(qnet.tensor(qops[-1].dst), refq[qops[-1].dst])
