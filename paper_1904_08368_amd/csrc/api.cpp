@@ -95,6 +95,8 @@ relay::ConvArgs make_args(const relay_conv2d_desc* d, int ho, int wo) {
   }
   a.Kred = a.R * a.S * a.C;
   a.Kp = relay::packed_pitch(a.Kred, esize_of(d->dtype));
+  a.fd_wo = relay::make_fastdiv((uint32_t)wo);
+  a.fd_howo = relay::make_fastdiv((uint32_t)(ho * wo));
   a.rcp_wo = 1.0f / (float)wo;
   a.rcp_ho = 1.0f / (float)ho;
   if (a.R * a.S <= 32)

@@ -93,17 +93,18 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
   const int nsplit = (EXT && a.split > 1) ? a.split : 1;
   const int wg = xcd_remap(blockIdx.x, tiles_m * tiles_n * nsplit);
   const int tile = wg / nsplit, ks = wg - tile * nsplit;
-  const int tile_n = a.n_major ? tile / tiles_m : tile % tiles_n;
-  const int tile_m = a.n_major ? tile % tiles_m : tile / tiles_n;
+  const int tile_q = (int)fast_div((uint32_t)tile, a.n_major ? a.fd_tiles_m : a.fd_tiles_n);
+  const int tile_n = a.n_major ? tile_q : tile - tile_q * tiles_n;
+  const int tile_m = a.n_major ? tile - tile_q * tiles_m : tile_q;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
   // ---- staging role of this lane inside a 16-row block: row srow, physical slot sphys.
   //      The tile's first pixel is decoded once (uniform); rows are small offsets from it.
   const int srow = lane >> 2, sphys = lane & 3;
   const int HoWo = a.Ho * a.Wo;
-  const int n_0 = m0 / HoWo;
+  const int n_0 = (int)fast_div((uint32_t)m0, a.fd_howo);
   const int rem_0 = m0 - n_0 * HoWo;
-  const int p_0 = rem_0 / a.Wo;
+  const int p_0 = (int)fast_div((uint32_t)rem_0, a.fd_wo);
   const int q_0 = rem_0 - p_0 * a.Wo;
   int x_off[XL];        // byte offset of tap (0,0), channel 0 of the row's k-vector
   unsigned x_taps[XL];  // bit t set: tap t of this row lies inside the image
@@ -490,13 +491,17 @@ constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 template <bool IS_I8, bool STOCH, int WAVES_M, int WAVES_N, int TM, int TN, int NS, int KP, int SK = 1>
 hipError_t launch_one(const ConvArgs& a, hipStream_t st) {
   constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
-  const int tiles = ((a.M + BM - 1) / BM) * ((a.K + BN - 1) / BN) * (a.split > 1 ? a.split : 1);
+  const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.K + BN - 1) / BN;
+  const int tiles = tiles_m * tiles_n * (a.split > 1 ? a.split : 1);
+  ConvArgs b = a;
+  b.fd_tiles_m = make_fastdiv((uint32_t)tiles_m);
+  b.fd_tiles_n = make_fastdiv((uint32_t)tiles_n);
   if (STOCH || a.nseg || a.split > 1)
     hipLaunchKernelGGL((igemm_dma_kernel<IS_I8, WAVES_M, WAVES_N, TM, TN, NS, KP, SK, STOCH, true>), dim3(tiles),
-                       dim3(64 * WAVES_M * WAVES_N * SK), 0, st, a);
+                       dim3(64 * WAVES_M * WAVES_N * SK), 0, st, b);
   else
     hipLaunchKernelGGL((igemm_dma_kernel<IS_I8, WAVES_M, WAVES_N, TM, TN, NS, KP, SK, false, false>), dim3(tiles),
-                       dim3(64 * WAVES_M * WAVES_N * SK), 0, st, a);
+                       dim3(64 * WAVES_M * WAVES_N * SK), 0, st, b);
   return hipGetLastError();
 }
 

@@ -40,13 +40,9 @@ constexpr unsigned kOob = 0x80000000u;  // beyond any num_records this library a
 __device__ __forceinline__ void small_divmod(int t, int d, float rcp_d, int& q, int& r) {
   q = (int)((float)t * rcp_d);
   r = t - q * d;
-  if (r < 0) {
-    r += d;
-    --q;
-  } else if (r >= d) {
-    r -= d;
-    ++q;
-  }
+  const int fix = (r >= d ? 1 : 0) - (r < 0 ? 1 : 0);  // selects, not branches: lanes differ
+  q += fix;
+  r -= fix * d;
 }
 
 // Epilogue constants of the 8 consecutive channels [ech, ech + 8) a lane owns after the

@@ -5,6 +5,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include "fastdiv.hpp"
+
 namespace relay {
 
 enum : unsigned { F_BIAS = 1, F_BN = 2, F_RES = 4, F_RELU = 8 };
@@ -30,6 +32,8 @@ struct ConvArgs {
   unsigned tap_spread;    // bit r*S set for every filter row r (R*S <= 32)
   int param_vec;          // per-channel constants are 16-byte aligned and K % 8 == 0: vector loads
   int n_major;            // tile order: consecutive workgroups share an output-channel tile (else a pixel tile)
+  FastDiv fd_wo, fd_howo;           // division by Wo and by Ho*Wo (tile decoding in the prologue)
+  FastDiv fd_tiles_m, fd_tiles_n;   // ... by the tile counts of the launched kernel variant (set by its launcher)
   int M;        // N*Ho*Wo  (rows of the implicit GEMM)
   int Kred;     // R*S*C    (reduction length)
   int Kp;       // row pitch of the packed filters, elements
