@@ -194,6 +194,16 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[tn][tm][v] = 0;
 
+  // ---- epilogue constants of this lane: after the transposition it owns channels
+  //      [ech, ech + 8) of whichever pixels it handles.  Their loads go out first; the values are
+  //      used only after the ring loads below have been issued, which takes longer than the
+  //      constants take to arrive.  (vmcnt counts these loads too; being older than every ring
+  //      load they never make a wait for ring loads wait longer.)
+  constexpr int CG = WTN / 8;  // lanes per pixel row in the epilogue
+  const int ech = n0 + wn * WTN + (lane % CG) * 8;
+  RawLaneParams rawp;
+  fetch_lane_params<IS_I8>(a, ech, rawp);
+
 #pragma unroll
   for (int s = 0; s < NS - 1; ++s) {
 #pragma unroll
@@ -201,16 +211,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
     next_chunk(s + 1 == NS ? 0 : s + 1);
   }
 
-  // ---- epilogue constants of this lane: after the transposition it owns channels
-  //      [ech, ech + 8) of whichever pixels it handles.  Fetched here, behind the first ring
-  //      loads (which are on the critical path) and ahead of the main loop that hides the
-  //      latency.  vmcnt counts these loads too: being younger than the prologue chunks they
-  //      only make the first waits stricter than needed, and every later ring load is younger
-  //      than they are.
-  constexpr int CG = WTN / 8;  // lanes per pixel row in the epilogue
-  const int ech = n0 + wn * WTN + (lane % CG) * 8;
   LaneParams lp;
-  load_lane_params<IS_I8>(a, ech, lp);
+  finish_lane_params<IS_I8>(rawp, lp);
 
   const int lrow = lane & 31, lhalf = lane >> 5;
   int stage = 0;      // ring stage of chunk kc

@@ -80,11 +80,17 @@ __device__ __forceinline__ OutLoc locate_output(const ConvArgs& a, int ech) {
   return ol;
 }
 
+// The loads of a lane's epilogue constants, kept apart from the arithmetic on them so that a
+// kernel can issue them ahead of its first ring loads and touch the values only after those
+// have been issued: the global-memory latency of the constants is then covered by the issue of
+// the ring loads instead of stalling the prologue.
+struct RawLaneParams {
+  float sc[8], sf[8], bb[8];
+  int ib[8];
+};
+
 template <bool IS_I8>
-__device__ __forceinline__ void load_lane_params(const ConvArgs& a, int ech, LaneParams& lp) {
-  float(&emul)[8] = lp.mul;
-  float(&eadd)[8] = lp.add;
-  int(&ebias)[8] = lp.ibias;
+__device__ __forceinline__ void fetch_lane_params(const ConvArgs& a, int ech, RawLaneParams& rp) {
   if (a.param_vec) {  // two 16-byte loads per array
     const int c8 = ech < a.K ? ech : a.K - 8;
     if constexpr (IS_I8) {
@@ -95,7 +101,7 @@ __device__ __forceinline__ void load_lane_params(const ConvArgs& a, int ech, Lan
       }
       const int t[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
 #pragma unroll
-      for (int e = 0; e < 8; ++e) ebias[e] = t[e];
+      for (int e = 0; e < 8; ++e) rp.ib[e] = t[e];
     } else {
       float4 s0 = make_float4(1.f, 1.f, 1.f, 1.f), s1 = s0;
       float4 f0 = make_float4(0.f, 0.f, 0.f, 0.f), f1 = f0, b0 = f0, b1 = f0;
@@ -114,8 +120,9 @@ __device__ __forceinline__ void load_lane_params(const ConvArgs& a, int ech, Lan
       const float bb[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        emul[e] = sc[e];
-        eadd[e] = bb[e] * sc[e] + sf[e];  // (acc + b)*sc + sf
+        rp.sc[e] = sc[e];
+        rp.sf[e] = sf[e];
+        rp.bb[e] = bb[e];
       }
     }
   } else {
@@ -123,16 +130,34 @@ __device__ __forceinline__ void load_lane_params(const ConvArgs& a, int ech, Lan
     for (int e = 0; e < 8; ++e) {
       const int c = ech + e < a.K ? ech + e : a.K - 1;
       if constexpr (IS_I8) {
-        ebias[e] = (a.flags & F_BIAS) ? a.qbias[c] : 0;
+        rp.ib[e] = (a.flags & F_BIAS) ? a.qbias[c] : 0;
       } else {
-        const float sc = (a.flags & F_BN) ? a.scale[c] : 1.f;
-        const float sf = (a.flags & F_BN) ? a.shift[c] : 0.f;
-        const float b = (a.flags & F_BIAS) ? a.bias[c] : 0.f;
-        emul[e] = sc;
-        eadd[e] = b * sc + sf;  // (acc + b)*sc + sf
+        rp.sc[e] = (a.flags & F_BN) ? a.scale[c] : 1.f;
+        rp.sf[e] = (a.flags & F_BN) ? a.shift[c] : 0.f;
+        rp.bb[e] = (a.flags & F_BIAS) ? a.bias[c] : 0.f;
       }
     }
   }
+}
+
+template <bool IS_I8>
+__device__ __forceinline__ void finish_lane_params(const RawLaneParams& rp, LaneParams& lp) {
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    if constexpr (IS_I8) {
+      lp.ibias[e] = rp.ib[e];
+    } else {
+      lp.mul[e] = rp.sc[e];
+      lp.add[e] = rp.bb[e] * rp.sc[e] + rp.sf[e];  // (acc + b)*sc + sf
+    }
+  }
+}
+
+template <bool IS_I8>
+__device__ __forceinline__ void load_lane_params(const ConvArgs& a, int ech, LaneParams& lp) {
+  RawLaneParams rp;
+  fetch_lane_params<IS_I8>(a, ech, rp);
+  finish_lane_params<IS_I8>(rp, lp);
 }
 
 // EXT: the instantiation that knows about output segments (the plain one ignores ol).
