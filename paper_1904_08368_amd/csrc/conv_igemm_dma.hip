@@ -145,8 +145,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
   const int per_split = (all_chunks + nsplit - 1) / nsplit;
   const int kbeg = ks * per_split;
   const int nchunks = min(all_chunks, kbeg + per_split);
-  // reduction position of the chunk being issued (wave-uniform); chunks past the end are
-  // issued as all-out-of-range loads into a free stage so that every iteration looks alike
+  // reduction position of the chunk being issued (wave-uniform)
   int is_tap = 0, is_r = 0, is_s = 0, is_c = 0, is_kc = kbeg;
   if (kbeg) {  // (uniform) position of the first chunk
     const int per_tap = a.C / CK;
@@ -157,16 +156,24 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
   }
   unsigned is_delta = (unsigned)((is_r * a.xs_h + is_s * a.xs_w + is_c) * ES), is_sbase = ring_base;
   bool is_live = is_kc < nchunks;
-  auto issue_one = [&](int idx) {  // idx-th load of the chunk: per plane XL activation blocks, then WL filter blocks
+  // Small wave tiles (the short reductions) never issue a load for a chunk past the end of the
+  // reduction: their loop ends in NS-1 iterations that only let the loads in flight run out.  The
+  // large ones keep one loop shape for every chunk and issue all-out-of-range loads there instead
+  // (a second copy of their loop body does not fit their register budget).
+  constexpr bool RUNOUT = TM * TN < 8;
+  // idx-th load of the chunk being issued: per plane XL activation blocks, then WL filter blocks
+  auto issue_one = [&](int idx) {
     const int plane = idx / (XL + WL), i = idx % (XL + WL);
     const unsigned pbase = is_sbase + (unsigned)(plane * PLANE) * 16u;
     if (i < XL) {
-      const unsigned voff =
-          (is_live && ((x_taps[i] >> is_tap) & 1u)) ? (unsigned)x_off[i] + is_delta + (unsigned)(plane * 64) : kOob;
+      const unsigned voff = ((RUNOUT || is_live) && ((x_taps[i] >> is_tap) & 1u))
+                                ? (unsigned)x_off[i] + is_delta + (unsigned)(plane * 64)
+                                : kOob;
       lds_dma16(rs_x, pbase + (unsigned)((wave * XL + i) * 64) * 16u, voff);
     } else {
       const int j = i - XL;
-      const unsigned voff = is_live ? w_off[j] + (unsigned)(is_kc * CK * ES + plane * 64) : kOob;
+      // (kOob + the chunk position stays out of range)
+      const unsigned voff = (RUNOUT || is_live) ? w_off[j] + (unsigned)(is_kc * CK * ES + plane * 64) : kOob;
       lds_dma16(rs_w, pbase + (unsigned)(BM * BKV + (wave * WL + j) * 64) * 16u, voff);
     }
   };
@@ -206,8 +213,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
 
 #pragma unroll
   for (int s = 0; s < NS - 1; ++s) {
+    if (!RUNOUT || is_live) {  // (uniform) a reduction shorter than the ring issues nothing for the chunks it does not have
 #pragma unroll
-    for (int i = 0; i < LPC; ++i) issue_one(i);
+      for (int i = 0; i < LPC; ++i) issue_one(i);
+    }
     next_chunk(s + 1 == NS ? 0 : s + 1);
   }
 
@@ -227,10 +236,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
   constexpr int DK = DEFER ? KSW - HK : 1;             // k-steps carried into the next one
   uint4 wfd[DK][TN], xfd[DK][TM];
   bool carried = false;
-  for (int kc = kbeg; kc < nchunks; ++kc) {
-    // chunk kc has landed once only the loads of the NS-2 chunks issued after it are pending
-    wait_loads<(NS - 2) * LPC>();
-    __builtin_amdgcn_s_barrier();  // everyone's part of chunk kc is in LDS; stage `fill` is free again
+  // One chunk of the reduction.  ISSUE: the loads of chunk kc+NS-1 ride behind this chunk's MFMAs
+  // (every chunk but the last NS-1 of the reduction, which have nothing left to fetch); PENDING:
+  // how many younger loads may still be in flight once this chunk's own have landed.
+  auto chunk = [&](auto issue_tag, auto pending_tag) {
+    constexpr bool ISSUE = decltype(issue_tag)::value;
+    constexpr int PENDING = decltype(pending_tag)::value;
+    wait_loads<PENDING>();
+    __builtin_amdgcn_s_barrier();  // everyone's part of this chunk is in LDS; stage `fill` is free again
     const uint4* st = ring + stage * STAGE;
     // operand fetch of k-step k: plane k/2, k-vectors 2*(k%2) + lane/32
     auto fetch = [&](int k, uint4(&wf)[TN], uint4(&xf)[TM]) {
@@ -251,7 +264,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
         for (int tm = 0; tm < TM; ++tm) {
           acc[tn][tm] = Mma<IS_I8>::mma(wf[tn], xf[tm], acc[tn][tm]);
           const int i = (slot * TN + tn) * TM + tm;
-          if (i < LPC) {
+          if (ISSUE && i < LPC) {
             __builtin_amdgcn_sched_barrier(0);  // keep the load behind this MFMA, not hoisted above all of them
             issue_one(i);
             __builtin_amdgcn_sched_barrier(0);
@@ -266,7 +279,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
       if (carried) {
 #pragma unroll
         for (int k = 0; k < DK; ++k) mma_step(k, wfd[k], xfd[k]);
-      } else {  // (first chunk) nothing carried: the loads of those slots go out in one go
+      } else if (ISSUE) {  // (first chunk) nothing carried: the loads of those slots go out in one go
 #pragma unroll
         for (int i = 0; i < DK * TN * TM && i < LPC; ++i) issue_one(i);
       }
@@ -288,9 +301,25 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
         mma_step(k, wf[k % (PD + 1)], xf[k % (PD + 1)]);
       }
     }
-    fill = fill + 1 == NS ? 0 : fill + 1;
-    next_chunk(fill);
+    if (ISSUE) {
+      fill = fill + 1 == NS ? 0 : fill + 1;
+      next_chunk(fill);
+    }
     stage = stage + 1 == NS ? 0 : stage + 1;
+  };
+  using std::integral_constant;
+  const int klen = max(nchunks - kbeg, 0);
+  if constexpr (RUNOUT) {
+    // all but the last NS-1 chunks: one more chunk is issued per chunk consumed, NS-2 stay in flight
+    for (int kc = NS - 1; kc < klen; ++kc) chunk(std::true_type{}, integral_constant<int, (NS - 2) * LPC>{});
+    // the last NS-1 (or fewer) chunks: nothing is issued any more, the loads in flight run out
+    for (int left = min(klen, NS - 1) - 1; left >= 0; --left) {  // `left` chunks follow this one
+      if (NS > 3 && left == 2) chunk(std::false_type{}, integral_constant<int, (NS > 3 ? 2 : 0) * LPC>{});
+      else if (NS > 2 && left == 1) chunk(std::false_type{}, integral_constant<int, (NS > 2 ? 1 : 0) * LPC>{});
+      else chunk(std::false_type{}, integral_constant<int, 0>{});
+    }
+  } else {
+    for (int kc = 0; kc < klen; ++kc) chunk(std::true_type{}, integral_constant<int, (NS - 2) * LPC>{});
   }
   if constexpr (DEFER) {
     if (carried) {  // the last chunk's second half
@@ -305,7 +334,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
 
   // ---- epilogue.  Element v of a 32x32 accumulator block is channel 8*(v/4) + 4*(lane/32) + v%4
   //      of pixel lane%32.  Each wave transposes its blocks through a private LDS region.
-  wait_loads<0>();               // the trailing out-of-range loads still write zeros into the ring
+  wait_loads<0>();               // (trailing out-of-range loads of the large tiles still write zeros into the ring)
   __builtin_amdgcn_s_barrier();  // every wave is done reading the ring
   constexpr int TM_E = SK == 2 ? TM / 2 : TM;  // accumulator block rows this wave finishes
   const int tm_lo = SK == 2 ? wk * TM_E : 0;
