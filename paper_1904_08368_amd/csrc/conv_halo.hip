@@ -25,6 +25,8 @@
 // compile-time constant of the unrolled tap loop.
 #include <cstdio>
 
+#include <atomic>
+
 #include "dma_common.hpp"
 
 namespace relay {
@@ -37,6 +39,8 @@ struct HaloGeom {
   int xblk;           // 16-row blocks per plane of a halo buffer
   int nxbuf;          // halo buffers: 2 when there are several channel chunks, else 1
   int ncc;            // channel chunks, C / CK
+  FastDiv fd_f, fd_xblk;            // division by F and by xblk
+  FastDiv fd_tiles_m, fd_tiles_n;   // ... by the tile counts of the launched variant
 };
 
 constexpr int NSW = 3;         // filter ring stages (9 taps per chunk keep step % NSW compile-time)
@@ -76,10 +80,11 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_halo_kernel
   const int wm = wave % WAVES_M, wn = wave / WAVES_M;
   const int tiles_m = (g.Mflat + BM - 1) / BM, tiles_n = (a.K + BN - 1) / BN;
   const int tile = xcd_remap(blockIdx.x, tiles_m * tiles_n);
-  const int tile_n = a.n_major ? tile / tiles_m : tile % tiles_n;
-  const int tile_m = a.n_major ? tile % tiles_m : tile / tiles_n;
+  const int tile_q = (int)fast_div((uint32_t)tile, a.n_major ? g.fd_tiles_m : g.fd_tiles_n);
+  const int tile_n = a.n_major ? tile_q : tile - tile_q * tiles_n;
+  const int tile_m = a.n_major ? tile - tile_q * tiles_m : tile_q;
   const int o0 = tile_m * BM, n0 = tile_n * BN;
-  const int n_0 = o0 / g.F;            // (uniform) image and in-image position of the tile's first position
+  const int n_0 = (int)fast_div((uint32_t)o0, g.fd_f);  // (uniform) image and in-image position of the tile's first position
   const int rem_0 = o0 - n_0 * g.F;
 
   // ---- this lane's part of a halo: block (t * NW + wave) of the KP * xblk blocks, for t < XS
@@ -90,7 +95,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_halo_kernel
 #pragma unroll
   for (int t = 0; t < XS; ++t) {
     const int b = t * NW + wave;
-    const int plane = b / g.xblk, blk = b - plane * g.xblk;
+    const int plane = (int)fast_div((uint32_t)b, g.fd_xblk), blk = b - plane * g.xblk;
     const bool live = plane < KP;
     const int row = blk * 16 + srow;
     const int kvl = sphys ^ lds_swizzle(row);
@@ -262,6 +267,8 @@ bool make_geom(const ConvArgs& a, bool is_i8, int v, HaloGeom& g, size_t& lds_by
   g.xblk = (rows + 15) / 16;
   g.ncc = a.C / (kp * BKV * ve);
   g.nxbuf = g.ncc > 1 ? 2 : 1;
+  g.fd_f = make_fastdiv((uint32_t)g.F);
+  g.fd_xblk = make_fastdiv((uint32_t)g.xblk);
   if (kp * g.xblk > XS * 4) return false;  // a halo must fit the load slots of XS steps x 4 waves
   const int nw = kHalo[v].waves_m * kHalo[v].waves_n;
   const size_t ring = (size_t)g.nxbuf * kp * g.xblk * 64 + (size_t)NSW * kp * kHalo[v].bn() * BKV + 64;
@@ -273,16 +280,19 @@ bool make_geom(const ConvArgs& a, bool is_i8, int v, HaloGeom& g, size_t& lds_by
 template <bool IS_I8, int WM, int WN, int TM, int TN, int KP>
 hipError_t launch_halo_one(const ConvArgs& a, const HaloGeom& g, size_t lds_bytes, hipStream_t st) {
   auto kern = conv3x3_halo_kernel<IS_I8, WM, WN, TM, TN, KP>;
-  static bool raised = false;  // dynamic LDS above the default limit has to be asked for once per kernel
-  if (!raised) {
+  static std::atomic<bool> raised{false};  // dynamic LDS above the default limit has to be asked for once per kernel
+  if (!raised.load(std::memory_order_acquire)) {
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                              160 * 1024);
     if (e != hipSuccess) return e;
-    raised = true;
+    raised.store(true, std::memory_order_release);
   }
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
-  const int tiles = ((g.Mflat + BM - 1) / BM) * ((a.K + BN - 1) / BN);
-  hipLaunchKernelGGL(kern, dim3(tiles), dim3(64 * WM * WN), lds_bytes, st, a, g);
+  const int tiles_m = (g.Mflat + BM - 1) / BM, tiles_n = (a.K + BN - 1) / BN;
+  HaloGeom gl = g;
+  gl.fd_tiles_m = make_fastdiv((uint32_t)tiles_m);
+  gl.fd_tiles_n = make_fastdiv((uint32_t)tiles_n);
+  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(64 * WM * WN), lds_bytes, st, a, gl);
   return hipGetLastError();
 }
 
