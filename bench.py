@@ -79,7 +79,7 @@ def _layer_table(net, ops, batch, reps, trials):
     return rows
 
 
-KERNEL_SOURCES = ("conv_igemm_dma.hip", "dma_common.hpp", "igemm_common.hpp", "rounding.hpp", "kernels.hpp")
+KERNEL_SOURCES = ("conv_igemm_dma.hip", "dma_common.hpp", "igemm_common.hpp", "rounding.hpp", "kernels.hpp", "fastdiv.hpp")
 
 
 def _kernel_source_digest():
