@@ -186,6 +186,26 @@ relay_status relay_maxpool2d(int32_t dtype, int32_t n, int32_t c, int32_t h, int
 relay_status relay_global_avgpool(int32_t dtype, int32_t n, int32_t c, int32_t hw, const void* x, void* y,
                                   void* hip_stream);
 
+/* A convolution primitive function with the 3x3 / stride 2 / pad 1 max pool that follows it run
+ * as ONE launch: the conv output never reaches memory.  This carries the operator fusion of
+ * paper Section 4.1 one operator past the elementwise tail (a window operator whose input tile
+ * the workgroup already holds); the result equals relay_fused_conv2d_bias_bn_relu (or
+ * relay_qconv2d_requant) followed by relay_maxpool2d(r=3, stride=2, pad=1) bit for bit, because
+ * each conv output is finished and narrowed exactly as there before the maximum is taken.
+ *   d          the CONVOLUTION (F16 or I8; NHWC or NHWC4_PADDED; flags without HAS_RESIDUAL;
+ *              I8 also without HAS_BN), with conv output ho % 14 == 0, wo % 16 == 0, k % 8 == 0
+ *   y_pooled   [n, ho/2, wo/2, k] NHWC in d->dtype; F16 16-byte, I8 8-byte aligned
+ *   the other operands as in the unpooled calls; the quantized call rounds to nearest.
+ * relay_conv2d_maxpool_fusable writes 1 if these calls take the descriptor, else 0 (the calls
+ * themselves return RELAY_ERR_UNSUPPORTED and launch nothing). */
+relay_status relay_conv2d_maxpool_fusable(const relay_conv2d_desc* d, int32_t* fusable);
+relay_status relay_fused_conv2d_bn_relu_maxpool(const relay_conv2d_desc* d, const void* x, const void* w_packed,
+                                                const float* bias, const float* bn_scale, const float* bn_shift,
+                                                void* y_pooled, void* hip_stream);
+relay_status relay_qconv2d_requant_maxpool(const relay_conv2d_desc* d, const int8_t* x, const int8_t* w_packed,
+                                           const int32_t* bias, int32_t out_rshift, int8_t* y_pooled,
+                                           void* hip_stream);
+
 /* One UNFUSED elementwise operator on an fp16 NHWC tensor [n_pixels, c] (c % 8 == 0): what runs
  * behind a convolution when operator fusion is switched off.  The paper measures fusion against
  * such a pipeline (Section 5.2); this entry point exists for that comparison and for checking

@@ -62,6 +62,9 @@ SIGNATURES = {
     "relay_fused_conv2d_combined": [_DP, _P, _I, _P, _P, _P, _P, _I, _P, _P, _P, _P],
     "relay_fold_scale_axis": [_I, _I, _I, _I, _I, _P, _P, _P, _P],
     "relay_fold_bias": [_I, _P, _P, _P, _P, _P],
+    "relay_conv2d_maxpool_fusable": [_DP, C.POINTER(_I)],
+    "relay_fused_conv2d_bn_relu_maxpool": [_DP, _P, _P, _P, _P, _P, _P, _P],
+    "relay_qconv2d_requant_maxpool": [_DP, _P, _P, _P, _I, _P, _P],
     "relay_set_conv_tile": [_I],
     "relay_set_conv_split": [_I],
     "relay_conv2d_kernel_name": [_DP, C.c_char_p, _SZ],
@@ -147,6 +150,22 @@ def relay_qconv2d_requant(d: ConvDesc, x, w_packed, bias, residual, residual_lsh
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().relay_qconv2d_requant(C.byref(d), _ptr(x), _ptr(w_packed), _ptr(bias), _ptr(residual),
                                        residual_lshift, out_rshift, _ptr(y), _ptr(workspace), ws_bytes, _stream()))
+
+
+def relay_conv2d_maxpool_fusable(d: ConvDesc) -> bool:
+    out = C.c_int32(0)
+    _check(lib().relay_conv2d_maxpool_fusable(C.byref(d), C.byref(out)))
+    return bool(out.value)
+
+
+def relay_fused_conv2d_bn_relu_maxpool(d: ConvDesc, x, w_packed, bias, bn_scale, bn_shift, y_pooled) -> None:
+    _check(lib().relay_fused_conv2d_bn_relu_maxpool(C.byref(d), _ptr(x), _ptr(w_packed), _ptr(bias), _ptr(bn_scale),
+                                                    _ptr(bn_shift), _ptr(y_pooled), _stream()))
+
+
+def relay_qconv2d_requant_maxpool(d: ConvDesc, x, w_packed, bias, out_rshift: int, y_pooled) -> None:
+    _check(lib().relay_qconv2d_requant_maxpool(C.byref(d), _ptr(x), _ptr(w_packed), _ptr(bias), out_rshift,
+                                               _ptr(y_pooled), _stream()))
 
 
 def relay_prepack_dwconv_weights(d: ConvDesc, w_crs, w_rsc) -> None:

@@ -461,6 +461,78 @@ relay_status relay_qconv2d_requant_rounding(const relay_conv2d_desc* d, const in
   return device_status(launch_igemm(a, true, static_cast<hipStream_t>(hip_stream)), "qconv2d launch");
 }
 
+// ---- conv2d + 3x3 / stride 2 / pad 1 max pool in one launch -------------------------------------
+
+static relay_status check_pool_fusable(const relay_conv2d_desc* d, int* ho, int* wo, relay::ConvArgs* out) {
+  relay_status st = check_geometry(d, ho, wo);
+  if (st != RELAY_OK) return st;
+  if (d->dtype != RELAY_F16 && d->dtype != RELAY_I8) return fail(RELAY_ERR_DTYPE, "the pooled conv2d takes F16 or I8");
+  if (d->flags & RELAY_HAS_RESIDUAL) return fail(RELAY_ERR_UNSUPPORTED, "the pooled conv2d has no residual operand");
+  if (d->dtype == RELAY_I8 && (d->flags & RELAY_HAS_BN))
+    return fail(RELAY_ERR_UNSUPPORTED, "the quantized epilogue has no float scale/shift");
+  if ((st = check_igemm_support(d)) != RELAY_OK) return st;
+  relay::ConvArgs a = make_args(d, *ho, *wo);
+  if (!relay::igemm_dma_pool_supported(a, d->dtype == RELAY_I8))
+    return fail(RELAY_ERR_UNSUPPORTED,
+                "the pooled conv2d needs a conv output of ho %% 14 == 0 and wo %% 16 == 0 and k %% 8 == 0 (ho=%d wo=%d k=%d)",
+                *ho, *wo, d->k);
+  relay::fill_pool_args(a);
+  *out = a;
+  return RELAY_OK;
+}
+
+relay_status relay_conv2d_maxpool_fusable(const relay_conv2d_desc* d, int32_t* fusable) {
+  if (!fusable) return fail(RELAY_ERR_NULL, "fusable is NULL");
+  int ho, wo;
+  relay::ConvArgs a;
+  *fusable = check_pool_fusable(d, &ho, &wo, &a) == RELAY_OK ? 1 : 0;
+  return RELAY_OK;
+}
+
+relay_status relay_fused_conv2d_bn_relu_maxpool(const relay_conv2d_desc* d, const void* x, const void* w_packed,
+                                                const float* bias, const float* bn_scale, const float* bn_shift,
+                                                void* y_pooled, void* hip_stream) {
+  int ho, wo;
+  relay::ConvArgs a;
+  relay_status st = check_pool_fusable(d, &ho, &wo, &a);
+  if (st != RELAY_OK) return st;
+  if (d->dtype != RELAY_F16) return fail(RELAY_ERR_DTYPE, "the float pooled conv2d takes F16");
+  if (!x || !w_packed || !y_pooled) return fail(RELAY_ERR_NULL, "x, w_packed and y_pooled are required");
+  if ((st = check_optional(bias, d->flags & RELAY_HAS_BIAS, "bias")) != RELAY_OK) return st;
+  if ((st = check_optional(bn_scale, d->flags & RELAY_HAS_BN, "bn_scale")) != RELAY_OK) return st;
+  if ((st = check_optional(bn_shift, d->flags & RELAY_HAS_BN, "bn_shift")) != RELAY_OK) return st;
+  if (y_pooled == x) return fail(RELAY_ERR_UNSUPPORTED, "output must not alias an input");
+  if (!aligned(x, 16) || !aligned(w_packed, 16) || !aligned(y_pooled, 16))
+    return fail(RELAY_ERR_ALIGN, "fp16 tensors must be 16-byte aligned");
+  a.x = x; a.w = w_packed; a.y = y_pooled; a.bias = bias; a.scale = bn_scale; a.shift = bn_shift;
+  finish_args(a);
+  return device_status(relay::launch_conv_igemm_dma_pool(a, false, static_cast<hipStream_t>(hip_stream)),
+                       "pooled conv2d fp16 launch");
+}
+
+relay_status relay_qconv2d_requant_maxpool(const relay_conv2d_desc* d, const int8_t* x, const int8_t* w_packed,
+                                           const int32_t* bias, int32_t out_rshift, int8_t* y_pooled,
+                                           void* hip_stream) {
+  int ho, wo;
+  relay::ConvArgs a;
+  relay_status st = check_pool_fusable(d, &ho, &wo, &a);
+  if (st != RELAY_OK) return st;
+  if (d->dtype != RELAY_I8) return fail(RELAY_ERR_DTYPE, "the quantized pooled conv2d takes I8");
+  if (!x || !w_packed || !y_pooled) return fail(RELAY_ERR_NULL, "x, w_packed and y_pooled are required");
+  if ((st = check_optional(bias, d->flags & RELAY_HAS_BIAS, "bias")) != RELAY_OK) return st;
+  if (out_rshift < 0 || out_rshift > 31) return fail(RELAY_ERR_UNSUPPORTED, "out_rshift=%d outside 0..31", out_rshift);
+  if (y_pooled == x) return fail(RELAY_ERR_UNSUPPORTED, "output must not alias an input");
+  if (!aligned(x, 16) || !aligned(w_packed, 16) || !aligned(y_pooled, 8) || (bias && !aligned(bias, 4)))
+    return fail(RELAY_ERR_ALIGN, "int8 x / w_packed must be 16-byte aligned, y_pooled 8-byte, bias 4-byte aligned");
+  a.x = x; a.w = w_packed; a.y = y_pooled; a.qbias = bias;
+  a.rshift = out_rshift;
+  a.round_mode = RELAY_ROUND_NEAREST;
+  a.round_add = out_rshift == 0 ? 0 : 1 << (out_rshift - 1);
+  finish_args(a);
+  return device_status(relay::launch_conv_igemm_dma_pool(a, true, static_cast<hipStream_t>(hip_stream)),
+                       "pooled qconv2d launch");
+}
+
 static relay_status check_dw(const relay_conv2d_desc* d, int* ho, int* wo) {
   relay_status st = check_geometry(d, ho, wo);
   if (st != RELAY_OK) return st;

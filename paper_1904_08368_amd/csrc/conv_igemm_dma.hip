@@ -54,7 +54,10 @@ using acc_t_scalar = typename std::conditional<IS_I8, int, float>::type;
 // EXT: the instantiation that can split a tile's reduction over workgroups and store output
 // channel segments.  Both are rare; kept out of the plain kernel because even as untaken uniform
 // branches they cost it about 1 % each (registers held across the main loop, code size).
-template <bool IS_I8, int WAVES_M, int WAVES_N, int TM, int TN, int NS, int KP, int SK, bool STOCH, bool EXT>
+// POOL: the tile is the 15 x 17 patch of conv outputs under a 7 x 8 block of 3x3/s2/p1 max-pool
+// outputs (255 of 256 rows); the finished patch goes to LDS and only the pooled block is stored.
+template <bool IS_I8, int WAVES_M, int WAVES_N, int TM, int TN, int NS, int KP, int SK, bool STOCH, bool EXT,
+          bool POOL = false>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
                              // two workgroups per CU where their LDS rings fit side by side
                              (NS * KP * (WAVES_M * TM + WAVES_N * TN) * 32 * 64 <= 80 * 1024 ? 2 : 1))
@@ -81,14 +84,18 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
   static_assert(NW * (32 * EP + XCH) <= NS * STAGE, "epilogue staging reuses the ring");
   typedef typename Mma<IS_I8>::acc_t acc_t;
 
-  __shared__ uint4 ring[NS * STAGE];
+  constexpr int PDY = 15, PDX = 17;                 // conv patch of a pooled 7 x 8 block
+  constexpr int PATCH = POOL ? BM * (BN / 8) : 0;   // 16-byte slots of the finished patch
+  static_assert(!POOL || (BM >= PDY * PDX && SK == 1 && !EXT && !STOCH), "pooled tiles hold one 15 x 17 patch");
+  constexpr int RING_SLOTS = NS * STAGE > NW * 32 * EP + PATCH ? NS * STAGE : NW * 32 * EP + PATCH;
+  __shared__ uint4 ring[RING_SLOTS];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wk = wave / (WAVES_M * WAVES_N), wsub = wave % (WAVES_M * WAVES_N);
   const int wm = wsub % WAVES_M, wn = wsub / WAVES_M;
-  const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.K + BN - 1) / BN;
+  const int tiles_m = POOL ? a.N * a.pool_tiles_img : (a.M + BM - 1) / BM, tiles_n = (a.K + BN - 1) / BN;
   // with a split reduction consecutive workgroups (same XCD) share a tile
   const int nsplit = (EXT && a.split > 1) ? a.split : 1;
   const int wg = xcd_remap(blockIdx.x, tiles_m * tiles_n * nsplit);
@@ -106,16 +113,36 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
   const int rem_0 = m0 - n_0 * HoWo;
   const int p_0 = (int)fast_div((uint32_t)rem_0, a.fd_wo);
   const int q_0 = rem_0 - p_0 * a.Wo;
+  // (pooled tiles: image, and row / column of the 7 x 8 block of pooled outputs inside it)
+  int pool_n = 0, pool_i = 0, pool_j = 0;
+  if constexpr (POOL) {
+    pool_n = (int)fast_div((uint32_t)tile_m, a.fd_pool_img);
+    const int rem = tile_m - pool_n * a.pool_tiles_img;
+    pool_i = (int)fast_div((uint32_t)rem, a.fd_pool_row);
+    pool_j = rem - pool_i * a.pool_tiles_row;
+  }
   int x_off[XL];        // byte offset of tap (0,0), channel 0 of the row's k-vector
   unsigned x_taps[XL];  // bit t set: tap t of this row lies inside the image
 #pragma unroll
   for (int j = 0; j < XL; ++j) {
     const int row = (wave * XL + j) * 16 + srow;
     const int kvl = sphys ^ lds_swizzle(row);
-    int dp, q, dn, p;
-    small_divmod(q_0 + row, a.Wo, a.rcp_wo, dp, q);
-    small_divmod(p_0 + dp, a.Ho, a.rcp_ho, dn, p);
-    const int n = n_0 + dn;
+    int dp, q, dn, p, n;
+    bool row_ok;
+    if constexpr (POOL) {  // row = dy * 17 + dx of the patch whose corner is conv output (14 i - 1, 16 j - 1)
+      const int dy = row / PDX, dx = row - dy * PDX;
+      p = 2 * 7 * pool_i - 1 + dy;
+      q = 2 * 8 * pool_j - 1 + dx;
+      n = pool_n;
+      row_ok = dy < PDY && (unsigned)p < (unsigned)a.Ho && (unsigned)q < (unsigned)a.Wo;
+      (void)dp;
+      (void)dn;
+    } else {
+      small_divmod(q_0 + row, a.Wo, a.rcp_wo, dp, q);
+      small_divmod(p_0 + dp, a.Ho, a.rcp_ho, dn, p);
+      n = n_0 + dn;
+      row_ok = m0 + row < a.M;
+    }
     const int ih0 = p * a.sh - a.ph, iw0 = q * a.sw - a.pw;
     // filter rows [rlo, rhi) and columns [clo, chi) fall inside the image: the tap mask is the
     // column run replicated at every valid row (a product, the runs do not overlap)
@@ -125,7 +152,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
     const unsigned rows = a.tap_spread & (unsigned)((1ull << (max(rhi, 0) * a.S)) - 1ull) &
                           ~(unsigned)((1ull << (rlo * a.S)) - 1ull);
     const unsigned taps = (rhi > rlo && chi > clo) ? colbits * rows : 0u;
-    x_taps[j] = (m0 + row < a.M) ? taps : 0u;
+    x_taps[j] = row_ok ? taps : 0u;
     x_off[j] = (n * a.xs_n + ih0 * a.xs_h + iw0 * a.xs_w + kvl * VE) * ES;
   }
   unsigned w_off[WL];
@@ -411,6 +438,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
       const int pix = it * PPI + epix;
       const uint4 lo = stg[pix * EP + ecg * 2], hi = stg[pix * EP + ecg * 2 + 1];
       const unsigned raw[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+      if constexpr (POOL) {  // the finished element goes to the patch in LDS (rows outside the image too: masked below)
+        if (ech < a.K) ring[NW * 32 * EP + (wm * WTM + tm * 32 + pix) * (BN / 8) + (ech - n0) / 8] = finish8_packed<IS_I8>(a, raw, lp);
+        continue;
+      }
       const int m = m0 + wm * WTM + tm * 32 + pix;
       if (m >= a.M || ech >= a.K) continue;
       if (EXT && nsplit > 1) {  // (uniform) leave the raw partial sums for the workgroup that finishes the tile
@@ -422,6 +453,67 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
         finish_store8<IS_I8, STOCH, EXT>(a, raw, m, ech, lp, ol, vec_ok);
       }
     }
+  }
+  if constexpr (POOL) {
+    // ---- 3x3 / stride 2 / pad 1 max pool over the finished patch: pooled output (7 i + py, 8 j + px)
+    //      takes conv outputs (2 oy - 1 + r, 2 ox - 1 + s), patch rows (2 py + r) * 17 + 2 px + s;
+    //      positions outside the conv output are skipped (the centre never is).
+    __syncthreads();
+    constexpr int GROUPS = BN / 8;
+    const uint4* patch = ring + NW * 32 * EP;
+    const int hp = a.Ho >> 1, wp = a.Wo >> 1;
+    for (int item = tid; item < 56 * GROUPS; item += NW * 64) {
+      const int pp = item / GROUPS, gch = item - pp * GROUPS;
+      const int py = pp >> 3, px = pp & 7;
+      const int oy = 7 * pool_i + py, ox = 8 * pool_j + px;
+      const int ch = n0 + gch * 8;
+      if (ch >= a.K) continue;
+      // Only the first row and column of the image have a window that sticks out (2 oy - 1 < 0; the far
+      // side ends at 2 oy + 1 <= Ho - 1): those read the centre row / column again instead, which
+      // leaves the maximum as it is and the loop free of branches.
+      const int r_lo = oy == 0 ? 1 : 0, s_lo = ox == 0 ? 1 : 0;
+      typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+      typedef short short2v __attribute__((ext_vector_type(2)));
+      uint4 best;
+      unsigned ev[2], od[2];  // int8: the even and the odd bytes of a word as the high bytes of 16-bit lanes
+#pragma unroll
+      for (int r = 0; r < 3; ++r)
+#pragma unroll
+        for (int s2 = 0; s2 < 3; ++s2) {
+          const int rr = r == 0 ? r_lo : r, ss = s2 == 0 ? s_lo : s2;
+          const uint4 v = patch[((2 * py + rr) * PDX + 2 * px + ss) * GROUPS + gch];
+          if constexpr (IS_I8) {
+            const unsigned vw[2] = {v.x, v.y};
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+              const unsigned e = (vw[h] << 8) & 0xff00ff00u, o = vw[h] & 0xff00ff00u;
+              if (r == 0 && s2 == 0) {
+                ev[h] = e;
+                od[h] = o;
+              } else {
+                ev[h] = __builtin_bit_cast(unsigned, __builtin_elementwise_max(__builtin_bit_cast(short2v, ev[h]), __builtin_bit_cast(short2v, e)));
+                od[h] = __builtin_bit_cast(unsigned, __builtin_elementwise_max(__builtin_bit_cast(short2v, od[h]), __builtin_bit_cast(short2v, o)));
+              }
+            }
+          } else {
+            if (r == 0 && s2 == 0) {
+              best = v;
+            } else {
+              unsigned bw[4] = {best.x, best.y, best.z, best.w};
+              const unsigned vw[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+              for (int h = 0; h < 4; ++h)
+                bw[h] = __builtin_bit_cast(unsigned, __builtin_elementwise_max(__builtin_bit_cast(half2v, bw[h]), __builtin_bit_cast(half2v, vw[h])));
+              best = make_uint4(bw[0], bw[1], bw[2], bw[3]);
+            }
+          }
+        }
+      if constexpr (IS_I8) best = make_uint4((ev[0] >> 8) | od[0], (ev[1] >> 8) | od[1], 0u, 0u);
+      const size_t o = ((size_t)(pool_n * hp + oy) * wp + ox) * a.K + ch;
+      if constexpr (IS_I8) *reinterpret_cast<uint2*>(static_cast<int8_t*>(a.y) + o) = make_uint2(best.x, best.y);
+      else *reinterpret_cast<uint4*>(static_cast<_Float16*>(a.y) + o) = best;
+    }
+    return;
   }
   if (EXT && nsplit > 1) {
     // The workgroup that counts itself last owns the tile.  The XCDs' L2s are not coherent with
@@ -600,6 +692,36 @@ bool igemm_dma_supported(const ConvArgs& a, bool is_i8) {
   // tile rows are decoded as small offsets from the tile's first pixel (float reciprocal, < 2^22)
   return (a.C % ck) == 0 && a.R * a.S <= 32 && (size_t)a.N * a.xs_n * es <= lim &&
          (size_t)a.K * a.Kp * es <= lim && a.Wo < (1 << 20) && a.Ho < (1 << 20);
+}
+
+bool igemm_dma_pool_supported(const ConvArgs& a, bool is_i8) {
+  // whole 7 x 8 blocks of pooled outputs, vector stores, the plain fused tail
+  return igemm_dma_supported(a, is_i8) && a.Ho % 14 == 0 && a.Wo % 16 == 0 && (a.K & 7) == 0 && !(a.flags & F_RES) &&
+         a.round_mode != ROUND_STOCHASTIC && a.nseg == 0;
+}
+
+void fill_pool_args(ConvArgs& a) {
+  a.pool = 1;
+  a.pool_tiles_row = (a.Wo / 2) / 8;
+  a.pool_tiles_img = ((a.Ho / 2) / 7) * a.pool_tiles_row;
+  a.fd_pool_row = make_fastdiv((uint32_t)a.pool_tiles_row);
+  a.fd_pool_img = make_fastdiv((uint32_t)a.pool_tiles_img);
+}
+
+hipError_t launch_conv_igemm_dma_pool(const ConvArgs& a, bool is_i8, hipStream_t st) {
+  constexpr int BN = 64;
+  const int tiles_m = a.N * a.pool_tiles_img, tiles_n = (a.K + BN - 1) / BN;
+  ConvArgs b = a;
+  b.fd_tiles_m = make_fastdiv((uint32_t)tiles_m);
+  b.fd_tiles_n = make_fastdiv((uint32_t)tiles_n);
+  b.split = 1;
+  if (is_i8)
+    hipLaunchKernelGGL((igemm_dma_kernel<true, 4, 1, 2, 2, 3, 1, 1, false, false, true>), dim3(tiles_m * tiles_n), dim3(256), 0,
+                       st, b);
+  else
+    hipLaunchKernelGGL((igemm_dma_kernel<false, 4, 1, 2, 2, 3, 1, 1, false, false, true>), dim3(tiles_m * tiles_n), dim3(256), 0,
+                       st, b);
+  return hipGetLastError();
 }
 
 int igemm_dma_tile_count() { return kNumTiles; }

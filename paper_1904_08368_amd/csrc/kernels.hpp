@@ -46,6 +46,12 @@ struct ConvArgs {
   // Section 4.4): channel ch in [seg_end[i-1], seg_end[i]) of output pixel m is stored at
   // seg_y[i] + m*seg_ld[i] + (ch - seg_end[i-1]) elements; boundaries are multiples of 8.
   // nseg == 0: the plain tensor y with pixel pitch K.  Only the direct-to-LDS kernels read these.
+  // Fused 3x3 / stride 2 / pad 1 max pool behind the conv (direct-to-LDS implicit GEMM, 256-pixel
+  // tiles): a workgroup computes the 15 x 17 conv outputs under a 7 x 8 block of pooled outputs
+  // and writes only those.  pool != 0: y is the pooled tensor [N][Ho/2][Wo/2][K].
+  int pool;
+  int pool_tiles_img, pool_tiles_row;   // 7 x 8 blocks per image and per row of blocks
+  FastDiv fd_pool_img, fd_pool_row;
   // Reduction split over workgroups (direct-to-LDS implicit GEMM only): `split` workgroups share one
   // output tile, each reducing a contiguous run of chunks; they leave raw partial tiles in ws_part
   // ([tile][split][BM][BN] accumulator words) and count themselves in ws_cnt[tile]; the workgroup
@@ -80,6 +86,10 @@ hipError_t launch_conv_igemm_dma(const ConvArgs& a, bool is_i8, int tile, hipStr
 // count, clamped to the number of chunks) and the bytes of zero-initialised device memory that takes:
 // counters first (counter_bytes, a multiple of 256), then the partial tiles.
 int igemm_dma_plan_split(const ConvArgs& a, bool is_i8, int tile, int want, size_t* counter_bytes, size_t* total_bytes);
+// conv + 3x3/s2/p1 max pool in one launch (a.pool set up by fill_pool_args); false: shape not taken
+bool igemm_dma_pool_supported(const ConvArgs& a, bool is_i8);
+void fill_pool_args(ConvArgs& a);
+hipError_t launch_conv_igemm_dma_pool(const ConvArgs& a, bool is_i8, hipStream_t st);
 int igemm_dma_tile_count();
 void igemm_dma_kernel_name(const ConvArgs& a, bool is_i8, int tile, char* buf, size_t len);
 // The 3x3 / stride 1 / pad 1 kernel that stages the activations once per channel chunk (conv_halo.hip).

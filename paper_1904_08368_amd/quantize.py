@@ -29,7 +29,7 @@ def calibrate(ops, params: Sequence[dict], x_f16: np.ndarray, global_scale: bool
     """Ranges of the input and of every layer output: the smallest power of two not exceeded on the
     calibration batch (one common range when global_scale, the paper's first strategy)."""
     n, c, h, w = x_f16.shape
-    net = FusedNet(ops, params, n, h, w, "f16", in_channels=c, device=device)
+    net = FusedNet(ops, params, n, h, w, "f16", in_channels=c, device=device, fuse_pool=False)   # every tensor is read back
     net.load_input(x_f16)
     net.run()
     torch.cuda.synchronize()

@@ -27,13 +27,16 @@ class FusedNet:
     def __init__(self, ops, params: List[dict], batch: int, h: int, w: int, mode: str = "f16",
                  shifts: Optional[List[dict]] = None, in_channels: int = 3, device: str = "cuda:0",
                  overlap_shortcuts: bool = True, fused: bool = True, combine: bool = False,
-                 fold_scale: bool = False):
+                 fold_scale: bool = False, fuse_pool: bool = True):
         assert mode in ("f16", "i8")
         assert fused or mode == "f16"
         # combine: convs that share input, window and tail run as one launch; fold_scale: the
         # batch-norm scale is multiplied into the filters ahead of time (paper Section 4.4, both)
         assert not (combine or fold_scale) or (mode == "f16" and fused)
         self.fold_scale = fold_scale
+        # fuse_pool: a conv whose only reader is a 3x3 / stride 2 / pad 1 max pool runs with it as one
+        # launch where the library takes the shape; the conv's own output tensor then does not exist
+        self.fuse_pool = fuse_pool and fused
         # fused=False launches every elementwise operator behind a contraction as a kernel of its
         # own on a tensor of its own: the pipeline of a framework without operator fusion, kept
         # for the fusion ablation (paper Section 5.2)
@@ -98,6 +101,29 @@ class FusedNet:
                 wsrc = torch.from_numpy(np.ascontiguousarray(p["w"])).to(self.dev)
                 wp = torch.empty(B.relay_packed_weight_bytes(d), dtype=torch.uint8, device=self.dev)
                 B.relay_prepack_conv2d_weights(d, wsrc, cin_l, wp)
+                pool = self._pool_behind(ops, i) if self.fuse_pool and B.relay_conv2d_maxpool_fusable(d) else None
+                if pool is not None:
+                    absorbed.add(pool)
+                    y = torch.empty((batch, ho // 2, wo // 2, op.cout), dtype=self.tdtype, device=self.dev)
+                    name = op.name + "+" + ops[pool].name
+                    if mode == "f16" and fold_scale and p.get("scale") is not None:
+                        bias = self._fold(op, p, wsrc, cin_l)
+                        B.relay_prepack_conv2d_weights(d, wsrc, cin_l, wp)
+                        d = B.conv_desc(d.n, d.c, d.h, d.w, d.k, d.r, d.s, d.stride_h, d.pad_h, self.dtype, d.layout,
+                                        B.flags_of(True, None, None, op.relu))
+                        self._add(name, B.relay_fused_conv2d_bn_relu_maxpool, (d, src, wp, bias, None, None, y))
+                    elif mode == "f16":
+                        bias, sc, sf = (self._f32(p.get(k)) for k in ("bias", "scale", "shift"))
+                        self._add(name, B.relay_fused_conv2d_bn_relu_maxpool, (d, src, wp, bias, sc, sf, y))
+                    else:
+                        qb = None
+                        if p.get("bias") is not None:
+                            qb = torch.from_numpy(np.ascontiguousarray(p["bias"], dtype=np.int32)).to(self.dev)
+                            self.keep.append(qb)
+                        self._add(name, B.relay_qconv2d_requant_maxpool, (d, src, wp, qb, int(shifts[i]["s"]), y))
+                    self.keep += [wp, d]
+                    self.bufs[ops[pool].dst], self.shape[ops[pool].dst] = y, (op.cout, ho // 2, wo // 2)
+                    continue
                 y = torch.empty((batch, ho, wo, op.cout), dtype=self.tdtype, device=self.dev)
                 res = self.bufs[op.res] if op.res else None
                 ws = self._workspace(d)     # None for most layers
@@ -191,6 +217,18 @@ class FusedNet:
                 self.side = torch.cuda.Stream(device=self.dev)
         torch.cuda.synchronize(self.dev)
         self.graph = None
+
+    @staticmethod
+    def _pool_behind(ops, i):
+        """Index of the 3x3 / stride 2 / pad 1 max pool that is the only reader of conv i's output, or None."""
+        op = ops[i]
+        if op.res:
+            return None
+        users = [j for j, o in enumerate(ops) if o.src == op.dst or o.res == op.dst or op.dst in (o.srcs or ())]
+        if len(users) != 1 or users[0] != i + 1:
+            return None
+        q = ops[users[0]]
+        return users[0] if (q.kind == "maxpool" and q.src == op.dst and (q.r, q.stride, q.pad) == (3, 2, 1)) else None
 
     def _plan_concats(self, ops, batch, h, w, in_channels, cpad):
         """A channel concatenation is free when every tensor it joins is written by a conv: the
@@ -366,6 +404,8 @@ class FusedNet:
         """Download a named tensor as NCHW with the logical channel count."""
         if name == "x":
             return self.x_nchw.cpu().numpy()
+        if name not in self.bufs:
+            raise KeyError(f"{name} is not stored: its producer runs fused with the operator that reads it")
         c, _, _ = self.shape[name]
         t = self.bufs[name][..., :c].permute(0, 3, 1, 2).contiguous().cpu().numpy()
         return t

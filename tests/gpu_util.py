@@ -120,3 +120,45 @@ def run_dwconv_f16(x, w, stride, pad, bias=None, scale=None, shift=None, relu=Fa
     B.relay_fused_dwconv_bias_relu(d, xd, wp, up(bias), up(scale), up(shift), y)
     torch.cuda.synchronize()
     return from_nhwc(y, c)
+
+
+def run_conv_pool_f16(x, w, stride, pad, bias=None, scale=None, shift=None, relu=False, nhwc4=True, fused=True):
+    """conv -> 3x3/s2/p1 max pool, fp16: one pooled launch (fused) or the two separate calls."""
+    n, c, h, wd = x.shape
+    k, _, r, s = w.shape
+    flags = B.flags_of(bias, scale, None, relu)
+    d, xd = _input(x, k, r, s, stride, pad, B.RELAY_F16, 8, flags, nhwc4)
+    ho, wo = B.relay_conv2d_out_shape(d)
+    wp = torch.empty(B.relay_packed_weight_bytes(d), dtype=torch.uint8, device=DEV)
+    B.relay_prepack_conv2d_weights(d, up(w), c, wp)
+    hp, wpo = (ho - 1) // 2 + 1, (wo - 1) // 2 + 1
+    yp = torch.full((n, hp, wpo, k), float("nan"), dtype=torch.float16, device=DEV)
+    if fused:
+        B.relay_fused_conv2d_bn_relu_maxpool(d, xd, wp, up(bias), up(scale), up(shift), yp)
+    else:
+        y = torch.full((n, ho, wo, k), float("nan"), dtype=torch.float16, device=DEV)
+        B.relay_fused_conv2d_bias_bn_relu(d, xd, wp, up(bias), up(scale), up(shift), None, y)
+        B.relay_maxpool2d(B.RELAY_F16, n, k, ho, wo, 3, 2, 1, y, yp)
+    torch.cuda.synchronize()
+    return from_nhwc(yp, k)
+
+
+def run_qconv_pool(x, w, stride, pad, bias=None, rshift=0, relu=False, nhwc4=True, fused=True):
+    n, c, h, wd = x.shape
+    k, _, r, s = w.shape
+    flags = B.flags_of(bias, None, None, relu)
+    d, xd = _input(x, k, r, s, stride, pad, B.RELAY_I8, 16, flags, nhwc4)
+    ho, wo = B.relay_conv2d_out_shape(d)
+    wp = torch.empty(B.relay_packed_weight_bytes(d), dtype=torch.uint8, device=DEV)
+    B.relay_prepack_conv2d_weights(d, up(w), c, wp)
+    hp, wpo = (ho - 1) // 2 + 1, (wo - 1) // 2 + 1
+    yp = torch.full((n, hp, wpo, k), -128, dtype=torch.int8, device=DEV)
+    bd = None if bias is None else up(np.asarray(bias, dtype=np.int32))
+    if fused:
+        B.relay_qconv2d_requant_maxpool(d, xd, wp, bd, rshift, yp)
+    else:
+        y = torch.full((n, ho, wo, k), -128, dtype=torch.int8, device=DEV)
+        B.relay_qconv2d_requant(d, xd, wp, bd, None, 0, rshift, y)
+        B.relay_maxpool2d(B.RELAY_I8, n, k, ho, wo, 3, 2, 1, y, yp)
+    torch.cuda.synchronize()
+    return from_nhwc(yp, k)

@@ -296,3 +296,38 @@ def test_scale_folding_argument_checks():
     assert g(0, None, FAKE, FAKE, FAKE, None) == 2
     assert g(8, None, None, FAKE, FAKE, None) == 1
     assert g(8, FAKE + 1, FAKE, FAKE, FAKE, None) == 5
+
+
+def _pool(d, x=FAKE, w=FAKE, bias=None, sc=None, sf=None, y=FAKE + 4096):
+    return _status("relay_fused_conv2d_bn_relu_maxpool", C.byref(d), x, w, bias, sc, sf, y, None)
+
+
+def _qpool(d, x=FAKE, w=FAKE, bias=None, s=8, y=FAKE + 4096):
+    return _status("relay_qconv2d_requant_maxpool", C.byref(d), x, w, bias, s, y, None)
+
+
+def test_pooled_conv_argument_checks():
+    ok = dict(h=14, w=16)                                         # conv output 14 x 16: one block of pooled outputs
+    assert B.relay_conv2d_maxpool_fusable(_d(**ok))
+    assert B.relay_conv2d_maxpool_fusable(_d(c=3, h=224, w=224, r=7, s=7, stride=2, pad=3, layout=B.RELAY_NHWC4_PADDED))
+    assert B.relay_conv2d_maxpool_fusable(_d(dtype=B.RELAY_I8, **ok))
+    for bad in (_d(), _d(h=14, w=24), _d(h=21, w=16), _d(k=60, **ok), _d(c=8, **ok), _d(flags=B.HAS_RESIDUAL, **ok),
+                _d(dtype=B.RELAY_F32, layout=B.RELAY_NCHW, **ok), _d(dtype=B.RELAY_I8, flags=B.HAS_BN, **ok)):
+        assert not B.relay_conv2d_maxpool_fusable(bad)
+    assert _pool(_d()) == 4                                       # 8 x 8 conv output: no whole block
+    assert _pool(_d(h=14, w=24)) == 4 and _pool(_d(h=21, w=16)) == 4
+    assert _pool(_d(flags=B.HAS_RESIDUAL, **ok)) == 4
+    assert _pool(_d(dtype=B.RELAY_I8, **ok)) == 3
+    assert _pool(_d(**ok), x=None) == 1 and _pool(_d(**ok), y=None) == 1
+    assert _pool(_d(flags=B.HAS_BN, **ok), sc=FAKE) == 1
+    assert _pool(_d(**ok), bias=FAKE) == 1
+    assert _pool(_d(**ok), y=FAKE) == 4
+    assert _pool(_d(**ok), y=FAKE + 4096 + 8) == 5
+    q = dict(dtype=B.RELAY_I8, **ok)
+    assert _qpool(_d(**ok)) == 3
+    assert _qpool(_d(**q), s=-1) == 4 and _qpool(_d(**q), s=32) == 4
+    assert _qpool(_d(flags=B.HAS_BN, **q)) == 4
+    assert _qpool(_d(**q), x=None) == 1
+    assert _qpool(_d(**q), y=FAKE + 4) == 5
+    assert _qpool(_d(flags=B.HAS_BIAS, **q)) == 1
+    assert _status("relay_conv2d_maxpool_fusable", C.byref(_d()), None) == 1

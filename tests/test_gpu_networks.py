@@ -26,9 +26,9 @@ def G():
     return gpu_util
 
 
-def _net(ops, params, batch, hw, mode, shifts=None, cin=3):
+def _net(ops, params, batch, hw, mode, shifts=None, cin=3, fuse_pool=True):
     from paper_1904_08368_amd.stack import FusedNet
-    return FusedNet(ops, params, batch, hw, hw, mode, shifts=shifts, in_channels=cin)
+    return FusedNet(ops, params, batch, hw, hw, mode, shifts=shifts, in_channels=cin, fuse_pool=fuse_pool)
 
 
 # ------------------------------------------------------------------ config 2: basic block
@@ -150,11 +150,15 @@ def test_config3_resnet18_fp16_chain_and_layers(G, batch):
     x = inputs.image(3, batch, 3, 224, 224, "f16")
     ref = run_float(ops, params, x, "f16")
     _per_layer_float(G, ops, params, ref)
-    net = _net(ops, params, batch, 224, "f16")
+    pooled = batch == 2      # the first conv and its max pool as one launch / as two
+    net = _net(ops, params, batch, 224, "f16", fuse_pool=pooled)
     net.load_input(x)
     net.run()
     torch.cuda.synchronize()
-    assert O.max_rel_err(net.tensor("c1"), ref["c1"]) <= TOL_F16
+    assert ("conv1+maxpool" in net.call_names) == pooled and ("c1" in net.bufs) != pooled
+    if not pooled:
+        assert O.max_rel_err(net.tensor("c1"), ref["c1"]) <= TOL_F16
+    assert O.max_rel_err(net.tensor("s1.in"), ref["s1.in"]) <= TOL_F16
     for name in ("l1.b1.out", "l2.b1.out", "l3.b1.out", "l4.b1.out"):
         assert O.max_rel_err(net.tensor(name), ref[name]) <= TOL_F16_CHAIN, name
     logits = net.tensor("logits").reshape(batch, 1000)
@@ -224,12 +228,15 @@ def test_config4_resnet18_int8_chain_bit_exact(G, batch):
     shifts = inputs.chain_shifts(ops)
     x = inputs.image(4, batch, 3, 224, 224, "i8")
     ref = run_quantized(ops, params, shifts, x)
-    net = _net(ops, params, batch, 224, "i8", shifts=shifts)
+    pooled = batch == 16     # the first conv and its max pool as one launch / as two
+    net = _net(ops, params, batch, 224, "i8", shifts=shifts, fuse_pool=pooled)
     net.load_input(x)
     net.run()
     torch.cuda.synchronize()
+    assert ("conv1+maxpool" in net.call_names) == pooled and ("c1" in net.bufs) != pooled
     for op in ops:
-        assert np.array_equal(net.tensor(op.dst), ref[op.dst]), op.name
+        if op.dst in net.bufs:
+            assert np.array_equal(net.tensor(op.dst), ref[op.dst]), op.name
     first = net.tensor("l4.b1.out").copy()
     net.run()
     torch.cuda.synchronize()

@@ -146,7 +146,8 @@ def test_calibrate_realize_flow_on_resnet18(G):
     net.run()
     torch.cuda.synchronize()
     for op in ops:
-        assert np.array_equal(net.tensor(op.dst), ref_q[op.dst]), op.name
+        if op.dst in net.bufs:      # (a conv that runs with its max pool leaves no tensor of its own)
+            assert np.array_equal(net.tensor(op.dst), ref_q[op.dst]), op.name
     last = ops[-1].dst
     ref = t[last].astype(np.float64)
     deq = R.dequantize(net.tensor(last), rho[last])
