@@ -85,10 +85,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
   typedef typename Mma<IS_I8>::acc_t acc_t;
 
   constexpr int PDY = 15, PDX = 17;                 // conv patch of a pooled 7 x 8 block
-  constexpr int PATCH = POOL ? BM * (BN / 8) : 0;   // 16-byte slots of the finished patch
-  static_assert(!POOL || (BM >= PDY * PDX && SK == 1 && !EXT && !STOCH), "pooled tiles hold one 15 x 17 patch");
-  constexpr int RING_SLOTS = NS * STAGE > NW * 32 * EP + PATCH ? NS * STAGE : NW * 32 * EP + PATCH;
-  __shared__ uint4 ring[RING_SLOTS];
+  // the finished patch in LDS, [conv pixel][channel] in the output type; 8 bytes of padding per row
+  // spread the accumulator layout's writes (32 lanes, 32 consecutive rows, one 4-channel group) over the banks
+  constexpr int PPITCH = POOL ? BN * ES + 8 : 0;
+  static_assert(!POOL || (BM >= PDY * PDX && SK == 1 && !EXT && !STOCH && WAVES_N == 1), "pooled tiles hold one 15 x 17 patch");
+  static_assert(BM * PPITCH <= NS * STAGE * 16, "the patch reuses the ring");
+  __shared__ uint4 ring[NS * STAGE];
+  __shared__ float pool_cst[POOL ? 2 * BN : 1];  // pooled tiles: the epilogue constants of the tile's channels
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -249,6 +252,19 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
 
   LaneParams lp;
   finish_lane_params<IS_I8>(rawp, lp);
+  if constexpr (POOL) {  // lanes 0 .. BN/8-1 of a wave hold the constants of all BN channels between them
+    if (wave == 0 && lane < BN / 8) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        if constexpr (IS_I8) {
+          pool_cst[lane * 8 + e] = __builtin_bit_cast(float, lp.ibias[e]);
+        } else {
+          pool_cst[lane * 8 + e] = lp.mul[e];
+          pool_cst[BN + lane * 8 + e] = lp.add[e];
+        }
+      }
+    }
+  }
 
   const int lrow = lane & 31, lhalf = lane >> 5;
   int stage = 0;      // ring stage of chunk kc
@@ -406,13 +422,57 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
           }
         }
   }
+  if constexpr (POOL) {
+    // Pooled tiles finish their accumulators where they are (element v of a block: pixel lane % 32,
+    // channels 8 (v / 4) + 4 (lane / 32) + v % 4) and write the narrowed values, four channels at a
+    // time, into the patch.
+    char* patch_w = reinterpret_cast<char*>(ring);
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int cb = tn * 32 + 8 * g + 4 * lhalf;  // first of the lane's four channels, within the tile
+        const float4 c0 = *reinterpret_cast<const float4*>(pool_cst + cb);
+        const float4 c1 = *reinterpret_cast<const float4*>(pool_cst + BN + cb);  // (fp16 only)
+        const float m4[4] = {c0.x, c0.y, c0.z, c0.w}, a4[4] = {c1.x, c1.y, c1.z, c1.w};
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) {
+          char* dst = patch_w + (wm * WTM + tm * 32 + lrow) * PPITCH + cb * ES;
+          if constexpr (IS_I8) {
+            unsigned pk = 0u;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              int q = (acc[tn][tm][4 * g + e] + __builtin_bit_cast(int, m4[e]) + a.round_add) >> a.rshift;
+              q = q < -127 ? -127 : (q > 127 ? 127 : q);
+              if (a.flags & F_RELU) q = q > 0 ? q : 0;
+              pk |= (unsigned)(q & 0xff) << (8 * e);
+            }
+            *reinterpret_cast<unsigned*>(dst) = pk;
+          } else {
+            typedef _Float16 half4v __attribute__((ext_vector_type(4)));
+            half4v hv;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              float t = acc[tn][tm][4 * g + e] * m4[e] + a4[e];
+              // rounded to fp32 before it is narrowed, as in the unpooled kernel's epilogue: left alone the
+              // compiler merges the multiply-add and the conversion into one instruction that rounds
+              // once, and one result in some thousands differs from that kernel's in its last bit
+              asm("" : "+v"(t));
+              if (a.flags & F_RELU) t = t > 0.f ? t : 0.f;
+              hv[e] = (_Float16)t;
+            }
+            *reinterpret_cast<uint2*>(dst) = __builtin_bit_cast(uint2, hv);
+          }
+        }
+      }
+  }
   uint4* stg = ring + NW * XCH + wave * (32 * EP);
   constexpr int PPI = 64 / CG;  // pixels per pass of 64 lanes
   const int epix = lane / CG, ecg = lane % CG;
   const bool vec_ok = (a.K & 7) == 0;
   const OutLoc ol = EXT ? locate_output(a, ech) : OutLoc{nullptr, 0, 0};
 #pragma unroll
-  for (int te = 0; te < TM_E; ++te) {
+  for (int te = 0; te < (POOL ? 0 : TM_E); ++te) {
     const int tm = tm_lo + te;  // block row in the workgroup tile
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn)
@@ -438,10 +498,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
       const int pix = it * PPI + epix;
       const uint4 lo = stg[pix * EP + ecg * 2], hi = stg[pix * EP + ecg * 2 + 1];
       const unsigned raw[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-      if constexpr (POOL) {  // the finished element goes to the patch in LDS (rows outside the image too: masked below)
-        if (ech < a.K) ring[NW * 32 * EP + (wm * WTM + tm * 32 + pix) * (BN / 8) + (ech - n0) / 8] = finish8_packed<IS_I8>(a, raw, lp);
-        continue;
-      }
       const int m = m0 + wm * WTM + tm * 32 + pix;
       if (m >= a.M || ech >= a.K) continue;
       if (EXT && nsplit > 1) {  // (uniform) leave the raw partial sums for the workgroup that finishes the tile
@@ -456,11 +512,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
   }
   if constexpr (POOL) {
     // ---- 3x3 / stride 2 / pad 1 max pool over the finished patch: pooled output (7 i + py, 8 j + px)
-    //      takes conv outputs (2 oy - 1 + r, 2 ox - 1 + s), patch rows (2 py + r) * 17 + 2 px + s;
-    //      positions outside the conv output are skipped (the centre never is).
+    //      takes conv outputs (2 oy - 1 + r, 2 ox - 1 + s), patch rows (2 py + r) * 17 + 2 px + s.
     __syncthreads();
     constexpr int GROUPS = BN / 8;
-    const uint4* patch = ring + NW * 32 * EP;
+    const char* patch = reinterpret_cast<const char*>(ring);
     const int hp = a.Ho >> 1, wp = a.Wo >> 1;
     for (int item = tid; item < 56 * GROUPS; item += NW * 64) {
       const int pp = item / GROUPS, gch = item - pp * GROUPS;
@@ -481,7 +536,18 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
 #pragma unroll
         for (int s2 = 0; s2 < 3; ++s2) {
           const int rr = r == 0 ? r_lo : r, ss = s2 == 0 ? s_lo : s2;
-          const uint4 v = patch[((2 * py + rr) * PDX + 2 * px + ss) * GROUPS + gch];
+          const char* src = patch + ((2 * py + rr) * PDX + 2 * px + ss) * PPITCH + gch * 8 * ES;  // 8-byte aligned
+          uint4 v = make_uint4(0u, 0u, 0u, 0u);
+          {
+            const uint2 lo = *reinterpret_cast<const uint2*>(src);
+            v.x = lo.x;
+            v.y = lo.y;
+            if constexpr (!IS_I8) {
+              const uint2 hi = *reinterpret_cast<const uint2*>(src + 8);
+              v.z = hi.x;
+              v.w = hi.y;
+            }
+          }
           if constexpr (IS_I8) {
             const unsigned vw[2] = {v.x, v.y};
 #pragma unroll
@@ -708,6 +774,9 @@ void fill_pool_args(ConvArgs& a) {
   a.fd_pool_img = make_fastdiv((uint32_t)a.pool_tiles_img);
 }
 
+// 256 x 64 tiles of four 64 x 64 waves with a two-stage ring: 41 KB of LDS, three workgroups per CU.
+// A workgroup's life is mostly latency (first loads, epilogue, pooling), so the third resident
+// workgroup buys more than a third ring stage (measured on the 7x7 first layer of ResNet-18).
 hipError_t launch_conv_igemm_dma_pool(const ConvArgs& a, bool is_i8, hipStream_t st) {
   constexpr int BN = 64;
   const int tiles_m = a.N * a.pool_tiles_img, tiles_n = (a.K + BN - 1) / BN;
@@ -716,10 +785,10 @@ hipError_t launch_conv_igemm_dma_pool(const ConvArgs& a, bool is_i8, hipStream_t
   b.fd_tiles_n = make_fastdiv((uint32_t)tiles_n);
   b.split = 1;
   if (is_i8)
-    hipLaunchKernelGGL((igemm_dma_kernel<true, 4, 1, 2, 2, 3, 1, 1, false, false, true>), dim3(tiles_m * tiles_n), dim3(256), 0,
+    hipLaunchKernelGGL((igemm_dma_kernel<true, 4, 1, 2, 2, 2, 1, 1, false, false, true>), dim3(tiles_m * tiles_n), dim3(256), 0,
                        st, b);
   else
-    hipLaunchKernelGGL((igemm_dma_kernel<false, 4, 1, 2, 2, 3, 1, 1, false, false, true>), dim3(tiles_m * tiles_n), dim3(256), 0,
+    hipLaunchKernelGGL((igemm_dma_kernel<false, 4, 1, 2, 2, 2, 1, 1, false, false, true>), dim3(tiles_m * tiles_n), dim3(256), 0,
                        st, b);
   return hipGetLastError();
 }

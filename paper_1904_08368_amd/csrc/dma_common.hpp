@@ -160,37 +160,6 @@ __device__ __forceinline__ void load_lane_params(const ConvArgs& a, int ech, Lan
   finish_lane_params<IS_I8>(rp, lp);
 }
 
-// The finished 8 channels of one output element as a packed 16-byte value (fp16: 8 halves; int8: 8
-// bytes in .x/.y), for epilogues that post-process in LDS instead of storing: no residual, no
-// stochastic rounding.
-template <bool IS_I8>
-__device__ __forceinline__ uint4 finish8_packed(const ConvArgs& a, const unsigned (&raw)[8], const LaneParams& lp) {
-  if constexpr (!IS_I8) {
-    half8 hv;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      float t = __builtin_bit_cast(float, raw[e]) * lp.mul[e] + lp.add[e];
-      // the fp32 value is rounded before it is narrowed, as in finish_store8: without this the
-      // compiler merges the multiply-add and the conversion into one instruction that rounds once,
-      // and one result in some thousands differs from the unpooled kernel's in its last bit
-      asm("" : "+v"(t));
-      if (a.flags & F_RELU) t = t > 0.f ? t : 0.f;
-      hv[e] = (_Float16)t;
-    }
-    return __builtin_bit_cast(uint4, hv);
-  } else {
-    unsigned pk[2] = {0u, 0u};
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      int q = ((int)raw[e] + lp.ibias[e] + a.round_add) >> a.rshift;  // arithmetic shift: floor
-      q = q < -127 ? -127 : (q > 127 ? 127 : q);
-      if (a.flags & F_RELU) q = q > 0 ? q : 0;
-      pk[e >> 2] |= (unsigned)(q & 0xff) << (8 * (e & 3));
-    }
-    return make_uint4(pk[0], pk[1], 0u, 0u);
-  }
-}
-
 // EXT: the instantiation that knows about output segments (the plain one ignores ol).
 // Finish the 8 consecutive channels [ech, ech + 8) of output pixel m (its index in the NHWC output;
 // residual and random draws are addressed in the plain [M][K] tensor, the store goes where ol says)
