@@ -826,7 +826,7 @@ int igemm_dma_plan_split(const ConvArgs& a, bool is_i8, int tile, int want, size
 void igemm_dma_kernel_name(const ConvArgs& a, bool is_i8, int tile, char* buf, size_t len) {
   const DmaTile& t = kTiles[resolve_tile(a, is_i8, tile)];
   const bool stoch = is_i8 && a.round_mode == ROUND_STOCHASTIC;
-  snprintf(buf, len, "igemm_dma_kernel<%s, %d, %d, %d, %d, %d, %d, %d, %s, %s>", is_i8 ? "true" : "false", t.waves_m,
+  snprintf(buf, len, "igemm_dma_kernel<%s, %d, %d, %d, %d, %d, %d, %d, %s, %s, false>", is_i8 ? "true" : "false", t.waves_m,
            t.waves_n, t.tm, t.tn, t.ns, t.kp, t.sk, stoch ? "true" : "false",
            (stoch || a.nseg || a.split > 1) ? "true" : "false");
 }
