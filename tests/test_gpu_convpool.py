@@ -125,3 +125,31 @@ def test_first_layer_at_full_size_equals_the_two_calls(G):
                             relu_flag=True, out_dtype="f16")
         want = yc.reshape(k, -1).max(axis=1).astype(np.float16)
         assert O.max_rel_err(got[i, :, oy, ox], want) <= TOL_F16, (i, oy, ox)
+
+
+@pytest.mark.parametrize("fold_scale", [False, True])
+def test_network_driver_takes_the_pooled_launch(G, fold_scale):
+    """The first four functions of ResNet-18 (conv, max pool, one residual block) through the network
+    driver, the pool inside the conv's launch and as its own: same bits both ways, and the oracle's
+    values (on parameters folded by the oracle where the driver folds the scale into the filters)."""
+    from oracle import combine as OC
+    from oracle.stack import run_float
+    from paper_1904_08368_amd.stack import FusedNet
+    ops = nets.resnet18()[:4]
+    params = inputs.net_params(ops, 3, "f16")
+    x = inputs.image(35, 2, 3, 224, 224, "f16")
+    ref = run_float(ops, [OC.fold_bn_into_conv(p, "f16") if (fold_scale and p) else p for p in params], x, "f16")
+    outs = {}
+    for pooled in (True, False):
+        net = FusedNet(ops, params, 2, 224, 224, "f16", fold_scale=fold_scale, fuse_pool=pooled)
+        assert ("conv1+maxpool" in net.call_names) == pooled and len(net.calls) == (4 if pooled else 5)
+        net.load_input(x)
+        net.run()
+        torch.cuda.synchronize()
+        outs[pooled] = {name: net.tensor(name) for name in (ops[1].dst, ops[-1].dst)}
+        with pytest.raises(KeyError):
+            net.tensor("c1") if pooled else net.tensor("no such tensor")
+    for name in outs[True]:
+        assert int((outs[True][name].view(np.uint16) != outs[False][name].view(np.uint16)).sum()) == 0, name
+    assert O.max_rel_err(outs[True][ops[1].dst], ref[ops[1].dst]) <= TOL_F16
+    assert O.max_rel_err(outs[True][ops[-1].dst], ref[ops[-1].dst]) <= 2e-2   # three layers deep: the chain tolerance of the network tests
