@@ -75,6 +75,16 @@ def _layer_table(net, ops, batch, reps, trials):
                 row["mbytes"] = (d.n * d.h * d.w * d.c + d.n * ho * wo * d.c + 9 * d.c) * es / 1e6
             row["tflops"] = row["gflop"] / row["us"] * 1e3           # GFLOP/us = 1000 TFLOP/s
             row["gbs"] = row["mbytes"] / row["us"] * 1e3              # MB/us = 1000 GB/s
+        elif fn in (B.relay_fused_conv2d_bn_relu_maxpool, B.relay_qconv2d_requant_maxpool):
+            # the conv with its max pool in the same launch: the conv's FLOP, input + pooled output + filters
+            ho, wo = B.relay_conv2d_out_shape(d)
+            es = 2 if d.dtype == B.RELAY_F16 else 1
+            op = next(o for o in ops if o.name == name.split("+")[0])
+            row["gflop"] = 2 * d.n * ho * wo * d.k * op.cin * d.r * d.s / 1e9
+            row["kernel"] = B.relay_conv2d_maxpool_kernel_name(d)
+            row["mbytes"] = (d.n * d.h * d.w * op.cin + d.n * (ho // 2) * (wo // 2) * d.k + d.k * op.cin * d.r * d.s) * es / 1e6
+            row["tflops"] = row["gflop"] / row["us"] * 1e3
+            row["gbs"] = row["mbytes"] / row["us"] * 1e3
         rows.append(row)
     return rows
 

@@ -197,8 +197,10 @@ relay_status relay_global_avgpool(int32_t dtype, int32_t n, int32_t c, int32_t h
  *   y_pooled   [n, ho/2, wo/2, k] NHWC in d->dtype; F16 16-byte, I8 8-byte aligned
  *   the other operands as in the unpooled calls; the quantized call rounds to nearest.
  * relay_conv2d_maxpool_fusable writes 1 if these calls take the descriptor, else 0 (the calls
- * themselves return RELAY_ERR_UNSUPPORTED and launch nothing). */
+ * themselves return RELAY_ERR_UNSUPPORTED and launch nothing).
+ * relay_conv2d_maxpool_kernel_name: the kernel a trace shows for these calls (cf. relay_conv2d_kernel_name). */
 relay_status relay_conv2d_maxpool_fusable(const relay_conv2d_desc* d, int32_t* fusable);
+relay_status relay_conv2d_maxpool_kernel_name(const relay_conv2d_desc* d, char* buf, size_t len);
 relay_status relay_fused_conv2d_bn_relu_maxpool(const relay_conv2d_desc* d, const void* x, const void* w_packed,
                                                 const float* bias, const float* bn_scale, const float* bn_shift,
                                                 void* y_pooled, void* hip_stream);

@@ -63,6 +63,7 @@ SIGNATURES = {
     "relay_fold_scale_axis": [_I, _I, _I, _I, _I, _P, _P, _P, _P],
     "relay_fold_bias": [_I, _P, _P, _P, _P, _P],
     "relay_conv2d_maxpool_fusable": [_DP, C.POINTER(_I)],
+    "relay_conv2d_maxpool_kernel_name": [_DP, C.c_char_p, _SZ],
     "relay_fused_conv2d_bn_relu_maxpool": [_DP, _P, _P, _P, _P, _P, _P, _P],
     "relay_qconv2d_requant_maxpool": [_DP, _P, _P, _P, _I, _P, _P],
     "relay_set_conv_tile": [_I],
@@ -266,6 +267,12 @@ def relay_fuse_extract(pattern: Sequence[int], in_offsets: Sequence[int], in_nod
 def relay_conv2d_kernel_name(d: ConvDesc) -> str:
     buf = C.create_string_buffer(128)
     _check(lib().relay_conv2d_kernel_name(C.byref(d), buf, 128))
+    return buf.value.decode()
+
+
+def relay_conv2d_maxpool_kernel_name(d: ConvDesc) -> str:
+    buf = C.create_string_buffer(128)
+    _check(lib().relay_conv2d_maxpool_kernel_name(C.byref(d), buf, 128))
     return buf.value.decode()
 
 

@@ -489,6 +489,16 @@ relay_status relay_conv2d_maxpool_fusable(const relay_conv2d_desc* d, int32_t* f
   return RELAY_OK;
 }
 
+relay_status relay_conv2d_maxpool_kernel_name(const relay_conv2d_desc* d, char* buf, size_t len) {
+  if (!buf || len == 0) return fail(RELAY_ERR_NULL, "name buffer is NULL or empty");
+  int ho, wo;
+  relay::ConvArgs a;
+  const relay_status st = check_pool_fusable(d, &ho, &wo, &a);
+  if (st != RELAY_OK) return st;
+  relay::igemm_dma_pool_kernel_name(d->dtype == RELAY_I8, buf, len);
+  return RELAY_OK;
+}
+
 relay_status relay_fused_conv2d_bn_relu_maxpool(const relay_conv2d_desc* d, const void* x, const void* w_packed,
                                                 const float* bias, const float* bn_scale, const float* bn_shift,
                                                 void* y_pooled, void* hip_stream) {

@@ -793,6 +793,10 @@ hipError_t launch_conv_igemm_dma_pool(const ConvArgs& a, bool is_i8, hipStream_t
   return hipGetLastError();
 }
 
+void igemm_dma_pool_kernel_name(bool is_i8, char* buf, size_t len) {
+  snprintf(buf, len, "igemm_dma_kernel<%s, 4, 1, 2, 2, 2, 1, 1, false, false, true>", is_i8 ? "true" : "false");
+}
+
 int igemm_dma_tile_count() { return kNumTiles; }
 
 int igemm_dma_plan_split(const ConvArgs& a, bool is_i8, int tile, int want, size_t* counter_bytes,

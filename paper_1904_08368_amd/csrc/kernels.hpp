@@ -90,6 +90,7 @@ int igemm_dma_plan_split(const ConvArgs& a, bool is_i8, int tile, int want, size
 bool igemm_dma_pool_supported(const ConvArgs& a, bool is_i8);
 void fill_pool_args(ConvArgs& a);
 hipError_t launch_conv_igemm_dma_pool(const ConvArgs& a, bool is_i8, hipStream_t st);
+void igemm_dma_pool_kernel_name(bool is_i8, char* buf, size_t len);
 int igemm_dma_tile_count();
 void igemm_dma_kernel_name(const ConvArgs& a, bool is_i8, int tile, char* buf, size_t len);
 // The 3x3 / stride 1 / pad 1 kernel that stages the activations once per channel chunk (conv_halo.hip).

@@ -331,3 +331,5 @@ def test_pooled_conv_argument_checks():
     assert _qpool(_d(**q), y=FAKE + 4) == 5
     assert _qpool(_d(flags=B.HAS_BIAS, **q)) == 1
     assert _status("relay_conv2d_maxpool_fusable", C.byref(_d()), None) == 1
+    assert B.relay_conv2d_maxpool_kernel_name(_d(**ok)) == "igemm_dma_kernel<false, 4, 1, 2, 2, 2, 1, 1, false, false, true>"
+    assert _status("relay_conv2d_maxpool_kernel_name", C.byref(_d()), C.create_string_buffer(64), 64) == 4
