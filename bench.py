@@ -150,7 +150,7 @@ def main() -> int:
                          "scales FETCH_SIZE / WRITE_SIZE counter readings of the same profiler run")
     a = ap.parse_args()
     if a.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; the path shards over the batch axis with no "
+        print("bench.py: this library runs on ONE GPU; the path shards over the batch axis with no "
               "collective, but nothing here launches more than one rank.", file=sys.stderr)
         return 2
 
@@ -301,6 +301,17 @@ def main() -> int:
             del inet
         res["speedup_from_combination"] = round(res["separate_ms"] / res["combined_ms"], 3)
         extra["parallel_conv_combination_inception_block_b32"] = res
+        # ---- the same pass on the headline stack: each stride-2 3x3 conv and the 1x1 shortcut conv beside it
+        #      as one launch (the shortcut as a centre-tap segment without relu); not the default, see the figures
+        mnet = FusedNet(ops, params, a.batch, 224, 224, "f16", combine="windows")
+        mnet.load_input(inputs.image(3, a.batch, 3, 224, 224, "f16"))
+        if use_graph:
+            mnet.capture()
+        msec = _time_steps(mnet, a.steps, a.warmup, use_graph)
+        extra["parallel_conv_combination_resnet18_shortcuts"] = {
+            "separate_ms": round(sec * 1e3, 4), "separate_launches": len(net.calls),
+            "merged_ms": round(msec * 1e3, 4), "merged_launches": len(mnet.calls)}
+        del mnet
 
     if not a.no_cpu:
         # ---- the CPU oracle on this host: 4 of the 32 images, one pass of the same stack

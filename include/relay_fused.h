@@ -35,7 +35,7 @@ typedef enum {
   RELAY_ERR_NULL = 1,        /* a required pointer is NULL, or an optional one disagrees with flags */
   RELAY_ERR_SHAPE = 2,       /* a non-positive extent, an empty output, padding >= kernel ... */
   RELAY_ERR_DTYPE = 3,       /* dtype not valid for this entry point */
-  RELAY_ERR_UNSUPPORTED = 4, /* a valid request this build has no kernel for */
+  RELAY_ERR_UNSUPPORTED = 4, /* a valid request this library has no kernel for */
   RELAY_ERR_ALIGN = 5,       /* pointer or channel count not aligned for vector access */
   RELAY_ERR_WORKSPACE = 6,   /* workspace smaller than relay_workspace_bytes() asks */
   RELAY_ERR_DEVICE = 7       /* the HIP runtime refused the launch */
@@ -246,6 +246,27 @@ relay_status relay_fused_conv2d_combined(const relay_conv2d_desc* d, const void*
                                          const void* w_packed, const float* bias, const float* bn_scale,
                                          const float* bn_shift, int32_t nseg, const int32_t* seg_channels,
                                          void* const* seg_y, const int32_t* seg_ld, void* hip_stream);
+
+/* relay_fused_conv2d_combined for members whose windows and tails differ in two ways that occur
+ * in residual networks (a stride-2 3x3 convolution and the 1x1 shortcut convolution beside it
+ * read the same tensor): a 1x1 convolution with the same stride and no padding reads, for every
+ * output pixel, the input pixel under the CENTRE tap of an odd r x s window padded by (r/2, s/2),
+ * so it is that window with zeros everywhere else; and one member may end in relu while another
+ * does not.  Per segment (host arrays of nseg entries):
+ *   seg_window[i]  RELAY_WINDOW_FULL: the descriptor's window.  RELAY_WINDOW_CENTRE: a 1x1
+ *                  convolution; its filters sit at the centre tap of rows packed for the r x s
+ *                  window (prepack the 1x1 filters embedded in zeros), and its tiles reduce over
+ *                  that tap only, so the zeros cost nothing.  Such a segment begins at and holds
+ *                  a multiple of 128 channels.
+ *   seg_relu[i]    1: relu (d->flags must hold RELAY_RELU), 0: none.
+ * Everything else as relay_fused_conv2d_combined. */
+typedef enum { RELAY_WINDOW_FULL = 0, RELAY_WINDOW_CENTRE = 1 } relay_segment_window;
+relay_status relay_fused_conv2d_combined_windows(const relay_conv2d_desc* d, const void* x, int32_t x_ld,
+                                                 const void* w_packed, const float* bias, const float* bn_scale,
+                                                 const float* bn_shift, int32_t nseg, const int32_t* seg_channels,
+                                                 void* const* seg_y, const int32_t* seg_ld,
+                                                 const int32_t* seg_window, const int32_t* seg_relu,
+                                                 void* hip_stream);
 
 /* Axis scale folding (paper Section 4.4, "Axis scale folding"): a multiplication by a
  * per-channel constant before or after a convolution is moved into the convolution's constant

@@ -52,21 +52,92 @@ def fold_bn_into_conv(p: Dict[str, np.ndarray], out_dtype: str) -> Dict[str, np.
     return q
 
 
+def embed_centre(w: np.ndarray, r: int) -> np.ndarray:
+    """A 1x1 filter bank [K, C, 1, 1] as an r x r one (r odd) that is zero except at the centre tap.
+    With the same stride, conv(x, w, pad 0) == conv(x, embed_centre(w, r), pad r // 2): output pixel
+    (p, q) of the padded r x r window starts at input (p*stride - r//2, q*stride - r//2), so its
+    centre tap reads input (p*stride, q*stride), the pixel the 1x1 convolution reads, and every
+    other tap is multiplied by zero."""
+    w = np.asarray(w)
+    assert w.ndim == 4 and w.shape[2:] == (1, 1) and r % 2 == 1
+    out = np.zeros(w.shape[:2] + (r, r), dtype=w.dtype)
+    out[:, :, r // 2, r // 2] = w[:, :, 0, 0]
+    return out
+
+
 def signature(op) -> tuple:
     """What two convolutions must share, besides their input, to be combined: the window and
     the elementwise tail fused behind them (so the per-channel constants can be stacked too)."""
     return (op.src, op.cin, op.r, op.stride, op.pad, bool(op.bias), bool(op.bn), bool(op.relu))
 
 
-def combine_groups(ops: Sequence) -> List[List[int]]:
+def combine_groups(ops: Sequence, windows: bool = False) -> List[List[int]]:
     """Indices of the convs to merge, one list per combined conv (lists of length >= 2, members
     in program order, lists ordered by first member).  A conv with a residual operand is left
-    alone: its tail reads a second tensor."""
-    found: Dict[tuple, List[int]] = {}
-    for i, op in enumerate(ops):
-        if op.kind == "conv" and not op.res:
-            found.setdefault(signature(op), []).append(i)
-    return sorted((g for g in found.values() if len(g) >= 2), key=lambda g: g[0])
+    alone: its tail reads a second tensor.
+
+    windows=True: convs over the same input with the same stride whose windows are odd and padded
+    by half their size are also merged when one kind is 1x1 and the other the widest window of
+    the set (embed_centre), whatever their relu; the wide members are listed first."""
+    if not windows:
+        found: Dict[tuple, List[int]] = {}
+        for i, op in enumerate(ops):
+            if op.kind == "conv" and not op.res:
+                found.setdefault(signature(op), []).append(i)
+        return sorted((g for g in found.values() if len(g) >= 2), key=lambda g: g[0])
+    convs = [i for i, op in enumerate(ops) if op.kind == "conv" and not op.res]
+    is_centred = lambda op: op.r % 2 == 1 and op.pad == op.r // 2
+    out: List[List[int]] = []
+    # convs that are not centred windows, and centred ones of middle sizes, merge as without `windows`
+    buckets: Dict[tuple, List[int]] = {}
+    for i in convs:
+        op = ops[i]
+        buckets.setdefault((op.src, op.cin, op.stride, bool(op.bias), bool(op.bn)) if is_centred(op) else (None,) + signature(op), []).append(i)
+    for key, members in buckets.items():
+        if key[0] is None:
+            if len(members) >= 2:
+                out.append(members)
+            continue
+        widest = max(ops[i].r for i in members)
+        if widest == 1:
+            for relu in (True, False):
+                same = [i for i in members if bool(ops[i].relu) == relu]
+                if len(same) >= 2:
+                    out.append(same)
+            continue
+        merged = [i for i in members if ops[i].r == widest] + [i for i in members if ops[i].r == 1]
+        if len(merged) >= 2:
+            out.append(merged)
+        for r in sorted({ops[i].r for i in members} - {1, widest}):
+            for relu in (True, False):
+                same = [i for i in members if ops[i].r == r and bool(ops[i].relu) == relu]
+                if len(same) >= 2:
+                    out.append(same)
+    return sorted(out, key=min)
+
+
+def combined_conv2d_windows(x, ops: Sequence, members: Sequence[Dict[str, np.ndarray]], out_dtype: str = "f16") -> List[np.ndarray]:
+    """A group found with windows=True evaluated as ONE conv: the 1x1 members' filters embedded at the
+    centre of the widest window, filters and per-channel constants stacked, no relu in the conv;
+    then every member's channel slice gets that member's relu (relu of the narrowed value equals the
+    narrowed relu: narrowing is monotone and keeps zero)."""
+    r = max(op.r for op in ops)
+    ws = [np.asarray(m["w"]) if op.r == r else embed_centre(m["w"], r) for op, m in zip(ops, members)]
+    def stack(key):
+        if members[0].get(key) is None:
+            assert all(m.get(key) is None for m in members)
+            return None
+        return np.concatenate([np.asarray(m[key]) for m in members], axis=0)
+    st = ops[0].stride
+    y = fused_conv2d(x, np.concatenate(ws, axis=0), stride=(st, st), pad=(r // 2, r // 2), bias=stack("bias"),
+                     scale=stack("scale"), shift=stack("shift"), relu_flag=False, out_dtype=out_dtype)
+    outs, k0 = [], 0
+    for op, m in zip(ops, members):
+        k = m["w"].shape[0]
+        part = y[:, k0:k0 + k]
+        outs.append(np.maximum(part, 0).astype(part.dtype) if op.relu else part)
+        k0 += k
+    return outs
 
 
 def combined_conv2d(x, members: Sequence[Dict[str, np.ndarray]], *, stride, pad, relu_flag,

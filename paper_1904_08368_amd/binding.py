@@ -60,6 +60,7 @@ SIGNATURES = {
     "relay_quantize": [C.c_int64, _I, _P, C.c_float, _I, _I, _I, C.c_uint64, _P, _P],
     "relay_sim_quantize": [C.c_int64, _P, C.c_float, _I, _I, _I, C.c_uint64, _P, _P],
     "relay_fused_conv2d_combined": [_DP, _P, _I, _P, _P, _P, _P, _I, _P, _P, _P, _P],
+    "relay_fused_conv2d_combined_windows": [_DP, _P, _I, _P, _P, _P, _P, _I, _P, _P, _P, _P, _P, _P],
     "relay_fold_scale_axis": [_I, _I, _I, _I, _I, _P, _P, _P, _P],
     "relay_fold_bias": [_I, _P, _P, _P, _P, _P],
     "relay_conv2d_maxpool_fusable": [_DP, C.POINTER(_I)],
@@ -243,6 +244,21 @@ def relay_fused_conv2d_combined(d: ConvDesc, x, x_ld: int, w_packed, bias, bn_sc
     _check(lib().relay_fused_conv2d_combined(C.byref(d), _ptr(x), x_ld, _ptr(w_packed), _ptr(bias), _ptr(bn_scale),
                                              _ptr(bn_shift), n, C.cast(ch, _P), C.cast(ys, _P), C.cast(ld, _P),
                                              _stream()))
+
+
+WINDOW_FULL, WINDOW_CENTRE = 0, 1
+
+
+def relay_fused_conv2d_combined_windows(d: ConvDesc, x, x_ld: int, w_packed, bias, bn_scale, bn_shift,
+                                        seg_channels: Sequence[int], seg_y: Sequence, seg_ld: Sequence[int],
+                                        seg_window: Sequence[int], seg_relu: Sequence[int]) -> None:
+    n = len(seg_y)
+    arr = lambda v: (C.c_int32 * max(n, len(v), 1))(*v)
+    ch, ld, win, rl = arr(seg_channels), arr(seg_ld), arr(seg_window), arr(seg_relu)
+    ys = (C.c_void_p * max(n, 1))(*[_ptr(t) for t in seg_y])
+    _check(lib().relay_fused_conv2d_combined_windows(C.byref(d), _ptr(x), x_ld, _ptr(w_packed), _ptr(bias),
+                                                     _ptr(bn_scale), _ptr(bn_shift), n, C.cast(ch, _P), C.cast(ys, _P),
+                                                     C.cast(ld, _P), C.cast(win, _P), C.cast(rl, _P), _stream()))
 
 
 def relay_fold_scale_axis(dtype: int, k: int, c: int, rs: int, axis: int, w, scale, w_out) -> None:

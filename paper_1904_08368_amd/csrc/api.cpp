@@ -344,10 +344,34 @@ relay_status relay_fused_conv2d_bias_bn_relu(const relay_conv2d_desc* d, const v
   return device_status(launch_igemm(a, false, s), "conv2d fp16 launch");
 }
 
+static relay_status combined_conv(const relay_conv2d_desc* d, const void* x, int32_t x_ld, const void* w_packed,
+                                  const float* bias, const float* bn_scale, const float* bn_shift, int32_t nseg,
+                                  const int32_t* seg_channels, void* const* seg_y, const int32_t* seg_ld,
+                                  const int32_t* seg_window, const int32_t* seg_relu, void* hip_stream);
+
 relay_status relay_fused_conv2d_combined(const relay_conv2d_desc* d, const void* x, int32_t x_ld,
                                          const void* w_packed, const float* bias, const float* bn_scale,
                                          const float* bn_shift, int32_t nseg, const int32_t* seg_channels,
                                          void* const* seg_y, const int32_t* seg_ld, void* hip_stream) {
+  return combined_conv(d, x, x_ld, w_packed, bias, bn_scale, bn_shift, nseg, seg_channels, seg_y, seg_ld, nullptr,
+                       nullptr, hip_stream);
+}
+
+relay_status relay_fused_conv2d_combined_windows(const relay_conv2d_desc* d, const void* x, int32_t x_ld,
+                                                 const void* w_packed, const float* bias, const float* bn_scale,
+                                                 const float* bn_shift, int32_t nseg, const int32_t* seg_channels,
+                                                 void* const* seg_y, const int32_t* seg_ld,
+                                                 const int32_t* seg_window, const int32_t* seg_relu,
+                                                 void* hip_stream) {
+  if (!seg_window || !seg_relu) return fail(RELAY_ERR_NULL, "seg_window and seg_relu are required");
+  return combined_conv(d, x, x_ld, w_packed, bias, bn_scale, bn_shift, nseg, seg_channels, seg_y, seg_ld, seg_window,
+                       seg_relu, hip_stream);
+}
+
+static relay_status combined_conv(const relay_conv2d_desc* d, const void* x, int32_t x_ld, const void* w_packed,
+                                  const float* bias, const float* bn_scale, const float* bn_shift, int32_t nseg,
+                                  const int32_t* seg_channels, void* const* seg_y, const int32_t* seg_ld,
+                                  const int32_t* seg_window, const int32_t* seg_relu, void* hip_stream) {
   int ho, wo;
   relay_status st = check_geometry(d, &ho, &wo);
   if (st != RELAY_OK) return st;
@@ -375,6 +399,22 @@ relay_status relay_fused_conv2d_combined(const relay_conv2d_desc* d, const void*
     for (int j = 0; j < i; ++j)
       if (seg_y[j] == seg_y[i]) return fail(RELAY_ERR_UNSUPPORTED, "segments %d and %d share an address", j, i);
     if ((long)a.M * seg_ld[i] > kMaxElems) return fail(RELAY_ERR_SHAPE, "output view %d exceeds 2^31-1 elements", i);
+    if (seg_window) {
+      if (seg_window[i] != RELAY_WINDOW_FULL && seg_window[i] != RELAY_WINDOW_CENTRE)
+        return fail(RELAY_ERR_UNSUPPORTED, "seg_window[%d]=%d is not a relay_segment_window", i, seg_window[i]);
+      if (seg_window[i] == RELAY_WINDOW_CENTRE) {
+        // the tiles of such a segment stop at its boundaries whatever tile the kernel takes (at most 128 channels wide)
+        if (total % 128 || seg_channels[i] % 128)
+          return fail(RELAY_ERR_SHAPE, "centre-tap segment %d must begin at and hold a multiple of 128 channels", i);
+        if (!(d->r & 1) || !(d->s & 1) || d->pad_h != d->r / 2 || d->pad_w != d->s / 2)
+          return fail(RELAY_ERR_UNSUPPORTED, "centre-tap segments need an odd window padded by half its size");
+        a.seg_centre |= 1u << i;
+      }
+      if (seg_relu[i] != 0 && seg_relu[i] != 1) return fail(RELAY_ERR_UNSUPPORTED, "seg_relu[%d] must be 0 or 1", i);
+      if (seg_relu[i] && !(d->flags & RELAY_RELU))
+        return fail(RELAY_ERR_UNSUPPORTED, "seg_relu[%d] is set but the descriptor has no RELAY_RELU", i);
+      if (!seg_relu[i] && (d->flags & RELAY_RELU)) a.seg_norelu |= 1u << i;
+    }
     total += seg_channels[i];
     a.seg_end[i] = (int)total;
     a.seg_ld[i] = seg_ld[i];

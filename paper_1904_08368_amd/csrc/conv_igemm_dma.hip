@@ -173,8 +173,23 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
   // this workgroup reduces chunks [kbeg, nchunks) of the layer's Kred / CK
   const int all_chunks = a.Kred / CK;
   const int per_split = (all_chunks + nsplit - 1) / nsplit;
-  const int kbeg = ks * per_split;
-  const int nchunks = min(all_chunks, kbeg + per_split);
+  int kbeg = ks * per_split;
+  int nchunks = min(all_chunks, kbeg + per_split);
+  if constexpr (EXT) {
+    if (a.seg_centre) {  // (uniform) a tile of a centre-tap segment reduces over that tap only (never split)
+      int begin = 0;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (i < a.nseg) {
+          if (n0 >= begin && n0 < a.seg_end[i] && ((a.seg_centre >> i) & 1u)) {
+            const int per_tap = a.C / CK;
+            kbeg = ((a.R >> 1) * a.S + (a.S >> 1)) * per_tap;
+            nchunks = kbeg + per_tap;
+          }
+          begin = a.seg_end[i];
+        }
+    }
+  }
   // reduction position of the chunk being issued (wave-uniform)
   int is_tap = 0, is_r = 0, is_s = 0, is_c = 0, is_kc = kbeg;
   if (kbeg) {  // (uniform) position of the first chunk

@@ -60,10 +60,11 @@ struct OutLoc {
   void* y;
   int ldy;
   int cho;
+  int norelu;  // the segment stays without relu although the flags ask for one
 };
 
 __device__ __forceinline__ OutLoc locate_output(const ConvArgs& a, int ech) {
-  OutLoc ol{nullptr, 0, 0};  // unused for the plain tensor: finish_store8 addresses that from the arguments
+  OutLoc ol{nullptr, 0, 0, 0};  // unused for the plain tensor: finish_store8 addresses that from the arguments
   if (a.nseg) {  // (uniform) which output segment holds the lane's channels
     int begin = 0;
 #pragma unroll
@@ -73,6 +74,7 @@ __device__ __forceinline__ OutLoc locate_output(const ConvArgs& a, int ech) {
           ol.y = a.seg_y[i];
           ol.ldy = a.seg_ld[i];
           ol.cho = ech - begin;
+          ol.norelu = (int)((a.seg_norelu >> i) & 1u);
         }
         begin = a.seg_end[i];
       }
@@ -172,6 +174,7 @@ __device__ __forceinline__ void finish_store8(const ConvArgs& a, const unsigned 
   const float(&eadd)[8] = lp.add;
   const int(&ebias)[8] = lp.ibias;
   const size_t o = (size_t)m * a.K + ech;
+  const bool relu = (a.flags & F_RELU) && !(EXT && ol.norelu);
   if constexpr (!IS_I8) {
     float t[8];
 #pragma unroll
@@ -191,7 +194,7 @@ __device__ __forceinline__ void finish_store8(const ConvArgs& a, const unsigned 
     half8 hv;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      if (a.flags & F_RELU) t[e] = t[e] > 0.f ? t[e] : 0.f;
+      if (relu) t[e] = t[e] > 0.f ? t[e] : 0.f;
       hv[e] = (_Float16)t[e];
     }
     _Float16* yp = static_cast<_Float16*>(a.y) + o;
@@ -231,7 +234,7 @@ __device__ __forceinline__ void finish_store8(const ConvArgs& a, const unsigned 
       if constexpr (STOCH) q = requant_shift(t[e], a.rshift, ROUND_STOCHASTIC, rng, o + e);
       else q = (t[e] + a.round_add) >> a.rshift;  // arithmetic shift: floor
       q = q < -127 ? -127 : (q > 127 ? 127 : q);
-      if (a.flags & F_RELU) q = q > 0 ? q : 0;
+      if (relu) q = q > 0 ? q : 0;
       t[e] = q;
       pk[e >> 2] |= (unsigned)(q & 0xff) << (8 * (e & 3));
     }

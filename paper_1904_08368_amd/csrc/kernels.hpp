@@ -60,6 +60,10 @@ struct ConvArgs {
   int split;
   unsigned* ws_part;
   unsigned* ws_cnt;
+  // seg_centre bit i: segment i is a 1x1 convolution embedded at the centre tap of the R x S window
+  // (same stride, padding R/2, S/2 reads the same input pixel): its tiles reduce over that tap's
+  // chunks only.  seg_norelu bit i: no relu for segment i although F_RELU is set.
+  unsigned seg_centre, seg_norelu;
   int nseg;
   int seg_end[4];
   int seg_ld[4];

@@ -99,13 +99,41 @@ def fuse(graph) -> List[FusedOp]:
     return lower(graph, extract_groups(graph))
 
 
-def combine_parallel(ops: Sequence[FusedOp]) -> List[List[int]]:
+def combine_parallel(ops: Sequence[FusedOp], windows: bool = False) -> List[List[int]]:
     """Parallel convolution combination (paper Section 4.4): indices of the fused convs that can
     run as one launch -- same input tensor, same window, stride and padding, same elementwise
     tail, no residual operand (its tail would read a second tensor).  One list per combined
-    conv, at least two members each, in program order."""
+    conv, at least two members each, in program order.
+
+    windows=True also lets a 1x1 conv without padding join convs with an odd r x r window padded by
+    r // 2 and the same stride (it is that window with zeros around the centre tap), and lets the
+    members differ in whether they end in relu: the stride-2 3x3 conv of a residual stage and the
+    1x1 shortcut conv beside it become one launch.  The widest-window members come first."""
     by_key: Dict[tuple, List[int]] = {}
     for i, op in enumerate(ops):
-        if op.kind == "conv" and op.res is None:
+        if op.kind != "conv" or op.res is not None:
+            continue
+        centred = op.r % 2 == 1 and op.pad == op.r // 2
+        if windows and centred:
+            by_key.setdefault((op.src, op.cin, op.stride, op.bias, op.bn, "centred"), []).append(i)
+        else:
             by_key.setdefault((op.src, op.cin, op.r, op.stride, op.pad, op.bias, op.bn, op.relu), []).append(i)
-    return [g for g in by_key.values() if len(g) > 1]
+    groups = []
+    for key, g in by_key.items():
+        if key[-1] == "centred":
+            rmax = max(ops[i].r for i in g)
+            rest: Dict[tuple, List[int]] = {}
+            for i in g:                                   # windows between 1 and the widest keep to themselves
+                if ops[i].r not in (1, rmax):
+                    rest.setdefault((ops[i].r, ops[i].relu), []).append(i)
+            g = [i for i in g if ops[i].r == rmax] + [i for i in g if ops[i].r == 1 and rmax > 1]
+            groups += [h for h in rest.values() if len(h) > 1]
+            if rmax == 1 and len({ops[i].relu for i in g}) > 1:   # plain 1x1 members: same tail, as without windows
+                by_relu: Dict[bool, List[int]] = {}
+                for i in g:
+                    by_relu.setdefault(ops[i].relu, []).append(i)
+                groups += [h for h in by_relu.values() if len(h) > 1]
+                continue
+        if len(g) > 1:
+            groups.append(g)
+    return sorted(groups, key=lambda g: min(g))

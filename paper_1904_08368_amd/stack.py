@@ -30,7 +30,8 @@ class FusedNet:
                  fold_scale: bool = False, fuse_pool: bool = True):
         assert mode in ("f16", "i8")
         assert fused or mode == "f16"
-        # combine: convs that share input, window and tail run as one launch; fold_scale: the
+        # combine: convs that share input, window and tail run as one launch ("windows": also a 1x1 conv
+        # beside a wider odd window of the same stride, and tails that differ in relu); fold_scale: the
         # batch-norm scale is multiplied into the filters ahead of time (paper Section 4.4, both)
         assert not (combine or fold_scale) or (mode == "f16" and fused)
         self.fold_scale = fold_scale
@@ -72,8 +73,8 @@ class FusedNet:
                       (self.dtype, batch, in_channels, h, w, cpad, self.x_nchw, self.bufs["x"]))
 
         from .fusion import combine_parallel
-        group_of = {g[0]: g for g in (combine_parallel(ops) if combine else [])}
-        absorbed = {j for g in group_of.values() for j in g[1:]}
+        group_of = {min(g): g for g in (combine_parallel(ops, windows=(combine == "windows")) if combine else [])}
+        absorbed = {j for i, g in group_of.items() for j in g if j != i}
         self._plan_concats(ops, batch, h, w, in_channels, cpad)
 
         for i, (op, p) in enumerate(zip(ops, params)):
@@ -264,7 +265,7 @@ class FusedNet:
     def _emit_conv_views(self, members, mparams, batch):
         """One launch for one or more fp16 convs over the same input (a channel range of a wider
         tensor or a plain one), each storing into its own tensor or channel range."""
-        op0 = members[0]
+        op0 = members[0]          # (a member with the widest window: combine_parallel lists those first)
         cin_l, hi, wi = self.shape[op0.src]
         src = self.bufs[op0.src]
         cin_p = src.shape[-1]
@@ -273,7 +274,9 @@ class FusedNet:
         has_bias = mparams[0].get("bias") is not None
         has_bn = mparams[0].get("scale") is not None
         fold = self.fold_scale and has_bn
-        flags = B.flags_of(True if (has_bias or fold) else None, None if fold or not has_bn else True, None, op0.relu)
+        any_relu = any(m.relu for m in members)
+        mixed = any(m.r != op0.r or m.relu != any_relu for m in members)   # needs the per-segment windows / tails
+        flags = B.flags_of(True if (has_bias or fold) else None, None if fold or not has_bn else True, None, any_relu)
         ktot = sum(m.cout for m in members)
         d = B.conv_desc(batch, cin_p, hi, wi, ktot, op0.r, op0.r, op0.stride, op0.pad, self.dtype, B.RELAY_NHWC, flags)
         ho, wo = B.relay_conv2d_out_shape(d)
@@ -281,7 +284,7 @@ class FusedNet:
         consts = {k: [] for k in ("bias", "scale", "shift")}
         ys, off = [], 0
         for m, p in zip(members, mparams):
-            dm = B.conv_desc(batch, cin_p, hi, wi, m.cout, m.r, m.r, m.stride, m.pad, self.dtype, B.RELAY_NHWC, flags)
+            dm = B.conv_desc(batch, cin_p, hi, wi, m.cout, op0.r, op0.r, m.stride, op0.pad, self.dtype, B.RELAY_NHWC, flags)
             nbytes = B.relay_packed_weight_bytes(dm)
             wsrc = torch.from_numpy(np.ascontiguousarray(p["w"])).to(self.dev)
             if fold:
@@ -290,6 +293,11 @@ class FusedNet:
                 consts["bias"].append(self._f32(p.get("bias")))
                 consts["scale"].append(self._f32(p.get("scale")))
                 consts["shift"].append(self._f32(p.get("shift")))
+            if m.r != op0.r:      # a 1x1 member: its filters at the centre tap of the group's window, zeros around
+                assert m.r == 1 and m.pad == 0 and op0.r % 2 == 1 and op0.pad == op0.r // 2 and m.stride == op0.stride
+                wide = torch.zeros((m.cout, wsrc.shape[1], op0.r, op0.r), dtype=wsrc.dtype, device=self.dev)
+                wide[:, :, op0.r // 2, op0.r // 2] = wsrc[:, :, 0, 0]
+                wsrc = wide
             B.relay_prepack_conv2d_weights(dm, wsrc, cin_l, wp[off:off + nbytes])
             off += nbytes
             if m.dst in self.view_of:
@@ -303,9 +311,16 @@ class FusedNet:
             self.keep.append(dm)
         joined = {k: (torch.cat(v) if v and v[0] is not None else None) for k, v in consts.items()}
         name = "+".join(m.name for m in members)
-        self._add(name, B.relay_fused_conv2d_combined,
-                  (d, src, src.stride(2), wp, joined["bias"], joined["scale"], joined["shift"],
-                   [m.cout for m in members], ys, [y.stride(2) for y in ys]))
+        if mixed:
+            self._add(name, B.relay_fused_conv2d_combined_windows,
+                      (d, src, src.stride(2), wp, joined["bias"], joined["scale"], joined["shift"],
+                       [m.cout for m in members], ys, [y.stride(2) for y in ys],
+                       [B.WINDOW_FULL if m.r == op0.r else B.WINDOW_CENTRE for m in members],
+                       [1 if m.relu else 0 for m in members]))
+        else:
+            self._add(name, B.relay_fused_conv2d_combined,
+                      (d, src, src.stride(2), wp, joined["bias"], joined["scale"], joined["shift"],
+                       [m.cout for m in members], ys, [y.stride(2) for y in ys]))
         self.keep += [wp, d, joined]
 
     def _workspace(self, d):

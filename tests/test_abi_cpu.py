@@ -333,3 +333,27 @@ def test_pooled_conv_argument_checks():
     assert _status("relay_conv2d_maxpool_fusable", C.byref(_d()), None) == 1
     assert B.relay_conv2d_maxpool_kernel_name(_d(**ok)) == "igemm_dma_kernel<false, 4, 1, 2, 2, 2, 1, 1, false, false, true>"
     assert _status("relay_conv2d_maxpool_kernel_name", C.byref(_d()), C.create_string_buffer(64), 64) == 4
+
+
+def _combw(d, ch, win, relu, arrays=True):
+    n = len(ch)
+    P = C.c_void_p
+    mk = lambda v: (C.c_int32 * max(len(v), 1))(*v)
+    cha, lda, wa, ra = mk(ch), mk(ch), mk(win), mk(relu)
+    ya = (C.c_void_p * max(n, 1))(*[FAKE + 4096 * (i + 1) for i in range(n)])
+    return _status("relay_fused_conv2d_combined_windows", C.byref(d), FAKE, d.c, FAKE, None, None, None, n, C.cast(cha, P),
+                   C.cast(ya, P), C.cast(lda, P), C.cast(wa, P) if arrays else None, C.cast(ra, P), None)
+
+
+def test_combined_windows_argument_checks():
+    """The per-segment window / relu arrays are validated on the host like everything else."""
+    s2 = dict(stride=2, k=256, flags=B.RELU)
+    assert _combw(_d(**s2), (128, 128), (0, 1), (1, 0), arrays=False) == 1
+    assert _combw(_d(**s2), (128, 128), (0, 2), (1, 0)) == 4                  # not a relay_segment_window
+    assert _combw(_d(**s2), (128, 128), (0, 1), (1, 2)) == 4                  # relu is 0 or 1
+    assert _combw(_d(stride=2, k=256), (128, 128), (0, 1), (1, 0)) == 4      # seg_relu without RELAY_RELU
+    assert _combw(_d(**s2), (64, 192), (0, 1), (1, 0)) == 2                   # centre segment off the 128-channel grid
+    assert _combw(_d(stride=2, k=192, flags=B.RELU), (128, 64), (0, 1), (1, 0)) == 2
+    assert _combw(_d(pad=0, **s2), (128, 128), (0, 1), (1, 0)) == 4           # window not padded by half its size
+    assert _combw(_d(r=4, s=4, pad=2, **s2), (128, 128), (0, 1), (1, 0)) == 4  # even window: no centre tap
+    # (a valid request is not tried here: it would launch)

@@ -121,3 +121,46 @@ def test_concat_in_the_network_oracle():
     # the pool branch really is a 3x3 / stride 1 max over the input
     assert float(t["pool.out"][0, 0, 0, 0]) == float(x[0, 0, :2, :2].max())
     assert nets.trace_shapes(ops, 6, 6, 8)["cat"] == (18, 6, 6)
+
+
+# ------------------------------------------------------- members with different windows (1x1 inside r x r)
+@pytest.mark.parametrize("r,stride,hw", [(3, 2, (8, 8)), (3, 2, (9, 7)), (3, 1, (5, 6)), (5, 2, (11, 8)), (7, 3, (13, 9))])
+def test_a_1x1_conv_is_the_centre_tap_of_a_padded_odd_window(r, stride, hw):
+    """The identity the merged launch rests on, in fp64, exact: same output shape and same values."""
+    rng = np.random.default_rng(50 + r + stride)
+    x = rng.standard_normal((2, 5) + hw)
+    w = rng.standard_normal((4, 5, 1, 1))
+    a = O.conv2d(x, w, (stride, stride), (0, 0))
+    b = O.conv2d(x, OC.embed_centre(w, r), (stride, stride), (r // 2, r // 2))
+    assert a.shape == b.shape and np.array_equal(a, b)
+    # an off-centre embedding is a different function: the pin fails for it
+    bad = np.zeros((4, 5, r, r))
+    bad[:, :, 0, 0] = w[:, :, 0, 0]
+    assert not np.array_equal(a, O.conv2d(x, bad, (stride, stride), (r // 2, r // 2)))
+
+
+def test_groups_with_windows_on_resnet_and_rules():
+    ops = nets.resnet18()
+    names = [[ops[i].name for i in g] for g in OC.combine_groups(ops, windows=True)]
+    assert names == [["l2.b0.conv1", "l2.b0.down"], ["l3.b0.conv1", "l3.b0.down"], ["l4.b0.conv1", "l4.b0.down"]]
+    assert OC.combine_groups(nets.inception_block(), windows=True) == OC.combine_groups(nets.inception_block())
+    assert OC.combine_groups(nets.mobilenet_v1(), windows=True) == []
+    c = nets.conv
+    ops = [c("a", "x", "a", 32, 8, 1, 2, 0, relu=False), c("b", "x", "b", 32, 16, 3, 2, 1),     # 1x1 + 3x3, stride 2
+           c("c", "x", "c", 32, 16, 3, 1, 1),                                                    # other stride
+           c("d", "x", "d", 32, 16, 5, 2, 2), c("e", "x", "e", 32, 16, 3, 2, 0),                 # wider window; not centred
+           c("f", "x", "f", 32, 16, 3, 2, 1, relu=False)]
+    # widest window (5x5, d) takes the 1x1 (a); the two 3x3/s2/p1 differ in relu and stay apart; e is not centred
+    assert OC.combine_groups(ops, windows=True) == [[3, 0]]
+
+
+def test_windowed_group_equals_its_members_exactly():
+    ops = [nets.conv("t", "x", "t", 6, 5, 3, 2, 1), nets.conv("d", "x", "d", 6, 7, 1, 2, 0, relu=False)]
+    members = [inputs.layer_params(op, 9, j, "f16") for j, op in enumerate(ops)]
+    x = np.random.default_rng(60).standard_normal((2, 6, 9, 8)).astype(np.float16)
+    outs = OC.combined_conv2d_windows(x, ops, members)
+    for op, m, got in zip(ops, members, outs):
+        want = O.fused_conv2d(x, m["w"], stride=(2, 2), pad=(op.pad, op.pad), scale=m["scale"], shift=m["shift"],
+                              relu_flag=op.relu, out_dtype="f16")
+        assert got.shape == want.shape and np.array_equal(got, want), op.name
+    assert outs[1].min() < 0 <= outs[0].min()

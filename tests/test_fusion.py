@@ -112,3 +112,21 @@ def test_fuse_extract_rejects_bad_graphs():
     assert call(3, ok[0], ok[1], arr([0, 2]), out) == E_SHAPE                # reads a later operator
     assert call(3, ok[0], arr([1, 1, 2, 3]), ok[2], out) == E_SHAPE          # offsets do not start at 0
     assert b"earlier" in lib.relay_last_error() or b"in_offsets" in lib.relay_last_error()
+
+
+def test_parallel_conv_grouping_equals_the_oracles():
+    """The product's grouping for parallel convolution combination (paper Section 4.4), with and
+    without members of different windows, against the oracle's own implementation of the rule."""
+    from oracle import combine as OC
+    from paper_1904_08368_amd import fusion
+    from workloads import nets
+    c = nets.conv
+    tables = [nets.resnet18(), nets.mobilenet_v1(), nets.inception_block(), nets.vgg16_convs(),
+              [c("a", "x", "a", 32, 8, 1, 2, 0, relu=False), c("b", "x", "b", 32, 16, 3, 2, 1), c("c", "x", "c", 32, 16, 3, 1, 1),
+               c("d", "x", "d", 32, 16, 5, 2, 2), c("e", "x", "e", 32, 16, 3, 2, 0), c("f", "x", "f", 32, 16, 3, 2, 1, relu=False),
+               c("g", "x", "g", 32, 24, 3, 2, 1, relu=False), c("h", "a", "h", 8, 8, 1, 1, 0), c("i", "a", "i", 8, 8, 1, 1, 0, relu=False),
+               c("j", "a", "j", 8, 16, 1, 1, 0), c("k", "a", "k", 8, 8, 1, 1, 0, res="h")]]
+    for ops in tables:
+        for w in (False, True):
+            assert fusion.combine_parallel(ops, windows=w) == OC.combine_groups(ops, windows=w), (ops[0].name, w)
+    assert fusion.combine_parallel(tables[-1], windows=True) == [[3, 0], [5, 6], [7, 9]]

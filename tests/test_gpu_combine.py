@@ -237,3 +237,101 @@ def test_inception_block_batch32_sampled(G):
         assert err <= TOL_F16, b.name
     # the 1x1 member that goes straight into the concatenation sits in its channel range
     assert np.array_equal(cat[:, :128], net.tensor(ops[0].dst))
+
+
+# ------------------------------------------------ members with different windows and tails
+def _run_windows(G, x, full, centre, stride, tile=-1, reps=0, poison=True, centre_window=True):
+    """full / centre: (op, params) of an r x r conv (relu) and of a 1x1 conv (no relu) reading x with
+    the same stride -> their outputs from ONE launch (NCHW numpy)."""
+    from paper_1904_08368_amd import binding as B
+    n, c, h, w = x.shape
+    (of, pf), (oc, pc) = full, centre
+    r = of.r
+    d = B.conv_desc(n, c, h, w, of.cout + oc.cout, r, r, stride, r // 2, B.RELAY_F16, B.RELAY_NHWC, B.HAS_BN | B.RELU)
+    ho, wo = B.relay_conv2d_out_shape(d)
+    xd = G.to_nhwc(x, c, B.RELAY_F16)
+    wp = torch.empty(B.relay_packed_weight_bytes(d), dtype=torch.uint8, device=G.DEV)
+    # the 1x1 filters at the centre tap; the taps around it are never read, so they can hold anything
+    wc = inputs.rng_for(22, 4242).standard_normal((oc.cout, c, r, r)).astype(np.float16) if poison else \
+        np.zeros((oc.cout, c, r, r), np.float16)
+    wc[:, :, r // 2, r // 2] = pc["w"][:, :, 0, 0]
+    B.relay_prepack_conv2d_weights(d, G.up(np.concatenate([pf["w"], wc])), c, wp)
+    cat = lambda key: G.up(np.concatenate([pf[key], pc[key]]))
+    ys = [torch.full((n, ho, wo, k), -77.0, dtype=torch.float16, device=G.DEV) for k in (of.cout, oc.cout)]
+    sc, sf = cat("scale"), cat("shift")
+    B.relay_set_conv_tile(tile)
+    try:
+        call = lambda: B.relay_fused_conv2d_combined_windows(d, xd, c, wp, None, sc, sf, [of.cout, oc.cout], ys,
+                                                             [of.cout, oc.cout],
+                                                             [B.WINDOW_FULL, B.WINDOW_CENTRE if centre_window else B.WINDOW_FULL], [1, 0])
+        call()
+        torch.cuda.synchronize()
+        us = None
+        if reps:
+            g = torch.cuda.CUDAGraph()                 # replayed from a graph: the spacing is the GPU's, not Python's
+            with torch.cuda.graph(g):
+                for _ in range(reps):
+                    call()
+            g.replay()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            g.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / reps
+    finally:
+        B.relay_set_conv_tile(-1)
+    return [G.from_nhwc(y, k) for y, k in zip(ys, (of.cout, oc.cout))], us
+
+
+@pytest.mark.parametrize("shape", [(2, 64, 56, 56, 128, 2), (3, 128, 28, 28, 256, 2), (2, 256, 14, 14, 512, 2),
+                                   (1, 64, 17, 13, 128, 1)])
+@pytest.mark.parametrize("tile", [-1, 0, 5])
+def test_strided_conv_and_its_shortcut_conv_in_one_launch(G, shape, tile):
+    """ResNet's 3x3 / stride 2 conv (bn, relu) and the 1x1 / stride 2 shortcut conv (bn) beside it:
+    one launch, the shortcut as a centre-tap segment without relu; each against its own oracle conv."""
+    n, c, h, w, k, st = shape
+    of = nets.conv("a", "x", "a", c, k, 3, st, 1)
+    oc = nets.conv("d", "x", "d", c, k, 1, st, 0, relu=False)
+    pf, pc = inputs.layer_params(of, 22, k, "f16"), inputs.layer_params(oc, 22, k + 1, "f16")
+    x = inputs.activation(22, c, (n, c, h, w), "f16")
+    (ya, yd), _ = _run_windows(G, x, (of, pf), (oc, pc), st, tile=tile)
+    wa = O.fused_conv2d(x, pf["w"], stride=(st, st), pad=(1, 1), scale=pf["scale"], shift=pf["shift"], relu_flag=True,
+                        out_dtype="f16")
+    wd = O.fused_conv2d(x, pc["w"], stride=(st, st), pad=(0, 0), scale=pc["scale"], shift=pc["shift"], relu_flag=False,
+                        out_dtype="f16")
+    assert ya.shape == wa.shape and yd.shape == wd.shape
+    assert O.max_rel_err(ya, wa) <= TOL_F16 and ya.min() >= 0
+    assert O.max_rel_err(yd, wd) <= TOL_F16 and yd.min() < 0          # the shortcut really has no relu
+
+
+@pytest.mark.parametrize("fold_scale", [False, True])
+def test_resnet18_with_stage_convs_and_shortcuts_merged(G, fold_scale):
+    """ResNet-18 with the three (3x3 / stride 2, 1x1 / stride 2 shortcut) pairs as one launch each: three
+    launches fewer, and the first pair's tensors the same bits as from the separate launches (the same
+    sums in the same order: a centre-tap segment reduces over exactly the 1x1 conv's channels)."""
+    from oracle.stack import run_float
+    from paper_1904_08368_amd.stack import FusedNet
+    ops = nets.resnet18()
+    params = inputs.net_params(ops, 3, "f16")
+    x = inputs.image(36, 2, 3, 224, 224, "f16")
+    outs, launches = {}, {}
+    for mode in (False, "windows"):
+        net = FusedNet(ops, params, 2, 224, 224, "f16", combine=mode, fold_scale=fold_scale)
+        net.load_input(x)
+        net.run()
+        torch.cuda.synchronize()
+        launches[mode] = len(net.calls)
+        outs[mode] = {name: net.tensor(name) for name in ("l2.b0.t", "l2.b0.d", "l2.b0.out", "l4.b1.out", "logits")
+                      if name in net.bufs}
+    assert launches[False] - launches["windows"] == 3
+    assert outs[False].keys() == outs["windows"].keys() and "l4.b1.out" in outs[False]
+    for name in ("l2.b0.t", "l2.b0.d", "l2.b0.out"):
+        assert int((outs[False][name].view(np.uint16) != outs["windows"][name].view(np.uint16)).sum()) == 0, name
+    # (at this batch the separate 256- and 512-channel convs split their reduction over workgroups, which
+    # orders the partial sums differently: the deeper tensors agree to rounding, not to the bit)
+    for name in ("l4.b1.out", "logits"):
+        assert O.max_rel_err(outs["windows"][name], outs[False][name]) <= TOL_F16, name
+    if not fold_scale:
+        ref = run_float(ops, params, x, "f16")
+        assert O.max_rel_err(outs["windows"]["logits"].reshape(2, 1000), ref["logits"]) <= 2e-2
