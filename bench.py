@@ -285,6 +285,21 @@ def main() -> int:
             "tflops": round(2.0 * nets.macs_per_image(vops, 224, 224) * 32 / vsec / 1e12, 2),
             "frac_of_fp16_mfma_peak": round(2.0 * nets.macs_per_image(vops, 224, 224) * 32 / vsec / 1e12 / PEAK["f16"], 4)}
         del vn
+        # ---- the deep Q-network of the paper's vision benchmarks (built from its operator graph), batch 1 and 32
+        dops = fusion.fuse(graphs.dqn())
+        dp = inputs.net_params(dops, 7, "f16")
+        dres = {}
+        for b in (1, 32):
+            dn = FusedNet(dops, dp, b, 84, 84, "f16", in_channels=4)
+            dn.load_input(inputs.image(7, b, 4, 84, 84, "f16"))
+            if use_graph:
+                dn.capture()
+            dsec = _time_steps(dn, a.steps, a.warmup, use_graph)
+            dres[f"batch{b}_us_per_step"] = round(dsec * 1e6, 2)
+            dres[f"batch{b}_tflops"] = round(2.0 * nets.macs_per_image(dops, 84, 84, 4) * b / dsec / 1e12, 3)
+            dres["launches"] = len(dn.calls)
+            del dn
+        extra["dqn_fp16"] = dres
         # ---- parallel convolution combination (paper Section 4.4) on an Inception-shaped block, batch 32:
         #      the three 1x1 convs that read the block input as one launch instead of three
         iops = fusion.fuse(graphs.inception_block())

@@ -34,7 +34,9 @@ def run_float(ops, params: List[dict], x: np.ndarray, out_dtype: str = "f16") ->
         elif op.kind == "avgpool":
             t[op.dst] = _narrow(global_avgpool(src), out_dtype)
         elif op.kind == "dense":
-            t[op.dst] = fused_dense(src, p["w"], bias=p.get("bias"), relu_flag=op.relu, out_dtype=out_dtype)
+            # a dense layer over a [C, H, W] tensor reads it flattened in (channel, row, column) order
+            t[op.dst] = fused_dense(src.reshape(src.shape[0], -1), p["w"], bias=p.get("bias"), relu_flag=op.relu,
+                                    out_dtype=out_dtype)
         elif op.kind == "concat":
             t[op.dst] = np.concatenate([t[s] for s in op.srcs], axis=1)   # channel axis of NCHW
         else:

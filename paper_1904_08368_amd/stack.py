@@ -187,6 +187,12 @@ class FusedNet:
                 self.bufs[op.dst], self.shape[op.dst] = y, (cin_l, 1, 1)
             elif op.kind == "dense":
                 wd = torch.from_numpy(np.ascontiguousarray(p["w"])).to(self.dev)
+                if hi * wi > 1:
+                    # a dense layer over a [C, H, W] tensor: its filters are given for (channel, row, column)
+                    # order; the NHWC buffer holds (row, column, channel), so the columns are permuted once here
+                    if cin_p != cin_l or op.cin != cin_l * hi * wi:
+                        raise ValueError(f"{op.name}: dense over a padded or mismatched [{cin_l},{hi},{wi}] tensor")
+                    wd = wd.reshape(op.cout, cin_l, hi, wi).permute(0, 2, 3, 1).reshape(op.cout, op.cin).contiguous()
                 bias = self._f32(p.get("bias"))
                 y = torch.empty((batch, 1, 1, op.cout), dtype=self.tdtype, device=self.dev)
                 if not fused and mode == "f16" and (bias is not None or op.relu) and op.cout % 8 == 0:

@@ -75,6 +75,7 @@ def test_fusing_the_network_graphs_reproduces_the_layer_tables():
     _same_layers(PF.fuse(graphs.single_block()), nets.basic_block())
     _same_layers(PF.fuse(graphs.vgg16_convs()), nets.vgg16_convs())
     _same_layers(PF.fuse(graphs.inception_block()), nets.inception_block())
+    _same_layers(PF.fuse(graphs.dqn()), nets.dqn())
 
 
 def test_lowering_refuses_groups_without_a_fused_kernel():

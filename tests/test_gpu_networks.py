@@ -131,7 +131,7 @@ def _per_layer_float(G, ops, params, ref, batch_note=""):
             m = src.shape[0]
             y = torch.empty((m, op.cout), dtype=torch.float16, device=G.DEV)
             B.relay_fused_dense_bias_act(m, op.cout, op.cin, B.RELAY_F16, G.up(src.reshape(m, -1)), G.up(p["w"]),
-                                         G.up(p["bias"]), 0, y)
+                                         G.up(p["bias"]), 1 if op.relu else 0, y)
             torch.cuda.synchronize()
             got = y.cpu().numpy()
         else:
@@ -335,3 +335,26 @@ def test_vgg16_conv_stack_fp16_batch1(G):
         if b.name in ("conv1_1", "pool1", "conv3_3", "pool5"):
             tol = TOL_F16 if b.name == "conv1_1" else TOL_F16_CHAIN
             assert O.max_rel_err(net.tensor(a.dst), ref[b.dst]) <= tol, b.name
+
+
+# ------------------------------------------------- the deep Q-network of the paper's vision benchmarks
+@pytest.mark.parametrize("batch", [1, 32])
+def test_dqn_fp16_chain_and_layers(G, batch):
+    """8x8 / stride 4, 4x4 / stride 2 and 3x3 convs without padding (bias, relu), then two dense layers,
+    the first over the last conv's [64, 7, 7] output: every layer on the oracle's input, then the chain."""
+    ops = nets.dqn()
+    params = inputs.net_params(ops, 7, "f16")
+    x = inputs.image(7, batch, 4, 84, 84, "f16")
+    ref = run_float(ops, params, x, "f16")
+    _per_layer_float(G, ops, params, ref)
+    net = _net(ops, params, batch, 84, "f16", cin=4)
+    assert len(net.calls) == 6                       # input packing + five fused functions
+    net.load_input(x)
+    net.run()
+    torch.cuda.synchronize()
+    assert O.max_rel_err(net.tensor("c1"), ref["c1"]) <= TOL_F16
+    for name in ("c2", "c3"):
+        assert O.max_rel_err(net.tensor(name), ref[name]) <= TOL_F16_CHAIN, name
+    for name in ("h", "q"):
+        assert O.max_rel_err(net.tensor(name).reshape(ref[name].shape), ref[name]) <= TOL_F16_CHAIN, name
+    assert net.tensor("h").min() >= 0 and net.tensor("q").min() < 0

@@ -55,3 +55,12 @@ def test_int8_chain_recipe_keeps_activations_alive():
         assert (np.abs(y) == 127).mean() < 0.5, op.name
         assert (y != 0).mean() > 0.3, op.name
         assert y.min() >= -127
+
+
+def test_dqn_table():
+    """The published deep Q-network shapes: 84 -> 20 -> 9 -> 7, 3136 inputs to the first dense layer."""
+    ops = nets.dqn()
+    shp = nets.trace_shapes(ops, 84, 84, 4)
+    assert [shp[o.dst] for o in ops] == [(32, 20, 20), (64, 9, 9), (64, 7, 7), (512, 1, 1), (18, 1, 1)]
+    assert ops[3].cin == 64 * 7 * 7
+    assert nets.macs_per_image(ops, 84, 84, 4) == 32 * 400 * 256 + 64 * 81 * 512 + 64 * 49 * 576 + 3136 * 512 + 512 * 18

@@ -120,6 +120,23 @@ def vgg16_convs() -> Graph:
     return g
 
 
+def dqn(actions: int = 18) -> Graph:
+    """Operator graph of the deep Q-network (see workloads.nets.dqn): three conv + bias + relu, dense +
+    bias + relu, dense + bias."""
+    g = Graph()
+    cur, cin = g.add("input", "x"), 4
+    for name, cout, r, stride in (("c1", 32, 8, 4), ("c2", 64, 4, 2), ("c3", 64, 3, 1)):
+        c = g.add("conv2d", name, (cur,), cin=cin, cout=cout, r=r, stride=stride, pad=0)
+        b = g.add("bias_add", name + ".bias", (c,))
+        cur, cin = g.add("relu", name + ".relu", (b,)), cout
+    d = g.add("dense", "fc1", (cur,), cin=64 * 7 * 7, cout=512)
+    b = g.add("bias_add", "fc1.bias", (d,))
+    cur = g.add("relu", "fc1.relu", (b,))
+    d = g.add("dense", "fc2", (cur,), cin=512, cout=actions)
+    g.add("bias_add", "fc2.bias", (d,))
+    return g
+
+
 def inception_block(widths=INCEPTION_WIDTHS) -> Graph:
     """Four branches over one input, joined by a channel concatenation."""
     cin, c1, c3r, c3, c5r, c5, cp = widths

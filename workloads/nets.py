@@ -136,6 +136,19 @@ def inception_block(widths=INCEPTION_WIDTHS) -> List[Op]:
     ]
 
 
+def dqn(actions: int = 18) -> List[Op]:
+    """The deep Q-network the paper lists among its vision benchmarks (Section 5): the published
+    architecture on a stack of four 84 x 84 frames -- 8x8 / stride 4 conv to 32 channels, 4x4 /
+    stride 2 conv to 64, 3x3 / stride 1 conv to 64, each with bias and relu and no padding, then
+    dense 3136 -> 512 with relu and dense 512 -> one value per action.  The first dense layer reads
+    the last conv's [64, 7, 7] output flattened in (channel, row, column) order."""
+    return [conv("c1", "x", "c1", 4, 32, 8, 4, 0, bn=False, bias=True),
+            conv("c2", "c1", "c2", 32, 64, 4, 2, 0, bn=False, bias=True),
+            conv("c3", "c2", "c3", 64, 64, 3, 1, 0, bn=False, bias=True),
+            Op("dense", "fc1", "c3", "h", cin=64 * 7 * 7, cout=512, bias=True, relu=True),
+            Op("dense", "fc2", "h", "q", cin=512, cout=actions, bias=True)]
+
+
 def out_hw(h: int, r: int, stride: int, pad: int) -> int:
     return (h + 2 * pad - r) // stride + 1
 
