@@ -149,10 +149,13 @@ relay_status relay_qconv2d_requant_rounding(const relay_conv2d_desc* d, const in
                                             void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* The quantization operators themselves (paper Section 4.2), elementwise over n_elems values:
- *   code = clip(round(x / rho * 2^(beta - sigma)), +-(2^(beta-1) - 1))
- *   relay_quantize       ("Realize", Q):    y_i8  = (int8) code          x: F32 or F16, 2 <= beta <= 8
+ *   code = clip(round(x / rho * 2^(beta - sigma)), qtype)
+ *          qtype signed (sigma >= 1): [-(2^(beta-1) - 1), 2^(beta-1) - 1];  unsigned (sigma == 0): [0, 2^beta - 1]
+ *          (the section lets a scheme choose between signed and unsigned integers)
+ *   relay_quantize       ("Realize", Q):    y = (int8) code, or (uint8) code in the same bytes for
+ *                                           sigma == 0            x: F32 or F16, 2 <= beta <= 8
  *   relay_sim_quantize   ("Annotate", simQ): y_f32 = code * rho / 2^(beta - sigma)   x: F32, 2 <= beta <= 24
- * beta = bits of the target type, sigma = bits that carry no magnitude (1 for a signed type),
+ * beta = bits of the target type, sigma = bits that carry no magnitude (1 for a signed type, 0 for an unsigned one),
  * rho > 0 = the range mapped onto full scale (this library's reading of the three parameters).
  * The code is decided in fp32 in the order written: IEEE division, exact scaling by the power of
  * two, then the rounding rule (nearest = floor(t + 0.5f); stochastic = floor(t + w * 2^-24) with

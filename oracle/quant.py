@@ -8,9 +8,10 @@ and the rounding strategies the section names: nearest, floor, ceiling, stochast
 strategies apply to the integer requantization `acc / 2^s` that a realized conv ends with.
 
 Readings (the section is terse): beta = bits of the target type, sigma = the bits that do not
-carry magnitude (1 for a signed type), rho = the range that maps onto the full scale; the clip
-is symmetric, +-(2^(beta-1) - 1); "nearest" breaks ties toward +infinity, as the integer path
-does.  Floating point decides the integer code here, so the decision is taken in the kernel's
+carry magnitude (1 for a signed type, 0 for an unsigned one: the section lets a scheme choose
+between signed and unsigned integers), rho = the range that maps onto the full scale; the clip
+is symmetric for a signed type, +-(2^(beta-1) - 1), and [0, 2^beta - 1] for an unsigned one;
+"nearest" breaks ties toward +infinity, as the integer path does.  Floating point decides the integer code here, so the decision is taken in the kernel's
 precision: fp32, in the operation order written above (x / rho, then times the power of two,
 then the rounding rule) -- numpy float32 performs the same IEEE operations.
 
@@ -96,14 +97,16 @@ def quantize_codes(x, rho: float, beta: int, sigma: int, mode: int = NEAREST, se
     t = (x32 / np.float32(rho)) * np.float32(2.0 ** (beta - sigma))
     idx = np.arange(x32.size, dtype=np.uint64).reshape(x32.shape)
     q = _round_f32(t, mode, seed, idx)
+    if sigma == 0:                                   # an unsigned target type; what is not positive is the code +0
+        return np.where(q > 0, np.minimum(q, np.float32(2 ** beta - 1)), np.float32(0)).astype(np.float32)
     lim = np.float32(2 ** (beta - 1) - 1)
     return np.clip(q, -lim, lim)
 
 
 def Q(x, rho: float, beta: int, sigma: int, mode: int = NEAREST, seed: int = 0) -> np.ndarray:
-    """The realized quantization operator; beta <= 8 gives int8 codes."""
+    """The realized quantization operator; beta <= 8 gives int8 codes, uint8 ones for an unsigned type (sigma 0)."""
     assert 2 <= beta <= 8
-    return quantize_codes(x, rho, beta, sigma, mode, seed).astype(np.int8)
+    return quantize_codes(x, rho, beta, sigma, mode, seed).astype(np.uint8 if sigma == 0 else np.int8)
 
 
 def simQ(x, beta: int, sigma: int, rho: float, mode: int = NEAREST, seed: int = 0) -> np.ndarray:

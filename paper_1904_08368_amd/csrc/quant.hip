@@ -11,21 +11,23 @@ namespace {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 
-__device__ __forceinline__ float quantize_code(float x, float rho, float pow2, float lim, int mode, WordStream& rng,
-                                               unsigned long long index) {
+__device__ __forceinline__ float quantize_code(float x, float rho, float pow2, float qlo, float qhi, int mode,
+                                               WordStream& rng, unsigned long long index) {
   const float t = (x / rho) * pow2;
   float q;
   if (mode == ROUND_NEAREST) q = floorf(t + 0.5f);  // ties toward +infinity
   else if (mode == ROUND_FLOOR) q = floorf(t);
   else if (mode == ROUND_CEIL) q = ceilf(t);
   else q = floorf(t + (float)(rng.word(index) >> 8) * 0x1p-24f);
-  return fminf(fmaxf(q, -lim), lim);
+  if (qlo == 0.f) return q > 0.f ? fminf(q, qhi) : 0.f;  // unsigned: whatever is not positive is the code +0
+  return fminf(fmaxf(q, qlo), qhi);
 }
 
 // 8 elements per thread
 template <bool SRC_F16, bool SIM>
-__global__ __launch_bounds__(256) void quantize_kernel(long n, const void* xv, float rho, float pow2, float lim,
-                                                       int mode, unsigned seed_lo, unsigned seed_hi, void* yv) {
+__global__ __launch_bounds__(256) void quantize_kernel(long n, const void* xv, float rho, float pow2, float qlo,
+                                                       float qhi, int mode, unsigned seed_lo, unsigned seed_hi,
+                                                       void* yv) {
   const long i0 = ((long)blockIdx.x * 256 + threadIdx.x) * 8;
   if (i0 >= n) return;
   float x[8];
@@ -53,7 +55,7 @@ __global__ __launch_bounds__(256) void quantize_kernel(long n, const void* xv, f
   WordStream rng{seed_lo, seed_hi};
   float q[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) q[e] = quantize_code(x[e], rho, pow2, lim, mode, rng, (unsigned long long)(i0 + e));
+  for (int e = 0; e < 8; ++e) q[e] = quantize_code(x[e], rho, pow2, qlo, qhi, mode, rng, (unsigned long long)(i0 + e));
   if constexpr (SIM) {
     float* yp = static_cast<float*>(yv) + i0;
 #pragma unroll
@@ -88,22 +90,26 @@ __global__ __launch_bounds__(256) void quantize_kernel(long n, const void* xv, f
 
 hipError_t launch_quantize(bool src_f16, long n, const void* x, float rho, int beta, int sigma, int mode,
                            unsigned seed_lo, unsigned seed_hi, int8_t* y, hipStream_t st) {
-  const float pow2 = __builtin_ldexpf(1.f, beta - sigma), lim = (float)((1 << (beta - 1)) - 1);
+  const float pow2 = __builtin_ldexpf(1.f, beta - sigma);
+  // a signed type (sigma >= 1) clips symmetrically, an unsigned one (sigma == 0) to [0, 2^beta - 1]
+  const float qhi = sigma == 0 ? (float)((1 << beta) - 1) : (float)((1 << (beta - 1)) - 1), qlo = sigma == 0 ? 0.f : -qhi;
   const unsigned grid = (unsigned)((n + 2047) / 2048);
   if (src_f16)
-    hipLaunchKernelGGL((quantize_kernel<true, false>), dim3(grid), dim3(256), 0, st, n, x, rho, pow2, lim, mode, seed_lo,
+    hipLaunchKernelGGL((quantize_kernel<true, false>), dim3(grid), dim3(256), 0, st, n, x, rho, pow2, qlo, qhi, mode, seed_lo,
                        seed_hi, (void*)y);
   else
-    hipLaunchKernelGGL((quantize_kernel<false, false>), dim3(grid), dim3(256), 0, st, n, x, rho, pow2, lim, mode, seed_lo,
+    hipLaunchKernelGGL((quantize_kernel<false, false>), dim3(grid), dim3(256), 0, st, n, x, rho, pow2, qlo, qhi, mode, seed_lo,
                        seed_hi, (void*)y);
   return hipGetLastError();
 }
 
 hipError_t launch_sim_quantize(long n, const float* x, float rho, int beta, int sigma, int mode, unsigned seed_lo,
                                unsigned seed_hi, float* y, hipStream_t st) {
-  const float pow2 = __builtin_ldexpf(1.f, beta - sigma), lim = (float)((1 << (beta - 1)) - 1);
+  const float pow2 = __builtin_ldexpf(1.f, beta - sigma);
+  // a signed type (sigma >= 1) clips symmetrically, an unsigned one (sigma == 0) to [0, 2^beta - 1]
+  const float qhi = sigma == 0 ? (float)((1 << beta) - 1) : (float)((1 << (beta - 1)) - 1), qlo = sigma == 0 ? 0.f : -qhi;
   const unsigned grid = (unsigned)((n + 2047) / 2048);
-  hipLaunchKernelGGL((quantize_kernel<false, true>), dim3(grid), dim3(256), 0, st, n, (const void*)x, rho, pow2, lim, mode,
+  hipLaunchKernelGGL((quantize_kernel<false, true>), dim3(grid), dim3(256), 0, st, n, (const void*)x, rho, pow2, qlo, qhi, mode,
                      seed_lo, seed_hi, (void*)y);
   return hipGetLastError();
 }

@@ -83,12 +83,13 @@ def test_quantize_and_sim_quantize_bit_exact(G, mode, src):
         x[4:6] = [60000, -60000]
         x = x.astype(np.float16)
     xd = G.up(x)
-    for rho, beta, sigma in ((2.0, 8, 1), (6.5, 8, 1), (0.75, 4, 1), (16.0, 8, 0)):
+    for rho, beta, sigma in ((2.0, 8, 1), (6.5, 8, 1), (0.75, 4, 1), (16.0, 8, 0), (3.0, 5, 0)):   # sigma 0: unsigned codes
         y = torch.full((n,), -128, dtype=torch.int8, device=G.DEV)
         B.relay_quantize(n, B.RELAY_F16 if src == "f16" else B.RELAY_F32, xd, rho, beta, sigma, mode, 42, y)
         torch.cuda.synchronize()
         ref = OQ.Q(x, rho, beta, sigma, mode, 42)
-        assert np.array_equal(y.cpu().numpy(), ref), (rho, beta)
+        assert ref.dtype == (np.uint8 if sigma == 0 else np.int8)
+        assert np.array_equal(y.cpu().numpy().view(np.uint8), ref.view(np.uint8)), (rho, beta)   # the same bytes
         if src == "f32":
             ys = torch.full((n,), float("nan"), dtype=torch.float32, device=G.DEV)
             B.relay_sim_quantize(n, xd, rho, beta, sigma, mode, 42, ys)

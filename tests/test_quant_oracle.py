@@ -121,3 +121,24 @@ def test_qconv_modes_reduce_to_the_plain_requant_and_bracket_it():
     e = ((n * 6 + p) * 7 + q) * 8 + k
     u = int(OQ.random_words(np.array([e]), 77)[0]) & ((1 << 11) - 1)
     assert st[n, k, p, q] == max(-127, min(127, (int(acc[n, k, p, q]) + u) >> 11))
+
+
+def test_unsigned_target_type():
+    """sigma = 0: an unsigned type.  For x >= 0 an unsigned beta-bit code is the signed (beta+1)-bit
+    code (same scale 2^beta, same upper clip 2^beta - 1); negative values clip to 0; the top code
+    is 2^beta - 1; simQ returns values on the grid rho / 2^beta."""
+    rng = np.random.default_rng(71)
+    for rho, beta in ((4.0, 8), (1.0, 7), (6.5, 4)):
+        x = rng.uniform(-0.5 * rho, 1.5 * rho, size=4000).astype(np.float32)
+        for mode in (OQ.NEAREST, OQ.FLOOR, OQ.CEIL, OQ.STOCHASTIC):
+            u = OQ.quantize_codes(x, rho, beta, 0, mode, seed=9)
+            s = OQ.quantize_codes(x, rho, beta + 1, 1, mode, seed=9)
+            assert np.array_equal(u[x >= 0], s[x >= 0])
+            assert (u[x < -rho / 2 ** beta] == 0).all() and u.min() == 0 and u.max() == 2 ** beta - 1
+        q = OQ.Q(x, rho, beta, 0)
+        assert q.dtype == np.uint8 and int(q.max()) == 2 ** beta - 1
+        y = OQ.simQ(x, beta, 0, rho)
+        assert y.min() == 0 and np.array_equal(OQ.simQ(y, beta, 0, rho), y)
+        assert np.allclose(y / (np.float32(rho) / np.float32(2 ** beta)), np.round(y / (np.float32(rho) / np.float32(2 ** beta))))
+    # hand values: rho = 2, beta = 3 -> scale 4, codes 0..7
+    assert OQ.Q(np.array([-1.0, 0.0, 0.12, 0.13, 0.9, 1.7, 1.8, 5.0], np.float32), 2.0, 3, 0).tolist() == [0, 0, 0, 1, 4, 7, 7, 7]
