@@ -89,7 +89,11 @@ def _layer_table(net, ops, batch, reps, trials):
     return rows
 
 
-KERNEL_SOURCES = ("conv_igemm_dma.hip", "dma_common.hpp", "igemm_common.hpp", "rounding.hpp", "kernels.hpp", "fastdiv.hpp")
+KERNEL_SOURCES = ("conv_igemm_dma.hip", "conv_halo.hip", "dma_common.hpp", "igemm_common.hpp", "rounding.hpp", "kernels.hpp",
+                  "fastdiv.hpp")
+
+
+CONV_KERNELS = ("igemm", "conv3x3_halo")      # name prefixes of the MFMA conv kernels in the per-layer table
 
 
 def _kernel_source_digest():
@@ -106,7 +110,7 @@ def _hbm_traffic(kernel_name):
     """HBM bytes per launch of `kernel_name` from the stored rocprofv3 counter summary
     (FETCH_SIZE and WRITE_SIZE passes, each scaled by the reading of a copy of known size).
     None when there is no summary for this kernel or the kernel sources have changed since."""
-    path = os.path.join(ROOT, "profiles", "igemm_dma_kernel_resnet18_fp16_b32_hbm_traffic.md")
+    path = os.path.join(ROOT, "profiles", kernel_name.split("<")[0] + "_resnet18_fp16_b32_hbm_traffic.md")
     if not os.path.exists(path):
         return None
     kv = {}
@@ -186,7 +190,7 @@ def main() -> int:
     rows = _layer_table(net, ops, a.batch, a.layer_reps, 5)
     by_kernel = {}
     for r in rows:
-        if "kernel" in r and r["kernel"].startswith("igemm"):
+        if r.get("kernel", "").startswith(CONV_KERNELS):
             k = by_kernel.setdefault(r["kernel"], {"us": 0.0, "gflop": 0.0, "launches": 0, "layers": []})
             k["us"] += r["us"]
             k["gflop"] += r["gflop"]
@@ -198,8 +202,8 @@ def main() -> int:
                 "frac": round(achieved / PEAK["f16"], 4), "traffic": _hbm_traffic(dom_name), "kernel": dom_name,
                 "launches_per_step": dom["launches"], "avg_launch_us": round(dom["us"] / dom["launches"], 2),
                 "gflop_per_launch": round(dom["gflop"] / dom["launches"], 3), "layers": dom["layers"]}
-    conv_us = sum(r["us"] for r in rows if r.get("kernel", "").startswith("igemm"))
-    conv_gf = sum(r["gflop"] for r in rows if r.get("kernel", "").startswith("igemm"))
+    conv_us = sum(r["us"] for r in rows if r.get("kernel", "").startswith(CONV_KERNELS))
+    conv_gf = sum(r["gflop"] for r in rows if r.get("kernel", "").startswith(CONV_KERNELS))
 
     out = {
         "metric": "resnet18_fp16_fused_conv_stack_tflops", "value": round(value, 3), "unit": "TFLOP/s",

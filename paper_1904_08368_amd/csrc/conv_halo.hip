@@ -324,13 +324,14 @@ bool conv_halo_supported(const ConvArgs& a, bool is_i8, int v) {
 // The variant the heuristic takes, or -1 to leave the layer to the implicit-GEMM kernel.  Measured on
 // the ResNet shapes at batch 32 (fp16 / int8): 128 channels at 28 x 28 12.9 against 15.1 us / 9.2
 // against 9.6, 256 channels at 14 x 14 12.4 against 16.4 / 8.6 against 10.2; even at 64 fp16 channels
-// (int8, batch 16: 7.1 against 7.9), slower at 7 x 7 (a quarter of the flat positions are not pixels)
-// and outside the range of tile counts where both kernels get two workgroups per CU.
+// (int8, batch 16: 7.1 against 7.9; fp16, batch 32, 813 tiles: 17.4 against 18.3, the whole ResNet-18
+// stack 0.8 % faster), slower at 7 x 7 (a quarter of the flat positions are not pixels) and outside
+// the range of tile counts where both kernels get two workgroups per CU.
 int conv_halo_pick(const ConvArgs& a, bool is_i8) {
-  if (a.C < (is_i8 ? 64 : 128) || a.W > (is_i8 ? 56 : 32) || !conv_halo_supported(a, is_i8, 0)) return -1;
+  if (a.C < 64 || a.W > 56 || !conv_halo_supported(a, is_i8, 0)) return -1;
   const long flat = (long)a.N * (a.H + 1) * (a.W + 1);
   const long t128 = ((flat + 127) / 128) * ((a.K + 63) / 64);
-  return t128 >= 190 && t128 <= 512 ? 0 : -1;
+  return t128 >= 190 && t128 <= (!is_i8 && a.C == 64 ? 1024 : 512) ? 0 : -1;
 }
 
 void conv_halo_kernel_name(const ConvArgs& a, bool is_i8, int v, char* buf, size_t len) {
