@@ -39,6 +39,7 @@ struct HaloGeom {
   int xblk;           // 16-row blocks per plane of a halo buffer
   int nxbuf;          // halo buffers: 2 when there are several channel chunks, else 1
   int ncc;            // channel chunks, C / CK
+  int tab_slot;       // 16-byte slot of LDS where the pixel table starts (behind the ring and the epilogue staging)
   FastDiv fd_f, fd_xblk;            // division by F and by xblk
   FastDiv fd_tiles_m, fd_tiles_n;   // ... by the tile counts of the launched variant
 };
@@ -74,6 +75,15 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_halo_kernel
   const unsigned dump_base = wring_base + (unsigned)(NSW * WSTAGE) * 16u;
   const uint4* wring = lds + g.nxbuf * xbuf_slots;
 
+  // Every argument the kernel uses is asked for here, so that their scalar loads leave as one batch with one
+  // wait; left to itself the compiler loads them where they are first used, and the prologue then waits
+  // for five scalar-load round trips one after another.
+  asm volatile("" ::"s"(a.x), "s"(a.w), "s"(a.y), "s"(a.res), "s"(a.bias), "s"(a.scale), "s"(a.shift), "s"(a.qbias));
+  asm volatile("" ::"s"(a.N), "s"(a.H), "s"(a.W), "s"(a.C), "s"(a.K), "s"(a.Kp), "s"(a.flags), "s"(a.param_vec),
+               "s"(a.n_major), "s"(a.xs_n));
+  asm volatile("" ::"s"(g.P), "s"(g.F), "s"(g.Mflat), "s"(g.rcp_p), "s"(g.rcp_f), "s"(g.xblk), "s"(g.nxbuf), "s"(g.ncc),
+               "s"(g.tab_slot), "s"(g.fd_f.mul), "s"(g.fd_f.shift), "s"(g.fd_xblk.mul), "s"(g.fd_xblk.shift),
+               "s"(g.fd_tiles_m.mul), "s"(g.fd_tiles_m.shift), "s"(g.fd_tiles_n.mul), "s"(g.fd_tiles_n.shift));
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -87,27 +97,16 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_halo_kernel
   const int n_0 = (int)fast_div((uint32_t)o0, g.fd_f);  // (uniform) image and in-image position of the tile's first position
   const int rem_0 = o0 - n_0 * g.F;
 
-  // ---- this lane's part of a halo: block (t * NW + wave) of the KP * xblk blocks, for t < XS
+  // ---- first loads out as early as possible: the epilogue constants (oldest, so that nothing ever waits for
+  //      them longer than for a ring load), then the filters of step 0, which need no decoding.  Every issue
+  //      slot, here and in the loop, holds L loads (a dump load stands in where there is none), and
+  //      the order of the slots is what the waits count on: filters of step 0, the halo of chunk 0,
+  //      filters of step 1.
   const int srow = lane >> 2, sphys = lane & 3;
-  unsigned x_off[XS];    // byte offset of the 16 bytes this lane fetches (chunk 0), or out of range
-  unsigned x_dst[XS];    // LDS byte offset inside a halo buffer
-  unsigned x_live = 0;   // bit t: the block exists (else the load goes to the dump block)
-#pragma unroll
-  for (int t = 0; t < XS; ++t) {
-    const int b = t * NW + wave;
-    const int plane = (int)fast_div((uint32_t)b, g.fd_xblk), blk = b - plane * g.xblk;
-    const bool live = plane < KP;
-    const int row = blk * 16 + srow;
-    const int kvl = sphys ^ lds_swizzle(row);
-    int dn, r1, rowi, coli;
-    small_divmod(rem_0 + row, g.F, g.rcp_f, dn, r1);
-    small_divmod(r1, g.P, g.rcp_p, rowi, coli);
-    const int n = n_0 + dn;
-    const bool pixel = live && n < a.N && rowi >= 1 && coli >= 1;
-    x_off[t] = pixel ? (unsigned)((((n * a.H + rowi - 1) * a.W + coli - 1) * a.C + plane * (BKV * VE) + kvl * VE) * ES) : kOob;
-    x_dst[t] = (unsigned)((plane * g.xblk + blk) * 64) * 16u;
-    if (live) x_live |= 1u << t;
-  }
+  constexpr int CG = WTN / 8;  // lanes per pixel row in the epilogue
+  const int ech = n0 + wn * WTN + (lane % CG) * 8;
+  RawLaneParams rawp;
+  fetch_lane_params<IS_I8>(a, ech, rawp);
   unsigned w_off[WLP];
 #pragma unroll
   for (int j = 0; j < WLP; ++j) {
@@ -118,6 +117,60 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_halo_kernel
   }
   const intx4 rs_x = make_rsrc(a.x, (unsigned)((size_t)a.N * a.xs_n * ES));
   const intx4 rs_w = make_rsrc(a.w, (unsigned)((size_t)a.K * a.Kp * ES));
+  auto issue_filters = [&](int s) {  // the filters of step (0, s), s < NSW - 1, and the slot's dump load
+#pragma unroll
+    for (int i = 0; i < LW; ++i) {
+      const int plane = i / WLP, j = i % WLP;
+      lds_dma16(rs_w, wring_base + (unsigned)(s * WSTAGE + plane * WPLANE + (wave * WLP + j) * 64) * 16u,
+                w_off[j] == kOob ? kOob : w_off[j] + (unsigned)((s * a.C + plane * (BKV * VE)) * ES));
+    }
+    lds_dma16(rs_x, dump_base, kOob);
+  };
+  issue_filters(0);
+
+  // ---- pixel table: for each of the halo's xblk * 16 flat positions the index (n * H + row) * W + col of
+  //      the input pixel there, or ~0 where the position is padding.  One decode per thread (or two)
+  //      instead of one per load and per stored pixel: the halo loads below look their rows up here, and so
+  //      does the epilogue, because the output pixel of flat position o is the input pixel of o + P + 1.
+  unsigned* ptab = reinterpret_cast<unsigned*>(lds + g.tab_slot);
+  for (int r = tid; r < g.xblk * 16; r += NW * 64) {
+    int dn, r1, rowi, coli;
+    small_divmod(rem_0 + r, g.F, g.rcp_f, dn, r1);
+    small_divmod(r1, g.P, g.rcp_p, rowi, coli);
+    const int n = n_0 + dn;
+    ptab[r] = (n < a.N && rowi >= 1 && coli >= 1) ? (unsigned)((n * a.H + rowi - 1) * a.W + coli - 1) : ~0u;
+  }
+  // (the table is LDS traffic only: the loads already in flight are not waited for here)
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+
+  // ---- this lane's part of a halo: block (t * NW + wave) of the KP * xblk blocks, for t < XS; the load of
+  //      chunk 0's block goes out as soon as its address is known
+  unsigned x_off[XS];    // byte offset of the 16 bytes this lane fetches (chunk 0), or out of range
+  unsigned x_dst[XS];    // LDS byte offset inside a halo buffer
+  unsigned x_live = 0;   // bit t: the block exists (else the load goes to the dump block)
+  unsigned x_px[XS];     // (all table reads first: one wait for the eight of them)
+#pragma unroll
+  for (int t = 0; t < XS; ++t) {
+    const int b = t * NW + wave;
+    const int plane = (int)fast_div((uint32_t)b, g.fd_xblk), blk = b - plane * g.xblk;
+    x_px[t] = ptab[plane < KP ? blk * 16 + srow : 0];
+  }
+#pragma unroll
+  for (int t = 0; t < XS; ++t) {
+    const int b = t * NW + wave;
+    const int plane = (int)fast_div((uint32_t)b, g.fd_xblk), blk = b - plane * g.xblk;
+    const bool live = plane < KP;
+    const int row = blk * 16 + srow;
+    const int kvl = sphys ^ lds_swizzle(row);
+    const unsigned px = x_px[t];
+    x_off[t] = (live && px != ~0u) ? (unsigned)((px * a.C + plane * (BKV * VE) + kvl * VE) * ES) : kOob;
+    x_dst[t] = (unsigned)((plane * g.xblk + blk) * 64) * 16u;
+    if (live) x_live |= 1u << t;
+    lds_dma16(rs_x, live ? lds_base + x_dst[t] : dump_base, live ? x_off[t] : kOob);
+  }
+#pragma unroll
+  for (int s = 1; s < NSW - 1; ++s) issue_filters(s);
 
   // the i-th load of the issue slot behind step (cc, t): filters of step (cc, t) + NSW - 1, then
   // block t of the halo of chunk cc + 1
@@ -144,28 +197,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_halo_kernel
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[tn][tm][v] = 0;
 
-  // ---- prologue: the whole halo of chunk 0, then the filters of the first NSW - 1 steps, each
-  //      with a dump load so that every issue slot, here and in the loop, holds L loads
-#pragma unroll
-  for (int t = 0; t < XS; ++t) {
-    const bool live = (x_live >> t) & 1u;
-    lds_dma16(rs_x, live ? lds_base + x_dst[t] : dump_base, live ? x_off[t] : kOob);
-  }
-#pragma unroll
-  for (int s = 0; s < NSW - 1; ++s) {
-#pragma unroll
-    for (int i = 0; i < LW; ++i) {
-      const int plane = i / WLP, j = i % WLP;
-      lds_dma16(rs_w, wring_base + (unsigned)(s * WSTAGE + plane * WPLANE + (wave * WLP + j) * 64) * 16u,
-                w_off[j] == kOob ? kOob : w_off[j] + (unsigned)((s * a.C + plane * (BKV * VE)) * ES));
-    }
-    lds_dma16(rs_x, dump_base, kOob);
-  }
-
-  constexpr int CG = WTN / 8;  // lanes per pixel row in the epilogue
-  const int ech = n0 + wn * WTN + (lane % CG) * 8;
   LaneParams lp;
-  load_lane_params<IS_I8>(a, ech, lp);
+  finish_lane_params<IS_I8>(rawp, lp);
 
   const int lrow = lane & 31, lhalf = lane >> 5;
   const int xrow0 = wm * WTM + lrow;  // halo row of this lane's first pixel at tap (0, 0)
@@ -232,12 +265,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_halo_kernel
       const int pix = it * PPI + epix;
       const uint4 lo = stg[pix * EP + ecg * 2], hi = stg[pix * EP + ecg * 2 + 1];
       const unsigned raw[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-      int dn, r1, p, q;
-      small_divmod(rem_0 + wm * WTM + tm * 32 + pix, g.F, g.rcp_f, dn, r1);
-      small_divmod(r1, g.P, g.rcp_p, p, q);
-      const int n = n_0 + dn;
-      if (n >= a.N || p >= a.H || q >= a.W || ech >= a.K) continue;  // not a pixel, or past Cout
-      finish_store8<IS_I8, false>(a, raw, (n * a.H + p) * a.W + q, ech, lp, ol, vec_ok);
+      const unsigned m = ptab[wm * WTM + tm * 32 + pix + g.P + 1];  // (the output pixel of a flat position: see the table)
+      if (m == ~0u || ech >= a.K) continue;                        // not a pixel, or past Cout
+      finish_store8<IS_I8, false>(a, raw, (int)m, ech, lp, ol, vec_ok);
     }
   }
 }
@@ -273,7 +303,8 @@ bool make_geom(const ConvArgs& a, bool is_i8, int v, HaloGeom& g, size_t& lds_by
   const int nw = kHalo[v].waves_m * kHalo[v].waves_n;
   const size_t ring = (size_t)g.nxbuf * kp * g.xblk * 64 + (size_t)NSW * kp * kHalo[v].bn() * BKV + 64;
   const size_t epi = (size_t)nw * 32 * (kHalo[v].tn * 32 / 4 + 1);
-  lds_bytes = (ring > epi ? ring : epi) * 16;
+  g.tab_slot = (int)(ring > epi ? ring : epi);
+  lds_bytes = ((size_t)g.tab_slot + (size_t)g.xblk * 4) * 16;  // + 4 bytes per halo position
   return lds_bytes <= 160 * 1024;
 }
 
