@@ -93,6 +93,15 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
   __shared__ uint4 ring[NS * STAGE];
   __shared__ float pool_cst[POOL ? 2 * BN : 1];  // pooled tiles: the epilogue constants of the tile's channels
 
+  // The arguments of the prologue are asked for here, so that their scalar loads leave as one batch with
+  // one wait; left to itself the compiler loads them where they are first used and the prologue waits
+  // for several scalar-load round trips one after another.
+  asm volatile("" ::"s"(a.x), "s"(a.w), "s"(a.bias), "s"(a.scale), "s"(a.shift), "s"(a.qbias));
+  asm volatile("" ::"s"(a.N), "s"(a.H), "s"(a.W), "s"(a.C), "s"(a.K), "s"(a.R), "s"(a.S), "s"(a.sh), "s"(a.sw), "s"(a.ph),
+               "s"(a.pw), "s"(a.Ho), "s"(a.Wo), "s"(a.xs_n), "s"(a.xs_h), "s"(a.xs_w), "s"(a.rcp_wo), "s"(a.rcp_ho),
+               "s"(a.tap_spread), "s"(a.param_vec), "s"(a.n_major), "s"(a.M), "s"(a.Kred), "s"(a.Kp), "s"(a.flags));
+  asm volatile("" ::"s"(a.fd_wo.mul), "s"(a.fd_wo.shift), "s"(a.fd_howo.mul), "s"(a.fd_howo.shift), "s"(a.fd_tiles_m.mul),
+               "s"(a.fd_tiles_m.shift), "s"(a.fd_tiles_n.mul), "s"(a.fd_tiles_n.shift));
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);

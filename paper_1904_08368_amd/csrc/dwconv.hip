@@ -42,6 +42,9 @@ __device__ __forceinline__ uint4 buffer_load16(__amdgpu_buffer_rsrc_t rsrc, unsi
 
 template <int STRIDE, int TH, int TW>
 __global__ __launch_bounds__(256) void dwconv3x3_f16_kernel(const ConvArgs a) {
+  // all arguments as one batch of scalar loads with one wait (the compiler would load them where first used)
+  asm volatile("" ::"s"(a.x), "s"(a.w), "s"(a.y), "s"(a.bias), "s"(a.scale), "s"(a.shift), "s"(a.N), "s"(a.H), "s"(a.W),
+               "s"(a.C), "s"(a.Ho), "s"(a.Wo), "s"(a.sh), "s"(a.ph), "s"(a.pw), "s"(a.flags));
   constexpr int IH = (TH - 1) * STRIDE + 3, IW = (TW - 1) * STRIDE + 3;
   constexpr unsigned kOob = 0x80000000u;
   const int cvecs = a.C >> 3;
@@ -160,6 +163,9 @@ __device__ __forceinline__ void lds_dma16(const int (&rsrc)[4], unsigned lds_bas
 
 template <int CBV, int MTH, int NT>
 __global__ __launch_bounds__(NT) void dwconv3x3_s1_lds_kernel(const ConvArgs a) {
+  // all arguments as one batch of scalar loads with one wait (the compiler would load them where first used)
+  asm volatile("" ::"s"(a.x), "s"(a.w), "s"(a.y), "s"(a.bias), "s"(a.scale), "s"(a.shift), "s"(a.N), "s"(a.H), "s"(a.W),
+               "s"(a.C), "s"(a.Ho), "s"(a.Wo), "s"(a.sh), "s"(a.ph), "s"(a.pw), "s"(a.flags));
   constexpr int MTW = 7;                       // micro-tiles (2 x 4 outputs) across the workgroup tile
   constexpr int TH = 2 * MTH, TW = 4 * MTW;    // output tile
   constexpr int PH = TH + 2, PW = TW + 2;      // input patch
