@@ -246,6 +246,19 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_halo_kernel
   const int epix = lane / CG, ecg = lane % CG;
   const bool vec_ok = (a.K & 7) == 0;
   const OutLoc ol{nullptr, 0, 0};  // this kernel stores plain tensors only
+  // all residual vectors of this lane first: in flight together, behind the transpositions below
+  constexpr int ITS = 32 / PPI;
+  const bool pre_res = (a.flags & F_RES) && vec_ok;
+  uint4 resv[TM][ITS];
+  if (pre_res) {
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+      for (int it = 0; it < ITS; ++it) {
+        const unsigned m = ptab[wm * WTM + tm * 32 + it * PPI + epix + g.P + 1];
+        resv[tm][it] = (m != ~0u && ech < a.K) ? load_residual8<IS_I8>(a, (int)m, ech) : make_uint4(0u, 0u, 0u, 0u);
+      }
+  }
 #pragma unroll
   for (int tm = 0; tm < TM; ++tm) {
 #pragma unroll
@@ -267,7 +280,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_halo_kernel
       const unsigned raw[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
       const unsigned m = ptab[wm * WTM + tm * 32 + pix + g.P + 1];  // (the output pixel of a flat position: see the table)
       if (m == ~0u || ech >= a.K) continue;                        // not a pixel, or past Cout
-      finish_store8<IS_I8, false>(a, raw, (int)m, ech, lp, ol, vec_ok);
+      finish_store8<IS_I8, false>(a, raw, (int)m, ech, lp, ol, vec_ok, pre_res, resv[tm][it]);
     }
   }
 }

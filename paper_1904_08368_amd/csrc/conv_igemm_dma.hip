@@ -495,6 +495,24 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
   const int epix = lane / CG, ecg = lane % CG;
   const bool vec_ok = (a.K & 7) == 0;
   const OutLoc ol = EXT ? locate_output(a, ech) : OutLoc{nullptr, 0, 0};
+  // All residual vectors of this lane first (tiles whose lanes finish at most 8 vectors: 32 registers), so
+  // that they are in flight together behind the transpositions instead of one memory latency -- and one
+  // wait for the previous store -- per stored vector.
+  constexpr int ITS = 32 / PPI;
+  constexpr bool PRE_RES = !POOL && TM_E * ITS <= 8;
+  const bool pre_res = PRE_RES && (a.flags & F_RES) && vec_ok && !(EXT && nsplit > 1);
+  uint4 resv[PRE_RES ? TM_E : 1][PRE_RES ? ITS : 1];
+  if constexpr (PRE_RES) {
+    if (pre_res) {
+#pragma unroll
+      for (int te = 0; te < TM_E; ++te)
+#pragma unroll
+        for (int it = 0; it < ITS; ++it) {
+          const int m = m0 + wm * WTM + (tm_lo + te) * 32 + it * PPI + epix;
+          resv[te][it] = (m < a.M && ech < a.K) ? load_residual8<IS_I8>(a, m, ech) : make_uint4(0u, 0u, 0u, 0u);
+        }
+    }
+  }
 #pragma unroll
   for (int te = 0; te < (POOL ? 0 : TM_E); ++te) {
     const int tm = tm_lo + te;  // block row in the workgroup tile
@@ -530,7 +548,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
         pp[0] = lo;
         pp[1] = hi;
       } else {
-        finish_store8<IS_I8, STOCH, EXT>(a, raw, m, ech, lp, ol, vec_ok);
+        finish_store8<IS_I8, STOCH, EXT>(a, raw, m, ech, lp, ol, vec_ok, PRE_RES && pre_res, resv[PRE_RES ? te : 0][PRE_RES ? it : 0]);
       }
     }
   }

@@ -167,9 +167,25 @@ __device__ __forceinline__ void load_lane_params(const ConvArgs& a, int ech, Lan
 // residual and random draws are addressed in the plain [M][K] tensor, the store goes where ol says)
 // from the raw accumulator bits and store them (bias, scale/shift, residual, relu, cast -- or the
 // quantized epilogue, with STOCH the stochastic rounding).
+// The 8 residual values of output element (m, ech..ech+7) as one vector load (fp16: 16 bytes; int8: 8 bytes
+// in .x/.y); for epilogues that fetch all their residual operands ahead of the arithmetic, so that the
+// loads are in flight together instead of one memory latency per stored vector.  K % 8 == 0 only.
+template <bool IS_I8>
+__device__ __forceinline__ uint4 load_residual8(const ConvArgs& a, int m, int ech) {
+  const size_t o = (size_t)m * a.K + ech;
+  if constexpr (IS_I8) {
+    const uint2 v = *reinterpret_cast<const uint2*>(static_cast<const int8_t*>(a.res) + o);
+    return make_uint4(v.x, v.y, 0u, 0u);
+  } else {
+    return *reinterpret_cast<const uint4*>(static_cast<const _Float16*>(a.res) + o);
+  }
+}
+
+// have_pre: `pre` is the element's residual vector from load_residual8; else it is loaded here
 template <bool IS_I8, bool STOCH, bool EXT = false>
 __device__ __forceinline__ void finish_store8(const ConvArgs& a, const unsigned (&raw)[8], int m, int ech,
-                                              const LaneParams& lp, const OutLoc& ol, bool vec_ok) {
+                                              const LaneParams& lp, const OutLoc& ol, bool vec_ok,
+                                              bool have_pre = false, uint4 pre = uint4{0u, 0u, 0u, 0u}) {
   const float(&emul)[8] = lp.mul;
   const float(&eadd)[8] = lp.add;
   const int(&ebias)[8] = lp.ibias;
@@ -182,7 +198,7 @@ __device__ __forceinline__ void finish_store8(const ConvArgs& a, const unsigned 
     if (a.flags & F_RES) {
       const _Float16* rp = static_cast<const _Float16*>(a.res) + o;
       if (vec_ok) {
-        const half8 rv = *reinterpret_cast<const half8*>(rp);
+        const half8 rv = have_pre ? __builtin_bit_cast(half8, pre) : *reinterpret_cast<const half8*>(rp);
 #pragma unroll
         for (int e = 0; e < 8; ++e) t[e] += (float)rv[e];
       } else {
@@ -214,7 +230,7 @@ __device__ __forceinline__ void finish_store8(const ConvArgs& a, const unsigned 
     if (a.flags & F_RES) {
       const int8_t* rp = static_cast<const int8_t*>(a.res) + o;
       if (vec_ok) {
-        const uint2 rv = *reinterpret_cast<const uint2*>(rp);
+        const uint2 rv = have_pre ? make_uint2(pre.x, pre.y) : *reinterpret_cast<const uint2*>(rp);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           t[e] += (int)(int8_t)(rv.x >> (8 * e)) * (1 << a.lshift);
