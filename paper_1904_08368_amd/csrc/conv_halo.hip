@@ -246,18 +246,23 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_halo_kernel
   const int epix = lane / CG, ecg = lane % CG;
   const bool vec_ok = (a.K & 7) == 0;
   const OutLoc ol{nullptr, 0, 0};  // this kernel stores plain tensors only
-  // all residual vectors of this lane first: in flight together, behind the transpositions below
+  // the output pixels of this lane (the output pixel of a flat position o is the table's entry for o + P + 1),
+  // read together, and all its residual vectors: in flight together, behind the transpositions below
   constexpr int ITS = 32 / PPI;
   const bool pre_res = (a.flags & F_RES) && vec_ok;
+  unsigned mpix[TM][ITS];
   uint4 resv[TM][ITS];
+#pragma unroll
+  for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+    for (int it = 0; it < ITS; ++it) mpix[tm][it] = ptab[wm * WTM + tm * 32 + it * PPI + epix + g.P + 1];
   if (pre_res) {
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
-      for (int it = 0; it < ITS; ++it) {
-        const unsigned m = ptab[wm * WTM + tm * 32 + it * PPI + epix + g.P + 1];
-        resv[tm][it] = (m != ~0u && ech < a.K) ? load_residual8<IS_I8>(a, (int)m, ech) : make_uint4(0u, 0u, 0u, 0u);
-      }
+      for (int it = 0; it < ITS; ++it)
+        resv[tm][it] = (mpix[tm][it] != ~0u && ech < a.K) ? load_residual8<IS_I8>(a, (int)mpix[tm][it], ech)
+                                                           : make_uint4(0u, 0u, 0u, 0u);
   }
 #pragma unroll
   for (int tm = 0; tm < TM; ++tm) {
@@ -278,8 +283,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_halo_kernel
       const int pix = it * PPI + epix;
       const uint4 lo = stg[pix * EP + ecg * 2], hi = stg[pix * EP + ecg * 2 + 1];
       const unsigned raw[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-      const unsigned m = ptab[wm * WTM + tm * 32 + pix + g.P + 1];  // (the output pixel of a flat position: see the table)
-      if (m == ~0u || ech >= a.K) continue;                        // not a pixel, or past Cout
+      const unsigned m = mpix[tm][it];
+      if (m == ~0u || ech >= a.K) continue;  // not a pixel, or past Cout
       finish_store8<IS_I8, false>(a, raw, (int)m, ech, lp, ol, vec_ok, pre_res, resv[tm][it]);
     }
   }
