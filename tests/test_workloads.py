@@ -64,3 +64,15 @@ def test_dqn_table():
     assert [shp[o.dst] for o in ops] == [(32, 20, 20), (64, 9, 9), (64, 7, 7), (512, 1, 1), (18, 1, 1)]
     assert ops[3].cin == 64 * 7 * 7
     assert nets.macs_per_image(ops, 84, 84, 4) == 32 * 400 * 256 + 64 * 81 * 512 + 64 * 49 * 576 + 3136 * 512 + 512 * 18
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark measures one GPU; asking for more ends with a message and a non-zero status
+    before anything touches a device."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in (r.stdout + r.stderr)
