@@ -141,8 +141,9 @@ typedef enum {
  * output element e = ((n*ho + p)*wo + q)*k + channel (its NHWC position) takes word e mod 4 of
  * the block with counter (e div 4 low word, high word, 0, 0) and key (seed low word, seed high
  * word), so a result depends on (seed, position) only, not on the launch shape.
- * Precondition: |acc| + 2^out_rshift < 2^31.  Everything else as relay_qconv2d_requant, which
- * is this call with RELAY_ROUND_NEAREST. */
+ * Precondition as for relay_qconv2d_requant: |acc| < 2^31 (bias and residual included); the rounding
+ * addend is never added to acc in 32 bits, so every mode is exact for all 0 <= out_rshift <= 31.
+ * Everything else as relay_qconv2d_requant, which is this call with RELAY_ROUND_NEAREST. */
 relay_status relay_qconv2d_requant_rounding(const relay_conv2d_desc* d, const int8_t* x, const int8_t* w_packed,
                                             const int32_t* bias, const int8_t* residual, int32_t residual_lshift,
                                             int32_t out_rshift, int32_t round_mode, uint64_t seed, int8_t* y,

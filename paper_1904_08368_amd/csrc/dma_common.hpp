@@ -2,39 +2,14 @@
 // helpers, the per-lane epilogue constants and the finish-and-store of 8 consecutive channels.
 #pragma once
 #include "igemm_common.hpp"
+#include "lds_dma.hpp"
 
 namespace relay {
-
-__device__ __forceinline__ void lds_dma16(intx4 rsrc, unsigned lds_base, unsigned voff) {
-  // m0 = wave-uniform LDS byte address; lane i lands at m0 + 16*i
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds_base), "v"(voff),
-               "s"(rsrc)
-               : "memory");
-}
-
-// Wait until at most N of this wave's global->LDS loads are pending and all of its LDS reads
-// have returned (so that the stage they read may be refilled after the barrier).
-template <int N>
-__device__ __forceinline__ void wait_loads() {
-  asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(N) : "memory");
-}
-
-__device__ __forceinline__ intx4 make_rsrc(const void* p, unsigned bytes) {
-  const unsigned long long pa = reinterpret_cast<unsigned long long>(p);
-  intx4 r;
-  r[0] = (int)(unsigned)pa;
-  r[1] = (int)(unsigned)((pa >> 32) & 0xffffu);  // stride 0: raw buffer
-  r[2] = (int)bytes;                            // num_records
-  r[3] = 0x00020000;                            // 32-bit data format, no swizzle
-  return r;
-}
 
 // 32-bit pattern of an accumulator element (taken by value: a bit cast applied directly to a
 // vector-element lvalue is not reliable)
 __device__ __forceinline__ unsigned as_u32(float f) { return __builtin_bit_cast(unsigned, f); }
 __device__ __forceinline__ unsigned as_u32(int i) { return (unsigned)i; }
-
-constexpr unsigned kOob = 0x80000000u;  // beyond any num_records this library accepts
 
 // floor(t / d) and remainder for 0 <= t < 2^22, d > 0: float reciprocal plus one fix-up step.
 __device__ __forceinline__ void small_divmod(int t, int d, float rcp_d, int& q, int& r) {
@@ -248,7 +223,7 @@ __device__ __forceinline__ void finish_store8(const ConvArgs& a, const unsigned 
     for (int e = 0; e < 8; ++e) {
       int q;
       if constexpr (STOCH) q = requant_shift(t[e], a.rshift, ROUND_STOCHASTIC, rng, o + e);
-      else q = (t[e] + a.round_add) >> a.rshift;  // arithmetic shift: floor
+      else q = shift_round(t[e], (unsigned)a.round_add, a.rshift);  // arithmetic shift: floor
       q = q < -127 ? -127 : (q > 127 ? 127 : q);
       if (relu) q = q > 0 ? q : 0;
       t[e] = q;

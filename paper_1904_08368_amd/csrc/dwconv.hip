@@ -11,6 +11,7 @@
 // Workgroups are renumbered so that one XCD works through a contiguous range of rows: the
 // rows two workgroups share are then fetched into one L2, not several.
 #include "kernels.hpp"
+#include "lds_dma.hpp"
 
 namespace relay {
 namespace {
@@ -23,12 +24,6 @@ __device__ __forceinline__ void fma_mix_lo(float& acc, unsigned x, unsigned w) {
 }
 __device__ __forceinline__ void fma_mix_hi(float& acc, unsigned x, unsigned w) {
   asm("v_fma_mix_f32 %0, %1, %2, %0 op_sel:[1,1,0] op_sel_hi:[1,1,0]" : "+v"(acc) : "v"(x), "v"(w));
-}
-
-__device__ __forceinline__ int xcd_order(int bid, int nb) {
-  const int xcd = bid & 7, idx = bid >> 3;
-  const int per = nb >> 3, rem = nb & 7;
-  return xcd < rem ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
 }
 
 typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
@@ -50,7 +45,7 @@ __global__ __launch_bounds__(256) void dwconv3x3_f16_kernel(const ConvArgs a) {
   const int cvecs = a.C >> 3;
   const int tiles_w = (a.Wo + TW - 1) / TW, tiles_h = (a.Ho + TH - 1) / TH;
   const unsigned total = (unsigned)(a.N * tiles_h * tiles_w * cvecs);  // < 2^31: checked by the launcher
-  unsigned idx = (unsigned)xcd_order(blockIdx.x, gridDim.x) * blockDim.x + threadIdx.x;
+  unsigned idx = (unsigned)xcd_remap(blockIdx.x, gridDim.x) * blockDim.x + threadIdx.x;
   if (idx >= total) return;
   const int cv = (int)(idx % (unsigned)cvecs);
   idx /= (unsigned)cvecs;
@@ -152,15 +147,6 @@ __global__ __launch_bounds__(256) void dwconv3x3_f16_kernel(const ConvArgs a) {
 // 28-pixel rows of the workloads; other widths run with a ragged last tile.  Measured: the
 // same kernel without its multiply-adds streams at 5.2 TB/s; the 9 fp32 FMAs per output
 // element that the vector ALUs must issue are what is left of the gap to the HBM rate.
-__device__ __forceinline__ void lds_dma16(const int (&rsrc)[4], unsigned lds_base, unsigned voff) {
-  typedef int intx4 __attribute__((ext_vector_type(4)));
-  intx4 r;
-  r[0] = rsrc[0]; r[1] = rsrc[1]; r[2] = rsrc[2]; r[3] = rsrc[3];
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds_base), "v"(voff),
-               "s"(r)
-               : "memory");
-}
-
 template <int CBV, int MTH, int NT>
 __global__ __launch_bounds__(NT) void dwconv3x3_s1_lds_kernel(const ConvArgs a) {
   // all arguments as one batch of scalar loads with one wait (the compiler would load them where first used)
@@ -173,14 +159,13 @@ __global__ __launch_bounds__(NT) void dwconv3x3_s1_lds_kernel(const ConvArgs a) 
   constexpr int LOADS = (NV + NT - 1) / NT;    // load instructions per thread
   constexpr int NW = NT / 64;
   static_assert(MTH * MTW * CBV <= NT, "one thread per micro-tile and channel vector");
-  constexpr unsigned kOob = 0x80000000u;
   __shared__ uint4 patch[LOADS * NT];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int cblocks = a.C / (8 * CBV);
   const int tiles_w = (a.Wo + TW - 1) / TW, tiles_h = (a.Ho + TH - 1) / TH;
-  int t = xcd_order(blockIdx.x, gridDim.x);  // (n, tile row, tile column, channel block), channel block fastest
+  int t = xcd_remap(blockIdx.x, gridDim.x);  // (n, tile row, tile column, channel block), channel block fastest
   const int cb = t % cblocks;
   t /= cblocks;
   const int tx = t % tiles_w;
@@ -191,9 +176,7 @@ __global__ __launch_bounds__(NT) void dwconv3x3_s1_lds_kernel(const ConvArgs a) 
   const int iy0 = oy0 - a.ph, ix0 = ox0 - a.pw;  // input coordinates of patch pixel (0, 0)
   const int c0 = cb * 8 * CBV;
 
-  const unsigned long long pa = reinterpret_cast<unsigned long long>(a.x);
-  const int rs[4] = {(int)(unsigned)pa, (int)(unsigned)((pa >> 32) & 0xffffu),
-                     (int)((unsigned)a.N * a.H * a.W * a.C * 2u), 0x00020000};
+  const intx4 rs = make_rsrc(a.x, (unsigned)a.N * a.H * a.W * a.C * 2u);
   const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) uint4*)(&patch[0]);
 #pragma unroll
   for (int j = 0; j < LOADS; ++j) {

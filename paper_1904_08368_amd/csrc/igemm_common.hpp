@@ -2,6 +2,7 @@
 // the fused epilogues (float: paper Section 4.1; quantized: Section 4.2, "Realize").
 #pragma once
 #include "kernels.hpp"
+#include "lds_dma.hpp"
 #include "rounding.hpp"
 
 namespace relay {
@@ -9,7 +10,6 @@ namespace relay {
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef int intx4 __attribute__((ext_vector_type(4)));
 typedef int intx16 __attribute__((ext_vector_type(16)));
 
 constexpr int BKV = 4;  // 16-byte k-vectors per tile row per chunk: 64 bytes of reduction
@@ -138,15 +138,6 @@ __device__ __forceinline__ void epilogue_store4(const ConvArgs& a, const S (&v)[
         if (ch + e < a.K) yp[e] = (int8_t)q[e];
     }
   }
-}
-
-// Workgroup id -> logical tile id such that consecutive logical ids run on the same XCD
-// (workgroups are dealt round-robin over the 8 XCDs, each with its own L2): tiles that
-// share input rows or filter tiles then share an L2.
-__device__ __forceinline__ int xcd_remap(int bid, int nb) {
-  const int xcd = bid & 7, idx = bid >> 3;
-  const int per = nb >> 3, rem = nb & 7;
-  return xcd < rem ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
 }
 
 }  // namespace relay

@@ -45,15 +45,23 @@ struct WordStream {
   }
 };
 
+// floor((acc + addend) / 2^s) for 0 <= addend < 2^s and 0 <= s <= 31, without forming acc + addend:
+// that sum can leave int32 (s near 31) although the quotient never does.  With acc = (acc >> s) * 2^s +
+// (acc & (2^s - 1)) the low part plus the addend stays below 2^32.
+__device__ __forceinline__ int shift_round(int acc, unsigned addend, int s) {
+  const unsigned mask = (1u << s) - 1u;
+  return (acc >> s) + (int)((((unsigned)acc & mask) + addend) >> s);
+}
+
 // acc / 2^s rounded by `mode` (arithmetic shift = floor division): what is added before the shift.
 __device__ __forceinline__ int requant_shift(int acc, int s, int mode, WordStream& rng, unsigned long long index) {
   if (s == 0) return acc;
-  int addend;
-  if (mode == ROUND_NEAREST) addend = 1 << (s - 1);  // ties toward +infinity
-  else if (mode == ROUND_FLOOR) addend = 0;
-  else if (mode == ROUND_CEIL) addend = (int)((1u << s) - 1u);
-  else addend = (int)(rng.word(index) & ((1u << s) - 1u));  // up with probability frac(acc / 2^s)
-  return (acc + addend) >> s;
+  unsigned addend;
+  if (mode == ROUND_NEAREST) addend = 1u << (s - 1);  // ties toward +infinity
+  else if (mode == ROUND_FLOOR) addend = 0u;
+  else if (mode == ROUND_CEIL) addend = (1u << s) - 1u;
+  else addend = rng.word(index) & ((1u << s) - 1u);  // up with probability frac(acc / 2^s)
+  return shift_round(acc, addend, s);
 }
 
 }  // namespace relay

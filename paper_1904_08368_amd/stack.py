@@ -217,7 +217,8 @@ class FusedNet:
                 a0, a1 = ops[j - 1], ops[j]
                 if a0.kind == "conv" and a1.kind == "conv" and a0.src == a1.src and not a1.res and not a0.res:
                     users = [o for o in ops if o.src == a1.dst or o.res == a1.dst]
-                    if len(users) == 1 and users[0].res == a1.dst and a1.name in idx_of and users[0].name in idx_of:
+                    if len(users) == 1 and users[0].res == a1.dst and a1.name in idx_of and users[0].name in idx_of \
+                            and idx_of.get(a0.name) == idx_of[a1.name] - 1:
                         self.side_calls.add(idx_of[a1.name])
                         self.join_before.add(idx_of[users[0].name])
             if self.side_calls:
@@ -385,17 +386,20 @@ class FusedNet:
 
         A conv whose output is only used as a later residual (the 1x1 shortcut of a ResNet
         block) is launched on a side stream between two events, so that it overlaps the block's
-        first conv: both read the block input, neither reads the other."""
+        first conv: both read the block input, neither reads the other.  The fork event is
+        recorded BEFORE that first conv is enqueued, so the side stream waits only for the
+        producer of the block input."""
         if not self.side_calls:
             for fn, args in self.calls:
                 fn(*args)
             return
         main = torch.cuda.current_stream()
-        pending = None
+        pending = fork = None
         for i, (fn, args) in enumerate(self.calls):
-            if i in self.side_calls:
+            if i + 1 in self.side_calls:      # the next call runs beside this one
                 fork = torch.cuda.Event()
                 fork.record(main)
+            if i in self.side_calls:
                 self.side.wait_event(fork)
                 with torch.cuda.stream(self.side):
                     fn(*args)

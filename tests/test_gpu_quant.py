@@ -54,6 +54,38 @@ def test_qconv_rounding_modes_bit_exact(G, mode, shape):
         assert np.array_equal(_qconv_mode(G, x, wt, 1, 1, rshift=12, relu=True), G.run_qconv(x, wt, 1, 1, rshift=12, relu=True))
 
 
+@pytest.mark.parametrize("mode", [OQ.NEAREST, OQ.FLOOR, OQ.CEIL, OQ.STOCHASTIC])
+def test_qconv_rounding_exact_for_shifts_up_to_31_and_sums_near_the_int32_limits(G, mode):
+    """Biases push the sums to +-(2^30 .. 2^31): adding the rounding addend in 32 bits would wrap
+    there (ceiling at s = 31 of acc = 1 would give -1); the library must still equal the oracle,
+    whose arithmetic is 64-bit."""
+    rng = np.random.default_rng(760 + mode)
+    x = rng.integers(-127, 128, (1, 64, 9, 10)).astype(np.int8)
+    wt = rng.integers(-127, 128, (72, 64, 3, 3)).astype(np.int8)
+    top = (1 << 31) - 1 - 9 * 64 * 127 * 127                   # leaves room for the largest possible conv sum
+    b = rng.integers(-top, top, 72).astype(np.int32)
+    b[:8] = [top, -top, (1 << 30), -(1 << 30), 0, 1, -1, top - 1]
+    for s in (31, 30, 24):
+        for bias in (b, None):
+            ref = OQ.qconv2d_requant_mode(x, wt, stride=(1, 1), pad=(1, 1), bias=bias, out_rshift=s, mode=mode, seed=11)
+            for tile in (-1, 100):                               # the implicit-GEMM kernel and the halo kernel
+                from paper_1904_08368_amd import binding as B
+                B.relay_set_conv_tile(tile)
+                try:
+                    got = _qconv_mode(G, x, wt, 1, 1, bias=bias, rshift=s, mode=mode, seed=11)
+                finally:
+                    B.relay_set_conv_tile(-1)
+                assert np.array_equal(got, ref), (mode, s, bias is None, tile)
+    # the zero-weight layer: acc = bias exactly, every code decided by the rounding rule alone
+    z = np.zeros_like(wt)
+    small = np.array([1, -1, 0, 2, -2, (1 << 30) + 1, -(1 << 30) - 1, (1 << 31) - 1] * 9, dtype=np.int32)
+    ref = OQ.qconv2d_requant_mode(x, z, stride=(1, 1), pad=(1, 1), bias=small, out_rshift=31, mode=mode, seed=11)
+    got = _qconv_mode(G, x, z, 1, 1, bias=small, rshift=31, mode=mode, seed=11)
+    assert np.array_equal(got, ref)
+    if mode == OQ.CEIL:
+        assert got[0, 0, 0, 0] == 1 and got[0, 1, 0, 0] == 0 and got[0, 5, 0, 0] == 1
+
+
 def test_qconv_stochastic_depends_on_seed_and_position_only(G):
     """The same layer with a different tile shape, and as two half-batches, draws the same words."""
     from paper_1904_08368_amd import binding as B

@@ -53,6 +53,51 @@ def test_handworked_requant_fixture():
         assert int(O.requant_points([acc], out_rshift=s, relu_flag=bool(rl))[0]) == want
 
 
+def test_handworked_float_epilogue_fixture():
+    """float_epilogue_points (the expected values of the full-size sampled GPU checks) on values
+    worked by hand: order bias -> scale, shift -> residual -> relu, constants indexed by channel."""
+    bias, scale, shift = [0.5, -1.0, 2.0], [2.0, 0.5, -1.5], [0.25, -0.75, 1.0]
+    with open(os.path.join(GOLD, "handworked_float_epilogue.txt")) as f:
+        rows = [l.split() for l in f if l.strip() and not l.startswith("#")]
+    assert len(rows) >= 6
+    for acc, k, res, rl, want in rows:
+        got = O.float_epilogue_points([float(acc)], [int(k)], bias=bias, scale=scale, shift=shift,
+                                      residual=[float(res)], relu_flag=bool(int(rl)))
+        assert got.tolist() == [float(want)], (acc, k, res, rl)
+    # without the optional operands the raw sum passes through
+    assert O.float_epilogue_points([1.25, -2.0], [0, 1]).tolist() == [1.25, -2.0]
+    assert O.float_epilogue_points([1.25, -2.0], [0, 1], relu_flag=True).tolist() == [1.25, 0.0]
+
+
+@pytest.mark.parametrize("flags", list(itertools.product([False, True], repeat=4)))
+def test_float_epilogue_points_equals_the_loop_nest_operators(flags):
+    """On every output element of a small random layer the point-wise path (conv2d_points +
+    float_epilogue_points + cast) gives the bits of the whole-tensor fused operator, which is
+    nothing but the unfused C loop nests called one after another."""
+    has_bias, has_bn, has_res, rl = flags
+    g = np.random.default_rng(77 + sum(b << i for i, b in enumerate(flags)))
+    x = g.standard_normal((2, 5, 7, 6)).astype(np.float16)
+    w = (g.standard_normal((4, 5, 3, 3)) * 0.2).astype(np.float16)
+    bias = g.standard_normal(4).astype(np.float32) if has_bias else None
+    scale = (1 + 0.1 * g.standard_normal(4)).astype(np.float32) if has_bn else None
+    shift = (0.1 * g.standard_normal(4)).astype(np.float32) if has_bn else None
+    for stride, pad in (((1, 1), (1, 1)), ((2, 2), (1, 1))):
+        ho, wo = O.out_hw(7, 3, stride[0], pad[0]), O.out_hw(6, 3, stride[1], pad[1])
+        res = g.standard_normal((2, 4, ho, wo)).astype(np.float16) if has_res else None
+        want = O.fused_conv2d(x, w, stride=stride, pad=pad, bias=bias, scale=scale, shift=shift, residual=res,
+                              relu_flag=rl, out_dtype="f16")
+        pts = [(n, k, p, q) for n in range(2) for k in range(4) for p in range(ho) for q in range(wo)]
+        acc = O.conv2d_points(x, w, pts, stride, pad)
+        rs = None if res is None else np.array([res[t] for t in pts], dtype=np.float64)
+        got = O.cast_f16(O.float_epilogue_points(acc, [t[1] for t in pts], bias=bias, scale=scale, shift=shift,
+                                                 residual=rs, relu_flag=rl))
+        # the two paths add the taps in different orders: equal up to the last bit of the fp64 sum,
+        # which the fp16 rounding hides except at a rounding boundary
+        d = np.abs(got.astype(np.float64) - want.reshape(-1).astype(np.float64))
+        assert np.all(d <= np.spacing(np.abs(want.reshape(-1)).astype(np.float16)).astype(np.float64))
+        assert (d == 0).mean() > 0.99
+
+
 # -------------------------------------------------------------------------- closed forms
 @pytest.mark.parametrize("cin", [1, 3])
 def test_all_ones_counts_valid_taps(cin):

@@ -56,6 +56,25 @@ def test_integer_rounding_modes_against_exact_rationals(s):
         assert not np.array_equal(st, OQ.rshift_mode(acc, s, OQ.STOCHASTIC, seed=100, index=idx))
 
 
+@pytest.mark.parametrize("s", [29, 30, 31])
+def test_integer_rounding_modes_near_the_int32_limits(s):
+    """Accumulators close to +-2^31 with shifts close to 31: acc + addend leaves int32 there, the
+    quotient does not, and the oracle (int64) must still equal the exact rationals."""
+    import math
+    edge = [-(1 << 31) + 1, -(1 << 31) + 2, -(1 << 30) - 1, -(1 << 30), -(1 << 30) + 1, -3, -1, 0, 1, 2, 3,
+            (1 << 30) - 1, 1 << 30, (1 << 30) + 1, (1 << 31) - 2, (1 << 31) - 1]
+    g = np.random.default_rng(31 + s)
+    acc = np.array(edge + g.integers(-(1 << 31) + 1, 1 << 31, 500).tolist(), dtype=np.int64)
+    fl = [math.floor(Fraction(int(a), 1 << s)) for a in acc]
+    ce = [math.ceil(Fraction(int(a), 1 << s)) for a in acc]
+    assert OQ.rshift_mode(acc, s, OQ.FLOOR).tolist() == fl
+    assert OQ.rshift_mode(acc, s, OQ.CEIL).tolist() == ce
+    assert OQ.rshift_mode(acc, s, OQ.NEAREST).tolist() == [math.floor(Fraction(int(a), 1 << s) + Fraction(1, 2)) for a in acc]
+    st = OQ.rshift_mode(acc, s, OQ.STOCHASTIC, seed=3, index=np.arange(acc.size))
+    assert np.all((st == fl) | (st == ce))
+    assert OQ.rshift_mode(np.array([1]), 31, OQ.CEIL).tolist() == [1]      # (a 32-bit add would wrap to -1)
+
+
 def test_stochastic_rounding_is_unbiased():
     # acc / 2^s = 2.25: rounds to 3 with probability 1/4 (over element indices, one seed)
     s, acc = 4, 36
