@@ -66,11 +66,18 @@ typedef struct {
   uint32_t flags;  /* RELAY_HAS_* | RELAY_RELU */
 } relay_conv2d_desc;
 
-/* Ho = floor((h + 2*pad_h - r)/stride_h) + 1, Wo likewise.  Validates the geometry. */
+/* The shape relation of conv2d (paper Section 3.2, "Operators and Type Relations": an operator's
+ * type carries a relation between the shapes of its arguments and of its result, enforced at every
+ * call site; here it is evaluated on the static shapes of the descriptor):
+ *   Ho = floor((h + 2*pad_h - r)/stride_h) + 1, Wo likewise.
+ * d: host pointer; ho, wo: host pointers that receive the result.  Validates the geometry
+ * (RELAY_ERR_NULL / _SHAPE / _DTYPE / _UNSUPPORTED as for the conv calls); touches no device. */
 relay_status relay_conv2d_out_shape(const relay_conv2d_desc* d, int32_t* ho, int32_t* wo);
 
-/* Bytes of device scratch the conv entry points (relay_fused_conv2d_bias_bn_relu, relay_qconv2d_requant*)
- * can use for this descriptor; 0 for most layers.  A layer with few output tiles and a long reduction
+/* Lowered operators work on inputs and outputs that are allocated beforehand (paper Section 3.3,
+ * "Backends"); the same holds for scratch memory, which the caller sizes with this query and owns.
+ * Bytes of device scratch the conv entry points (relay_fused_conv2d_bias_bn_relu, relay_qconv2d_requant*)
+ * can use for this descriptor (d, bytes: host pointers); 0 for most layers.  A layer with few output tiles and a long reduction
  * (the deep layers at small batch) is split along the reduction over several workgroups per tile, which
  * leave partial sums and a per-tile arrival count in the workspace; the last to arrive adds the partials
  * in a fixed order (results do not depend on timing; int8 stays bit-exact) and runs the fused tail.
@@ -95,8 +102,9 @@ relay_status relay_prepack_conv2d_weights(const relay_conv2d_desc* d, const void
                                           void* w_packed, size_t packed_bytes, void* hip_stream);
 
 /* Pre-padded 4-channel input of a RELAY_NHWC4_PADDED conv (F16 or I8): its extents, and the
- * conversion from NCHW [n,c,h,w] (descriptor geometry; a per-inference layout alteration,
- * the filter packing above is the compile-time one).  y: device, 16-byte aligned,
+ * conversion from NCHW [n,c,h,w] (descriptor geometry; an alteration of the operator's data layout
+ * in the sense of paper Section 5.3, done per inference -- the filter packing above is the
+ * compile-time one).  y: device, 16-byte aligned,
  * n*hp*wp*4 elements. */
 relay_status relay_nhwc4_padded_shape(const relay_conv2d_desc* d, int32_t* hp, int32_t* wp);
 relay_status relay_pack_input_nhwc4(const relay_conv2d_desc* d, const void* x_nchw, void* y, void* hip_stream);
@@ -134,7 +142,8 @@ typedef enum {
   RELAY_ROUND_STOCHASTIC = 3  /* up with probability frac(t) */
 } relay_round_mode;
 
-/* relay_qconv2d_requant with a rounding strategy for acc / 2^out_rshift:
+/* relay_qconv2d_requant with a rounding strategy for acc / 2^out_rshift (paper Section 4.2: a
+ * quantization scheme chooses its rounding):
  *   nearest: (acc + 2^(s-1)) >> s;  floor: acc >> s;  ceiling: (acc + 2^s - 1) >> s;
  *   stochastic: (acc + u) >> s with u = the low s bits of the element's random word.
  * Random words come from Philox-4x32-10 (Salmon et al., SC'11), a counter-based generator:
@@ -167,24 +176,42 @@ relay_status relay_quantize(int64_t n_elems, int32_t src_dtype, const void* x, f
 relay_status relay_sim_quantize(int64_t n_elems, const float* x, float rho, int32_t beta, int32_t sigma,
                                 int32_t round_mode, uint64_t seed, float* y, void* hip_stream);
 
-/* Depthwise conv2d (k == c) -> [+bias] -> [*scale + shift] -> [relu] -> cast.  F16 NHWC,
- * c % 8 == 0, fp32 accumulation.  w_rsc: filters repacked [r][s][c] by
- * relay_prepack_dwconv_weights from [c][r][s]. */
+/* Depthwise conv2d as a fused primitive function (paper Section 4.1, "Extraction": the contraction
+ * with the elementwise operators that post-dominate it; MobileNet, one of the vision models of
+ * Section 5.1, is built from such layers):
+ *   y[n,c,p,q] = sum_{r,s} x[n,c,p*stride-pad+r,q*stride-pad+s] * w[c,r,s]
+ *   -> [+bias[c]] -> [*bn_scale[c] + bn_shift[c]] -> [relu] -> cast to fp16 (nearest even).
+ * d: k == c, 3x3, stride 1 or 2 (equal in both directions), F16, NHWC, c % 8 == 0, no residual;
+ * fp32 accumulation.  x [n,h,w,c], y [n,ho,wo,c] device, 16-byte aligned, caller-owned; bias /
+ * bn_scale / bn_shift fp32 [c] device or NULL with the flag clear.  w_rsc: filters repacked
+ * [r][s][c] by relay_prepack_dwconv_weights from w_crs [c][r][s] (both device; compile-time work).
+ * Errors: RELAY_ERR_SHAPE (k != c, input above 2^31-1 bytes), _UNSUPPORTED (window, stride,
+ * residual, layout), _DTYPE, _ALIGN, _NULL, _DEVICE; nothing is launched on an error. */
 relay_status relay_prepack_dwconv_weights(const relay_conv2d_desc* d, const void* w_crs, void* w_rsc,
                                           void* hip_stream);
 relay_status relay_fused_dwconv_bias_relu(const relay_conv2d_desc* d, const void* x, const void* w_rsc,
                                           const float* bias, const float* bn_scale, const float* bn_shift,
                                           void* y, void* hip_stream);
 
-/* dense: y[m,j] = sum_i x[m,i] * w[j,i]  [+ bias[j]]  [act: 0 none, 1 relu].
- * dtype F16 (fp32 accumulation; k % 8 == 0, x and w 16-byte aligned) or F32.
- * x [m,k], w [n,k] (one row per output unit), bias fp32 [n] or NULL, y [m,n]. */
+/* dense as a fused primitive function (paper Section 4.1: a contraction with its elementwise tail;
+ * Section 3.3 "Backends": operators are lowered to dense linear algebra kernels; the classifier
+ * layers of the vision models of Section 5.1):
+ *   y[m,j] = sum_i x[m,i] * w[j,i]  [+ bias[j]]  [act: 0 none, 1 relu].
+ * dtype F16 (fp32 accumulation, result rounded to nearest even; k % 8 == 0) or F32 (k % 4 == 0).
+ * x [m,k], w [n,k] (one row per output unit; the orientation is this library's reading), y [m,n]:
+ * device, row-major, caller-owned, x and w 16-byte aligned; bias fp32 [n] device or NULL.
+ * Errors: RELAY_ERR_SHAPE (non-positive or above 2^31-1 elements), _DTYPE, _UNSUPPORTED (act),
+ * _ALIGN, _NULL, _DEVICE.  y must not alias x or w. */
 relay_status relay_fused_dense_bias_act(int32_t m, int32_t n, int32_t k, int32_t dtype, const void* x,
                                         const void* w, const float* bias, int32_t act, void* y,
                                         void* hip_stream);
 
-/* Operators that only chain real layer shapes (standard architectures, not the paper's
- * subject).  NHWC; F16 needs c % 8 == 0, I8 c % 16 == 0. */
+/* Window operators that only chain the real layer shapes of the vision models of paper Section 5.1
+ * (standard architectures; the fusion rule of Section 4.1 leaves them as groups of their own).
+ * NHWC; F16 needs c % 8 == 0, I8 c % 16 == 0.  x, y: device, 16-byte aligned, caller-owned.
+ *   relay_maxpool2d       y[n,p,q,c] = max over the r x r window at stride `stride`, padding `pad`
+ *                         (padding never wins the maximum); F16 or I8
+ *   relay_global_avgpool  y[n,c] = mean over the hw pixels of image n, fp32 sum, F16 */
 relay_status relay_maxpool2d(int32_t dtype, int32_t n, int32_t c, int32_t h, int32_t w, int32_t r,
                              int32_t stride, int32_t pad, const void* x, void* y, void* hip_stream);
 relay_status relay_global_avgpool(int32_t dtype, int32_t n, int32_t c, int32_t hw, const void* x, void* y,
@@ -251,8 +278,8 @@ relay_status relay_fused_conv2d_combined(const relay_conv2d_desc* d, const void*
                                          const float* bn_shift, int32_t nseg, const int32_t* seg_channels,
                                          void* const* seg_y, const int32_t* seg_ld, void* hip_stream);
 
-/* relay_fused_conv2d_combined for members whose windows and tails differ in two ways that occur
- * in residual networks (a stride-2 3x3 convolution and the 1x1 shortcut convolution beside it
+/* relay_fused_conv2d_combined (paper Section 4.4, "Parallel convolution combination") for members
+ * whose windows and tails differ in two ways that occur in residual networks (a stride-2 3x3 convolution and the 1x1 shortcut convolution beside it
  * read the same tensor): a 1x1 convolution with the same stride and no padding reads, for every
  * output pixel, the input pixel under the CENTRE tap of an odd r x s window padded by (r/2, s/2),
  * so it is that window with zeros everywhere else; and one member may end in relu while another
@@ -286,25 +313,74 @@ relay_status relay_fold_scale_axis(int32_t dtype, int32_t k, int32_t c, int32_t 
 relay_status relay_fold_bias(int32_t k, const float* bias, const float* scale, const float* shift, float* out,
                              void* hip_stream);
 
-/* [n,c,h,w] -> [n,h,w,c_pad], channels c..c_pad-1 zero.  Any dtype; c_pad >= c. */
+/* The compile-time half of the quantization flow on the device (paper Section 4.2, "Calibrate" and
+ * "Realize", after the axis scale folding of Section 4.4), 8-bit signed scheme (beta = 8, sigma = 1)
+ * with power-of-two ranges: a tensor with range rho holds code * rho / 2^7.
+ *
+ * relay_calibrate_pow2_range: the "no overflow" rule for one tensor -- *rho_out = the smallest
+ *   power of two that no |x[i]| exceeds (2^-20 for a tensor of zeros; NaN is ignored).
+ *   x: device, F32 or F16, n_elems values; rho_out: DEVICE float; cell: DEVICE scratch of 4 bytes
+ *   (4-byte aligned; the call clears it).
+ *
+ * relay_realize_conv: one convolution with filters w [k][per_k] (OIHW flattened, per_k = c*r*s),
+ *   tail [+bias] -> [*scale + shift], input range rho_x, output range rho_y, residual range
+ *   rho_res (0: no residual operand); all device pointers, fp32:
+ *     w'[k][i]  = w[k][i] * scale[k]           (exact product, one rounding to fp32; scale NULL: w)
+ *     rho_w     = smallest power of two >= max |w'|
+ *     wq        = Q(w', rho_w, 8, 1), round to nearest            -> int8 [k][per_k]
+ *     unit      = rho_x * rho_w / 2^14                            (worth of one accumulator count)
+ *     bias_q[k] = floor((bias[k]*scale[k] + shift[k]) / unit + 1/2)   -> int32 [k]  (fp64; bias NULL: 0;
+ *                 scale NULL: bias[k]; bias_q NULL allowed when bias and shift are both NULL)
+ *     out_rshift = log2(2^7 rho_y / (rho_x rho_w)),  residual_lshift = log2(2^7 rho_res / (rho_x rho_w))
+ *   out: DEVICE relay_realized_conv; status is 0 or an OR of RELAY_REALIZE_* bits (a shift that is not
+ *   an integer in the range relay_qconv2d_requant takes, a bias outside int32 -- stored as 0).
+ *   workspace: device, 16-byte aligned, at least k*per_k*4 + 16 bytes (the folded filters and the
+ *   maximum), else RELAY_ERR_WORKSPACE.  scale and shift are given together or not at all.
+ * Both calls only enqueue kernels on hip_stream; the caller copies the few result words back when
+ * it needs them on the host.  Errors: RELAY_ERR_NULL, _SHAPE (extents, non-positive or infinite
+ * ranges), _DTYPE, _ALIGN, _WORKSPACE, _DEVICE. */
+typedef struct {
+  float rho_w;
+  int32_t out_rshift, residual_lshift, status;
+} relay_realized_conv;
+enum { RELAY_REALIZE_BAD_OUT_SHIFT = 1, RELAY_REALIZE_BAD_RES_SHIFT = 2, RELAY_REALIZE_BIAS_OVERFLOW = 4 };
+relay_status relay_calibrate_pow2_range(int32_t dtype, int64_t n_elems, const void* x, float* rho_out, void* cell,
+                                        void* hip_stream);
+relay_status relay_realize_conv(int32_t k, int64_t per_k, const float* w, const float* bias, const float* scale,
+                                const float* shift, float rho_x, float rho_y, float rho_res, int8_t* wq,
+                                int32_t* bias_q, relay_realized_conv* out, void* workspace, size_t workspace_bytes,
+                                void* hip_stream);
+
+/* Layout alteration of an activation tensor (paper Section 5.3 lists the alteration of operator
+ * data layouts among the compiler's passes): [n,c,h,w] -> [n,h,w,c_pad], channels c..c_pad-1 zero.
+ * Any dtype; c_pad >= c; x, y device, y must not alias x. */
 relay_status relay_nchw_to_nhwc(int32_t dtype, int32_t n, int32_t c, int32_t h, int32_t w, int32_t c_pad,
                                 const void* x, void* y, void* hip_stream);
 
-/* Tuning aid: force the implicit-GEMM workgroup tile of later fp16 / int8 conv calls made
- * by this process (0 .. count-1, largest first; negative = choose by layer shape, the
- * default).  Results do not depend on the tile (int8: bit for bit). */
+/* Tuning aid (the library's stand-in for the schedule search of paper Section 4.1, "Lowering":
+ * which schedule a fused operator gets is a choice made per shape and platform): force the
+ * implicit-GEMM workgroup tile of later fp16 / int8 conv calls made BY THE CALLING THREAD
+ * (0 .. count-1, largest first; 100 + v: variant v of the 3x3 stride-1 kernel; -1 = choose by
+ * layer shape, the default; -2 = by layer shape without the 3x3 stride-1 kernel).  The setting is
+ * thread-local: other threads' calls are unaffected and nothing is shared between threads.
+ * Results do not depend on the tile (int8: bit for bit). */
 relay_status relay_set_conv_tile(int32_t tile);
-/* Tuning aid: workgroups per output tile of later conv calls that are given a workspace
- * (0 = choose by layer shape, the default; 1 = never split; n <= 64, clamped to the number of
- * reduction chunks).  relay_workspace_bytes follows the setting. */
+/* Tuning aid (paper Section 4.1, "Lowering", as above), thread-local like relay_set_conv_tile: workgroups per output tile of the calling
+ * thread's later conv calls that are given a workspace (0 = choose by layer shape, the default;
+ * 1 = never split; n <= 64, clamped to the number of reduction chunks).  relay_workspace_bytes
+ * called from the same thread follows the setting. */
 relay_status relay_set_conv_split(int32_t split);
 
-/* Profiling aid: the name, as a kernel trace prints it, of the implicit-GEMM kernel variant
- * a fp16 / int8 descriptor runs on (template arguments give the workgroup's wave grid and
+/* Profiling aid (lowered code is specific to shape and platform, paper Section 4.1 "Lowering": this
+ * tells which specialisation a shape gets): the name, as a kernel trace prints it, of the
+ * implicit-GEMM kernel variant a fp16 / int8 descriptor runs on (template arguments give the workgroup's wave grid and
  * per-wave MFMA tile).  buf receives a NUL-terminated string of at most len bytes. */
 relay_status relay_conv2d_kernel_name(const relay_conv2d_desc* d, char* buf, size_t len);
 
-/* Message of the calling thread's last failed call (static storage, never NULL). */
+/* Part of the fixed calling convention (paper Section 3.3, "Backends"): every entry point returns a
+ * relay_status and raises nothing; this returns the message of the calling thread's last failed
+ * call (thread-local static storage owned by the library, never NULL, valid until that thread's
+ * next failing call). */
 const char* relay_last_error(void);
 
 #ifdef __cplusplus

@@ -31,6 +31,7 @@ typedef enum {
 } relay_op_pattern;
 
 /*
+ * The extraction step of operator fusion (paper Section 4.1, "Extraction").
  * All pointers are HOST pointers owned by the caller; nothing is retained.
  *   n_ops        number of operators, numbered in dataflow order: operator i reads only
  *                operators j < i.  1 <= n_ops <= 2^20.

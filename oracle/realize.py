@@ -12,7 +12,7 @@ Flow (one reading of the section; its choices are listed in the design notes):
              w'[k] = w[k] * scale[k]; the shift stays as a bias;
   realize    x_q = Q(x, rho_x); w_q = Q(w', rho_w); with real = code * rho / 2^7 the int32
              accumulator of a conv is in units of rho_x * rho_w / 2^14, hence
-               bias_q[k] = round(shift[k] * 2^14 / (rho_x * rho_w))
+               bias_q[k] = round((bias[k] * scale[k] + shift[k]) * 2^14 / (rho_x * rho_w))
                s = log2(2^7 * rho_y / (rho_x * rho_w))        (output requantization shift)
                l = log2(2^7 * rho_r / (rho_x * rho_w))        (residual alignment shift)
              all integers because every rho is a power of two.
@@ -68,7 +68,14 @@ def realize(ops, params: Sequence[dict], rho: Dict[str, float]):
         wq = OQ.Q(wf, rho_w, 8, 1)
         unit = rho[op.src] * rho_w / 2.0 ** 14          # real value of one accumulator count
         q = {"w": wq}
-        shift = p.get("shift") if p.get("shift") is not None else p.get("bias")
+        # additive term of the float tail in its order bias -> scale, shift:
+        # (acc + bias) * scale + shift = acc * scale + (bias * scale + shift)
+        shift = None
+        if p.get("bias") is not None:
+            shift = np.asarray(p["bias"], dtype=np.float64)
+        if p.get("scale") is not None:
+            shift = (shift if shift is not None else 0.0) * np.asarray(p["scale"], dtype=np.float64) \
+                + np.asarray(p["shift"], dtype=np.float64)
         if shift is not None:
             b = np.floor(np.asarray(shift, dtype=np.float64) / unit + 0.5)
             assert np.all(np.abs(b) < 2 ** 31)

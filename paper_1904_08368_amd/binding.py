@@ -67,6 +67,8 @@ SIGNATURES = {
     "relay_conv2d_maxpool_kernel_name": [_DP, C.c_char_p, _SZ],
     "relay_fused_conv2d_bn_relu_maxpool": [_DP, _P, _P, _P, _P, _P, _P, _P],
     "relay_qconv2d_requant_maxpool": [_DP, _P, _P, _P, _I, _P, _P],
+    "relay_calibrate_pow2_range": [_I, C.c_int64, _P, _P, _P, _P],
+    "relay_realize_conv": [_I, C.c_int64, _P, _P, _P, _P, C.c_float, C.c_float, C.c_float, _P, _P, _P, _P, _SZ, _P],
     "relay_set_conv_tile": [_I],
     "relay_set_conv_split": [_I],
     "relay_conv2d_kernel_name": [_DP, C.c_char_p, _SZ],
@@ -228,6 +230,22 @@ def relay_quantize(n_elems: int, src_dtype: int, x, rho: float, beta: int, sigma
 
 def relay_sim_quantize(n_elems: int, x, rho: float, beta: int, sigma: int, round_mode: int, seed: int, y) -> None:
     _check(lib().relay_sim_quantize(n_elems, _ptr(x), rho, beta, sigma, round_mode, seed, _ptr(y), _stream()))
+
+
+REALIZE_BAD_OUT_SHIFT, REALIZE_BAD_RES_SHIFT, REALIZE_BIAS_OVERFLOW = 1, 2, 4
+
+
+def relay_calibrate_pow2_range(dtype: int, n_elems: int, x, rho_out, cell) -> None:
+    """rho_out: device float32[1]; cell: device scratch of 4 bytes."""
+    _check(lib().relay_calibrate_pow2_range(dtype, n_elems, _ptr(x), _ptr(rho_out), _ptr(cell), _stream()))
+
+
+def relay_realize_conv(k: int, per_k: int, w, bias, scale, shift, rho_x: float, rho_y: float, rho_res: float, wq,
+                       bias_q, out, workspace) -> None:
+    """out: device int32[4] that receives (rho_w as float bits, out_rshift, residual_lshift, status)."""
+    _check(lib().relay_realize_conv(k, per_k, _ptr(w), _ptr(bias), _ptr(scale), _ptr(shift), rho_x, rho_y, rho_res,
+                                    _ptr(wq), _ptr(bias_q), _ptr(out), _ptr(workspace),
+                                    0 if workspace is None else workspace.numel() * workspace.element_size(), _stream()))
 
 
 FOLD_OUT, FOLD_IN = 0, 1

@@ -118,8 +118,10 @@ relay_status device_status(hipError_t e, const char* what) {
   return fail(RELAY_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
 }
 
-int g_force_tile = -1;
-int g_force_split = 0;  // 0: by layer shape; n >= 1: n workgroups per tile where the kernel can split
+// Tuning overrides of the calling thread (relay_set_conv_tile / relay_set_conv_split): thread-local, so
+// that threads cannot disturb each other's calls and nothing is shared between them.
+thread_local int g_force_tile = -1;
+thread_local int g_force_split = 0;  // 0: by layer shape; n >= 1: n workgroups per tile where the kernel can split
 
 // implicit-GEMM paths: which (dtype, layout, channel count) combinations have a kernel
 relay_status check_igemm_support(const relay_conv2d_desc* d) {
@@ -711,6 +713,51 @@ relay_status relay_sim_quantize(int64_t n_elems, const float* x, float rho, int3
   return device_status(relay::launch_sim_quantize(n_elems, x, rho, beta, sigma, round_mode, (unsigned)seed,
                                                   (unsigned)(seed >> 32), y, static_cast<hipStream_t>(hip_stream)),
                        "sim_quantize launch");
+}
+
+relay_status relay_calibrate_pow2_range(int32_t dtype, int64_t n_elems, const void* x, float* rho_out, void* cell,
+                                        void* hip_stream) {
+  if (dtype != RELAY_F32 && dtype != RELAY_F16) return fail(RELAY_ERR_DTYPE, "calibration takes F32 or F16 tensors");
+  if (n_elems <= 0 || n_elems > ((int64_t)1 << 40)) return fail(RELAY_ERR_SHAPE, "n_elems=%lld outside 1..2^40", (long long)n_elems);
+  if (!x || !rho_out || !cell) return fail(RELAY_ERR_NULL, "x, rho_out and cell are required");
+  if (!aligned(x, esize_of(dtype)) || !aligned(rho_out, 4) || !aligned(cell, 4))
+    return fail(RELAY_ERR_ALIGN, "pointers must be aligned to their element size");
+  return device_status(relay::launch_pow2_range(esize_of(dtype), n_elems, x, rho_out, static_cast<unsigned*>(cell),
+                                                static_cast<hipStream_t>(hip_stream)),
+                       "range calibration");
+}
+
+static_assert(sizeof(relay_realized_conv) == sizeof(relay::RealizedConv), "public and internal result records differ");
+static_assert((int)RELAY_REALIZE_BAD_OUT_SHIFT == (int)relay::REALIZE_BAD_OUT_SHIFT &&
+                  (int)RELAY_REALIZE_BAD_RES_SHIFT == (int)relay::REALIZE_BAD_RES_SHIFT &&
+                  (int)RELAY_REALIZE_BIAS_OVERFLOW == (int)relay::REALIZE_BIAS_OVERFLOW,
+              "public and internal status bits differ");
+
+relay_status relay_realize_conv(int32_t k, int64_t per_k, const float* w, const float* bias, const float* scale,
+                                const float* shift, float rho_x, float rho_y, float rho_res, int8_t* wq,
+                                int32_t* bias_q, relay_realized_conv* out, void* workspace, size_t workspace_bytes,
+                                void* hip_stream) {
+  if (k <= 0 || per_k <= 0 || per_k > kMaxElems || (long)k * per_k > kMaxElems)
+    return fail(RELAY_ERR_SHAPE, "bad filter extent (k=%d per_k=%lld)", k, (long long)per_k);
+  if (!w || !wq || !out || !workspace) return fail(RELAY_ERR_NULL, "w, wq, out and workspace are required");
+  if ((scale == nullptr) != (shift == nullptr)) return fail(RELAY_ERR_NULL, "scale and shift are given together or not at all");
+  if ((bias || shift) && !bias_q) return fail(RELAY_ERR_NULL, "bias_q is required when the tail adds a bias or a shift");
+  if (!(rho_x > 0.f) || !(rho_y > 0.f) || !(rho_res >= 0.f) || rho_x > 3.0e38f || rho_y > 3.0e38f || rho_res > 3.0e38f)
+    return fail(RELAY_ERR_SHAPE, "ranges must be positive and finite (rho_res may be 0: no residual)");
+  if (!aligned(w, 4) || !aligned(bias, 4) || !aligned(scale, 4) || !aligned(shift, 4) || !aligned(bias_q, 4) ||
+      !aligned(out, 4) || !aligned(workspace, 16))
+    return fail(RELAY_ERR_ALIGN, "fp32 / int32 pointers must be 4-byte and the workspace 16-byte aligned");
+  const size_t need = (size_t)k * (size_t)per_k * 4 + 16;
+  if (workspace_bytes < need) return fail(RELAY_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+  if ((const void*)wq == (const void*)w) return fail(RELAY_ERR_UNSUPPORTED, "output must not alias an input");
+  // layout of the workspace: the maximum's cell first (16 bytes), then the folded filters
+  unsigned* cell = static_cast<unsigned*>(workspace);
+  float* folded = reinterpret_cast<float*>(static_cast<char*>(workspace) + 16);
+  return device_status(relay::launch_realize_conv(k, per_k, w, bias, scale, shift, rho_x, rho_y, rho_res, wq,
+                                                  (bias || shift) ? bias_q : nullptr,
+                                                  reinterpret_cast<relay::RealizedConv*>(out), folded, cell,
+                                                  static_cast<hipStream_t>(hip_stream)),
+                       "realize launch");
 }
 
 relay_status relay_fuse_extract(int32_t n_ops, const int32_t* pattern, const int32_t* in_offsets,

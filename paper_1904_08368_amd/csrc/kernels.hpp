@@ -132,6 +132,17 @@ hipError_t launch_quantize(bool src_f16, long n, const void* x, float rho, int b
                            unsigned seed_lo, unsigned seed_hi, int8_t* y, hipStream_t st);
 hipError_t launch_sim_quantize(long n, const float* x, float rho, int beta, int sigma, int mode, unsigned seed_lo,
                                unsigned seed_hi, float* y, hipStream_t st);
+// Calibration and realization of the quantization flow (realize.hip).  RealizedConv mirrors the
+// public relay_realized_conv; `cell` is one zero-initialised-by-the-launcher word of device scratch.
+struct RealizedConv {
+  float rho_w;
+  int out_rshift, residual_lshift, status;
+};
+enum : int { REALIZE_BAD_OUT_SHIFT = 1, REALIZE_BAD_RES_SHIFT = 2, REALIZE_BIAS_OVERFLOW = 4 };
+hipError_t launch_pow2_range(int esize, long n, const void* x, float* rho, unsigned* cell, hipStream_t st);
+hipError_t launch_realize_conv(int K, long per_k, const float* w, const float* bias, const float* scale,
+                               const float* shift, float rho_x, float rho_y, float rho_r, int8_t* wq, int32_t* bias_q,
+                               RealizedConv* out, float* folded, unsigned* cell, hipStream_t st);
 hipError_t launch_pack_filters_rows(const void* w_oihw, void* w_packed, int K, int Csrc, int R, int S, int ck,
                                     int Kp, int esize, hipStream_t st);
 

@@ -359,3 +359,60 @@ def test_combined_windows_argument_checks():
     assert _combw(_d(pad=0, **s2), (128, 128), (0, 1), (1, 0)) == 4           # window not padded by half its size
     assert _combw(_d(r=4, s=4, pad=2, **s2), (128, 128), (0, 1), (1, 0)) == 4  # even window: no centre tap
     # (a valid request is not tried here: it would launch)
+
+
+def test_realize_and_calibrate_validate_on_the_host():
+    f = C.c_float
+    ok = dict(k=4, per_k=72, w=FAKE, bias=None, scale=None, shift=None, rx=f(4.0), ry=f(16.0), rr=f(0.0), wq=FAKE + 4096,
+              bq=None, out=FAKE + 8192, ws=FAKE + 16384, wsb=4 * 72 * 4 + 16)
+
+    def call(**kw):
+        a = dict(ok)
+        a.update(kw)
+        return _status("relay_realize_conv", a["k"], a["per_k"], a["w"], a["bias"], a["scale"], a["shift"], a["rx"], a["ry"],
+                       a["rr"], a["wq"], a["bq"], a["out"], a["ws"], a["wsb"], None)
+    assert call(k=0) == 2 and call(per_k=0) == 2 and call(k=1 << 20, per_k=1 << 20) == 2
+    assert call(w=None) == 1 and call(wq=None) == 1 and call(out=None) == 1 and call(ws=None) == 1
+    assert call(scale=FAKE) == 1 and call(shift=FAKE) == 1            # scale and shift come together
+    assert call(bias=FAKE) == 1                                       # a bias needs bias_q
+    assert call(rx=f(0.0)) == 2 and call(ry=f(-1.0)) == 2 and call(rr=f(-1.0)) == 2 and call(rx=f(float("inf"))) == 2
+    assert call(wsb=4 * 72 * 4) == 6
+    assert call(ws=FAKE + 16384 + 8) == 5 and call(w=FAKE + 2) == 5
+    assert call(wq=FAKE) == 4                                          # output aliases the input
+    cal = lambda dtype=B.RELAY_F32, n=10, x=FAKE, rho=FAKE + 64, cell=FAKE + 128: _status(
+        "relay_calibrate_pow2_range", dtype, n, x, rho, cell, None)
+    assert cal(dtype=B.RELAY_I8) == 3 and cal(n=0) == 2 and cal(x=None) == 1 and cal(rho=None) == 1 and cal(cell=None) == 1
+    assert cal(rho=FAKE + 2) == 5
+
+
+def test_tuning_overrides_are_thread_local():
+    """A tile forced by one thread must not change what another thread's calls choose."""
+    import threading
+    d = _d(n=32, c=128, h=28, w=28, k=128)
+    B.relay_set_conv_tile(-1)
+    default = B.relay_conv2d_kernel_name(d)
+    seen = {}
+
+    def other():
+        B.relay_set_conv_tile(5)
+        seen["forced"] = B.relay_conv2d_kernel_name(d)
+    t = threading.Thread(target=other)
+    t.start()
+    t.join()
+    assert seen["forced"] != default and "igemm_dma_kernel" in seen["forced"]
+    assert B.relay_conv2d_kernel_name(d) == default          # this thread still has its own setting
+
+
+def test_every_entry_point_declaration_cites_its_source():
+    """Each declared function sits behind a comment that names the passage defining the operation
+    (a section of the paper) or, for the allocation-free variant, the callers it is for."""
+    text = "".join(open(os.path.join(ROOT, "include", f)).read() for f in sorted(os.listdir(os.path.join(ROOT, "include")))
+                   if f.endswith(".h"))
+    missing = []
+    for m in re.finditer(r"\brelay_status\s+(relay_[a-z0-9_]+)\s*\(|const char\*\s+(relay_last_error)\s*\(", text):
+        name = m.group(1) or m.group(2)
+        head = text[:m.start()]
+        comment = head[head.rfind("/*"):]
+        if "Section" not in comment and "cannot allocate" not in comment:
+            missing.append(name)
+    assert not missing, missing

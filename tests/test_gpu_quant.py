@@ -186,3 +186,67 @@ def test_calibrate_realize_flow_on_resnet18(G):
     deq = R.dequantize(net.tensor(last), rho[last])
     sqnr = 10 * np.log10((ref ** 2).sum() / ((deq - ref) ** 2).sum())
     assert sqnr > 20, sqnr
+
+
+def test_realize_conv_and_range_entry_points_against_the_oracle(G):
+    """relay_realize_conv (device kernels) against oracle.realize (numpy): filters with the scale
+    folded in, the bias with a conv bias in front of the scale, both shifts, the filter range, and
+    the status bits; relay_calibrate_pow2_range against the oracle's rule, edge values included."""
+    from oracle import realize as R
+    from paper_1904_08368_amd import binding as B
+    rng = np.random.default_rng(780)
+
+    class Op:
+        kind, name, src, dst, res = "conv", "c", "x", "y", "r"
+    for k, c, r, with_bias, with_bn in ((24, 16, 3, True, True), (7, 5, 1, False, True), (9, 3, 7, True, False), (4, 8, 3, False, False)):
+        w = (rng.standard_normal((k, c, r, r)) * 0.3).astype(np.float32)
+        p = {"w": w}
+        if with_bias:
+            p["bias"] = rng.standard_normal(k).astype(np.float32)
+        if with_bn:
+            p["scale"] = (1 + 0.3 * rng.standard_normal(k)).astype(np.float32)
+            p["shift"] = rng.standard_normal(k).astype(np.float32)
+        rho = {"x": 4.0, "y": 16.0, "r": 8.0}
+        qp_ref, sh_ref = R.realize([Op], [p], rho)
+        wq = torch.full(w.shape, -128, dtype=torch.int8, device=G.DEV)
+        bq = torch.full((k,), 12345, dtype=torch.int32, device=G.DEV) if (with_bias or with_bn) else None
+        out = torch.zeros(4, dtype=torch.int32, device=G.DEV)
+        ws = torch.empty(w.size * 4 + 16, dtype=torch.uint8, device=G.DEV)
+        B.relay_realize_conv(k, c * r * r, G.up(w), G.up(p.get("bias")), G.up(p.get("scale")), G.up(p.get("shift")),
+                             rho["x"], rho["y"], rho["r"], wq, bq, out, ws)
+        torch.cuda.synchronize()
+        rho_w_bits, s, l, status = out.cpu().tolist()
+        rho_w = float(np.array([rho_w_bits], dtype=np.int32).view(np.float32)[0])
+        wf = R.fold_scale(w, p.get("scale")).astype(np.float32)
+        assert rho_w == R.pow2_range(float(np.abs(wf).max())) and status == 0
+        assert {"s": s, "l": l} == sh_ref[0]
+        assert np.array_equal(wq.cpu().numpy(), qp_ref[0]["w"])
+        if bq is not None:
+            assert np.array_equal(bq.cpu().numpy(), qp_ref[0]["bias"])
+        else:
+            assert "bias" not in qp_ref[0]
+    # status bits: an output range too small for the accumulator scale, a range that is no power of two, a bias out of int32
+    w = np.ones((4, 8, 3, 3), dtype=np.float32)
+    for args, bit in (((4.0, 2.0 ** -12, 0.0), B.REALIZE_BAD_OUT_SHIFT), ((4.0, 3.0, 0.0), B.REALIZE_BAD_OUT_SHIFT),
+                      ((4.0, 16.0, 2.0 ** 40), B.REALIZE_BAD_RES_SHIFT)):
+        out = torch.zeros(4, dtype=torch.int32, device=G.DEV)
+        wq = torch.empty(w.shape, dtype=torch.int8, device=G.DEV)
+        ws = torch.empty(w.size * 4 + 16, dtype=torch.uint8, device=G.DEV)
+        B.relay_realize_conv(4, 72, G.up(w), None, None, None, *args, wq, None, out, ws)
+        torch.cuda.synchronize()
+        assert out.cpu().tolist()[3] & bit, args
+    out = torch.zeros(4, dtype=torch.int32, device=G.DEV)
+    bq = torch.empty(4, dtype=torch.int32, device=G.DEV)
+    B.relay_realize_conv(4, 72, G.up(w), G.up(np.array([1e9, 0, -1e9, 1], dtype=np.float32)), None, None, 2.0 ** -8, 2.0 ** -8, 0.0,
+                         wq, bq, out, ws)
+    torch.cuda.synchronize()
+    assert out.cpu().tolist()[3] & B.REALIZE_BIAS_OVERFLOW
+    # ranges
+    cell = torch.empty(1, dtype=torch.int32, device=G.DEV)
+    rho_d = torch.empty(1, dtype=torch.float32, device=G.DEV)
+    for vals, dt in (([0.0, -0.0], "f32"), ([1.0, -0.25], "f32"), ([1.0001, 0.5], "f32"), ([-5.9, 3.0], "f16"), ([0.5], "f16"),
+                     ([3e-4, -2e-4], "f32"), (rng.standard_normal(70001) * 37, "f32"), (rng.standard_normal(4099), "f16")):
+        a = np.asarray(vals, dtype=np.float32 if dt == "f32" else np.float16)
+        B.relay_calibrate_pow2_range(B.RELAY_F32 if dt == "f32" else B.RELAY_F16, a.size, G.up(a), rho_d, cell)
+        torch.cuda.synchronize()
+        assert float(rho_d.cpu()[0]) == R.pow2_range(float(np.max(np.abs(a.astype(np.float64))))), vals if len(vals) < 5 else dt

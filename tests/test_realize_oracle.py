@@ -28,8 +28,9 @@ def test_axis_scale_folding_moves_the_multiply_into_the_filters():
     assert R.fold_scale(w, None) is not None and np.array_equal(R.fold_scale(w, None), w)
 
 
+@pytest.mark.parametrize("with_bias", [False, True])
 @pytest.mark.parametrize("with_res", [False, True])
-def test_realized_conv_is_exact_on_representable_values(with_res):
+def test_realized_conv_is_exact_on_representable_values(with_res, with_bias):
     """When inputs, folded filters, shift and residual already lie on their 8-bit grids, the integer
     conv with the realized bias and shifts reproduces Q(float result) bit for bit: pins the
     formulas for bias_q, s and l (a wrong power of two or a dropped term changes every output)."""
@@ -49,10 +50,19 @@ def test_realized_conv_is_exact_on_representable_values(with_res):
 
     class Op:
         kind, name, src, dst, res = "conv", "c", "x", "y", ("r" if with_res else None)
-    qp, sh = R.realize([Op], [{"w": w, "scale": scale, "shift": shift}], rho)
+    p = {"w": w, "scale": scale, "shift": shift}
+    bias = None
+    if with_bias:          # a conv bias in front of the scale: it reaches the accumulator as bias * scale
+        bias = rng.integers(-30000, 30000, 4) * unit / scale
+        p["bias"] = bias
+    qp, sh = R.realize([Op], [p], rho)
     assert np.array_equal(qp[0]["w"][1:], wq[1:]) and qp[0]["w"][0, 0, 0, 0] == 127
     assert sh[0]["s"] == int(np.log2(2 ** 7 * 64.0 / (4.0 * 0.5)))
-    y_float = O.conv2d(x, R.fold_scale(w, scale), (1, 1), (1, 1)) + shift.reshape(1, -1, 1, 1)
+    # the float operator sequence itself, unfolded: conv -> [bias] -> scale, shift
+    y_float = O.conv2d(x, w, (1, 1), (1, 1))
+    if with_bias:
+        y_float = O.bias_add(y_float, bias)
+    y_float = O.scale_shift(y_float, scale, shift)
     if with_res:
         y_float = y_float + res
         assert sh[0]["l"] == int(np.log2(2 ** 7 * 16.0 / (4.0 * 0.5)))
