@@ -14,9 +14,14 @@ pytestmark = pytest.mark.gpu
 TOL_F16 = 1e-2
 # A chained fp16 network re-rounds every layer's output; one-ulp differences (2^-11
 # relative) between the two sides re-enter the next layer and add up like a random walk
-# over the 20 layers: about sqrt(20) * 2^-11 * (a few) = 5e-3.  Bound for the end-to-end comparison:
-TOL_F16_CHAIN = 2e-2
-TOL_F16_CHAIN_DEEP = 4e-2     # MobileNet: 28 layers
+# over the layers.  Observed end to end at batch 32, worst element of each tensor: ResNet-18
+# 1.0e-3 after the first layer, 5.6e-3 after the 20th, 1.1e-3 on the logits; so the chained
+# comparison holds the same 1e-2 as a single layer.  MobileNet-v1 (27 layers in a chain, its
+# depthwise layers sum 9 terms only, so a one-ulp input difference is a larger share of an
+# output): 1.0e-3 after the stem, 7.4e-3 after block 9, 1.13e-2 after block 13 (1.6 M elements),
+# 1.4e-3 on the logits: bounded by 2e-2 inside the network and by 1e-2 on the logits.
+TOL_F16_CHAIN = 1e-2
+TOL_F16_CHAIN_DEEP = 2e-2
 
 
 @pytest.fixture(scope="module")
@@ -30,6 +35,12 @@ def G():
 def _net(ops, params, batch, hw, mode, shifts=None, cin=3, fuse_pool=True):
     from paper_1904_08368_amd.stack import FusedNet
     return FusedNet(ops, params, batch, hw, hw, mode, shifts=shifts, in_channels=cin, fuse_pool=fuse_pool)
+
+
+def _report(capsys, title, errs):
+    """The observed end-to-end errors go to the test log (they are what the chained tolerance rests on)."""
+    with capsys.disabled():
+        print(f"\n[observed] {title}: " + ", ".join(f"{k}={v:.2e}" for k, v in errs.items()), flush=True)
 
 
 # ------------------------------------------------------------------ config 2: basic block
@@ -91,7 +102,7 @@ def test_networks_built_by_the_fusion_pass(G):
     assert np.array_equal(net.tensor(ops[-1].dst), ref[table[-1].dst])
 
 
-def test_unfused_pipeline_against_the_unfused_oracle(G):
+def test_unfused_pipeline_against_the_unfused_oracle(G, capsys):
     """Fusion switched off (every elementwise operator a launch and an fp16 tensor of its own): the
     GPU pipeline equals the oracle's unfused operator sequence, and both stay close to the fused
     result, which skips the intermediate fp16 roundings."""
@@ -110,9 +121,11 @@ def test_unfused_pipeline_against_the_unfused_oracle(G):
         torch.cuda.synchronize()
         last = ops[-1].dst
         got = net.tensor(last)
-        tol = TOL_F16_CHAIN if len(ops) <= 23 else 2 * TOL_F16_CHAIN
-        assert O.max_rel_err(got, ref_u[last]) <= tol, ops[0].name
-        assert O.max_rel_err(got, ref_f[last]) <= 2 * tol, ops[0].name
+        tol = TOL_F16_CHAIN if len(ops) <= 23 else TOL_F16_CHAIN_DEEP
+        e_u, e_f = O.max_rel_err(got, ref_u[last]), O.max_rel_err(got, ref_f[last])
+        _report(capsys, f"unfused pipeline of {len(ops)} operators, last tensor", {"vs unfused oracle": e_u, "vs fused oracle": e_f})
+        assert e_u <= tol, ops[0].name
+        assert e_f <= 2 * tol, ops[0].name
         first = ops[0].dst                                    # one layer deep both sides saw the same input bits
         assert O.max_rel_err(net.tensor(first), ref_u[first]) <= TOL_F16
 
@@ -221,16 +234,9 @@ def test_config3_resnet18_fp16_batch32_sampled(G):
         assert not np.isnan(got).any() and (not op.relu or got.min() >= 0)
 
 
-def _report(capsys, title, errs):
-    """The observed end-to-end errors go to the test log (they are what the chained tolerance rests on)."""
-    with capsys.disabled():
-        print(f"\n[observed] {title}: " + ", ".join(f"{k}={v:.2e}" for k, v in errs.items()), flush=True)
-
-
 def test_config3_resnet18_fp16_batch32_end_to_end_as_timed(G, capsys):
     """The configuration the benchmark times -- the network built by the fusion pass, batch 32, the
-    first conv with its max pool in one launch, the shortcut convs on the forked stream, replayed
-    from a HIP graph -- against the oracle's whole-batch run: every stage output and the logits,
+    first conv with its max pool in one launch, replayed from a HIP graph -- against the oracle's whole-batch run: every stage output and the logits,
     element by element."""
     from paper_1904_08368_amd import fusion
     from workloads import graphs
@@ -240,7 +246,7 @@ def test_config3_resnet18_fp16_batch32_end_to_end_as_timed(G, capsys):
     x = inputs.image(3, 32, 3, 224, 224, "f16")
     ref = run_float(table, params, x, "f16")
     net = _net(ops, params, 32, 224, "f16")
-    assert net.side_calls and "conv1+maxpool" in net.call_names
+    assert "conv1+maxpool" in net.call_names
     net.load_input(x)
     net.capture()
     names = {a.dst: b.dst for a, b in zip(ops, table)}
@@ -258,6 +264,18 @@ def test_config3_resnet18_fp16_batch32_end_to_end_as_timed(G, capsys):
         for k, v in errs.items():
             assert v <= TOL_F16_CHAIN, (k, v, rep)
     _report(capsys, "ResNet-18 fp16 batch 32, graph replay, max rel err vs oracle", errs)
+    # the same network with the shortcut convs on a forked stream beside their sibling conv: same bits
+    from paper_1904_08368_amd.stack import FusedNet
+    want = net.tensor(ops[-1].dst).copy()
+    side = FusedNet(ops, params, 32, 224, 224, "f16", overlap_shortcuts=True)
+    assert side.side_calls
+    side.load_input(x)
+    side.capture()
+    for _ in range(2):
+        side.bufs[ops[-1].dst].zero_()
+        side.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(side.tensor(ops[-1].dst), want)
 
 
 def test_config5_mobilenet_fp16_batch32_end_to_end_as_timed(G, capsys):
@@ -352,8 +370,8 @@ def test_config5_mobilenet_fp16_chain_and_layers(G):
     torch.cuda.synchronize()
     assert O.max_rel_err(net.tensor("b1.t"), ref["b1.t"]) <= TOL_F16
     for name in ("b4.out", "b9.out", "b13.out"):
-        assert O.max_rel_err(net.tensor(name), ref[name]) <= TOL_F16_CHAIN, name
-    assert O.max_rel_err(net.tensor("logits").reshape(1, 1000), ref["logits"]) <= 2 * TOL_F16_CHAIN
+        assert O.max_rel_err(net.tensor(name), ref[name]) <= TOL_F16_CHAIN_DEEP, name
+    assert O.max_rel_err(net.tensor("logits").reshape(1, 1000), ref["logits"]) <= TOL_F16_CHAIN
 
 
 def test_config5_mobilenet_batch32_sampled(G):
