@@ -351,6 +351,22 @@ relay_status relay_realize_conv(int32_t k, int64_t per_k, const float* w, const 
                                 int32_t* bias_q, relay_realized_conv* out, void* workspace, size_t workspace_bytes,
                                 void* hip_stream);
 
+/* For callers that cannot allocate device memory (code under HIP-graph capture, serving loops and
+ * harnesses that forbid hipMalloc): relay_fused_conv2d_bias_bn_relu for F16 NHWC / NHWC4_PADDED
+ * descriptors with the reduction-split scratch (see relay_workspace_bytes) taken from a static
+ * device array inside the library instead of a caller workspace.  Same operands, same results bit
+ * for bit as that call given a workspace.  Nothing is allocated or freed, by this call or by any
+ * routine it uses.  Limits: relay_workspace_bytes(d) must not exceed RELAY_STATIC_SCRATCH_BYTES, else
+ * RELAY_ERR_WORKSPACE and nothing is launched (every ResNet-18 / MobileNet layer at any batch fits).
+ * Every GPU the library runs on holds one such array until the process ends; all calls on a GPU
+ * share it, so two of these calls that may overlap in time on one GPU (different streams or
+ * threads) race -- serialise them, or use the workspace form.  The arrival counters at its start are
+ * cleared by a small kernel ahead of each launch that uses them. */
+#define RELAY_STATIC_SCRATCH_BYTES (4u << 20)
+relay_status relay_fused_conv2d_bias_bn_relu_static(const relay_conv2d_desc* d, const void* x, const void* w_packed,
+                                                    const float* bias, const float* bn_scale, const float* bn_shift,
+                                                    const void* residual, void* y, void* hip_stream);
+
 /* Layout alteration of an activation tensor (paper Section 5.3 lists the alteration of operator
  * data layouts among the compiler's passes): [n,c,h,w] -> [n,h,w,c_pad], channels c..c_pad-1 zero.
  * Any dtype; c_pad >= c; x, y device, y must not alias x. */

@@ -45,6 +45,7 @@ SIGNATURES = {
     "relay_packed_weight_bytes": [_DP, C.POINTER(_SZ)],
     "relay_prepack_conv2d_weights": [_DP, _P, _I, _P, _SZ, _P],
     "relay_fused_conv2d_bias_bn_relu": [_DP, _P, _P, _P, _P, _P, _P, _P, _P, _SZ, _P],
+    "relay_fused_conv2d_bias_bn_relu_static": [_DP, _P, _P, _P, _P, _P, _P, _P, _P],
     "relay_qconv2d_requant": [_DP, _P, _P, _P, _P, _I, _I, _P, _P, _SZ, _P],
     "relay_prepack_dwconv_weights": [_DP, _P, _P, _P],
     "relay_fused_dwconv_bias_relu": [_DP, _P, _P, _P, _P, _P, _P, _P],
@@ -147,6 +148,11 @@ def relay_fused_conv2d_bias_bn_relu(d: ConvDesc, x, w_packed, bias, bn_scale, bn
     _check(lib().relay_fused_conv2d_bias_bn_relu(C.byref(d), _ptr(x), _ptr(w_packed), _ptr(bias), _ptr(bn_scale),
                                                  _ptr(bn_shift), _ptr(residual), _ptr(y), _ptr(workspace),
                                                  ws_bytes, _stream()))
+
+
+def relay_fused_conv2d_bias_bn_relu_static(d: ConvDesc, x, w_packed, bias, bn_scale, bn_shift, residual, y) -> None:
+    _check(lib().relay_fused_conv2d_bias_bn_relu_static(C.byref(d), _ptr(x), _ptr(w_packed), _ptr(bias), _ptr(bn_scale),
+                                                        _ptr(bn_shift), _ptr(residual), _ptr(y), _stream()))
 
 
 def relay_qconv2d_requant(d: ConvDesc, x, w_packed, bias, residual, residual_lshift: int, out_rshift: int, y,

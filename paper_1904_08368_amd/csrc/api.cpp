@@ -1,6 +1,7 @@
 // C-ABI layer: argument checks on the host, then dispatch to the gfx950 kernels.
 // Every check runs before the first HIP call, so the error paths are testable on a
 // machine without a GPU.
+#include <atomic>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -140,6 +141,38 @@ relay_status check_igemm_support(const relay_conv2d_desc* d) {
   return RELAY_OK;
 }
 
+}  // namespace
+
+// ---- the allocation-free variant: reduction-split scratch in a static device array ----------------
+// `scratch` is the name of the device array in device code; in host code the name is only a handle
+// for hipGetSymbolAddress.  Each GPU holds its own copy at its own address: the address is looked
+// up once per device (with that device current) and host code uses only that pointer.
+static __device__ __align__(256) unsigned char scratch[RELAY_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+__global__ void clear_words_kernel(unsigned* p, int n) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = 0u;
+}
+
+// device address of `scratch` on the current device
+relay_status scratch_address(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return device_status(e, "hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices) return fail(RELAY_ERR_DEVICE, "device ordinal %d outside 0..%d", dev, kMaxDevices - 1);
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return device_status(e == hipSuccess ? hipErrorInvalidSymbol : e, "hipGetSymbolAddress(scratch)");
+    g_scratch_ptr[dev].store(p, std::memory_order_release);  // (two threads racing here store the same address)
+  }
+  *out = p;
+  return RELAY_OK;
+}
 }  // namespace
 
 extern "C" {
@@ -343,6 +376,49 @@ relay_status relay_fused_conv2d_bias_bn_relu(const relay_conv2d_desc* d, const v
   if (!aligned(x, 16) || !aligned(w_packed, 16) || !aligned(y, 16) || (residual && !aligned(residual, 16)))
     return fail(RELAY_ERR_ALIGN, "fp16 tensors must be 16-byte aligned");
   if ((st = use_workspace(a, false, workspace, workspace_bytes)) != RELAY_OK) return st;
+  return device_status(launch_igemm(a, false, s), "conv2d fp16 launch");
+}
+
+// ---- the allocation-free variant of the fp16 conv (scratch: the static device array declared at the top)
+relay_status relay_fused_conv2d_bias_bn_relu_static(const relay_conv2d_desc* d, const void* x, const void* w_packed,
+                                                    const float* bias, const float* bn_scale, const float* bn_shift,
+                                                    const void* residual, void* y, void* hip_stream) {
+  int ho, wo;
+  relay_status st = check_geometry(d, &ho, &wo);
+  if (st != RELAY_OK) return st;
+  if (d->dtype != RELAY_F16) return fail(RELAY_ERR_DTYPE, "the allocation-free conv2d takes F16");
+  if (!x || !w_packed || !y) return fail(RELAY_ERR_NULL, "x, w_packed and y are required");
+  if ((st = check_optional(bias, d->flags & RELAY_HAS_BIAS, "bias")) != RELAY_OK) return st;
+  if ((st = check_optional(bn_scale, d->flags & RELAY_HAS_BN, "bn_scale")) != RELAY_OK) return st;
+  if ((st = check_optional(bn_shift, d->flags & RELAY_HAS_BN, "bn_shift")) != RELAY_OK) return st;
+  if ((st = check_optional(residual, d->flags & RELAY_HAS_RESIDUAL, "residual")) != RELAY_OK) return st;
+  if (y == x || y == residual) return fail(RELAY_ERR_UNSUPPORTED, "output must not alias an input");
+  if ((st = check_igemm_support(d)) != RELAY_OK) return st;
+  if (!aligned(x, 16) || !aligned(w_packed, 16) || !aligned(y, 16) || (residual && !aligned(residual, 16)))
+    return fail(RELAY_ERR_ALIGN, "fp16 tensors must be 16-byte aligned");
+  relay::ConvArgs a = make_args(d, ho, wo);
+  a.x = x; a.w = w_packed; a.y = y; a.res = residual; a.bias = bias; a.scale = bn_scale; a.shift = bn_shift;
+  finish_args(a);
+  size_t cb = 0, need = 0;
+  const int split = plan_split(a, false, &cb, &need);
+  if (need > RELAY_STATIC_SCRATCH_BYTES)
+    return fail(RELAY_ERR_WORKSPACE, "this layer's reduction split needs %zu bytes of scratch, the static array holds %u", need,
+                (unsigned)RELAY_STATIC_SCRATCH_BYTES);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  a.split = 1;
+  if (split > 1) {
+    void* base = nullptr;
+    if ((st = scratch_address(&base)) != RELAY_OK) return st;
+    a.split = split;
+    a.ws_cnt = static_cast<unsigned*>(base);
+    a.ws_part = reinterpret_cast<unsigned*>(static_cast<char*>(base) + cb);
+    // the arrival counters must start at zero whatever an earlier call left behind; a fill kernel,
+    // not a memset, so that the call can be recorded into a HIP graph
+    const int words = (int)(cb / sizeof(unsigned));
+    hipLaunchKernelGGL(clear_words_kernel, dim3((words + 255) / 256), dim3(256), 0, s, a.ws_cnt, words);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return device_status(e, "scratch clear launch");
+  }
   return device_status(launch_igemm(a, false, s), "conv2d fp16 launch");
 }
 
