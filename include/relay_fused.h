@@ -386,6 +386,24 @@ relay_status relay_set_conv_tile(int32_t tile);
  * 1 = never split; n <= 64, clamped to the number of reduction chunks).  relay_workspace_bytes
  * called from the same thread follows the setting. */
 relay_status relay_set_conv_split(int32_t split);
+/* Tuning aid (paper Section 4.1, "Lowering", as above), thread-local: upper bound on the number of
+ * workgroups in the grid of the persistent 3x3 stride-1 kernel, whose workgroups each walk a list
+ * of output tiles (0 = one per workgroup slot of the chip, the default).  A smaller grid leaves
+ * compute units to other streams and makes every workgroup walk more tiles; results do not depend
+ * on it. */
+relay_status relay_set_conv_workgroups(int32_t workgroups);
+
+/* Measurement aids for the roofline figures (paper Section 5.1 states how its measurements are
+ * taken; these give the chip's measured ceilings to set beside the nominal ones):
+ *   relay_probe_mfma  every wave of `workgroups` workgroups of 256 threads runs `iters` rounds of four
+ *                     independent 32x32 matrix instructions (F16: 32x32x16, I8: 32x32x32) on registers
+ *                     only: 2 * 32*32*K * 4 * iters * 4 * workgroups operations per launch.
+ *                     out: device, 4 bytes (practically never written).
+ *   relay_probe_copy  dst[i] = src[i] over `bytes` bytes (a multiple of 16) in 16-byte pieces, a
+ *                     grid-stride loop of 4096 workgroups: reads and writes `bytes` each.
+ * Device pointers owned by the caller; only enqueue on hip_stream. */
+relay_status relay_probe_mfma(int32_t dtype, int32_t iters, int32_t workgroups, void* out, void* hip_stream);
+relay_status relay_probe_copy(const void* src, void* dst, int64_t bytes, void* hip_stream);
 
 /* Profiling aid (lowered code is specific to shape and platform, paper Section 4.1 "Lowering": this
  * tells which specialisation a shape gets): the name, as a kernel trace prints it, of the

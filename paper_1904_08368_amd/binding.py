@@ -70,8 +70,11 @@ SIGNATURES = {
     "relay_qconv2d_requant_maxpool": [_DP, _P, _P, _P, _I, _P, _P],
     "relay_calibrate_pow2_range": [_I, C.c_int64, _P, _P, _P, _P],
     "relay_realize_conv": [_I, C.c_int64, _P, _P, _P, _P, C.c_float, C.c_float, C.c_float, _P, _P, _P, _P, _SZ, _P],
+    "relay_probe_mfma": [_I, _I, _I, _P, _P],
+    "relay_probe_copy": [_P, _P, C.c_int64, _P],
     "relay_set_conv_tile": [_I],
     "relay_set_conv_split": [_I],
+    "relay_set_conv_workgroups": [_I],
     "relay_conv2d_kernel_name": [_DP, C.c_char_p, _SZ],
 }
 
@@ -316,8 +319,20 @@ def relay_conv2d_maxpool_kernel_name(d: ConvDesc) -> str:
     return buf.value.decode()
 
 
+def relay_probe_mfma(dtype: int, iters: int, workgroups: int, out) -> None:
+    _check(lib().relay_probe_mfma(dtype, iters, workgroups, _ptr(out), _stream()))
+
+
+def relay_probe_copy(src, dst, nbytes: int) -> None:
+    _check(lib().relay_probe_copy(_ptr(src), _ptr(dst), nbytes, _stream()))
+
+
 def relay_set_conv_tile(tile: int) -> None:
     _check(lib().relay_set_conv_tile(tile))
+
+
+def relay_set_conv_workgroups(workgroups: int) -> None:
+    _check(lib().relay_set_conv_workgroups(workgroups))
 
 
 def relay_set_conv_split(split: int) -> None:

@@ -105,10 +105,17 @@ relay::ConvArgs make_args(const relay_conv2d_desc* d, int ho, int wo) {
   return a;
 }
 
+// Tuning overrides of the calling thread (relay_set_conv_tile / relay_set_conv_split): thread-local, so
+// that threads cannot disturb each other's calls and nothing is shared between them.
+thread_local int g_force_tile = -1;
+thread_local int g_force_split = 0;  // 0: by layer shape; n >= 1: n workgroups per tile where the kernel can split
+thread_local int g_max_wgs = 0;      // 0: fill the chip; n >= 1: at most n workgroups in a persistent kernel's grid
+
 // after the operand pointers are in place
 void finish_args(relay::ConvArgs& a) {
   const bool al = aligned(a.bias, 16) && aligned(a.scale, 16) && aligned(a.shift, 16) && aligned(a.qbias, 16);
   a.param_vec = (al && (a.K & 7) == 0) ? 1 : 0;
+  a.max_wgs = g_max_wgs;
   // an XCD works through a run of consecutive tiles: let the run share whichever operand is
   // larger, so that the XCD's L2 only has to hold a slab of it
   a.n_major = (size_t)a.K * a.Kred > (size_t)a.N * a.H * a.W * a.C ? 1 : 0;
@@ -118,11 +125,6 @@ relay_status device_status(hipError_t e, const char* what) {
   if (e == hipSuccess) return RELAY_OK;
   return fail(RELAY_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
 }
-
-// Tuning overrides of the calling thread (relay_set_conv_tile / relay_set_conv_split): thread-local, so
-// that threads cannot disturb each other's calls and nothing is shared between them.
-thread_local int g_force_tile = -1;
-thread_local int g_force_split = 0;  // 0: by layer shape; n >= 1: n workgroups per tile where the kernel can split
 
 // implicit-GEMM paths: which (dtype, layout, channel count) combinations have a kernel
 relay_status check_igemm_support(const relay_conv2d_desc* d) {
@@ -275,29 +277,47 @@ relay_status relay_prepack_conv2d_weights(const relay_conv2d_desc* d, const void
                        "filter packing");
 }
 
-// g_force_tile: -1 heuristics; -2 heuristics without the halo kernel; 0.. a tile of the implicit-GEMM
-// kernels; kHaloBase + v the halo kernel's variant v (where it applies)
+// g_force_tile: -1 heuristics; -2 heuristics without the 3x3 stride-1 kernels; 0.. a tile of the
+// implicit-GEMM kernels; kHaloBase + v the halo kernel's variant v, kStreamBase + v the persistent
+// kernel's variant v (where they apply)
 constexpr int kHaloBase = 100;
+constexpr int kStreamBase = 200;
 
 relay_status relay_set_conv_tile(int32_t tile) {
   const int most = relay::igemm_dma_tile_count() > relay::igemm_tile_count() ? relay::igemm_dma_tile_count()
                                                                              : relay::igemm_tile_count();
-  const bool halo = tile >= kHaloBase && tile < kHaloBase + relay::conv_halo_variant_count();
+  const bool halo = (tile >= kHaloBase && tile < kHaloBase + relay::conv_halo_variant_count()) ||
+                    (tile >= kStreamBase && tile < kStreamBase + relay::conv_stream_variant_count());
   if (tile >= most && !halo) return fail(RELAY_ERR_UNSUPPORTED, "no tile %d", tile);
   g_force_tile = tile < -1 ? -2 : tile;
   return RELAY_OK;
 }
 
+// which variant of the persistent 3x3 stride-1 kernel runs this layer, or -1
+static int stream_choice(const relay::ConvArgs& a, bool is_i8) {
+  if (g_force_tile >= kStreamBase)
+    return relay::conv_stream_supported(a, is_i8, g_force_tile - kStreamBase) ? g_force_tile - kStreamBase : -1;
+  return g_force_tile == -1 ? relay::conv_stream_pick(a, is_i8) : -1;
+}
+
 // which halo variant runs this layer, or -1
 static int halo_choice(const relay::ConvArgs& a, bool is_i8) {
+  if (stream_choice(a, is_i8) >= 0) return -1;
+  if (g_force_tile >= kStreamBase) return -1;
   if (g_force_tile >= kHaloBase) return relay::conv_halo_supported(a, is_i8, g_force_tile - kHaloBase) ? g_force_tile - kHaloBase : -1;
   return g_force_tile == -1 ? relay::conv_halo_pick(a, is_i8) : -1;
 }
 
 static int plan_split(const relay::ConvArgs& a, bool is_i8, size_t* counter_bytes, size_t* total_bytes) {
   *counter_bytes = *total_bytes = 0;
-  if (halo_choice(a, is_i8) >= 0 || !relay::igemm_dma_supported(a, is_i8)) return 1;
+  if (stream_choice(a, is_i8) >= 0 || halo_choice(a, is_i8) >= 0 || !relay::igemm_dma_supported(a, is_i8)) return 1;
   return relay::igemm_dma_plan_split(a, is_i8, g_force_tile, g_force_split, counter_bytes, total_bytes);
+}
+
+relay_status relay_set_conv_workgroups(int32_t workgroups) {
+  if (workgroups < 0 || workgroups > (1 << 20)) return fail(RELAY_ERR_UNSUPPORTED, "workgroups=%d outside 0..2^20", workgroups);
+  g_max_wgs = workgroups;
+  return RELAY_OK;
 }
 
 relay_status relay_set_conv_split(int32_t split) {
@@ -323,6 +343,8 @@ static relay_status use_workspace(relay::ConvArgs& a, bool is_i8, void* workspac
 }
 
 static hipError_t launch_igemm(const relay::ConvArgs& a, bool is_i8, hipStream_t s) {
+  const int sv = stream_choice(a, is_i8);
+  if (sv >= 0) return relay::launch_conv_stream(a, is_i8, sv, s);
   const int hv = halo_choice(a, is_i8);
   if (hv >= 0) return relay::launch_conv_halo(a, is_i8, hv, s);
   if (relay::igemm_dma_supported(a, is_i8)) return relay::launch_conv_igemm_dma(a, is_i8, g_force_tile, s);
@@ -339,7 +361,9 @@ relay_status relay_conv2d_kernel_name(const relay_conv2d_desc* d, char* buf, siz
   if ((st = check_igemm_support(d)) != RELAY_OK) return st;
   relay::ConvArgs a = make_args(d, ho, wo);
   const bool i8 = d->dtype == RELAY_I8;
-  if (halo_choice(a, i8) >= 0)
+  if (stream_choice(a, i8) >= 0)
+    relay::conv_stream_kernel_name(a, i8, stream_choice(a, i8), buf, len);
+  else if (halo_choice(a, i8) >= 0)
     relay::conv_halo_kernel_name(a, i8, halo_choice(a, i8), buf, len);
   else if (relay::igemm_dma_supported(a, i8))
     relay::igemm_dma_kernel_name(a, i8, g_force_tile, buf, len);
@@ -834,6 +858,25 @@ relay_status relay_realize_conv(int32_t k, int64_t per_k, const float* w, const 
                                                   reinterpret_cast<relay::RealizedConv*>(out), folded, cell,
                                                   static_cast<hipStream_t>(hip_stream)),
                        "realize launch");
+}
+
+relay_status relay_probe_mfma(int32_t dtype, int32_t iters, int32_t workgroups, void* out, void* hip_stream) {
+  if (dtype != RELAY_F16 && dtype != RELAY_I8) return fail(RELAY_ERR_DTYPE, "the matrix-instruction probe takes F16 or I8");
+  if (iters < 1 || iters > (1 << 24) || workgroups < 1 || workgroups > (1 << 20))
+    return fail(RELAY_ERR_SHAPE, "iters=%d workgroups=%d outside their ranges", iters, workgroups);
+  if (!out) return fail(RELAY_ERR_NULL, "out is required");
+  if (!aligned(out, 4)) return fail(RELAY_ERR_ALIGN, "out must be 4-byte aligned");
+  return device_status(relay::launch_probe_mfma(dtype == RELAY_I8, iters, workgroups, static_cast<unsigned*>(out),
+                                                static_cast<hipStream_t>(hip_stream)),
+                       "probe launch");
+}
+
+relay_status relay_probe_copy(const void* src, void* dst, int64_t bytes, void* hip_stream) {
+  if (!src || !dst) return fail(RELAY_ERR_NULL, "src and dst are required");
+  if (bytes < 16 || bytes % 16 || bytes > ((int64_t)1 << 40)) return fail(RELAY_ERR_SHAPE, "bytes=%lld must be a multiple of 16 in 16..2^40", (long long)bytes);
+  if (!aligned(src, 16) || !aligned(dst, 16)) return fail(RELAY_ERR_ALIGN, "src and dst must be 16-byte aligned");
+  if (src == dst) return fail(RELAY_ERR_UNSUPPORTED, "output must not alias the input");
+  return device_status(relay::launch_probe_copy(src, dst, bytes, static_cast<hipStream_t>(hip_stream)), "probe launch");
 }
 
 relay_status relay_fuse_extract(int32_t n_ops, const int32_t* pattern, const int32_t* in_offsets,

@@ -58,6 +58,9 @@ struct ConvArgs {
   // that arrives last adds the partials in split order and runs the epilogue, then puts the
   // counter back to zero.  split <= 1: one workgroup per tile, nothing of this is touched.
   int split;
+  // host-side only: upper bound on the workgroups a persistent kernel launches (0: one per workgroup
+  // slot of the chip)
+  int max_wgs;
   unsigned* ws_part;
   unsigned* ws_cnt;
   // seg_centre bit i: segment i is a 1x1 convolution embedded at the centre tap of the R x S window
@@ -103,6 +106,12 @@ int conv_halo_pick(const ConvArgs& a, bool is_i8);  // variant, or -1: leave the
 int conv_halo_variant_count();
 hipError_t launch_conv_halo(const ConvArgs& a, bool is_i8, int variant, hipStream_t st);
 void conv_halo_kernel_name(const ConvArgs& a, bool is_i8, int variant, char* buf, size_t len);
+// The persistent 3x3 / stride 1 / pad 1 kernel whose workgroups stream tile after tile (conv_stream.hip).
+bool conv_stream_supported(const ConvArgs& a, bool is_i8, int variant);
+int conv_stream_pick(const ConvArgs& a, bool is_i8);  // variant, or -1
+int conv_stream_variant_count();
+hipError_t launch_conv_stream(const ConvArgs& a, bool is_i8, int variant, hipStream_t st);
+void conv_stream_kernel_name(const ConvArgs& a, bool is_i8, int variant, char* buf, size_t len);
 hipError_t launch_dwconv_f16(const ConvArgs& a, hipStream_t st);
 hipError_t launch_dense(int m, int n, int k, bool is_f16, const void* x, const void* w, const float* bias,
                         int act, void* y, hipStream_t st);
@@ -143,6 +152,9 @@ hipError_t launch_pow2_range(int esize, long n, const void* x, float* rho, unsig
 hipError_t launch_realize_conv(int K, long per_k, const float* w, const float* bias, const float* scale,
                                const float* shift, float rho_x, float rho_y, float rho_r, int8_t* wq, int32_t* bias_q,
                                RealizedConv* out, float* folded, unsigned* cell, hipStream_t st);
+// measured ceilings (probe.hip): register-only matrix-instruction loop, streaming copy
+hipError_t launch_probe_mfma(bool is_i8, int iters, int workgroups, unsigned* out, hipStream_t st);
+hipError_t launch_probe_copy(const void* src, void* dst, long bytes, hipStream_t st);
 hipError_t launch_pack_filters_rows(const void* w_oihw, void* w_packed, int K, int Csrc, int R, int S, int ck,
                                     int Kp, int esize, hipStream_t st);
 
