@@ -75,6 +75,7 @@ def _layer_table(net, ops, batch, reps, trials):
                 row["mbytes"] = (d.n * d.h * d.w * d.c + d.n * ho * wo * d.c + 9 * d.c) * es / 1e6
             row["tflops"] = row["gflop"] / row["us"] * 1e3           # GFLOP/us = 1000 TFLOP/s
             row["gbs"] = row["mbytes"] / row["us"] * 1e3              # MB/us = 1000 GB/s
+            _bounds(row, d.dtype == B.RELAY_I8, fn is B.relay_fused_dwconv_bias_relu)
         elif fn in (B.relay_fused_conv2d_bn_relu_maxpool, B.relay_qconv2d_requant_maxpool):
             # the conv with its max pool in the same launch: the conv's FLOP, input + pooled output + filters
             ho, wo = B.relay_conv2d_out_shape(d)
@@ -85,15 +86,75 @@ def _layer_table(net, ops, batch, reps, trials):
             row["mbytes"] = (d.n * d.h * d.w * op.cin + d.n * (ho // 2) * (wo // 2) * d.k + d.k * op.cin * d.r * d.s) * es / 1e6
             row["tflops"] = row["gflop"] / row["us"] * 1e3
             row["gbs"] = row["mbytes"] / row["us"] * 1e3
+            _bounds(row, d.dtype == B.RELAY_I8, False)
         rows.append(row)
     return rows
 
 
-KERNEL_SOURCES = ("conv_igemm_dma.hip", "conv_halo.hip", "dma_common.hpp", "igemm_common.hpp", "rounding.hpp", "kernels.hpp",
-                  "fastdiv.hpp")
+def _bounds(row, is_i8, is_dw):
+    """Roofline position of one layer: arithmetic intensity (FLOP per algorithmic byte), the
+    fraction of the matrix-core peak, and the fraction of min(matrix-core peak, intensity x HBM
+    peak), the bound that applies to the layer (a depthwise layer: the HBM peak alone)."""
+    peak = PEAK["i8" if is_i8 else "f16"]
+    row["ai"] = row["gflop"] * 1e3 / row["mbytes"]
+    if is_dw:
+        row["frac_hbm"] = row["gbs"] / HBM_PEAK_GBS
+        row["frac_bound"] = row["frac_hbm"]
+        return
+    bound = min(peak, row["ai"] * HBM_PEAK_GBS / 1e3)          # TFLOP/s
+    row["bound"] = "mfma" if bound == peak else "hbm"
+    row["frac_mfma"] = row["tflops"] / peak
+    row["frac_bound"] = row["tflops"] / bound
 
 
-CONV_KERNELS = ("igemm", "conv3x3_halo")      # name prefixes of the MFMA conv kernels in the per-layer table
+def _measured_ceilings():
+    """The chip's measured ceilings on this machine: the register-only matrix-instruction loop and a
+    streaming copy (library probes), timed with events over back-to-back launches."""
+    import torch
+    from paper_1904_08368_amd import binding as B
+    out = torch.zeros(1, dtype=torch.int32, device="cuda")
+    src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    iters, wgs = 256, 2048
+    res = {}
+    for name, fn, work in (("mfma_f16_tflops", lambda: B.relay_probe_mfma(B.RELAY_F16, iters, wgs, out), 2.0 * 32 * 32 * 16 * 4 * iters * 4 * wgs / 1e12),
+                           ("mfma_i8_tops", lambda: B.relay_probe_mfma(B.RELAY_I8, iters, wgs, out), 2.0 * 32 * 32 * 32 * 4 * iters * 4 * wgs / 1e12),
+                           ("copy_gbs", lambda: B.relay_probe_copy(src, dst, src.numel()), 2.0 * src.numel() / 1e9)):
+        for _ in range(3):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            fn()
+        e1.record()
+        e1.synchronize()
+        res[name] = round(work / (e0.elapsed_time(e1) / 10 * 1e-3), 1)
+    return res
+
+
+def _dominant(rows, peak):
+    """The conv kernel variant with the most time per step among `rows`: (name, roofline dict)."""
+    by_kernel = {}
+    for r in rows:
+        if r.get("kernel", "").startswith(CONV_KERNELS):
+            k = by_kernel.setdefault(r["kernel"], {"us": 0.0, "gflop": 0.0, "launches": 0, "layers": []})
+            k["us"] += r["us"]
+            k["gflop"] += r["gflop"]
+            k["launches"] += 1
+            k["layers"].append(r["name"])
+    name, dom = max(by_kernel.items(), key=lambda kv: kv[1]["us"])
+    achieved = dom["gflop"] / dom["us"] * 1e3
+    return name, {"bound": "mfma", "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s" if peak == PEAK["f16"] else "TOP/s",
+                  "frac": round(achieved / peak, 4), "traffic": None, "kernel": name, "launches_per_step": dom["launches"],
+                  "avg_launch_us": round(dom["us"] / dom["launches"], 2), "gflop_per_launch": round(dom["gflop"] / dom["launches"], 3),
+                  "layers": dom["layers"]}
+
+
+KERNEL_SOURCES = ("conv_igemm_dma.hip", "conv_halo.hip", "dma_common.hpp", "igemm_common.hpp", "lds_dma.hpp", "rounding.hpp",
+                  "kernels.hpp", "fastdiv.hpp")
+
+
+CONV_KERNELS = ("igemm", "conv3x3_halo", "conv3x3_stream")      # name prefixes of the MFMA conv kernels in the per-layer table
 
 
 def _kernel_source_digest():
@@ -188,20 +249,11 @@ def main() -> int:
     value = flop / sec / 1e12
 
     rows = _layer_table(net, ops, a.batch, a.layer_reps, 5)
-    by_kernel = {}
-    for r in rows:
-        if r.get("kernel", "").startswith(CONV_KERNELS):
-            k = by_kernel.setdefault(r["kernel"], {"us": 0.0, "gflop": 0.0, "launches": 0, "layers": []})
-            k["us"] += r["us"]
-            k["gflop"] += r["gflop"]
-            k["launches"] += 1
-            k["layers"].append(r["name"])
-    dom_name, dom = max(by_kernel.items(), key=lambda kv: kv[1]["us"])
-    achieved = dom["gflop"] / dom["us"] * 1e3          # TFLOP/s
-    roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK["f16"], "unit": "TFLOP/s",
-                "frac": round(achieved / PEAK["f16"], 4), "traffic": _hbm_traffic(dom_name), "kernel": dom_name,
-                "launches_per_step": dom["launches"], "avg_launch_us": round(dom["us"] / dom["launches"], 2),
-                "gflop_per_launch": round(dom["gflop"] / dom["launches"], 3), "layers": dom["layers"]}
+    dom_name, roofline = _dominant(rows, PEAK["f16"])
+    roofline["traffic"] = _hbm_traffic(dom_name)
+    ceil = _measured_ceilings()
+    roofline["measured_peak"] = ceil["mfma_f16_tflops"]          # register-only matrix-instruction loop on this machine
+    roofline["frac_of_measured_peak"] = round(roofline["achieved"] / ceil["mfma_f16_tflops"], 4)
     conv_us = sum(r["us"] for r in rows if r.get("kernel", "").startswith(CONV_KERNELS))
     conv_gf = sum(r["gflop"] for r in rows if r.get("kernel", "").startswith(CONV_KERNELS))
 
@@ -215,7 +267,8 @@ def main() -> int:
         "ms_per_img": round(sec * 1e3 / a.batch, 5),
         "roofline": roofline,
     }
-    extra = {"fusion_extraction": {"operators": len(graph.nodes), "groups": len(groups),
+    extra = {"measured_ceilings": ceil,
+             "fusion_extraction": {"operators": len(graph.nodes), "groups": len(groups),
                                    "host_us_per_call_incl_marshalling": round(fuse_us, 1)},
              "conv_kernels_only_tflops": round(conv_gf / conv_us * 1e3, 2),
              "sum_of_kernel_us": round(sum(r["us"] for r in rows), 1),
@@ -251,7 +304,11 @@ def main() -> int:
         qrows = _layer_table(qn, qops, 16, a.layer_reps, 3)
         qus = sum(r["us"] for r in qrows if "gflop" in r)
         qgf = sum(r["gflop"] for r in qrows if "gflop" in r)
+        _, qroof = _dominant(qrows, PEAK["i8"])
+        qroof["measured_peak"] = ceil["mfma_i8_tops"]
+        qroof["frac_of_measured_peak"] = round(qroof["achieved"] / ceil["mfma_i8_tops"], 4)
         extra["resnet18_int8_batch16"] = {
+            "roofline": qroof,
             "tops": round(2.0 * nets.macs_per_image(qops, 224, 224) * 16 / qsec / 1e12, 3),
             "ms_per_img": round(qsec * 1e3 / 16, 5), "conv_kernels_only_tops": round(qgf / qus * 1e3, 2),
             "frac_of_int8_mfma_peak": round(qgf / qus * 1e3 / PEAK["i8"], 4),
@@ -273,6 +330,7 @@ def main() -> int:
             "ms_per_img": round(msec * 1e3 / 32, 5),
             "tflops": round(2.0 * nets.macs_per_image(mops, 224, 224) * 32 / msec / 1e12, 3),
             "depthwise_gbs": round(dw_gbs, 1), "depthwise_frac_of_hbm_peak": round(dw_gbs / HBM_PEAK_GBS, 4),
+            "depthwise_frac_of_measured_copy": round(dw_gbs / ceil["copy_gbs"], 4),
             "pointwise_tflops": round(sum(r["gflop"] for r in pw) / sum(r["us"] for r in pw) * 1e3, 2),
             "layers": [{k: (round(v, 3) if isinstance(v, float) else v) for k, v in r.items()} for r in mrows]}
         del mn

@@ -127,7 +127,7 @@ def main() -> int:
 
     # ---- measured ceilings
     out = torch.zeros(1, dtype=torch.int32, device=dev)
-    iters, wgs = 4096, 256 * 8
+    iters, wgs = 256, 256 * 8      # ~0.1 ms per launch: long enough to fill the chip, short enough for 32-bit counters
     run("ceiling_mfma_f16", "mfma_loop_kernel<false>", lambda: B.relay_probe_mfma(B.RELAY_F16, iters, wgs, out),
         2.0 * 32 * 32 * 16 * 4 * iters * 4 * wgs / 1e9, 0.0)
     run("ceiling_mfma_i8", "mfma_loop_kernel<true>", lambda: B.relay_probe_mfma(B.RELAY_I8, iters, wgs, out),
