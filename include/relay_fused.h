@@ -41,7 +41,7 @@ typedef enum {
   RELAY_ERR_DEVICE = 7       /* the HIP runtime refused the launch */
 } relay_status;
 
-typedef enum { RELAY_F32 = 0, RELAY_F16 = 1, RELAY_I8 = 2 } relay_dtype;
+typedef enum { RELAY_F32 = 0, RELAY_F16 = 1, RELAY_I8 = 2, RELAY_I16 = 3 /* the 16/32 scheme only */ } relay_dtype;
 /* RELAY_NHWC4_PADDED: input of a first-layer conv with c <= 4 channels, stored [n][h + 2*pad_h]
  * [wp][4] with the zero border, wp - w - 2*pad_w slack columns and channels c..3 all zero
  * (relay_pack_input_nhwc4 writes it from NCHW; relay_nhwc4_padded_shape gives hp, wp).  The
@@ -157,6 +157,55 @@ relay_status relay_qconv2d_requant_rounding(const relay_conv2d_desc* d, const in
                                             const int32_t* bias, const int8_t* residual, int32_t residual_lshift,
                                             int32_t out_rshift, int32_t round_mode, uint64_t seed, int8_t* y,
                                             void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Further quantization schemes (paper Section 4.2: a scheme chooses its integer types, signed or
+ * unsigned, and the realized operator scales by "multiplication and rounding"; the accuracy table of
+ * Section 5.4 lists m/n = 8/16 and 16/32 -- m-bit multiplies accumulated in n bits -- beside 8/32).
+ * Each is relay_qconv2d_requant with another tail or other operand types; operands, alignment,
+ * workspace and errors as there unless said otherwise.  This library's readings of what the paper
+ * leaves open are stated with each call.
+ *
+ * relay_qconv2d_requant_scaled: a general (not power-of-two) scale per output channel,
+ *     q = floor(acc * mult[k] / 2^(31 + rshift[k]) + 1/2)          (ties toward +infinity)
+ *   mult, rshift: device int32 [k], 0 < mult[k] < 2^31, 0 <= rshift[k] <= 31 (not checked on the
+ *   device; relay_quantize_multiplier produces such pairs).  The product is formed in 64 bits.
+ * relay_quantize_multiplier: host helper, scale = mult / 2^31 * 2^-rshift with 2^30 <= mult < 2^31,
+ *   mult rounded to nearest; 2^-32 < scale < 1, else RELAY_ERR_SHAPE.  mult, rshift: host pointers.
+ * relay_qconv2d_requant_acc16: the 8/16 scheme.  The matrix cores accumulate in 32 bits; the scheme's
+ *   16-bit accumulator is the exact sum (bias and residual included) saturated to [-32768, 32767]
+ *   before the rounding shift -- equal to a 16-bit accumulation whenever that does not overflow,
+ *   which is the scheme's precondition, and defined beyond it.
+ * relay_qconv2d_requant_i16: the 16/32 scheme.  d->dtype == RELAY_I16, NHWC, c % 8 == 0, k % 4 == 0;
+ *   x, y int16 [n,h,w,c] / [n,ho,wo,k]; w_packed from relay_prepack_conv2d_weights with the same
+ *   descriptor; tail [+bias] -> round(acc / 2^out_rshift) -> clip +-32767 -> [relu].  Precondition:
+ *   the sums fit int32 (they wrap otherwise).  Runs on the vector ALUs (no 16-bit integer matrix form).
+ * relay_qconv2d_requant_u8: unsigned 8-bit activations (codes 0..255, zero padding = code 0) with
+ *   signed 8-bit filters on the signed matrix cores: the activations are re-coded (x - 128) into a
+ *   physically padded signed copy in `workspace` whose border holds -128, and the constant
+ *   128 * sum(w[k]) is part of the bias.  d: the I8 NHWC descriptor of the convolution with
+ *   RELAY_HAS_BIAS set and no residual, c % 16 == 0; bias_zp [k] = relay_fold_zero_point(w, bias, 128);
+ *   out_unsigned 1: y holds uint8 codes clipped to [0, 255] (which contains the relu), 0: int8 codes
+ *   clipped to +-127 [and relu].  workspace: device, 16-byte aligned, at least
+ *   relay_qconv2d_u8_workspace_bytes(d), else RELAY_ERR_WORKSPACE.  Two launches.
+ * relay_fold_zero_point: out[k] = bias[k] (NULL: 0) + zero_point * sum_i w[k][i] over the OIHW int8
+ *   filters (per_k = c*r*s), exact; device pointers; compile-time work. */
+relay_status relay_qconv2d_requant_scaled(const relay_conv2d_desc* d, const int8_t* x, const int8_t* w_packed,
+                                          const int32_t* bias, const int8_t* residual, int32_t residual_lshift,
+                                          const int32_t* mult, const int32_t* rshift, int8_t* y, void* workspace,
+                                          size_t workspace_bytes, void* hip_stream);
+relay_status relay_quantize_multiplier(double scale, int32_t* mult, int32_t* rshift);
+relay_status relay_qconv2d_requant_acc16(const relay_conv2d_desc* d, const int8_t* x, const int8_t* w_packed,
+                                         const int32_t* bias, const int8_t* residual, int32_t residual_lshift,
+                                         int32_t out_rshift, int8_t* y, void* workspace, size_t workspace_bytes,
+                                         void* hip_stream);
+relay_status relay_qconv2d_requant_i16(const relay_conv2d_desc* d, const int16_t* x, const int16_t* w_packed,
+                                       const int32_t* bias, int32_t out_rshift, int16_t* y, void* hip_stream);
+relay_status relay_qconv2d_u8_workspace_bytes(const relay_conv2d_desc* d, size_t* bytes);
+relay_status relay_fold_zero_point(int32_t k, int64_t per_k, const int8_t* w, const int32_t* bias, int32_t zero_point,
+                                   int32_t* out, void* hip_stream);
+relay_status relay_qconv2d_requant_u8(const relay_conv2d_desc* d, const uint8_t* x, const int8_t* w_packed,
+                                      const int32_t* bias_zp, int32_t out_rshift, int32_t out_unsigned, void* y,
+                                      void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* The quantization operators themselves (paper Section 4.2), elementwise over n_elems values:
  *   code = clip(round(x / rho * 2^(beta - sigma)), qtype)

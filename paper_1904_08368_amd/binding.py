@@ -14,7 +14,7 @@ from typing import Sequence, Optional, Tuple
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "librelayfused.so")
 
-RELAY_F32, RELAY_F16, RELAY_I8 = 0, 1, 2
+RELAY_F32, RELAY_F16, RELAY_I8, RELAY_I16 = 0, 1, 2, 3
 RELAY_NCHW, RELAY_NHWC, RELAY_NHWC4_PADDED = 0, 1, 2
 HAS_BIAS, HAS_BN, HAS_RESIDUAL, RELU = 1, 2, 4, 8
 
@@ -47,6 +47,13 @@ SIGNATURES = {
     "relay_fused_conv2d_bias_bn_relu": [_DP, _P, _P, _P, _P, _P, _P, _P, _P, _SZ, _P],
     "relay_fused_conv2d_bias_bn_relu_static": [_DP, _P, _P, _P, _P, _P, _P, _P, _P],
     "relay_qconv2d_requant": [_DP, _P, _P, _P, _P, _I, _I, _P, _P, _SZ, _P],
+    "relay_qconv2d_requant_scaled": [_DP, _P, _P, _P, _P, _I, _P, _P, _P, _P, _SZ, _P],
+    "relay_quantize_multiplier": [C.c_double, C.POINTER(_I), C.POINTER(_I)],
+    "relay_qconv2d_requant_acc16": [_DP, _P, _P, _P, _P, _I, _I, _P, _P, _SZ, _P],
+    "relay_qconv2d_requant_i16": [_DP, _P, _P, _P, _I, _P, _P],
+    "relay_qconv2d_u8_workspace_bytes": [_DP, C.POINTER(_SZ)],
+    "relay_fold_zero_point": [_I, C.c_int64, _P, _P, _I, _P, _P],
+    "relay_qconv2d_requant_u8": [_DP, _P, _P, _P, _I, _I, _P, _P, _SZ, _P],
     "relay_prepack_dwconv_weights": [_DP, _P, _P, _P],
     "relay_fused_dwconv_bias_relu": [_DP, _P, _P, _P, _P, _P, _P, _P],
     "relay_fused_dense_bias_act": [_I, _I, _I, _I, _P, _P, _P, _I, _P, _P],
@@ -231,6 +238,45 @@ def relay_qconv2d_requant_rounding(d: ConvDesc, x, w_packed, bias, residual, res
     _check(lib().relay_qconv2d_requant_rounding(C.byref(d), _ptr(x), _ptr(w_packed), _ptr(bias), _ptr(residual),
                                                 residual_lshift, out_rshift, round_mode, seed, _ptr(y), _ptr(workspace),
                                                 ws_bytes, _stream()))
+
+
+def relay_qconv2d_requant_scaled(d: ConvDesc, x, w_packed, bias, residual, residual_lshift: int, mult, rshift, y,
+                                 workspace=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().relay_qconv2d_requant_scaled(C.byref(d), _ptr(x), _ptr(w_packed), _ptr(bias), _ptr(residual), residual_lshift,
+                                              _ptr(mult), _ptr(rshift), _ptr(y), _ptr(workspace), ws_bytes, _stream()))
+
+
+def relay_quantize_multiplier(scale: float) -> Tuple[int, int]:
+    m, s = _I(), _I()
+    _check(lib().relay_quantize_multiplier(scale, C.byref(m), C.byref(s)))
+    return m.value, s.value
+
+
+def relay_qconv2d_requant_acc16(d: ConvDesc, x, w_packed, bias, residual, residual_lshift: int, out_rshift: int, y,
+                                workspace=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().relay_qconv2d_requant_acc16(C.byref(d), _ptr(x), _ptr(w_packed), _ptr(bias), _ptr(residual), residual_lshift,
+                                             out_rshift, _ptr(y), _ptr(workspace), ws_bytes, _stream()))
+
+
+def relay_qconv2d_requant_i16(d: ConvDesc, x, w_packed, bias, out_rshift: int, y) -> None:
+    _check(lib().relay_qconv2d_requant_i16(C.byref(d), _ptr(x), _ptr(w_packed), _ptr(bias), out_rshift, _ptr(y), _stream()))
+
+
+def relay_qconv2d_u8_workspace_bytes(d: ConvDesc) -> int:
+    b = _SZ()
+    _check(lib().relay_qconv2d_u8_workspace_bytes(C.byref(d), C.byref(b)))
+    return b.value
+
+
+def relay_fold_zero_point(k: int, per_k: int, w, bias, zero_point: int, out) -> None:
+    _check(lib().relay_fold_zero_point(k, per_k, _ptr(w), _ptr(bias), zero_point, _ptr(out), _stream()))
+
+
+def relay_qconv2d_requant_u8(d: ConvDesc, x, w_packed, bias_zp, out_rshift: int, out_unsigned: bool, y, workspace) -> None:
+    _check(lib().relay_qconv2d_requant_u8(C.byref(d), _ptr(x), _ptr(w_packed), _ptr(bias_zp), out_rshift, 1 if out_unsigned else 0,
+                                          _ptr(y), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
 
 
 def relay_quantize(n_elems: int, src_dtype: int, x, rho: float, beta: int, sigma: int, round_mode: int, seed: int, y) -> None:

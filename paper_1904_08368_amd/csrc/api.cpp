@@ -2,6 +2,7 @@
 // Every check runs before the first HIP call, so the error paths are testable on a
 // machine without a GPU.
 #include <atomic>
+#include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -23,7 +24,7 @@ relay_status fail(relay_status st, const char* fmt, ...) {
   return st;
 }
 
-int esize_of(int dtype) { return dtype == RELAY_F32 ? 4 : dtype == RELAY_F16 ? 2 : dtype == RELAY_I8 ? 1 : 0; }
+int esize_of(int dtype) { return dtype == RELAY_F32 ? 4 : (dtype == RELAY_F16 || dtype == RELAY_I16) ? 2 : dtype == RELAY_I8 ? 1 : 0; }
 
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
@@ -94,6 +95,8 @@ relay::ConvArgs make_args(const relay_conv2d_desc* d, int ho, int wo) {
     a.xs_h = d->w * d->c;
     a.xs_n = d->h * d->w * d->c;
   }
+  a.clip_lo = -127;
+  a.clip_hi = 127;
   a.Kred = a.R * a.S * a.C;
   a.Kp = relay::packed_pitch(a.Kred, esize_of(d->dtype));
   a.fd_wo = relay::make_fastdiv((uint32_t)wo);
@@ -569,10 +572,138 @@ relay_status relay_qconv2d_requant(const relay_conv2d_desc* d, const int8_t* x, 
                                         RELAY_ROUND_NEAREST, 0, y, workspace, workspace_bytes, hip_stream);
 }
 
+// The quantized conv behind all of its entry points: the scaling rule of the tail (qmode, with its
+// per-channel operands) and the bounds of the code type are the only things they differ in.
+static relay_status qconv_common(const relay_conv2d_desc* d, const int8_t* x, const int8_t* w_packed, const int32_t* bias,
+                                 const int8_t* residual, int32_t residual_lshift, int32_t out_rshift, int32_t round_mode,
+                                 uint64_t seed, int qmode, const int32_t* qmult, const int32_t* qshift, int clip_lo,
+                                 int clip_hi, void* y, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 relay_status relay_qconv2d_requant_rounding(const relay_conv2d_desc* d, const int8_t* x, const int8_t* w_packed,
                                             const int32_t* bias, const int8_t* residual, int32_t residual_lshift,
                                             int32_t out_rshift, int32_t round_mode, uint64_t seed, int8_t* y,
                                             void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return qconv_common(d, x, w_packed, bias, residual, residual_lshift, out_rshift, round_mode, seed, relay::QMODE_SHIFT, nullptr,
+                      nullptr, -127, 127, y, workspace, workspace_bytes, hip_stream);
+}
+
+relay_status relay_qconv2d_requant_scaled(const relay_conv2d_desc* d, const int8_t* x, const int8_t* w_packed,
+                                          const int32_t* bias, const int8_t* residual, int32_t residual_lshift,
+                                          const int32_t* mult, const int32_t* rshift, int8_t* y, void* workspace,
+                                          size_t workspace_bytes, void* hip_stream) {
+  if (!mult || !rshift) return fail(RELAY_ERR_NULL, "mult and rshift are required");
+  if (!aligned(mult, 4) || !aligned(rshift, 4)) return fail(RELAY_ERR_ALIGN, "mult and rshift must be 4-byte aligned");
+  return qconv_common(d, x, w_packed, bias, residual, residual_lshift, 0, RELAY_ROUND_NEAREST, 0, relay::QMODE_SCALED, mult, rshift,
+                      -127, 127, y, workspace, workspace_bytes, hip_stream);
+}
+
+relay_status relay_qconv2d_requant_acc16(const relay_conv2d_desc* d, const int8_t* x, const int8_t* w_packed,
+                                         const int32_t* bias, const int8_t* residual, int32_t residual_lshift,
+                                         int32_t out_rshift, int8_t* y, void* workspace, size_t workspace_bytes,
+                                         void* hip_stream) {
+  return qconv_common(d, x, w_packed, bias, residual, residual_lshift, out_rshift, RELAY_ROUND_NEAREST, 0, relay::QMODE_ACC16,
+                      nullptr, nullptr, -127, 127, y, workspace, workspace_bytes, hip_stream);
+}
+
+relay_status relay_fold_zero_point(int32_t k, int64_t per_k, const int8_t* w, const int32_t* bias, int32_t zero_point,
+                                   int32_t* out, void* hip_stream) {
+  if (k <= 0 || per_k <= 0 || (long)k * per_k > kMaxElems) return fail(RELAY_ERR_SHAPE, "bad filter extent (k=%d per_k=%lld)", k, (long long)per_k);
+  if (!w || !out) return fail(RELAY_ERR_NULL, "w and out are required");
+  if (zero_point < -255 || zero_point > 255) return fail(RELAY_ERR_UNSUPPORTED, "zero_point=%d outside -255..255", zero_point);
+  if (!aligned(bias, 4) || !aligned(out, 4)) return fail(RELAY_ERR_ALIGN, "bias and out must be 4-byte aligned");
+  return device_status(relay::launch_fold_zero_point(k, per_k, w, bias, zero_point, out, static_cast<hipStream_t>(hip_stream)),
+                       "zero-point folding");
+}
+
+relay_status relay_qconv2d_u8_workspace_bytes(const relay_conv2d_desc* d, size_t* bytes) {
+  if (!bytes) return fail(RELAY_ERR_NULL, "bytes is NULL");
+  int ho, wo;
+  relay_status st = check_geometry(d, &ho, &wo);
+  if (st != RELAY_OK) return st;
+  if (d->dtype != RELAY_I8 || d->layout != RELAY_NHWC) return fail(RELAY_ERR_DTYPE, "unsigned activations take an I8 NHWC descriptor");
+  *bytes = (size_t)d->n * (d->h + 2 * d->pad_h) * (d->w + 2 * d->pad_w) * d->c;
+  return RELAY_OK;
+}
+
+relay_status relay_qconv2d_requant_u8(const relay_conv2d_desc* d, const uint8_t* x, const int8_t* w_packed,
+                                      const int32_t* bias_zp, int32_t out_rshift, int32_t out_unsigned, void* y,
+                                      void* workspace, size_t workspace_bytes, void* hip_stream) {
+  size_t need = 0;
+  relay_status st = relay_qconv2d_u8_workspace_bytes(d, &need);
+  if (st != RELAY_OK) return st;
+  if (d->flags & RELAY_HAS_RESIDUAL) return fail(RELAY_ERR_UNSUPPORTED, "the unsigned-activation conv2d has no residual operand");
+  if (!(d->flags & RELAY_HAS_BIAS)) return fail(RELAY_ERR_NULL, "bias_zp (bias + 128 * sum of the filters) is required: set RELAY_HAS_BIAS");
+  if (out_unsigned != 0 && out_unsigned != 1) return fail(RELAY_ERR_UNSUPPORTED, "out_unsigned must be 0 or 1");
+  if (!x || !workspace) return fail(RELAY_ERR_NULL, "x and workspace are required");
+  if (d->c % 16) return fail(RELAY_ERR_ALIGN, "c=%d must be a multiple of 16 (pad the channel axis)", d->c);
+  if (!aligned(x, 16) || !aligned(workspace, 16)) return fail(RELAY_ERR_ALIGN, "x and workspace must be 16-byte aligned");
+  if (workspace_bytes < need) return fail(RELAY_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+  if (need > 0x7fffffffu) return fail(RELAY_ERR_SHAPE, "padded input exceeds 2^31-1 bytes");
+  // the signed conv over the physically padded copy: same filters, no padding left
+  relay_conv2d_desc d2 = *d;
+  d2.h = d->h + 2 * d->pad_h;
+  d2.w = d->w + 2 * d->pad_w;
+  d2.pad_h = d2.pad_w = 0;
+  // validate the conv call before anything is launched (the checks touch no pointer)
+  if (!w_packed || !y || !bias_zp) return fail(RELAY_ERR_NULL, "w_packed, bias_zp and y are required");
+  if (out_rshift < 0 || out_rshift > 31) return fail(RELAY_ERR_UNSUPPORTED, "out_rshift=%d outside 0..31", out_rshift);
+  if (!aligned(w_packed, 16) || !aligned(y, 8) || !aligned(bias_zp, 4))
+    return fail(RELAY_ERR_ALIGN, "w_packed must be 16-byte, y 8-byte, bias_zp 4-byte aligned");
+  if (y == (const void*)x || y == workspace) return fail(RELAY_ERR_UNSUPPORTED, "output must not alias an input");
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  st = device_status(relay::launch_recode_u8_padded(x, workspace, d->n, d->h, d->w, d->c, d->pad_h, d->pad_w, s), "activation re-coding");
+  if (st != RELAY_OK) return st;
+  return qconv_common(&d2, static_cast<const int8_t*>(workspace), w_packed, bias_zp, nullptr, 0, out_rshift, RELAY_ROUND_NEAREST, 0,
+                      relay::QMODE_SHIFT, nullptr, nullptr, out_unsigned ? 0 : -127, out_unsigned ? 255 : 127, y, nullptr, 0, hip_stream);
+}
+
+relay_status relay_qconv2d_requant_i16(const relay_conv2d_desc* d, const int16_t* x, const int16_t* w_packed,
+                                       const int32_t* bias, int32_t out_rshift, int16_t* y, void* hip_stream) {
+  int ho, wo;
+  relay_status st = check_geometry(d, &ho, &wo);
+  if (st != RELAY_OK) return st;
+  if (d->dtype != RELAY_I16) return fail(RELAY_ERR_DTYPE, "the 16/32 conv2d takes I16");
+  if (d->layout != RELAY_NHWC) return fail(RELAY_ERR_UNSUPPORTED, "the 16/32 conv2d needs NHWC activations");
+  if (d->flags & (RELAY_HAS_BN | RELAY_HAS_RESIDUAL)) return fail(RELAY_ERR_UNSUPPORTED, "the 16/32 conv2d takes a bias and relu only");
+  if (d->c % 8 || d->k % 4) return fail(RELAY_ERR_ALIGN, "c=%d must be a multiple of 8 and k=%d of 4", d->c, d->k);
+  if (!x || !w_packed || !y) return fail(RELAY_ERR_NULL, "x, w_packed and y are required");
+  if ((st = check_optional(bias, d->flags & RELAY_HAS_BIAS, "bias")) != RELAY_OK) return st;
+  if (out_rshift < 0 || out_rshift > 31) return fail(RELAY_ERR_UNSUPPORTED, "out_rshift=%d outside 0..31", out_rshift);
+  if (!aligned(x, 16) || !aligned(w_packed, 16) || !aligned(y, 8) || !aligned(bias, 4))
+    return fail(RELAY_ERR_ALIGN, "x / w_packed must be 16-byte aligned, y 8-byte, bias 4-byte");
+  if ((const void*)y == (const void*)x) return fail(RELAY_ERR_UNSUPPORTED, "output must not alias an input");
+  relay::ConvArgs a = make_args(d, ho, wo);
+  a.x = x; a.w = w_packed; a.y = y; a.qbias = bias;
+  a.rshift = out_rshift;
+  a.round_add = out_rshift == 0 ? 0 : 1 << (out_rshift - 1);
+  return device_status(relay::launch_qconv16_direct(a, static_cast<hipStream_t>(hip_stream)), "16/32 conv2d launch");
+}
+
+relay_status relay_quantize_multiplier(double scale, int32_t* mult, int32_t* rshift) {
+  if (!mult || !rshift) return fail(RELAY_ERR_NULL, "mult and rshift are required");
+  if (!(scale > 0.0) || !(scale < 1.0)) return fail(RELAY_ERR_SHAPE, "scale must lie in (2^-32, 1)");
+  int e = 0;
+  const double m = frexp(scale, &e);   // scale = m * 2^e, 0.5 <= m < 1
+  long long M = (long long)floor(ldexp(m, 31) + 0.5);
+  if (M == (1ll << 31)) {              // m rounded up to 1
+    M = 1ll << 30;
+    ++e;
+  }
+  int s = -e;
+  if (s == -1) {                       // so close to 1 that M rounded up to 2^31: the largest representable scale
+    M = (1ll << 31) - 1;
+    s = 0;
+  }
+  if (s < 0 || s > 31) return fail(RELAY_ERR_SHAPE, "scale must lie in (2^-32, 1)");
+  *mult = (int32_t)M;
+  *rshift = s;
+  return RELAY_OK;
+}
+
+static relay_status qconv_common(const relay_conv2d_desc* d, const int8_t* x, const int8_t* w_packed, const int32_t* bias,
+                                 const int8_t* residual, int32_t residual_lshift, int32_t out_rshift, int32_t round_mode,
+                                 uint64_t seed, int qmode, const int32_t* qmult, const int32_t* qshift, int clip_lo,
+                                 int clip_hi, void* y, void* workspace, size_t workspace_bytes, void* hip_stream) {
   int ho, wo;
   relay_status st = check_geometry(d, &ho, &wo);
   if (st != RELAY_OK) return st;
@@ -598,6 +729,7 @@ relay_status relay_qconv2d_requant_rounding(const relay_conv2d_desc* d, const in
   a.round_add = out_rshift == 0 ? 0
                 : round_mode == RELAY_ROUND_NEAREST ? 1 << (out_rshift - 1)
                 : round_mode == RELAY_ROUND_CEIL ? (int)((1u << out_rshift) - 1u) : 0;
+  a.qmode = qmode; a.qmult = qmult; a.qshift = qshift; a.clip_lo = clip_lo; a.clip_hi = clip_hi;
   finish_args(a);
   if ((st = use_workspace(a, true, workspace, workspace_bytes)) != RELAY_OK) return st;
   return device_status(launch_igemm(a, true, static_cast<hipStream_t>(hip_stream)), "qconv2d launch");

@@ -467,7 +467,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
               int q = shift_round(acc[tn][tm][4 * g + e] + __builtin_bit_cast(int, m4[e]), (unsigned)a.round_add, a.rshift);
-              q = q < -127 ? -127 : (q > 127 ? 127 : q);
+              q = q < a.clip_lo ? a.clip_lo : (q > a.clip_hi ? a.clip_hi : q);
               if (a.flags & F_RELU) q = q > 0 ? q : 0;
               pk |= (unsigned)(q & 0xff) << (8 * e);
             }

@@ -290,7 +290,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, WGS) void conv3x3_stream_ke
             for (int e = 0; e < 4; ++e) {
               int t = acc[tn][tm][4 * q4 + e] + ib[e] + (int)(int8_t)(rv >> (8 * e)) * (1 << a.lshift);
               int q = shift_round(t, (unsigned)a.round_add, a.rshift);
-              q = q < -127 ? -127 : (q > 127 ? 127 : q);
+              q = q < a.clip_lo ? a.clip_lo : (q > a.clip_hi ? a.clip_hi : q);
               if (a.flags & F_RELU) q = q > 0 ? q : 0;
               pk |= (unsigned)(q & 0xff) << (8 * e);
             }
@@ -514,6 +514,7 @@ bool conv_stream_supported(const ConvArgs& a, bool is_i8, int v) {
   if (a.R != 3 || a.S != 3 || a.sh != 1 || a.sw != 1 || a.ph != 1 || a.pw != 1) return false;
   if (a.xs_w != a.C || a.xs_h != a.W * a.C || a.xs_n != a.H * a.W * a.C) return false;
   if (a.C % (BKV * ve) != 0 || (a.K & 7) != 0 || a.round_mode == ROUND_STOCHASTIC || a.nseg || a.split > 1 || a.pool) return false;
+  if (a.qmode != QMODE_SHIFT) return false;   // the other scaling rules of the quantized tail live in the one-tile kernels
   if ((size_t)a.N * a.xs_n * es > 0x7fffffffu || (size_t)a.K * a.Kp * es > 0x7fffffffu || (size_t)a.M * a.K * es > 0x7fffffffu)
     return false;
   StreamGeom g;

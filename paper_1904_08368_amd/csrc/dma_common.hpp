@@ -219,12 +219,26 @@ __device__ __forceinline__ void finish_store8(const ConvArgs& a, const unsigned 
     }
     unsigned pk[2] = {0u, 0u};
     WordStream rng{a.seed_lo, a.seed_hi};
+    // The other scaling rules of the quantized tail, behind one uniform branch and with their
+    // per-channel operands fetched here, behind the main loop, so that the default path holds
+    // nothing for them in registers.
+    int qm[8], qs[8];
+    const bool scaled = !STOCH && a.qmode == QMODE_SCALED;
+    if (scaled) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int c = ech + e < a.K ? ech + e : a.K - 1;
+        qm[e] = a.qmult[c];
+        qs[e] = a.qshift[c];
+      }
+    }
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       int q;
       if constexpr (STOCH) q = requant_shift(t[e], a.rshift, ROUND_STOCHASTIC, rng, o + e);
-      else q = shift_round(t[e], (unsigned)a.round_add, a.rshift);  // arithmetic shift: floor
-      q = q < -127 ? -127 : (q > 127 ? 127 : q);
+      else if (scaled) q = scale_round(t[e], qm[e], qs[e]);
+      else q = shift_round(a.qmode == QMODE_ACC16 ? saturate16(t[e]) : t[e], (unsigned)a.round_add, a.rshift);  // arithmetic shift: floor
+      q = q < a.clip_lo ? a.clip_lo : (q > a.clip_hi ? a.clip_hi : q);
       if (relu) q = q > 0 ? q : 0;
       t[e] = q;
       pk[e >> 2] |= (unsigned)(q & 0xff) << (8 * (e & 3));

@@ -123,8 +123,13 @@ __device__ __forceinline__ void epilogue_store4(const ConvArgs& a, const S (&v)[
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       int t = v[e] + p.ibias[e] + rs[e] * (1 << a.lshift);
-      t = requant_shift(t, a.rshift, a.round_mode, rng, o + e);
-      t = t < -127 ? -127 : (t > 127 ? 127 : t);
+      if (a.qmode == QMODE_SCALED) {
+        const int c = ch + e < a.K ? ch + e : a.K - 1;
+        t = scale_round(t, a.qmult[c], a.qshift[c]);
+      } else {
+        t = requant_shift(a.qmode == QMODE_ACC16 ? saturate16(t) : t, a.rshift, a.round_mode, rng, o + e);
+      }
+      t = t < a.clip_lo ? a.clip_lo : (t > a.clip_hi ? a.clip_hi : t);
       if (a.flags & F_RELU) t = t > 0 ? t : 0;
       q[e] = t;
     }

@@ -11,6 +11,11 @@ namespace relay {
 
 enum : unsigned { F_BIAS = 1, F_BN = 2, F_RES = 4, F_RELU = 8 };
 enum : int { ROUND_NEAREST = 0, ROUND_FLOOR = 1, ROUND_CEIL = 2, ROUND_STOCHASTIC = 3 };
+// how the quantized epilogue scales the accumulator (paper Section 4.2: a scheme chooses its scaling)
+//   QMODE_SHIFT   q = round(acc / 2^rshift)                                 (power-of-two scales)
+//   QMODE_SCALED  q = round(acc * qmult[k] / 2^(31 + qshift[k])), ties up    (any scale, per output channel)
+//   QMODE_ACC16   the accumulator is saturated to int16 first, then QMODE_SHIFT (16-bit accumulation scheme)
+enum : int { QMODE_SHIFT = 0, QMODE_SCALED = 1, QMODE_ACC16 = 2 };
 
 // Geometry and operands of one conv-like primitive function.
 struct ConvArgs {
@@ -40,6 +45,10 @@ struct ConvArgs {
   int lshift, rshift;
   int round_mode;          // ROUND_* rule of the requantization acc / 2^rshift
   int round_add;           // what the deterministic rules add before the shift (0 when rshift == 0)
+  int qmode;               // QMODE_* of the quantized epilogue
+  int clip_lo, clip_hi;    // bounds of the code type: -127 .. 127 (signed), 0 .. 255 (unsigned)
+  const int32_t* qmult;    // QMODE_SCALED: per-channel multiplier [K] and shift [K]
+  const int32_t* qshift;
   unsigned seed_lo, seed_hi;  // key of the stochastic rounding draws
   unsigned flags;
   // Output channel segments (parallel convolution combination and concatenation views, paper
@@ -152,6 +161,11 @@ hipError_t launch_pow2_range(int esize, long n, const void* x, float* rho, unsig
 hipError_t launch_realize_conv(int K, long per_k, const float* w, const float* bias, const float* scale,
                                const float* shift, float rho_x, float rho_y, float rho_r, int8_t* wq, int32_t* bias_q,
                                RealizedConv* out, float* folded, unsigned* cell, hipStream_t st);
+// further quantization schemes (qschemes.hip): unsigned activations re-coded into a padded signed tensor,
+// the zero-point term of the bias, the 16/32 direct convolution
+hipError_t launch_recode_u8_padded(const void* x, void* y, int N, int H, int W, int C, int ph, int pw, hipStream_t st);
+hipError_t launch_fold_zero_point(int K, long per_k, const int8_t* w, const int32_t* bias, int zero_point, int32_t* out, hipStream_t st);
+hipError_t launch_qconv16_direct(const ConvArgs& a, hipStream_t st);
 // measured ceilings (probe.hip): register-only matrix-instruction loop, streaming copy
 hipError_t launch_probe_mfma(bool is_i8, int iters, int workgroups, unsigned* out, hipStream_t st);
 hipError_t launch_probe_copy(const void* src, void* dst, long bytes, hipStream_t st);

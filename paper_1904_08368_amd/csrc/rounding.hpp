@@ -53,6 +53,17 @@ __device__ __forceinline__ int shift_round(int acc, unsigned addend, int s) {
   return (acc >> s) + (int)((((unsigned)acc & mask) + addend) >> s);
 }
 
+// round(acc * mult / 2^(31 + s)), ties toward +infinity: the requantization by a general scale
+// mult / 2^31 * 2^-s (0 < mult < 2^31, 0 <= s <= 31).  |acc * mult| < 2^62 and the rounding addend
+// is at most 2^61, so the 64-bit sum cannot overflow.
+__device__ __forceinline__ int scale_round(int acc, int mult, int s) {
+  const long long p = (long long)acc * (long long)mult + (1ll << (30 + s));
+  return (int)(p >> (31 + s));
+}
+
+// the exact sum as a 16-bit accumulator holds it: saturated
+__device__ __forceinline__ int saturate16(int acc) { return acc < -32768 ? -32768 : (acc > 32767 ? 32767 : acc); }
+
 // acc / 2^s rounded by `mode` (arithmetic shift = floor division): what is added before the shift.
 __device__ __forceinline__ int requant_shift(int acc, int s, int mode, WordStream& rng, unsigned long long index) {
   if (s == 0) return acc;

@@ -416,3 +416,46 @@ def test_every_entry_point_declaration_cites_its_source():
         if "Section" not in comment and "cannot allocate" not in comment:
             missing.append(name)
     assert not missing, missing
+
+
+def test_scheme_entry_points_validate_on_the_host():
+    d8 = _d(dtype=B.RELAY_I8, flags=B.HAS_BIAS)
+    by = C.byref
+    # general scale: the per-channel arrays are required
+    assert _status("relay_qconv2d_requant_scaled", by(d8), FAKE, FAKE + 4096, FAKE + 8192, None, 0, None, FAKE, FAKE + 65536, None, 0, None) == 1
+    assert _status("relay_qconv2d_requant_scaled", by(d8), FAKE, FAKE + 4096, FAKE + 8192, None, 0, FAKE + 2, FAKE, FAKE + 65536, None, 0, None) == 5
+    # 16-bit accumulator: same argument rules as the plain quantized conv
+    assert _status("relay_qconv2d_requant_acc16", by(d8), FAKE, FAKE + 4096, FAKE + 8192, None, 0, 32, FAKE + 65536, None, 0, None) == 4
+    assert _status("relay_qconv2d_requant_acc16", by(_d(dtype=B.RELAY_F16)), FAKE, FAKE + 4096, None, None, 0, 3, FAKE + 65536, None, 0, None) == 3
+    # 16/32
+    d16 = _d(dtype=B.RELAY_I16, flags=0)
+    assert _status("relay_qconv2d_requant_i16", by(_d(dtype=B.RELAY_I8)), FAKE, FAKE + 4096, None, 3, FAKE + 65536, None) == 3
+    assert _status("relay_qconv2d_requant_i16", by(_d(dtype=B.RELAY_I16, c=12)), FAKE, FAKE + 4096, None, 3, FAKE + 65536, None) == 5
+    assert _status("relay_qconv2d_requant_i16", by(_d(dtype=B.RELAY_I16, k=6)), FAKE, FAKE + 4096, None, 3, FAKE + 65536, None) == 5
+    assert _status("relay_qconv2d_requant_i16", by(_d(dtype=B.RELAY_I16, flags=B.HAS_BN)), FAKE, FAKE + 4096, None, 3, FAKE + 65536, None) == 4
+    assert _status("relay_qconv2d_requant_i16", by(d16), FAKE, FAKE + 4096, None, 40, FAKE + 65536, None) == 4
+    assert _status("relay_qconv2d_requant_i16", by(d16), None, FAKE + 4096, None, 3, FAKE + 65536, None) == 1
+    assert B.relay_packed_weight_bytes(d16) == 64 * 576 * 2                 # packed like the other 2-byte type
+    # the other entry points do not take the 16-bit integer type
+    assert _status("relay_fused_conv2d_bias_bn_relu", by(d16), FAKE, FAKE + 4096, None, None, None, None, FAKE + 65536, None, 0, None) == 3
+    assert _status("relay_qconv2d_requant", by(d16), FAKE, FAKE + 4096, None, None, 0, 3, FAKE + 65536, None, 0, None) == 3
+    # unsigned activations
+    need = B.relay_qconv2d_u8_workspace_bytes(d8)
+    assert need == 1 * 10 * 10 * 64
+    call = lambda d=d8, x=FAKE, ws=FAKE + (1 << 20), wsb=need, s=5, ou=1, bz=FAKE + 8192: _status(
+        "relay_qconv2d_requant_u8", by(d), x, FAKE + 4096, bz, s, ou, FAKE + 65536, ws, wsb, None)
+    assert call(wsb=need - 1) == 6 and call(ws=None) == 1 and call(x=None) == 1 and call(ou=2) == 4 and call(s=32) == 4
+    assert call(d=_d(dtype=B.RELAY_I8, flags=0)) == 1                      # the zero-point term needs the bias operand
+    assert call(d=_d(dtype=B.RELAY_I8, flags=B.HAS_BIAS | B.HAS_RESIDUAL)) == 4
+    assert call(d=_d(dtype=B.RELAY_I8, c=24, flags=B.HAS_BIAS)) == 5 and call(d=_d(dtype=B.RELAY_F16, flags=B.HAS_BIAS)) == 3
+    assert _status("relay_fold_zero_point", 0, 72, FAKE, None, 128, FAKE + 4096, None) == 2
+    assert _status("relay_fold_zero_point", 4, 72, None, None, 128, FAKE + 4096, None) == 1
+    assert _status("relay_fold_zero_point", 4, 72, FAKE, None, 300, FAKE + 4096, None) == 4
+    # the multiplier decomposition is host code: 0.5 = 2^30 / 2^31, 3/16 = 0.75 * 2^-2
+    assert B.relay_quantize_multiplier(0.5) == (1 << 30, 0) and B.relay_quantize_multiplier(0.1875) == (3 << 29, 2)
+    m, s = B.relay_quantize_multiplier(1e-3)
+    assert abs(m / 2.0 ** (31 + s) - 1e-3) < 1e-12 and (1 << 30) <= m < (1 << 31)
+    for bad in (0.0, 1.0, 2.0 ** -40):
+        with pytest.raises(B.RelayError) as e:
+            B.relay_quantize_multiplier(bad)
+        assert e.value.status == 2
