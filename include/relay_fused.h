@@ -327,6 +327,19 @@ relay_status relay_fused_conv2d_combined(const relay_conv2d_desc* d, const void*
                                          const float* bn_shift, int32_t nseg, const int32_t* seg_channels,
                                          void* const* seg_y, const int32_t* seg_ld, void* hip_stream);
 
+/* The quantized form of relay_fused_conv2d_combined (paper Section 4.4, "Parallel convolution
+ * combination", on the realized int8 convolutions of Section 4.2): d->dtype == RELAY_I8, flags
+ * HAS_BIAS | RELU; x int8 with x_ld a multiple of 16, c % 64 == 0; bias int32 [k] over all segments;
+ * segments of int8 with seg_channels / seg_ld multiples of 8 and seg_y 8-byte aligned.  Scaling of the
+ * tail: mult == rshift == NULL -> one power-of-two shift out_rshift for every member (as
+ * relay_qconv2d_requant); else per output channel round(acc * mult[k] / 2^(31 + rshift[k])) as
+ * relay_qconv2d_requant_scaled, so that every member keeps its own scale (device int32 [k] each).
+ * Clip +-127, [relu].  Bit-equal to the members' separate launches. */
+relay_status relay_qconv2d_combined(const relay_conv2d_desc* d, const int8_t* x, int32_t x_ld, const int8_t* w_packed,
+                                    const int32_t* bias, const int32_t* mult, const int32_t* rshift, int32_t out_rshift,
+                                    int32_t nseg, const int32_t* seg_channels, void* const* seg_y, const int32_t* seg_ld,
+                                    void* hip_stream);
+
 /* relay_fused_conv2d_combined (paper Section 4.4, "Parallel convolution combination") for members
  * whose windows and tails differ in two ways that occur in residual networks (a stride-2 3x3 convolution and the 1x1 shortcut convolution beside it
  * read the same tensor): a 1x1 convolution with the same stride and no padding reads, for every

@@ -69,6 +69,7 @@ SIGNATURES = {
     "relay_sim_quantize": [C.c_int64, _P, C.c_float, _I, _I, _I, C.c_uint64, _P, _P],
     "relay_fused_conv2d_combined": [_DP, _P, _I, _P, _P, _P, _P, _I, _P, _P, _P, _P],
     "relay_fused_conv2d_combined_windows": [_DP, _P, _I, _P, _P, _P, _P, _I, _P, _P, _P, _P, _P, _P],
+    "relay_qconv2d_combined": [_DP, _P, _I, _P, _P, _P, _P, _I, _I, _P, _P, _P, _P],
     "relay_fold_scale_axis": [_I, _I, _I, _I, _I, _P, _P, _P, _P],
     "relay_fold_bias": [_I, _P, _P, _P, _P, _P],
     "relay_conv2d_maxpool_fusable": [_DP, C.POINTER(_I)],
@@ -320,6 +321,16 @@ def relay_fused_conv2d_combined(d: ConvDesc, x, x_ld: int, w_packed, bias, bn_sc
 
 
 WINDOW_FULL, WINDOW_CENTRE = 0, 1
+
+
+def relay_qconv2d_combined(d: ConvDesc, x, x_ld: int, w_packed, bias, mult, rshift, out_rshift: int,
+                           seg_channels: Sequence[int], seg_y: Sequence, seg_ld: Sequence[int]) -> None:
+    n = len(seg_y)
+    ch = (C.c_int32 * max(n, 1))(*seg_channels)
+    ld = (C.c_int32 * max(n, 1))(*seg_ld)
+    ys = (C.c_void_p * max(n, 1))(*[_ptr(t) for t in seg_y])
+    _check(lib().relay_qconv2d_combined(C.byref(d), _ptr(x), x_ld, _ptr(w_packed), _ptr(bias), _ptr(mult), _ptr(rshift), out_rshift,
+                                        n, C.cast(ch, _P), C.cast(ys, _P), C.cast(ld, _P), _stream()))
 
 
 def relay_fused_conv2d_combined_windows(d: ConvDesc, x, x_ld: int, w_packed, bias, bn_scale, bn_shift,

@@ -449,10 +449,18 @@ relay_status relay_fused_conv2d_bias_bn_relu_static(const relay_conv2d_desc* d, 
   return device_status(launch_igemm(a, false, s), "conv2d fp16 launch");
 }
 
+// quantized form of a combined launch: the int32 bias and the scaling rule of the tail (NULL: the float form)
+struct CombinedQuant {
+  const int32_t* bias;
+  const int32_t* mult;     // per-channel multiplier and shift (QMODE_SCALED), or NULL: one power-of-two shift
+  const int32_t* rshift_k;
+  int out_rshift;
+};
 static relay_status combined_conv(const relay_conv2d_desc* d, const void* x, int32_t x_ld, const void* w_packed,
                                   const float* bias, const float* bn_scale, const float* bn_shift, int32_t nseg,
                                   const int32_t* seg_channels, void* const* seg_y, const int32_t* seg_ld,
-                                  const int32_t* seg_window, const int32_t* seg_relu, void* hip_stream);
+                                  const int32_t* seg_window, const int32_t* seg_relu, void* hip_stream,
+                                  const CombinedQuant* q = nullptr);
 
 relay_status relay_fused_conv2d_combined(const relay_conv2d_desc* d, const void* x, int32_t x_ld,
                                          const void* w_packed, const float* bias, const float* bn_scale,
@@ -473,23 +481,40 @@ relay_status relay_fused_conv2d_combined_windows(const relay_conv2d_desc* d, con
                        seg_relu, hip_stream);
 }
 
+relay_status relay_qconv2d_combined(const relay_conv2d_desc* d, const int8_t* x, int32_t x_ld, const int8_t* w_packed,
+                                    const int32_t* bias, const int32_t* mult, const int32_t* rshift, int32_t out_rshift,
+                                    int32_t nseg, const int32_t* seg_channels, void* const* seg_y, const int32_t* seg_ld,
+                                    void* hip_stream) {
+  if ((mult == nullptr) != (rshift == nullptr)) return fail(RELAY_ERR_NULL, "mult and rshift are given together or not at all");
+  if (!mult && (out_rshift < 0 || out_rshift > 31)) return fail(RELAY_ERR_UNSUPPORTED, "out_rshift=%d outside 0..31", out_rshift);
+  if (!aligned(mult, 4) || !aligned(rshift, 4) || !aligned(bias, 4)) return fail(RELAY_ERR_ALIGN, "bias, mult and rshift must be 4-byte aligned");
+  const CombinedQuant q{bias, mult, rshift, out_rshift};
+  return combined_conv(d, x, x_ld, w_packed, nullptr, nullptr, nullptr, nseg, seg_channels, seg_y, seg_ld, nullptr, nullptr,
+                       hip_stream, &q);
+}
+
 static relay_status combined_conv(const relay_conv2d_desc* d, const void* x, int32_t x_ld, const void* w_packed,
                                   const float* bias, const float* bn_scale, const float* bn_shift, int32_t nseg,
                                   const int32_t* seg_channels, void* const* seg_y, const int32_t* seg_ld,
-                                  const int32_t* seg_window, const int32_t* seg_relu, void* hip_stream) {
+                                  const int32_t* seg_window, const int32_t* seg_relu, void* hip_stream,
+                                  const CombinedQuant* q) {
   int ho, wo;
   relay_status st = check_geometry(d, &ho, &wo);
   if (st != RELAY_OK) return st;
-  if (d->dtype != RELAY_F16) return fail(RELAY_ERR_DTYPE, "the combined conv2d takes F16");
+  const bool i8 = q != nullptr;
+  const int xa = i8 ? 16 : 8;   // channel granularity of the input view (one 16-byte vector)
+  if (i8 && d->dtype != RELAY_I8) return fail(RELAY_ERR_DTYPE, "the combined quantized conv2d takes I8");
+  if (i8 && (d->flags & RELAY_HAS_BN)) return fail(RELAY_ERR_UNSUPPORTED, "the quantized epilogue has no float scale/shift");
+  if (!i8 && d->dtype != RELAY_F16) return fail(RELAY_ERR_DTYPE, "the combined conv2d takes F16");
   if (d->layout != RELAY_NHWC) return fail(RELAY_ERR_UNSUPPORTED, "the combined conv2d takes NHWC");
   if (d->flags & RELAY_HAS_RESIDUAL) return fail(RELAY_ERR_UNSUPPORTED, "the combined conv2d has no residual operand");
   if (!x || !w_packed || !seg_channels || !seg_y || !seg_ld)
     return fail(RELAY_ERR_NULL, "x, w_packed and the segment arrays are required");
-  if ((st = check_optional(bias, d->flags & RELAY_HAS_BIAS, "bias")) != RELAY_OK) return st;
+  if ((st = check_optional(i8 ? (const void*)q->bias : (const void*)bias, d->flags & RELAY_HAS_BIAS, "bias")) != RELAY_OK) return st;
   if ((st = check_optional(bn_scale, d->flags & RELAY_HAS_BN, "bn_scale")) != RELAY_OK) return st;
   if ((st = check_optional(bn_shift, d->flags & RELAY_HAS_BN, "bn_shift")) != RELAY_OK) return st;
   if (nseg < 1 || nseg > 4) return fail(RELAY_ERR_SHAPE, "nseg=%d outside 1..4", nseg);
-  if (x_ld < d->c || x_ld % 8) return fail(RELAY_ERR_SHAPE, "x_ld=%d must be a multiple of 8 and at least c=%d", x_ld, d->c);
+  if (x_ld < d->c || x_ld % xa) return fail(RELAY_ERR_SHAPE, "x_ld=%d must be a multiple of %d and at least c=%d", x_ld, xa, d->c);
   if ((long)d->n * d->h * d->w * x_ld > kMaxElems) return fail(RELAY_ERR_SHAPE, "input view exceeds 2^31-1 elements");
   relay::ConvArgs a = make_args(d, ho, wo);
   long total = 0;
@@ -499,7 +524,7 @@ static relay_status combined_conv(const relay_conv2d_desc* d, const void* x, int
     if (seg_ld[i] < seg_channels[i] || seg_ld[i] % 8)
       return fail(RELAY_ERR_SHAPE, "seg_ld[%d]=%d must be a multiple of 8 and at least %d", i, seg_ld[i], seg_channels[i]);
     if (!seg_y[i]) return fail(RELAY_ERR_NULL, "seg_y[%d] is NULL", i);
-    if (!aligned(seg_y[i], 16)) return fail(RELAY_ERR_ALIGN, "seg_y[%d] must be 16-byte aligned", i);
+    if (!aligned(seg_y[i], i8 ? 8 : 16)) return fail(RELAY_ERR_ALIGN, "seg_y[%d] must be %d-byte aligned", i, i8 ? 8 : 16);
     if (seg_y[i] == x) return fail(RELAY_ERR_UNSUPPORTED, "output must not alias an input");
     for (int j = 0; j < i; ++j)
       if (seg_y[j] == seg_y[i]) return fail(RELAY_ERR_UNSUPPORTED, "segments %d and %d share an address", j, i);
@@ -527,17 +552,27 @@ static relay_status combined_conv(const relay_conv2d_desc* d, const void* x, int
   }
   if (total != d->k) return fail(RELAY_ERR_SHAPE, "segments hold %ld channels, the descriptor k=%d", total, d->k);
   if ((st = check_igemm_support(d)) != RELAY_OK) return st;
-  if (!aligned(x, 16) || !aligned(w_packed, 16)) return fail(RELAY_ERR_ALIGN, "fp16 tensors must be 16-byte aligned");
+  if (!aligned(x, 16) || !aligned(w_packed, 16)) return fail(RELAY_ERR_ALIGN, "x and w_packed must be 16-byte aligned");
   a.nseg = nseg;
   a.xs_w = x_ld;
   a.xs_h = d->w * x_ld;
   a.xs_n = d->h * d->w * x_ld;
   a.x = x; a.w = w_packed; a.y = seg_y[0]; a.bias = bias; a.scale = bn_scale; a.shift = bn_shift;
+  if (i8) {
+    a.qbias = q->bias;
+    a.round_mode = RELAY_ROUND_NEAREST;
+    if (q->mult) {
+      a.qmode = relay::QMODE_SCALED; a.qmult = q->mult; a.qshift = q->rshift_k;
+    } else {
+      a.rshift = q->out_rshift;
+      a.round_add = q->out_rshift == 0 ? 0 : 1 << (q->out_rshift - 1);
+    }
+  }
   finish_args(a);
-  if (!relay::igemm_dma_supported(a, false))
-    return fail(RELAY_ERR_UNSUPPORTED, "the combined conv2d needs c %% 32 == 0 and r*s <= 32 (c=%d, r=%d, s=%d)", d->c,
+  if (!relay::igemm_dma_supported(a, i8))
+    return fail(RELAY_ERR_UNSUPPORTED, "the combined conv2d needs c %% %d == 0 and r*s <= 32 (c=%d, r=%d, s=%d)", i8 ? 64 : 32, d->c,
                 d->r, d->s);
-  return device_status(launch_igemm(a, false, static_cast<hipStream_t>(hip_stream)), "combined conv2d launch");
+  return device_status(launch_igemm(a, i8, static_cast<hipStream_t>(hip_stream)), "combined conv2d launch");
 }
 
 relay_status relay_fold_scale_axis(int32_t dtype, int32_t k, int32_t c, int32_t rs, int32_t axis, const void* w,

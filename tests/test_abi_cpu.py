@@ -286,6 +286,31 @@ def test_combined_conv_argument_checks():
     assert _comb(_d(n=4096, h=64, w=64, c=64), x_ld=256) == 2                 # view beyond 2^31-1 elements
 
 
+def _qcomb(d, x=FAKE, x_ld=None, bias=None, mult=None, rsh=None, s=7, ch=(32, 32), ys=(FAKE + 4096, FAKE + 8192), ld=None):
+    n = len(ch)
+    P = C.c_void_p
+    cha = (C.c_int32 * max(n, 1))(*ch)
+    lda = (C.c_int32 * max(n, 1))(*(ld if ld is not None else ch))
+    ya = (C.c_void_p * max(n, 1))(*ys)
+    return _status("relay_qconv2d_combined", C.byref(d), x, d.c if x_ld is None else x_ld, FAKE, bias, mult, rsh, s, n,
+                   C.cast(cha, P), C.cast(ya, P), C.cast(lda, P), None)
+
+
+def test_quantized_combined_conv_argument_checks():
+    """The 8-bit combination validates on the host like the fp16 one, plus its requantization arguments."""
+    q = lambda **kw: _d(dtype=B.RELAY_I8, c=64, **kw)
+    assert _qcomb(_d(c=64)) == 3                                               # fp16 descriptor
+    assert _qcomb(q(), mult=FAKE) == 1 and _qcomb(q(), rsh=FAKE) == 1          # multiplier and shift come together
+    assert _qcomb(q(), s=32) == 4 and _qcomb(q(), s=-1) == 4
+    assert _qcomb(q(), mult=FAKE + 2, rsh=FAKE) == 5
+    assert _qcomb(q(flags=B.HAS_BN)) == 4
+    assert _qcomb(q(flags=B.HAS_BIAS)) == 1
+    assert _qcomb(q(), x_ld=72) == 2                                           # input pitch not a multiple of 16
+    assert _qcomb(q(), ys=(FAKE + 4096, FAKE + 8196)) == 5                     # an 8-byte store would straddle
+    assert _qcomb(q(), ch=(32, 24)) == 2
+    assert _qcomb(_d(dtype=B.RELAY_I8, c=32)) == 4                             # c % 64: no direct-to-LDS kernel
+
+
 def test_scale_folding_argument_checks():
     f = lambda *a: _status("relay_fold_scale_axis", *a)
     assert f(B.RELAY_I8, 8, 8, 9, 0, FAKE, FAKE, FAKE, None) == 3

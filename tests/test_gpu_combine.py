@@ -335,3 +335,58 @@ def test_resnet18_with_stage_convs_and_shortcuts_merged(G, fold_scale):
     if not fold_scale:
         ref = run_float(ops, params, x, "f16")
         assert O.max_rel_err(outs["windows"]["logits"].reshape(2, 1000), ref["logits"]) <= 2e-2
+
+
+@pytest.mark.parametrize("r", [1, 3])
+def test_int8_combined_convs_bit_exact(r):
+    """Quantized convs over the same input as one launch: every member equals its own oracle conv and its
+    own separate launch bit for bit, with one common shift and with a scale per member; input and
+    outputs are channel ranges of wider tensors."""
+    from oracle import schemes as S
+    from paper_1904_08368_amd import binding as B
+    from tests import gpu_util as G
+    g = np.random.default_rng(520 + r)
+    n, c, hw, widths = 2, 64, 14, (64, 24, 40)
+    k = sum(widths)
+    pad = r // 2
+    wide = g.integers(-127, 128, (n, c + 64, hw, hw)).astype(np.int8)            # the convs read channels 64 .. 127 of this
+    x = wide[:, 64:]
+    ws = [g.integers(-127, 128, (kk, c, r, r)).astype(np.int8) for kk in widths]
+    bs = [g.integers(-4000, 4000, kk).astype(np.int32) for kk in widths]
+    d = B.conv_desc(n, c, hw, hw, k, r, r, 1, pad, B.RELAY_I8, B.RELAY_NHWC, B.flags_of(True, None, None, True))
+    xw = G.to_nhwc(wide, c + 64, B.RELAY_I8)
+    xv = xw[..., 64:]
+    wp = torch.empty(B.relay_packed_weight_bytes(d), dtype=torch.uint8, device=G.DEV)
+    off = 0
+    for wt, kk in zip(ws, widths):
+        dm = B.conv_desc(n, c, hw, hw, kk, r, r, 1, pad, B.RELAY_I8, B.RELAY_NHWC, 0)
+        nb = B.relay_packed_weight_bytes(dm)
+        B.relay_prepack_conv2d_weights(dm, G.up(wt), c, wp[off:off + nb])
+        off += nb
+    bias = G.up(np.concatenate(bs))
+    cat = torch.full((n, hw, hw, widths[0] + widths[1]), -128, dtype=torch.int8, device=G.DEV)   # members 0 and 1 share a joined tensor
+    y2 = torch.full((n, hw, hw, widths[2]), -128, dtype=torch.int8, device=G.DEV)
+    ys = [cat[..., :widths[0]], cat[..., widths[0]:], y2]
+    lds = [cat.shape[-1], cat.shape[-1], widths[2]]
+    s = 12 if r == 3 else 10
+    # (i) one common power-of-two shift
+    B.relay_qconv2d_combined(d, xv, xw.shape[-1], wp, bias, None, None, s, list(widths), ys, lds)
+    torch.cuda.synchronize()
+    outs = [G.from_nhwc(cat, cat.shape[-1])[:, :widths[0]], G.from_nhwc(cat, cat.shape[-1])[:, widths[0]:], G.from_nhwc(y2, widths[2])]
+    for wt, b, got in zip(ws, bs, outs):
+        ref = O.qconv2d_requant(x, wt, stride=(1, 1), pad=(pad, pad), bias=b, out_rshift=s, relu_flag=True)
+        assert np.array_equal(got, ref)
+        assert np.array_equal(got, G.run_qconv(np.ascontiguousarray(x), wt, 1, pad, bias=b, rshift=s, relu=True))
+    # (ii) a scale of its own for every member
+    scales = [2.0 ** -11.3, 2.0 ** -10.1, 2.0 ** -12.6] if r == 3 else [2.0 ** -9.3, 2.0 ** -8.1, 2.0 ** -10.6]
+    ms = [S.quantize_multiplier(v) for v in scales]
+    mult = np.concatenate([np.full(kk, m, dtype=np.int32) for kk, (m, _) in zip(widths, ms)])
+    rsh = np.concatenate([np.full(kk, sh, dtype=np.int32) for kk, (_, sh) in zip(widths, ms)])
+    cat.fill_(-128)
+    y2.fill_(-128)
+    B.relay_qconv2d_combined(d, xv, xw.shape[-1], wp, bias, G.up(mult), G.up(rsh), 0, list(widths), ys, lds)
+    torch.cuda.synchronize()
+    outs = [G.from_nhwc(cat, cat.shape[-1])[:, :widths[0]], G.from_nhwc(cat, cat.shape[-1])[:, widths[0]:], G.from_nhwc(y2, widths[2])]
+    for wt, b, (m, sh), got in zip(ws, bs, ms, outs):
+        ref = S.qconv2d_requant_scaled(x, wt, stride=(1, 1), pad=(pad, pad), bias=b, mult=m, rshift=sh, relu_flag=True)
+        assert np.array_equal(got, ref)
