@@ -242,6 +242,26 @@ relay_status relay_fused_dwconv_bias_relu(const relay_conv2d_desc* d, const void
                                           const float* bias, const float* bn_scale, const float* bn_shift,
                                           void* y, void* hip_stream);
 
+/* A depthwise conv2d and the 1x1 conv2d that consumes it, each with its fused tail, as ONE launch
+ * (paper Section 4.1: a primitive function is one kernel; Section 5.2: the cost of every extra launch and
+ * every intermediate that goes through memory; MobileNet's separable block, Section 5.1):
+ *   t = fp16( relay_fused_dwconv_bias_relu(dw, x, dw_w_rsc, dw_bias, dw_scale, dw_shift) )
+ *   y[n,p,q,k'] = sum_c t[n,p,q,c] * pw_w[k',c] -> [+pw_bias] -> [*pw_scale + pw_shift] -> [relu] -> fp16
+ * t never leaves the chip; both reductions run in the order of the two separate entry points, so the result
+ * equals theirs bit for bit.  dw: as for relay_fused_dwconv_bias_relu, additionally padding 1 and
+ * c % 32 == 0.  k: output channels of the 1x1 conv (a multiple of 8); pw_flags: RELAY_HAS_BIAS / _HAS_BN /
+ * _RELU.  pw_w_packed: the 1x1 filters [k][c] packed by relay_prepack_conv2d_weights for a 1x1 / stride 1 /
+ * F16 / NHWC descriptor of c input channels.  x [n,h,w,c], y [n,ho,wo,k] device, 16-byte aligned,
+ * caller-owned, distinct.  Per-channel arrays fp32 device ([c] for dw_*, [k] for pw_*) or NULL with the
+ * flag clear.  relay_set_conv_tile(300 + v) forces kernel variant v for the calling thread.
+ * Errors: as relay_fused_dwconv_bias_relu, plus RELAY_ERR_UNSUPPORTED (padding, c % 32, residual flag, no
+ * variant for the stride) and _SHAPE (k); nothing is launched on an error. */
+relay_status relay_fused_dwconv_pwconv(const relay_conv2d_desc* dw, const void* x, const void* dw_w_rsc,
+                                       const float* dw_bias, const float* dw_scale, const float* dw_shift,
+                                       int32_t k, uint32_t pw_flags, const void* pw_w_packed,
+                                       const float* pw_bias, const float* pw_scale, const float* pw_shift,
+                                       void* y, void* hip_stream);
+
 /* dense as a fused primitive function (paper Section 4.1: a contraction with its elementwise tail;
  * Section 3.3 "Backends": operators are lowered to dense linear algebra kernels; the classifier
  * layers of the vision models of Section 5.1):

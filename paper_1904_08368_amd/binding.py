@@ -56,6 +56,7 @@ SIGNATURES = {
     "relay_qconv2d_requant_u8": [_DP, _P, _P, _P, _I, _I, _P, _P, _SZ, _P],
     "relay_prepack_dwconv_weights": [_DP, _P, _P, _P],
     "relay_fused_dwconv_bias_relu": [_DP, _P, _P, _P, _P, _P, _P, _P],
+    "relay_fused_dwconv_pwconv": [_DP, _P, _P, _P, _P, _P, C.c_int32, C.c_uint32, _P, _P, _P, _P, _P, _P],
     "relay_fused_dense_bias_act": [_I, _I, _I, _I, _P, _P, _P, _I, _P, _P],
     "relay_maxpool2d": [_I, _I, _I, _I, _I, _I, _I, _I, _P, _P, _P],
     "relay_global_avgpool": [_I, _I, _I, _I, _P, _P, _P],
@@ -196,6 +197,13 @@ def relay_prepack_dwconv_weights(d: ConvDesc, w_crs, w_rsc) -> None:
 def relay_fused_dwconv_bias_relu(d: ConvDesc, x, w_rsc, bias, bn_scale, bn_shift, y) -> None:
     _check(lib().relay_fused_dwconv_bias_relu(C.byref(d), _ptr(x), _ptr(w_rsc), _ptr(bias), _ptr(bn_scale),
                                               _ptr(bn_shift), _ptr(y), _stream()))
+
+
+def relay_fused_dwconv_pwconv(dw: ConvDesc, x, dw_w_rsc, dw_bias, dw_scale, dw_shift, k: int, pw_flags: int, pw_w_packed,
+                              pw_bias, pw_scale, pw_shift, y) -> None:
+    _check(lib().relay_fused_dwconv_pwconv(C.byref(dw), _ptr(x), _ptr(dw_w_rsc), _ptr(dw_bias), _ptr(dw_scale), _ptr(dw_shift),
+                                           k, pw_flags, _ptr(pw_w_packed), _ptr(pw_bias), _ptr(pw_scale), _ptr(pw_shift),
+                                           _ptr(y), _stream()))
 
 
 def relay_fused_dense_bias_act(m: int, n: int, k: int, dtype: int, x, w, bias, act: int, y) -> None:

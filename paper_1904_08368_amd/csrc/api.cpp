@@ -285,12 +285,14 @@ relay_status relay_prepack_conv2d_weights(const relay_conv2d_desc* d, const void
 // kernel's variant v (where they apply)
 constexpr int kHaloBase = 100;
 constexpr int kStreamBase = 200;
+constexpr int kDwPwBase = 300;   // ... of the fused depthwise + 1x1 kernel (its own entry point)
 
 relay_status relay_set_conv_tile(int32_t tile) {
   const int most = relay::igemm_dma_tile_count() > relay::igemm_tile_count() ? relay::igemm_dma_tile_count()
                                                                              : relay::igemm_tile_count();
   const bool halo = (tile >= kHaloBase && tile < kHaloBase + relay::conv_halo_variant_count()) ||
-                    (tile >= kStreamBase && tile < kStreamBase + relay::conv_stream_variant_count());
+                    (tile >= kStreamBase && tile < kStreamBase + relay::conv_stream_variant_count()) ||
+                    (tile >= kDwPwBase && tile < kDwPwBase + relay::dwpw_variant_count());
   if (tile >= most && !halo) return fail(RELAY_ERR_UNSUPPORTED, "no tile %d", tile);
   g_force_tile = tile < -1 ? -2 : tile;
   return RELAY_OK;
@@ -298,7 +300,7 @@ relay_status relay_set_conv_tile(int32_t tile) {
 
 // which variant of the persistent 3x3 stride-1 kernel runs this layer, or -1
 static int stream_choice(const relay::ConvArgs& a, bool is_i8) {
-  if (g_force_tile >= kStreamBase)
+  if (g_force_tile >= kStreamBase && g_force_tile < kDwPwBase)
     return relay::conv_stream_supported(a, is_i8, g_force_tile - kStreamBase) ? g_force_tile - kStreamBase : -1;
   return g_force_tile == -1 ? relay::conv_stream_pick(a, is_i8) : -1;
 }
@@ -894,6 +896,47 @@ relay_status relay_fused_dwconv_bias_relu(const relay_conv2d_desc* d, const void
   relay::ConvArgs a = make_args(d, ho, wo);
   a.x = x; a.w = w_rsc; a.y = y; a.bias = bias; a.scale = bn_scale; a.shift = bn_shift;
   return device_status(relay::launch_dwconv_f16(a, static_cast<hipStream_t>(hip_stream)), "depthwise launch");
+}
+
+relay_status relay_fused_dwconv_pwconv(const relay_conv2d_desc* dw, const void* x, const void* dw_w_rsc, const float* dw_bias,
+                                       const float* dw_scale, const float* dw_shift, int32_t k, uint32_t pw_flags,
+                                       const void* pw_w_packed, const float* pw_bias, const float* pw_scale,
+                                       const float* pw_shift, void* y, void* hip_stream) {
+  int ho, wo;
+  relay_status st = check_dw(dw, &ho, &wo);
+  if (st != RELAY_OK) return st;
+  if (dw->pad_h != 1 || dw->pad_w != 1) return fail(RELAY_ERR_UNSUPPORTED, "the fused depthwise + 1x1 kernel takes padding 1");
+  if (dw->c % 32) return fail(RELAY_ERR_UNSUPPORTED, "c=%d must be a multiple of 32", dw->c);
+  if (k <= 0 || k % 8) return fail(RELAY_ERR_SHAPE, "k=%d must be a positive multiple of 8", k);
+  if (pw_flags & ~(RELAY_HAS_BIAS | RELAY_HAS_BN | RELAY_RELU))
+    return fail(RELAY_ERR_UNSUPPORTED, "the 1x1 conv takes bias, scale/shift and relu only (flags=0x%x)", pw_flags);
+  if (!x || !dw_w_rsc || !pw_w_packed || !y) return fail(RELAY_ERR_NULL, "x, dw_w_rsc, pw_w_packed and y are required");
+  if ((st = check_optional(dw_bias, dw->flags & RELAY_HAS_BIAS, "dw_bias")) != RELAY_OK) return st;
+  if ((st = check_optional(dw_scale, dw->flags & RELAY_HAS_BN, "dw_scale")) != RELAY_OK) return st;
+  if ((st = check_optional(dw_shift, dw->flags & RELAY_HAS_BN, "dw_shift")) != RELAY_OK) return st;
+  if ((st = check_optional(pw_bias, pw_flags & RELAY_HAS_BIAS, "pw_bias")) != RELAY_OK) return st;
+  if ((st = check_optional(pw_scale, pw_flags & RELAY_HAS_BN, "pw_scale")) != RELAY_OK) return st;
+  if ((st = check_optional(pw_shift, pw_flags & RELAY_HAS_BN, "pw_shift")) != RELAY_OK) return st;
+  if (y == x) return fail(RELAY_ERR_UNSUPPORTED, "output must not alias an input");
+  if (!aligned(x, 16) || !aligned(dw_w_rsc, 16) || !aligned(pw_w_packed, 16) || !aligned(y, 16))
+    return fail(RELAY_ERR_ALIGN, "fp16 tensors must be 16-byte aligned");
+  if ((long)dw->n * ho * wo * k > kMaxElems) return fail(RELAY_ERR_SHAPE, "output exceeds 2^31-1 elements");
+  relay_conv2d_desc pd;
+  memset(&pd, 0, sizeof(pd));
+  pd.n = dw->n; pd.c = dw->c; pd.h = ho; pd.w = wo; pd.k = k; pd.r = pd.s = 1;
+  pd.stride_h = pd.stride_w = 1;
+  pd.dtype = RELAY_F16; pd.layout = RELAY_NHWC; pd.flags = pw_flags;
+  relay::DwPwArgs a;
+  memset(&a, 0, sizeof(a));
+  a.x = x; a.dw_w = dw_w_rsc; a.dw_bias = dw_bias; a.dw_scale = dw_scale; a.dw_shift = dw_shift; a.dw_flags = dw->flags;
+  a.N = dw->n; a.H = dw->h; a.W = dw->w; a.C = dw->c; a.Ho = ho; a.Wo = wo; a.stride = dw->stride_h;
+  a.pw = make_args(&pd, ho, wo);
+  a.pw.w = pw_w_packed; a.pw.y = y; a.pw.bias = pw_bias; a.pw.scale = pw_scale; a.pw.shift = pw_shift;
+  finish_args(a.pw);
+  int variant = g_force_tile >= kDwPwBase ? g_force_tile - kDwPwBase : relay::dwpw_pick(a);
+  if (variant < 0 || !relay::dwpw_supported(a, variant))
+    return fail(RELAY_ERR_UNSUPPORTED, "no fused depthwise + 1x1 kernel variant takes this shape (variant %d)", variant);
+  return device_status(relay::launch_dwpw(a, variant, static_cast<hipStream_t>(hip_stream)), "depthwise + 1x1 launch");
 }
 
 relay_status relay_fused_dense_bias_act(int32_t m, int32_t n, int32_t k, int32_t dtype, const void* x,

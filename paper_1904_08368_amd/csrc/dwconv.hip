@@ -10,6 +10,7 @@
 // fp16 + fp32), with no conversion instructions.
 // Workgroups are renumbered so that one XCD works through a contiguous range of rows: the
 // rows two workgroups share are then fetched into one L2, not several.
+#include "dw_math.hpp"
 #include "kernels.hpp"
 #include "lds_dma.hpp"
 
@@ -17,14 +18,6 @@ namespace relay {
 namespace {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-
-// acc += x.lo*w.lo (fp16 halves of 32-bit registers), fp32 accumulate
-__device__ __forceinline__ void fma_mix_lo(float& acc, unsigned x, unsigned w) {
-  asm("v_fma_mix_f32 %0, %1, %2, %0 op_sel:[0,0,0] op_sel_hi:[1,1,0]" : "+v"(acc) : "v"(x), "v"(w));
-}
-__device__ __forceinline__ void fma_mix_hi(float& acc, unsigned x, unsigned w) {
-  asm("v_fma_mix_f32 %0, %1, %2, %0 op_sel:[1,1,0] op_sel_hi:[1,1,0]" : "+v"(acc) : "v"(x), "v"(w));
-}
 
 typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
 

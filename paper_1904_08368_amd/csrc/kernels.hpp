@@ -82,6 +82,21 @@ struct ConvArgs {
   void* seg_y[4];
 };
 
+// A depthwise 3x3 conv2d (pad 1, stride 1 or 2, NHWC fp16, filters [r][s][c]) with its fused tail and the 1x1
+// conv2d that consumes it, as one kernel.  `pw` describes the 1x1 conv over the depthwise output
+// (N x Ho x Wo pixels of C channels -> K channels; w, bias, scale, shift, flags, y; its x is unused).
+struct DwPwArgs {
+  const void* x;
+  const void* dw_w;
+  const float* dw_bias;
+  const float* dw_scale;
+  const float* dw_shift;
+  unsigned dw_flags;
+  int N, H, W, C, Ho, Wo, stride;
+  int tiles_x, tiles_y, tiles_n;   // set by the launcher of the kernel variant
+  ConvArgs pw;
+};
+
 // Row pitch (elements) of packed filters for a reduction of kred elements of esize bytes:
 // whole 128-byte groups.
 inline int packed_pitch(int kred, int esize) {
@@ -122,6 +137,12 @@ int conv_stream_variant_count();
 hipError_t launch_conv_stream(const ConvArgs& a, bool is_i8, int variant, hipStream_t st);
 void conv_stream_kernel_name(const ConvArgs& a, bool is_i8, int variant, char* buf, size_t len);
 hipError_t launch_dwconv_f16(const ConvArgs& a, hipStream_t st);
+// The depthwise conv and its 1x1 conv in one launch (dwpw.hip).
+int dwpw_variant_count();
+bool dwpw_supported(const DwPwArgs& a, int variant);
+int dwpw_pick(const DwPwArgs& a);   // variant, or -1: no variant takes the shape
+hipError_t launch_dwpw(const DwPwArgs& a, int variant, hipStream_t st);
+void dwpw_kernel_name(int variant, char* buf, size_t len);
 hipError_t launch_dense(int m, int n, int k, bool is_f16, const void* x, const void* w, const float* bias,
                         int act, void* y, hipStream_t st);
 hipError_t launch_pack_filters(const void* w_oihw, void* w_packed, int K, int Csrc, int C, int R, int S,
