@@ -262,6 +262,14 @@ relay_status relay_fused_dwconv_pwconv(const relay_conv2d_desc* dw, const void* 
                                        const float* pw_bias, const float* pw_scale, const float* pw_shift,
                                        void* y, void* hip_stream);
 
+/* Whether the single launch above is expected to be faster than relay_fused_dwconv_bias_relu followed by
+ * the 1x1 relay_fused_conv2d_bias_bn_relu (paper Section 4.1: fusion is a choice the compiler makes per
+ * group of operators; Section 5.2 measures what it buys): *pays = 1 on the layers that stream from
+ * memory (many pixels, at most 256 channels), 0 on the deep layers, where the single launch would have to
+ * recompute the depthwise tile once per tile of output channels.  From measurements on MI355X; host-only,
+ * nothing is launched.  dw, k as for relay_fused_dwconv_pwconv; same errors for shapes it does not take. */
+relay_status relay_dwconv_pwconv_fusion_pays(const relay_conv2d_desc* dw, int32_t k, int32_t* pays);
+
 /* dense as a fused primitive function (paper Section 4.1: a contraction with its elementwise tail;
  * Section 3.3 "Backends": operators are lowered to dense linear algebra kernels; the classifier
  * layers of the vision models of Section 5.1):

@@ -56,6 +56,7 @@ SIGNATURES = {
     "relay_qconv2d_requant_u8": [_DP, _P, _P, _P, _I, _I, _P, _P, _SZ, _P],
     "relay_prepack_dwconv_weights": [_DP, _P, _P, _P],
     "relay_fused_dwconv_bias_relu": [_DP, _P, _P, _P, _P, _P, _P, _P],
+    "relay_dwconv_pwconv_fusion_pays": [_DP, C.c_int32, C.POINTER(C.c_int32)],
     "relay_fused_dwconv_pwconv": [_DP, _P, _P, _P, _P, _P, C.c_int32, C.c_uint32, _P, _P, _P, _P, _P, _P],
     "relay_fused_dense_bias_act": [_I, _I, _I, _I, _P, _P, _P, _I, _P, _P],
     "relay_maxpool2d": [_I, _I, _I, _I, _I, _I, _I, _I, _P, _P, _P],
@@ -197,6 +198,12 @@ def relay_prepack_dwconv_weights(d: ConvDesc, w_crs, w_rsc) -> None:
 def relay_fused_dwconv_bias_relu(d: ConvDesc, x, w_rsc, bias, bn_scale, bn_shift, y) -> None:
     _check(lib().relay_fused_dwconv_bias_relu(C.byref(d), _ptr(x), _ptr(w_rsc), _ptr(bias), _ptr(bn_scale),
                                               _ptr(bn_shift), _ptr(y), _stream()))
+
+
+def relay_dwconv_pwconv_fusion_pays(dw: ConvDesc, k: int) -> bool:
+    pays = C.c_int32(0)
+    _check(lib().relay_dwconv_pwconv_fusion_pays(C.byref(dw), k, C.byref(pays)))
+    return bool(pays.value)
 
 
 def relay_fused_dwconv_pwconv(dw: ConvDesc, x, dw_w_rsc, dw_bias, dw_scale, dw_shift, k: int, pw_flags: int, pw_w_packed,

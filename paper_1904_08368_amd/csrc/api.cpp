@@ -898,10 +898,8 @@ relay_status relay_fused_dwconv_bias_relu(const relay_conv2d_desc* d, const void
   return device_status(relay::launch_dwconv_f16(a, static_cast<hipStream_t>(hip_stream)), "depthwise launch");
 }
 
-relay_status relay_fused_dwconv_pwconv(const relay_conv2d_desc* dw, const void* x, const void* dw_w_rsc, const float* dw_bias,
-                                       const float* dw_scale, const float* dw_shift, int32_t k, uint32_t pw_flags,
-                                       const void* pw_w_packed, const float* pw_bias, const float* pw_scale,
-                                       const float* pw_shift, void* y, void* hip_stream) {
+// validation and kernel arguments shared by the fused depthwise + 1x1 entry point and its query (pointers may be NULL in the query)
+static relay_status dwpw_args(const relay_conv2d_desc* dw, int32_t k, uint32_t pw_flags, relay::DwPwArgs* out) {
   int ho, wo;
   relay_status st = check_dw(dw, &ho, &wo);
   if (st != RELAY_OK) return st;
@@ -910,6 +908,36 @@ relay_status relay_fused_dwconv_pwconv(const relay_conv2d_desc* dw, const void* 
   if (k <= 0 || k % 8) return fail(RELAY_ERR_SHAPE, "k=%d must be a positive multiple of 8", k);
   if (pw_flags & ~(RELAY_HAS_BIAS | RELAY_HAS_BN | RELAY_RELU))
     return fail(RELAY_ERR_UNSUPPORTED, "the 1x1 conv takes bias, scale/shift and relu only (flags=0x%x)", pw_flags);
+  if ((long)dw->n * ho * wo * k > kMaxElems) return fail(RELAY_ERR_SHAPE, "output exceeds 2^31-1 elements");
+  relay_conv2d_desc pd;
+  memset(&pd, 0, sizeof(pd));
+  pd.n = dw->n; pd.c = dw->c; pd.h = ho; pd.w = wo; pd.k = k; pd.r = pd.s = 1;
+  pd.stride_h = pd.stride_w = 1;
+  pd.dtype = RELAY_F16; pd.layout = RELAY_NHWC; pd.flags = pw_flags;
+  relay::DwPwArgs& a = *out;
+  memset(&a, 0, sizeof(a));
+  a.dw_flags = dw->flags;
+  a.N = dw->n; a.H = dw->h; a.W = dw->w; a.C = dw->c; a.Ho = ho; a.Wo = wo; a.stride = dw->stride_h;
+  a.pw = make_args(&pd, ho, wo);
+  return RELAY_OK;
+}
+
+relay_status relay_dwconv_pwconv_fusion_pays(const relay_conv2d_desc* dw, int32_t k, int32_t* pays) {
+  if (!pays) return fail(RELAY_ERR_NULL, "pays is NULL");
+  relay::DwPwArgs a;
+  const relay_status st = dwpw_args(dw, k, 0, &a);
+  if (st != RELAY_OK) return st;
+  *pays = relay::dwpw_pick(a) >= 0 ? 1 : 0;
+  return RELAY_OK;
+}
+
+relay_status relay_fused_dwconv_pwconv(const relay_conv2d_desc* dw, const void* x, const void* dw_w_rsc, const float* dw_bias,
+                                       const float* dw_scale, const float* dw_shift, int32_t k, uint32_t pw_flags,
+                                       const void* pw_w_packed, const float* pw_bias, const float* pw_scale,
+                                       const float* pw_shift, void* y, void* hip_stream) {
+  relay::DwPwArgs a;
+  relay_status st = dwpw_args(dw, k, pw_flags, &a);
+  if (st != RELAY_OK) return st;
   if (!x || !dw_w_rsc || !pw_w_packed || !y) return fail(RELAY_ERR_NULL, "x, dw_w_rsc, pw_w_packed and y are required");
   if ((st = check_optional(dw_bias, dw->flags & RELAY_HAS_BIAS, "dw_bias")) != RELAY_OK) return st;
   if ((st = check_optional(dw_scale, dw->flags & RELAY_HAS_BN, "dw_scale")) != RELAY_OK) return st;
@@ -920,20 +948,10 @@ relay_status relay_fused_dwconv_pwconv(const relay_conv2d_desc* dw, const void* 
   if (y == x) return fail(RELAY_ERR_UNSUPPORTED, "output must not alias an input");
   if (!aligned(x, 16) || !aligned(dw_w_rsc, 16) || !aligned(pw_w_packed, 16) || !aligned(y, 16))
     return fail(RELAY_ERR_ALIGN, "fp16 tensors must be 16-byte aligned");
-  if ((long)dw->n * ho * wo * k > kMaxElems) return fail(RELAY_ERR_SHAPE, "output exceeds 2^31-1 elements");
-  relay_conv2d_desc pd;
-  memset(&pd, 0, sizeof(pd));
-  pd.n = dw->n; pd.c = dw->c; pd.h = ho; pd.w = wo; pd.k = k; pd.r = pd.s = 1;
-  pd.stride_h = pd.stride_w = 1;
-  pd.dtype = RELAY_F16; pd.layout = RELAY_NHWC; pd.flags = pw_flags;
-  relay::DwPwArgs a;
-  memset(&a, 0, sizeof(a));
-  a.x = x; a.dw_w = dw_w_rsc; a.dw_bias = dw_bias; a.dw_scale = dw_scale; a.dw_shift = dw_shift; a.dw_flags = dw->flags;
-  a.N = dw->n; a.H = dw->h; a.W = dw->w; a.C = dw->c; a.Ho = ho; a.Wo = wo; a.stride = dw->stride_h;
-  a.pw = make_args(&pd, ho, wo);
+  a.x = x; a.dw_w = dw_w_rsc; a.dw_bias = dw_bias; a.dw_scale = dw_scale; a.dw_shift = dw_shift;
   a.pw.w = pw_w_packed; a.pw.y = y; a.pw.bias = pw_bias; a.pw.scale = pw_scale; a.pw.shift = pw_shift;
   finish_args(a.pw);
-  int variant = g_force_tile >= kDwPwBase ? g_force_tile - kDwPwBase : relay::dwpw_pick(a);
+  const int variant = g_force_tile >= kDwPwBase ? g_force_tile - kDwPwBase : relay::dwpw_any(a);
   if (variant < 0 || !relay::dwpw_supported(a, variant))
     return fail(RELAY_ERR_UNSUPPORTED, "no fused depthwise + 1x1 kernel variant takes this shape (variant %d)", variant);
   return device_status(relay::launch_dwpw(a, variant, static_cast<hipStream_t>(hip_stream)), "depthwise + 1x1 launch");

@@ -140,7 +140,8 @@ hipError_t launch_dwconv_f16(const ConvArgs& a, hipStream_t st);
 // The depthwise conv and its 1x1 conv in one launch (dwpw.hip).
 int dwpw_variant_count();
 bool dwpw_supported(const DwPwArgs& a, int variant);
-int dwpw_pick(const DwPwArgs& a);   // variant, or -1: no variant takes the shape
+int dwpw_pick(const DwPwArgs& a);   // variant expected to beat the two separate launches, or -1
+int dwpw_any(const DwPwArgs& a);    // dwpw_pick, else any variant that takes the shape, or -1
 hipError_t launch_dwpw(const DwPwArgs& a, int variant, hipStream_t st);
 void dwpw_kernel_name(int variant, char* buf, size_t len);
 hipError_t launch_dense(int m, int n, int k, bool is_f16, const void* x, const void* w, const float* bias,

@@ -27,7 +27,7 @@ class FusedNet:
     def __init__(self, ops, params: List[dict], batch: int, h: int, w: int, mode: str = "f16",
                  shifts: Optional[List[dict]] = None, in_channels: int = 3, device: str = "cuda:0",
                  overlap_shortcuts: bool = False, fused: bool = True, combine: bool = False,
-                 fold_scale: bool = False, fuse_pool: bool = True):
+                 fold_scale: bool = False, fuse_pool: bool = True, fuse_dwpw: bool = True):
         assert mode in ("f16", "i8")
         assert fused or mode == "f16"
         # combine: convs that share input, window and tail run as one launch ("windows": also a 1x1 conv
@@ -38,6 +38,10 @@ class FusedNet:
         # fuse_pool: a conv whose only reader is a 3x3 / stride 2 / pad 1 max pool runs with it as one
         # launch where the library takes the shape; the conv's own output tensor then does not exist
         self.fuse_pool = fuse_pool and fused
+        # fuse_dwpw: a depthwise conv whose only reader is a plain 1x1 conv runs with it as one launch where
+        # the library expects that to be faster; the depthwise output tensor then does not exist
+        # ("always": wherever the library has a kernel for the shape, profitable or not)
+        self.fuse_dwpw = fuse_dwpw if (fused and mode == "f16" and not fold_scale) else False
         # fused=False launches every elementwise operator behind a contraction as a kernel of its
         # own on a tensor of its own: the pipeline of a framework without operator fusion, kept
         # for the fusion ablation (paper Section 5.2)
@@ -163,6 +167,23 @@ class FusedNet:
                 wsrc = torch.from_numpy(np.ascontiguousarray(p["w"])).to(self.dev)
                 wp = torch.empty((op.r * op.r, cin_p), dtype=self.tdtype, device=self.dev)
                 B.relay_prepack_dwconv_weights(d, wsrc, wp)
+                pw = self._pointwise_behind(ops, i, group_of, absorbed) if self.fuse_dwpw and op.r == 3 and op.pad == 1 \
+                    and cin_p % 32 == 0 and src.is_contiguous() else None
+                if pw is not None and (self.fuse_dwpw == "always" or B.relay_dwconv_pwconv_fusion_pays(d, ops[pw].cout)):
+                    q, pp = ops[pw], params[pw]
+                    pflags = B.flags_of(pp.get("bias"), pp.get("scale"), None, q.relu)
+                    pd = B.conv_desc(batch, cin_p, ho, wo, q.cout, 1, 1, 1, 0, self.dtype, B.RELAY_NHWC, pflags)
+                    pwp = torch.empty(B.relay_packed_weight_bytes(pd), dtype=torch.uint8, device=self.dev)
+                    B.relay_prepack_conv2d_weights(pd, torch.from_numpy(np.ascontiguousarray(pp["w"])).to(self.dev), cin_l, pwp)
+                    y = torch.empty((batch, ho, wo, q.cout), dtype=self.tdtype, device=self.dev)
+                    bias, sc, sf = (self._f32(p.get(k)) for k in ("bias", "scale", "shift"))
+                    pb, psc, psf = (self._f32(pp.get(k)) for k in ("bias", "scale", "shift"))
+                    self._add(op.name + "+" + q.name, B.relay_fused_dwconv_pwconv,
+                              (d, src, wp, bias, sc, sf, q.cout, pflags, pwp, pb, psc, psf, y))
+                    absorbed.add(pw)
+                    self.keep += [wp, d, pwp, pd]
+                    self.bufs[q.dst], self.shape[q.dst] = y, (q.cout, ho, wo)
+                    continue
                 y = torch.empty((batch, ho, wo, cin_p), dtype=self.tdtype, device=self.dev)
                 if not fused and flags:
                     d0 = B.conv_desc(d.n, d.c, d.h, d.w, d.k, d.r, d.s, d.stride_h, d.pad_h, self.dtype, d.layout, 0)
@@ -228,6 +249,18 @@ class FusedNet:
                 self.side = torch.cuda.Stream(device=self.dev)
         torch.cuda.synchronize(self.dev)
         self.graph = None
+
+    def _pointwise_behind(self, ops, i, group_of, absorbed):
+        """Index of the plain 1x1 / stride 1 conv that is the only reader of depthwise conv i's output, or None."""
+        op = ops[i]
+        users = [j for j, o in enumerate(ops) if o.src == op.dst or o.res == op.dst or op.dst in (getattr(o, "srcs", None) or ())]
+        if len(users) != 1 or users[0] != i + 1:
+            return None
+        q = ops[users[0]]
+        plain = q.kind == "conv" and q.src == op.dst and q.r == 1 and q.stride == 1 and q.pad == 0 and not q.res
+        if not plain or users[0] in group_of or users[0] in absorbed or q.dst in self.view_of or op.dst in self.view_of:
+            return None
+        return users[0]
 
     @staticmethod
     def _pool_behind(ops, i):

@@ -311,6 +311,28 @@ def test_quantized_combined_conv_argument_checks():
     assert _qcomb(_d(dtype=B.RELAY_I8, c=32)) == 4                             # c % 64: no direct-to-LDS kernel
 
 
+def test_fused_depthwise_pointwise_argument_checks():
+    """The one-launch depthwise + 1x1 entry point and its profitability query validate on the host."""
+    lib = B.lib()
+    dw = lambda **kw: _d(**{**dict(c=64, k=64, r=3, s=3, pad=1, h=56, w=56), **kw})
+    call = lambda d, k=128, pf=0, x=FAKE, w=FAKE + 4096, pw=FAKE + 8192, y=FAKE + (1 << 20), pb=None: \
+        lib.relay_fused_dwconv_pwconv(C.byref(d), x, w, None, None, None, k, pf, pw, pb, None, None, y, None)
+    assert call(dw(pad=0)) == 4 and call(dw(c=40, k=40)) == 4              # padding 1 only; c % 32
+    assert call(dw(dtype=B.RELAY_I8)) == 3
+    assert call(dw(), k=12) == 2 and call(dw(), k=0) == 2
+    assert call(dw(), pf=B.HAS_RESIDUAL) == 4
+    assert call(dw(), pf=B.HAS_BIAS) == 1 and call(dw(), pb=FAKE) == 1      # flag and pointer disagree
+    assert call(dw(), x=None) == 1 and call(dw(), y=FAKE) == 4             # output aliases the input
+    assert call(dw(), pw=FAKE + 8200) == 5
+    assert call(dw(flags=B.HAS_BN)) == 1                                   # dw_scale missing
+    pays = C.c_int32(-1)
+    q = lambda d, k: (lib.relay_dwconv_pwconv_fusion_pays(C.byref(d), k, C.byref(pays)), pays.value)
+    assert q(dw(n=32, c=128, k=128), 128) == (0, 1)                        # streams from memory: one launch pays
+    assert q(dw(n=32, c=512, k=512, h=14, w=14), 512) == (0, 0)            # deep layer: two launches are faster
+    assert q(dw(n=1, c=128, k=128), 128) == (0, 0)                         # too few pixels
+    assert q(dw(pad=0), 128)[0] == 4 and lib.relay_dwconv_pwconv_fusion_pays(C.byref(dw()), 128, None) == 1
+
+
 def test_scale_folding_argument_checks():
     f = lambda *a: _status("relay_fold_scale_axis", *a)
     assert f(B.RELAY_I8, 8, 8, 9, 0, FAKE, FAKE, FAKE, None) == 3

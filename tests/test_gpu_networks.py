@@ -32,9 +32,9 @@ def G():
     return gpu_util
 
 
-def _net(ops, params, batch, hw, mode, shifts=None, cin=3, fuse_pool=True):
+def _net(ops, params, batch, hw, mode, shifts=None, cin=3, fuse_pool=True, fuse_dwpw=True):
     from paper_1904_08368_amd.stack import FusedNet
-    return FusedNet(ops, params, batch, hw, hw, mode, shifts=shifts, in_channels=cin, fuse_pool=fuse_pool)
+    return FusedNet(ops, params, batch, hw, hw, mode, shifts=shifts, in_channels=cin, fuse_pool=fuse_pool, fuse_dwpw=fuse_dwpw)
 
 
 def _report(capsys, title, errs):
@@ -295,13 +295,26 @@ def test_config5_mobilenet_fp16_batch32_end_to_end_as_timed(G, capsys):
     torch.cuda.synchronize()
     names = {a.dst: b.dst for a, b in zip(ops, table)}
     errs = {}
+    fused_blocks = [n for n in net.call_names if n.endswith(".dw+" + n.split(".")[0] + ".pw")]
+    assert len(fused_blocks) >= 3, net.call_names          # the early blocks run as one launch each at this batch
     for a, b in zip(ops, table):
-        if b.dst in ("stem.out", "b1.t", "b1.out", "b4.out", "b9.out", "b13.out") or b.name == "stem":
+        # (the depthwise output of a block that runs as one launch is never written)
+        if (b.dst in ("stem.out", "b1.t", "b1.out", "b4.out", "b9.out", "b13.out") or b.name == "stem") and a.dst in net.bufs:
             errs[b.dst] = O.max_rel_err(net.tensor(a.dst), ref[b.dst])
     errs["logits"] = O.max_rel_err(net.tensor(ops[-1].dst).reshape(32, 1000), ref["logits"])
     _report(capsys, "MobileNet-v1 fp16 batch 32, graph replay, max rel err vs oracle", errs)
+    assert {"b0.out", "b1.out", "b4.out", "b9.out", "b13.out", "logits"} <= set(errs)
     for k, v in errs.items():
         assert v <= TOL_F16_CHAIN_DEEP, (k, v)
+    # the same network with every block as two launches: the one-launch blocks change no bit
+    net2 = _net(ops, params, 32, 224, "f16", fuse_dwpw=False)
+    assert not any("+" in n and ".dw" in n for n in net2.call_names)
+    net2.load_input(x)
+    net2.run()
+    torch.cuda.synchronize()
+    mine = {b.dst: a.dst for a, b in zip(ops, table)}     # the fused graph names its tensors itself
+    for name in ("b1.out", "b5.out", "b13.out", table[-1].dst):
+        assert np.array_equal(net.tensor(mine[name]).view(np.uint16), net2.tensor(mine[name]).view(np.uint16)), name
 
 
 # ------------------------------------------------------------- config 4: ResNet-18 int8
@@ -372,6 +385,14 @@ def test_config5_mobilenet_fp16_chain_and_layers(G):
     for name in ("b4.out", "b9.out", "b13.out"):
         assert O.max_rel_err(net.tensor(name), ref[name]) <= TOL_F16_CHAIN_DEEP, name
     assert O.max_rel_err(net.tensor("logits").reshape(1, 1000), ref["logits"]) <= TOL_F16_CHAIN
+    # every block as one launch (also where the library would not choose to): same bits
+    net1 = _net(ops, params, 1, 224, "f16", fuse_dwpw="always")
+    assert sum(1 for n in net1.call_names if ".dw+" in n) == 13
+    net1.load_input(x)
+    net1.run()
+    torch.cuda.synchronize()
+    for name in ("b1.out", "b6.out", "b13.out", "logits"):
+        assert np.array_equal(net1.tensor(name).view(np.uint16), net.tensor(name).view(np.uint16)), name
 
 
 def test_config5_mobilenet_batch32_sampled(G):
