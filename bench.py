@@ -76,6 +76,17 @@ def _layer_table(net, ops, batch, reps, trials):
             row["tflops"] = row["gflop"] / row["us"] * 1e3           # GFLOP/us = 1000 TFLOP/s
             row["gbs"] = row["mbytes"] / row["us"] * 1e3              # MB/us = 1000 GB/s
             _bounds(row, d.dtype == B.RELAY_I8, fn is B.relay_fused_dwconv_bias_relu)
+        elif fn is B.relay_fused_dwconv_pwconv:
+            # a depthwise conv and its 1x1 conv in one launch: both convs' FLOP; input + output + both filter sets
+            ho, wo = B.relay_conv2d_out_shape(d)
+            k = args[6]
+            row["gflop"] = 2 * d.n * ho * wo * d.c * (9 + k) / 1e9
+            row["kernel"] = B.relay_dwconv_pwconv_kernel_name(d, k)
+            row["mbytes"] = (d.n * d.h * d.w * d.c + d.n * ho * wo * k + 9 * d.c + k * d.c) * 2 / 1e6
+            row["tflops"] = row["gflop"] / row["us"] * 1e3
+            row["gbs"] = row["mbytes"] / row["us"] * 1e3
+            _bounds(row, False, False)
+            row["frac_hbm"] = row["gbs"] / HBM_PEAK_GBS
         elif fn in (B.relay_fused_conv2d_bn_relu_maxpool, B.relay_qconv2d_requant_maxpool):
             # the conv with its max pool in the same launch: the conv's FLOP, input + pooled output + filters
             ho, wo = B.relay_conv2d_out_shape(d)
@@ -326,8 +337,20 @@ def main() -> int:
         dw = [r for r in mrows if r.get("kernel") == "dwconv3x3_f16_kernel"]
         pw = [r for r in mrows if r.get("kernel", "").startswith("igemm")]
         dw_gbs = sum(r["mbytes"] for r in dw) / sum(r["us"] for r in dw) * 1e3
+        blocks = [r for r in mrows if r.get("kernel", "").startswith("dwpw_fused")]
+        # the same network with every block as two launches (what the one-launch blocks are measured against)
+        mn2 = FusedNet(mops, mp, 32, 224, 224, "f16", fuse_dwpw=False)
+        mn2.load_input(inputs.image(5, 32, 3, 224, 224, "f16"))
+        if use_graph:
+            mn2.capture()
+        msec2 = _time_steps(mn2, a.steps, a.warmup, use_graph)
+        del mn2
         extra["mobilenet_v1_fp16_batch32"] = {
             "ms_per_img": round(msec * 1e3 / 32, 5),
+            "ms_per_img_every_block_two_launches": round(msec2 * 1e3 / 32, 5),
+            "one_launch_blocks": [{"name": r["name"], "us": round(r["us"], 2), "gbs": round(r["gbs"], 1),
+                                   "frac_of_hbm_peak": round(r["frac_hbm"], 4),
+                                   "frac_of_measured_copy": round(r["gbs"] / ceil["copy_gbs"], 4)} for r in blocks],
             "tflops": round(2.0 * nets.macs_per_image(mops, 224, 224) * 32 / msec / 1e12, 3),
             "depthwise_gbs": round(dw_gbs, 1), "depthwise_frac_of_hbm_peak": round(dw_gbs / HBM_PEAK_GBS, 4),
             "depthwise_frac_of_measured_copy": round(dw_gbs / ceil["copy_gbs"], 4),

@@ -269,6 +269,9 @@ relay_status relay_fused_dwconv_pwconv(const relay_conv2d_desc* dw, const void* 
  * recompute the depthwise tile once per tile of output channels.  From measurements on MI355X; host-only,
  * nothing is launched.  dw, k as for relay_fused_dwconv_pwconv; same errors for shapes it does not take. */
 relay_status relay_dwconv_pwconv_fusion_pays(const relay_conv2d_desc* dw, int32_t k, int32_t* pays);
+/* Profiling aid (paper Section 4.1 "Lowering": the lowered code is specific to the shape): the name, as a
+ * kernel trace prints it, of the variant relay_fused_dwconv_pwconv runs for this shape. */
+relay_status relay_dwconv_pwconv_kernel_name(const relay_conv2d_desc* dw, int32_t k, char* buf, size_t len);
 
 /* dense as a fused primitive function (paper Section 4.1: a contraction with its elementwise tail;
  * Section 3.3 "Backends": operators are lowered to dense linear algebra kernels; the classifier

@@ -86,6 +86,7 @@ SIGNATURES = {
     "relay_set_conv_split": [_I],
     "relay_set_conv_workgroups": [_I],
     "relay_conv2d_kernel_name": [_DP, C.c_char_p, _SZ],
+    "relay_dwconv_pwconv_kernel_name": [_DP, C.c_int32, C.c_char_p, _SZ],
 }
 
 
@@ -382,6 +383,12 @@ def relay_fuse_extract(pattern: Sequence[int], in_offsets: Sequence[int], in_nod
 def relay_conv2d_kernel_name(d: ConvDesc) -> str:
     buf = C.create_string_buffer(128)
     _check(lib().relay_conv2d_kernel_name(C.byref(d), buf, 128))
+    return buf.value.decode()
+
+
+def relay_dwconv_pwconv_kernel_name(dw: ConvDesc, k: int) -> str:
+    buf = C.create_string_buffer(160)
+    _check(lib().relay_dwconv_pwconv_kernel_name(C.byref(dw), k, buf, 160))
     return buf.value.decode()
 
 

@@ -931,6 +931,18 @@ relay_status relay_dwconv_pwconv_fusion_pays(const relay_conv2d_desc* dw, int32_
   return RELAY_OK;
 }
 
+relay_status relay_dwconv_pwconv_kernel_name(const relay_conv2d_desc* dw, int32_t k, char* buf, size_t len) {
+  if (!buf || len == 0) return fail(RELAY_ERR_NULL, "name buffer is NULL or empty");
+  relay::DwPwArgs a;
+  const relay_status st = dwpw_args(dw, k, 0, &a);
+  if (st != RELAY_OK) return st;
+  const int variant = g_force_tile >= kDwPwBase ? g_force_tile - kDwPwBase : relay::dwpw_any(a);
+  if (variant < 0 || !relay::dwpw_supported(a, variant))
+    return fail(RELAY_ERR_UNSUPPORTED, "no fused depthwise + 1x1 kernel variant takes this shape (variant %d)", variant);
+  relay::dwpw_kernel_name(variant, buf, len);
+  return RELAY_OK;
+}
+
 relay_status relay_fused_dwconv_pwconv(const relay_conv2d_desc* dw, const void* x, const void* dw_w_rsc, const float* dw_bias,
                                        const float* dw_scale, const float* dw_shift, int32_t k, uint32_t pw_flags,
                                        const void* pw_w_packed, const float* pw_bias, const float* pw_scale,
