@@ -125,6 +125,35 @@ def main() -> int:
         run(name, kernel, lambda d=d, x=x, wq=wq, sc=sc, sf=sf, y=y: B.relay_fused_dwconv_bias_relu(d, x, wq, None, sc, sf, y),
             2.0 * 32 * ho * wo * c * 9 / 1e9, (32 * hw * hw * c + 32 * ho * wo * c + 9 * c) * 2 / 1e6)
 
+    # ---- a depthwise conv and its 1x1 conv as one launch (MobileNet-v1 blocks 1-5, batch 32), and block 7, forced
+    for name, c, hw, stride, k, tile in (("dwpw_b1_c32_112", 32, 112, 1, 64, -1), ("dwpw_b2_c64_112_s2", 64, 112, 2, 128, -1),
+                                         ("dwpw_b3_c128_56", 128, 56, 1, 128, -1), ("dwpw_b4_c128_56_s2", 128, 56, 2, 256, -1),
+                                         ("dwpw_b5_c256_28", 256, 28, 1, 256, -1), ("dwpw_b7_c512_14_forced", 512, 14, 1, 512, 305)):
+        d = B.conv_desc(32, c, hw, hw, c, 3, 3, stride, 1, B.RELAY_F16, B.RELAY_NHWC, B.flags_of(None, 1, None, True))
+        ho, wo = B.relay_conv2d_out_shape(d)
+        pflags = B.flags_of(None, 1, None, True)
+        pd = B.conv_desc(32, c, ho, wo, k, 1, 1, 1, 0, B.RELAY_F16, B.RELAY_NHWC, pflags)
+        x = tensor((32, hw, hw, c), False)
+        wq = torch.empty((9, c), dtype=torch.float16, device=dev)
+        B.relay_prepack_dwconv_weights(d, tensor((c, 3, 3), False), wq)
+        wpk = torch.empty(B.relay_packed_weight_bytes(pd), dtype=torch.uint8, device=dev)
+        B.relay_prepack_conv2d_weights(pd, (tensor((k, c, 1, 1), False) * 0.1).to(torch.float16), c, wpk)
+        y = torch.empty((32, ho, wo, k), dtype=torch.float16, device=dev)
+        sc, sf, psc, psf = torch.ones(c, device=dev), torch.zeros(c, device=dev), torch.ones(k, device=dev), torch.zeros(k, device=dev)
+        B.relay_set_conv_tile(tile)
+        try:
+            kernel = B.relay_dwconv_pwconv_kernel_name(d, k)
+        finally:
+            B.relay_set_conv_tile(-1)
+
+        def fn(d=d, x=x, wq=wq, sc=sc, sf=sf, k=k, pflags=pflags, wpk=wpk, psc=psc, psf=psf, y=y, tile=tile):
+            B.relay_set_conv_tile(tile)
+            try:
+                B.relay_fused_dwconv_pwconv(d, x, wq, None, sc, sf, k, pflags, wpk, None, psc, psf, y)
+            finally:
+                B.relay_set_conv_tile(-1)
+        run(name, kernel, fn, 2.0 * 32 * ho * wo * c * (9 + k) / 1e9, (32 * hw * hw * c + 32 * ho * wo * k + 9 * c + k * c) * 2 / 1e6)
+
     # ---- measured ceilings
     out = torch.zeros(1, dtype=torch.int32, device=dev)
     iters, wgs = 256, 256 * 8      # ~0.1 ms per launch: long enough to fill the chip, short enough for 32-bit counters
