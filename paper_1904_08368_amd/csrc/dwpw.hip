@@ -26,12 +26,15 @@
 namespace relay {
 namespace {
 
-// Slot of patch pixel p (in units of one pixel's CV vectors).  Threads that read the same tap of
-// neighbouring micro-tiles are MW*STRIDE pixels apart, a multiple of the LDS bank period; the XOR
-// with a few higher bits of p spreads them over the banks.  An involution inside aligned groups of
-// 16 pixels, so the loader applies the same function to find the pixel that belongs in a slot.
-template <int CV>
+// Slot of patch pixel p (in units of one pixel's CV vectors).  Stride 1: the pixel itself -- with micro-tiles one
+// pixel wide, consecutive lanes read consecutive pixels, a contiguous run of LDS that touches every bank once, and
+// every tap is a compile-time offset from one base address.  Stride 2: neighbouring micro-tiles are an even
+// number of pixels apart, a multiple of the bank period; the XOR with a few higher bits of p spreads them over
+// the banks (an involution inside aligned groups of 16 pixels, so the loader applies the same function to find
+// the pixel that belongs in a slot).
+template <int CV, int STRIDE>
 __device__ __forceinline__ int patch_slot(int p) {
+  if (STRIDE == 1) return p;
   return CV <= 4 ? p ^ ((p >> 2) & 3) : p ^ ((p >> 1) & 1);
 }
 
@@ -146,7 +149,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void dwpw_fused_kernel
   for (int j = 0; j < PL; ++j) {
     const int v = ((j * NW + wave) * 64 + lane);
     const int slot = v / CV, cvl = v % CV;
-    const int p = patch_slot<CV>(slot);
+    const int p = patch_slot<CV, STRIDE>(slot);
     const int py = p / PW, px = p - py * PW;
     const int iy = iy0 + py, ix = ix0 + px;
     const bool ok = p < PH * PW && (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W;
@@ -284,7 +287,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void dwpw_fused_kernel
       uint4 xr[2][IW];
       auto load_row = [&](int pbase, int r, uint4(&dst)[IW]) {
 #pragma unroll
-        for (int q = 0; q < IW; ++q) dst[q] = pt[patch_slot<CV>(pbase + r * PW + q) * CV + cv];
+        for (int q = 0; q < IW; ++q) dst[q] = pt[patch_slot<CV, STRIDE>(pbase + r * PW + q) * CV + cv];
       };
       bool has;
       int pbase, row0;
@@ -426,10 +429,10 @@ struct DwPwVariant {
 };
 // must match launch_variant
 constexpr DwPwVariant kVariants[] = {
-    {1, 4, 28, 1, 2, 2, 2, 2, 2, 1, 2, 3, 256, 2},   // 0: 4 x 28 pixels x 128 channels, 32-channel chunks, two workgroups per CU (many pixels, up to 256 channels)
-    {1, 4, 14, 1, 2, 1, 4, 2, 2, 1, 3, 2, 256, 2},   // 1: 4 x 14 x 256 in a 64-row tile, three patches in flight, two filter stages (256 output channels without recomputation)
-    {1, 4, 28, 1, 4, 2, 2, 2, 4, 1, 2, 3, 256, 1},   // 2: 4 x 28 x 256
-    {1, 8, 16, 1, 2, 2, 2, 2, 1, 1, 1, 3, 32, 4},   // 3: single-chunk layers of 32 channels: 8 x 16 x 64, one buffer of everything, four to six workgroups per CU
+    {1, 4, 28, 2, 1, 2, 2, 2, 2, 1, 2, 3, 256, 2},   // 0: 4 x 28 pixels x 128 channels, 32-channel chunks, two workgroups per CU (many pixels, up to 256 channels)
+    {1, 4, 14, 2, 1, 1, 4, 2, 2, 1, 3, 2, 256, 2},   // 1: 4 x 14 x 256 in a 64-row tile, three patches in flight, two filter stages (256 output channels without recomputation)
+    {1, 4, 28, 2, 1, 2, 2, 2, 4, 1, 2, 3, 256, 1},   // 2: 4 x 28 x 256
+    {1, 8, 16, 2, 1, 2, 2, 2, 1, 1, 1, 3, 32, 4},   // 3: single-chunk layers of 32 channels: 8 x 16 x 64, one buffer of everything, four to six workgroups per CU
     {1, 4, 14, 1, 1, 1, 4, 2, 2, 1, 3, 3, 1024, 1},   // 4: 4 x 14 x 256 in a 64-row tile, up to 1024 channels, three patches in flight (the deep layers: one workgroup per CU)
     {1, 7, 7, 1, 1, 1, 4, 2, 2, 1, 3, 3, 1024, 1},   // 5: a whole 7 x 7 image x 256
     {2, 4, 28, 1, 2, 2, 2, 2, 2, 1, 2, 3, 256, 1},   // 6: stride 2, 4 x 28 x 128
@@ -437,6 +440,10 @@ constexpr DwPwVariant kVariants[] = {
     {2, 4, 14, 1, 2, 2, 2, 1, 2, 2, 1, 3, 64, 2},   // 8: stride 2, single-chunk layers of 64 channels: 4 x 14 x 128
     {2, 4, 14, 1, 1, 1, 4, 2, 2, 1, 3, 3, 1024, 1},   // 9: stride 2, 4 x 14 x 256 in a 64-row tile, up to 1024 channels
     {2, 7, 7, 1, 1, 1, 4, 2, 2, 1, 3, 3, 1024, 1},   // 10: stride 2, 7 x 7 x 256
+    {1, 4, 14, 1, 1, 2, 4, 1, 2, 2, 3, 2, 1024, 2},   // 11: 4 x 14 x 256, eight waves (two per SIMD), 64-channel chunks
+    {2, 4, 14, 1, 1, 2, 4, 1, 2, 1, 3, 2, 1024, 2},   // 12: stride 2, 4 x 14 x 256, eight waves
+    {1, 7, 7, 1, 1, 2, 4, 1, 2, 2, 3, 2, 1024, 2},   // 13: a whole 7 x 7 image x 256, eight waves, 64-channel chunks
+    {2, 7, 7, 1, 1, 2, 4, 1, 2, 1, 3, 2, 1024, 2},   // 14: stride 2, 7 x 7 x 256, eight waves
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
@@ -454,17 +461,21 @@ hipError_t launch_one(const DwPwArgs& a, hipStream_t st) {
 
 hipError_t launch_variant(const DwPwArgs& a, int v, hipStream_t st) {
   switch (v) {
-    case 0: return launch_one<1, 4, 28, 1, 2, 2, 2, 2, 2, 1, 2, 3, 256, 2>(a, st);
-    case 1: return launch_one<1, 4, 14, 1, 2, 1, 4, 2, 2, 1, 3, 2, 256, 2>(a, st);
-    case 2: return launch_one<1, 4, 28, 1, 4, 2, 2, 2, 4, 1, 2, 3, 256, 1>(a, st);
-    case 3: return launch_one<1, 8, 16, 1, 2, 2, 2, 2, 1, 1, 1, 3, 32, 4>(a, st);
+    case 0: return launch_one<1, 4, 28, 2, 1, 2, 2, 2, 2, 1, 2, 3, 256, 2>(a, st);
+    case 1: return launch_one<1, 4, 14, 2, 1, 1, 4, 2, 2, 1, 3, 2, 256, 2>(a, st);
+    case 2: return launch_one<1, 4, 28, 2, 1, 2, 2, 2, 4, 1, 2, 3, 256, 1>(a, st);
+    case 3: return launch_one<1, 8, 16, 2, 1, 2, 2, 2, 1, 1, 1, 3, 32, 4>(a, st);
     case 4: return launch_one<1, 4, 14, 1, 1, 1, 4, 2, 2, 1, 3, 3, 1024, 1>(a, st);
     case 5: return launch_one<1, 7, 7, 1, 1, 1, 4, 2, 2, 1, 3, 3, 1024, 1>(a, st);
     case 6: return launch_one<2, 4, 28, 1, 2, 2, 2, 2, 2, 1, 2, 3, 256, 1>(a, st);
     case 7: return launch_one<2, 4, 28, 1, 2, 2, 2, 2, 4, 1, 2, 3, 256, 1>(a, st);
     case 8: return launch_one<2, 4, 14, 1, 2, 2, 2, 1, 2, 2, 1, 3, 64, 2>(a, st);
     case 9: return launch_one<2, 4, 14, 1, 1, 1, 4, 2, 2, 1, 3, 3, 1024, 1>(a, st);
-    default: return launch_one<2, 7, 7, 1, 1, 1, 4, 2, 2, 1, 3, 3, 1024, 1>(a, st);
+    case 10: return launch_one<2, 7, 7, 1, 1, 1, 4, 2, 2, 1, 3, 3, 1024, 1>(a, st);
+    case 11: return launch_one<1, 4, 14, 1, 1, 2, 4, 1, 2, 2, 3, 2, 1024, 2>(a, st);
+    case 12: return launch_one<2, 4, 14, 1, 1, 2, 4, 1, 2, 1, 3, 2, 1024, 2>(a, st);
+    case 13: return launch_one<1, 7, 7, 1, 1, 2, 4, 1, 2, 2, 3, 2, 1024, 2>(a, st);
+    default: return launch_one<2, 7, 7, 1, 1, 2, 4, 1, 2, 1, 3, 2, 1024, 2>(a, st);
   }
 }
 
@@ -482,21 +493,24 @@ bool dwpw_supported(const DwPwArgs& a, int v) {
 
 // The variant measured fastest on the layer shapes of the MobileNet family at batch 32, where it beats
 // the two separate launches; -1 where it does not.  What the fused kernel saves is the round trip of the
-// depthwise output through memory, so it pays on the layers that stream from memory (many pixels, up
-// to 256 channels: 32 % to 15 % less time per block).  On the deep layers (few pixels, 512 channels and
-// more) the work has to be cut along the output channels to fill the chip, every such workgroup
-// recomputes the depthwise tile on the vector ALUs, and the two launches are faster (measured 16.8 us
-// against 18.0 us for the best variant on 512 channels at 14 x 14).
+// depthwise output through memory and one launch.  It pays most on the layers that stream from memory
+// (many pixels, up to 256 channels: 35 % to 15 % less time per block).  With few pixels (the deep
+// layers) the work has to be cut along the output channels to fill the chip and every such workgroup
+// recomputes the depthwise tile on the vector ALUs: with eight waves per workgroup (two per SIMD, so that
+// one wave's LDS and barrier waits are covered by the other) the 512-channel layers at 14 x 14 still gain
+// 14 % (two channel tiles), the layers with 1024 output channels (four tiles) lose and stay two launches.
 int dwpw_pick(const DwPwArgs& a) {
   const long px = (long)a.N * a.Ho * a.Wo;
   const int k = a.pw.K;
   int v = -1;
   if (a.stride == 1) {
     if (a.C == 32 && px >= 65536) v = 3;
-    else if (a.C >= 64 && a.C <= 256 && px >= 16384) v = k >= 256 ? 1 : 0;
+    else if (a.C >= 64 && a.C <= 256 && px >= 16384) v = k >= 256 ? 2 : 0;
+    else if (a.C > 256 && a.C <= 512 && k <= 512 && px >= 4096) v = 11;
   } else {
     if (a.C == 64 && px >= 65536) v = 8;
-    else if (a.C <= 256 && k >= 256 && px >= 16384) v = 7;
+    else if (a.C <= 256 && k >= 256 && k <= 512 && px >= 16384) v = 7;
+    else if (a.C <= 256 && k <= 512 && px >= 4096 && px < 16384) v = 14;
   }
   return (v >= 0 && dwpw_supported(a, v)) ? v : -1;
 }

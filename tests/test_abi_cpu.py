@@ -328,7 +328,7 @@ def test_fused_depthwise_pointwise_argument_checks():
     pays = C.c_int32(-1)
     q = lambda d, k: (lib.relay_dwconv_pwconv_fusion_pays(C.byref(d), k, C.byref(pays)), pays.value)
     assert q(dw(n=32, c=128, k=128), 128) == (0, 1)                        # streams from memory: one launch pays
-    assert q(dw(n=32, c=512, k=512, h=14, w=14), 512) == (0, 0)            # deep layer: two launches are faster
+    assert q(dw(n=32, c=1024, k=1024, h=7, w=7), 1024) == (0, 0)           # deepest layer: two launches are faster
     assert q(dw(n=1, c=128, k=128), 128) == (0, 0)                         # too few pixels
     assert q(dw(pad=0), 128)[0] == 4 and lib.relay_dwconv_pwconv_fusion_pays(C.byref(dw()), 128, None) == 1
 

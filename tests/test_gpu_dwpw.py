@@ -11,7 +11,7 @@ pytestmark = pytest.mark.gpu
 
 TOL_F16 = 1e-2
 # stride of every kernel variant, in the library's order
-VARIANT_STRIDE = (1, 1, 1, 1, 1, 1, 2, 2, 2, 2, 2)
+VARIANT_STRIDE = (1, 1, 1, 1, 1, 1, 2, 2, 2, 2, 2, 1, 2, 1, 2)
 # variants that take one channel count only (the whole reduction is one chunk)
 VARIANT_ONLY_C = {3: 32, 8: 64}
 N_VARIANTS = len(VARIANT_STRIDE)
