@@ -429,21 +429,16 @@ struct DwPwVariant {
 };
 // must match launch_variant
 constexpr DwPwVariant kVariants[] = {
-    {1, 4, 28, 2, 1, 2, 2, 2, 2, 1, 2, 3, 256, 2},   // 0: 4 x 28 pixels x 128 channels, 32-channel chunks, two workgroups per CU (many pixels, up to 256 channels)
-    {1, 4, 14, 2, 1, 1, 4, 2, 2, 1, 3, 2, 256, 2},   // 1: 4 x 14 x 256 in a 64-row tile, three patches in flight, two filter stages (256 output channels without recomputation)
-    {1, 4, 28, 2, 1, 2, 2, 2, 4, 1, 2, 3, 256, 1},   // 2: 4 x 28 x 256
-    {1, 8, 16, 2, 1, 2, 2, 2, 1, 1, 1, 3, 32, 4},   // 3: single-chunk layers of 32 channels: 8 x 16 x 64, one buffer of everything, four to six workgroups per CU
-    {1, 4, 14, 1, 1, 1, 4, 2, 2, 1, 3, 3, 1024, 1},   // 4: 4 x 14 x 256 in a 64-row tile, up to 1024 channels, three patches in flight (the deep layers: one workgroup per CU)
-    {1, 7, 7, 1, 1, 1, 4, 2, 2, 1, 3, 3, 1024, 1},   // 5: a whole 7 x 7 image x 256
-    {2, 4, 28, 1, 2, 2, 2, 2, 2, 1, 2, 3, 256, 1},   // 6: stride 2, 4 x 28 x 128
-    {2, 4, 28, 1, 2, 2, 2, 2, 4, 1, 2, 3, 256, 1},   // 7: stride 2, 4 x 28 x 256
-    {2, 4, 14, 1, 2, 2, 2, 1, 2, 2, 1, 3, 64, 2},   // 8: stride 2, single-chunk layers of 64 channels: 4 x 14 x 128
-    {2, 4, 14, 1, 1, 1, 4, 2, 2, 1, 3, 3, 1024, 1},   // 9: stride 2, 4 x 14 x 256 in a 64-row tile, up to 1024 channels
-    {2, 7, 7, 1, 1, 1, 4, 2, 2, 1, 3, 3, 1024, 1},   // 10: stride 2, 7 x 7 x 256
-    {1, 4, 14, 1, 1, 2, 4, 1, 2, 2, 3, 2, 1024, 2},   // 11: 4 x 14 x 256, eight waves (two per SIMD), 64-channel chunks
-    {2, 4, 14, 1, 1, 2, 4, 1, 2, 1, 3, 2, 1024, 2},   // 12: stride 2, 4 x 14 x 256, eight waves
-    {1, 7, 7, 1, 1, 2, 4, 1, 2, 2, 3, 2, 1024, 2},   // 13: a whole 7 x 7 image x 256, eight waves, 64-channel chunks
-    {2, 7, 7, 1, 1, 2, 4, 1, 2, 1, 3, 2, 1024, 2},   // 14: stride 2, 7 x 7 x 256, eight waves
+    {1, 4, 28, 2, 1, 2, 2, 2, 2, 1, 2, 3, 256, 2},   // 0: 4 x 28 pixels x 128 channels, 32-channel chunks, four waves, two workgroups per CU (many pixels, up to 256 channels in, 128 out)
+    {1, 8, 16, 2, 1, 2, 2, 2, 1, 1, 1, 3, 32, 4},   // 1: single-chunk layers of 32 channels: 8 x 16 x 64, one buffer of everything, four to six workgroups per CU
+    {1, 4, 28, 1, 1, 2, 4, 2, 2, 1, 3, 2, 256, 2},   // 2: 4 x 28 x 256, eight waves (two per SIMD: one wave's LDS and barrier waits are covered by the other), three patches in flight, two filter stages
+    {1, 4, 14, 1, 1, 2, 4, 1, 2, 2, 3, 2, 1024, 2},   // 3: 4 x 14 x 256 in a 64-row tile, eight waves, 64-channel chunks, up to 1024 channels (the layers with few pixels)
+    {1, 4, 14, 1, 1, 1, 4, 2, 2, 1, 3, 3, 1024, 1},   // 4: 4 x 14 x 256 in a 64-row tile, four waves, 32-channel chunks: takes every stride-1 shape
+    {2, 4, 14, 1, 1, 2, 4, 1, 1, 2, 1, 3, 64, 4},   // 5: stride 2, single-chunk layers of 64 channels: 4 x 14 x 128, eight waves
+    {2, 4, 28, 1, 1, 2, 4, 2, 2, 1, 2, 3, 256, 2},   // 6: stride 2, 4 x 28 x 256, eight waves
+    {2, 7, 7, 1, 1, 2, 4, 1, 2, 1, 3, 2, 1024, 2},   // 7: stride 2, 7 x 7 x 256 in a 64-row tile, eight waves (the layers with few pixels)
+    {2, 4, 28, 1, 2, 2, 2, 2, 2, 1, 2, 3, 256, 1},   // 8: stride 2, 4 x 28 x 128, four waves
+    {2, 4, 14, 1, 1, 1, 4, 2, 2, 1, 3, 3, 1024, 1},   // 9: stride 2, 4 x 14 x 256 in a 64-row tile, four waves: takes every stride-2 shape
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
@@ -462,20 +457,15 @@ hipError_t launch_one(const DwPwArgs& a, hipStream_t st) {
 hipError_t launch_variant(const DwPwArgs& a, int v, hipStream_t st) {
   switch (v) {
     case 0: return launch_one<1, 4, 28, 2, 1, 2, 2, 2, 2, 1, 2, 3, 256, 2>(a, st);
-    case 1: return launch_one<1, 4, 14, 2, 1, 1, 4, 2, 2, 1, 3, 2, 256, 2>(a, st);
-    case 2: return launch_one<1, 4, 28, 2, 1, 2, 2, 2, 4, 1, 2, 3, 256, 1>(a, st);
-    case 3: return launch_one<1, 8, 16, 2, 1, 2, 2, 2, 1, 1, 1, 3, 32, 4>(a, st);
+    case 1: return launch_one<1, 8, 16, 2, 1, 2, 2, 2, 1, 1, 1, 3, 32, 4>(a, st);
+    case 2: return launch_one<1, 4, 28, 1, 1, 2, 4, 2, 2, 1, 3, 2, 256, 2>(a, st);
+    case 3: return launch_one<1, 4, 14, 1, 1, 2, 4, 1, 2, 2, 3, 2, 1024, 2>(a, st);
     case 4: return launch_one<1, 4, 14, 1, 1, 1, 4, 2, 2, 1, 3, 3, 1024, 1>(a, st);
-    case 5: return launch_one<1, 7, 7, 1, 1, 1, 4, 2, 2, 1, 3, 3, 1024, 1>(a, st);
-    case 6: return launch_one<2, 4, 28, 1, 2, 2, 2, 2, 2, 1, 2, 3, 256, 1>(a, st);
-    case 7: return launch_one<2, 4, 28, 1, 2, 2, 2, 2, 4, 1, 2, 3, 256, 1>(a, st);
-    case 8: return launch_one<2, 4, 14, 1, 2, 2, 2, 1, 2, 2, 1, 3, 64, 2>(a, st);
-    case 9: return launch_one<2, 4, 14, 1, 1, 1, 4, 2, 2, 1, 3, 3, 1024, 1>(a, st);
-    case 10: return launch_one<2, 7, 7, 1, 1, 1, 4, 2, 2, 1, 3, 3, 1024, 1>(a, st);
-    case 11: return launch_one<1, 4, 14, 1, 1, 2, 4, 1, 2, 2, 3, 2, 1024, 2>(a, st);
-    case 12: return launch_one<2, 4, 14, 1, 1, 2, 4, 1, 2, 1, 3, 2, 1024, 2>(a, st);
-    case 13: return launch_one<1, 7, 7, 1, 1, 2, 4, 1, 2, 2, 3, 2, 1024, 2>(a, st);
-    default: return launch_one<2, 7, 7, 1, 1, 2, 4, 1, 2, 1, 3, 2, 1024, 2>(a, st);
+    case 5: return launch_one<2, 4, 14, 1, 1, 2, 4, 1, 1, 2, 1, 3, 64, 4>(a, st);
+    case 6: return launch_one<2, 4, 28, 1, 1, 2, 4, 2, 2, 1, 2, 3, 256, 2>(a, st);
+    case 7: return launch_one<2, 7, 7, 1, 1, 2, 4, 1, 2, 1, 3, 2, 1024, 2>(a, st);
+    case 8: return launch_one<2, 4, 28, 1, 2, 2, 2, 2, 2, 1, 2, 3, 256, 1>(a, st);
+    default: return launch_one<2, 4, 14, 1, 1, 1, 4, 2, 2, 1, 3, 3, 1024, 1>(a, st);
   }
 }
 
@@ -504,13 +494,13 @@ int dwpw_pick(const DwPwArgs& a) {
   const int k = a.pw.K;
   int v = -1;
   if (a.stride == 1) {
-    if (a.C == 32 && px >= 65536) v = 3;
+    if (a.C == 32 && px >= 65536) v = 1;
     else if (a.C >= 64 && a.C <= 256 && px >= 16384) v = k >= 256 ? 2 : 0;
-    else if (a.C > 256 && a.C <= 512 && k <= 512 && px >= 4096) v = 11;
+    else if (a.C > 256 && a.C <= 512 && k <= 512 && px >= 4096) v = 3;
   } else {
-    if (a.C == 64 && px >= 65536) v = 8;
-    else if (a.C <= 256 && k >= 256 && k <= 512 && px >= 16384) v = 7;
-    else if (a.C <= 256 && k <= 512 && px >= 4096 && px < 16384) v = 14;
+    if (a.C == 64 && px >= 65536) v = 5;
+    else if (a.C <= 256 && k >= 256 && k <= 512 && px >= 16384) v = 6;
+    else if (a.C <= 256 && k <= 512 && px >= 4096 && px < 16384) v = 7;
   }
   return (v >= 0 && dwpw_supported(a, v)) ? v : -1;
 }
@@ -519,7 +509,7 @@ int dwpw_pick(const DwPwArgs& a) {
 int dwpw_any(const DwPwArgs& a) {
   const int p = dwpw_pick(a);
   if (p >= 0) return p;
-  const int prefer[] = {0, 4, 6, 9};
+  const int prefer[] = {0, 4, 8, 9};
   for (int v : prefer)
     if (dwpw_supported(a, v)) return v;
   for (int v = 0; v < kNumVariants; ++v)

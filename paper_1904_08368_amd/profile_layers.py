@@ -125,10 +125,11 @@ def main() -> int:
         run(name, kernel, lambda d=d, x=x, wq=wq, sc=sc, sf=sf, y=y: B.relay_fused_dwconv_bias_relu(d, x, wq, None, sc, sf, y),
             2.0 * 32 * ho * wo * c * 9 / 1e9, (32 * hw * hw * c + 32 * ho * wo * c + 9 * c) * 2 / 1e6)
 
-    # ---- a depthwise conv and its 1x1 conv as one launch (MobileNet-v1 blocks 1-5, batch 32), and block 7, forced
+    # ---- a depthwise conv and its 1x1 conv as one launch (MobileNet-v1 blocks 1-5 and 7, batch 32), and block 13, forced
     for name, c, hw, stride, k, tile in (("dwpw_b1_c32_112", 32, 112, 1, 64, -1), ("dwpw_b2_c64_112_s2", 64, 112, 2, 128, -1),
                                          ("dwpw_b3_c128_56", 128, 56, 1, 128, -1), ("dwpw_b4_c128_56_s2", 128, 56, 2, 256, -1),
-                                         ("dwpw_b5_c256_28", 256, 28, 1, 256, -1), ("dwpw_b7_c512_14_forced", 512, 14, 1, 512, 304)):
+                                         ("dwpw_b5_c256_28", 256, 28, 1, 256, -1), ("dwpw_b7_c512_14", 512, 14, 1, 512, -1),
+                                         ("dwpw_b13_c1024_7_forced", 1024, 7, 1, 1024, 303)):
         d = B.conv_desc(32, c, hw, hw, c, 3, 3, stride, 1, B.RELAY_F16, B.RELAY_NHWC, B.flags_of(None, 1, None, True))
         ho, wo = B.relay_conv2d_out_shape(d)
         pflags = B.flags_of(None, 1, None, True)
