@@ -71,8 +71,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void dwpw_fused_kernel
   constexpr int PBUF = PL * NW * 64;               // slots (16 bytes) of one patch buffer
   constexpr int APLANE = BM * BKV, ACT = KP * APLANE;   // depthwise output tile: KP planes of [BM][64 B]
   constexpr int WB = BN / 16;                      // 1 KiB load blocks of one filter plane
-  static_assert(WB % NW == 0, "filter blocks must divide over the waves");
-  constexpr int WL = WB / NW;
+  // (single-chunk layers wait for all their loads at once, so their waves need not issue equal numbers of them)
+  static_assert(NP == 1 || WB % NW == 0, "filter blocks must divide over the waves");
+  constexpr int WL = (WB + NW - 1) / NW;
   constexpr int FL = KP * WL;                      // filter loads per chunk per wave
   constexpr int LPI = PL + FL;                     // loads per iteration per wave
   static_assert(LPI <= 63, "vmcnt is a 6-bit counter");
@@ -183,8 +184,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void dwpw_fused_kernel
     for (int plane = 0; plane < KP; ++plane)
 #pragma unroll
       for (int j = 0; j < WL; ++j)
-        lds_dma16(rs_w, stage + (unsigned)(plane * FPLANE + (wave * WL + j) * 64) * 16u,
-                  live ? w_off[j] + (unsigned)((kc * CK + plane * 32) * 2) : kOob);
+        if (WB % NW == 0 || wave * WL + j < WB)   // (uniform)
+          lds_dma16(rs_w, stage + (unsigned)(plane * FPLANE + (wave * WL + j) * 64) * 16u,
+                    live ? w_off[j] + (unsigned)((kc * CK + plane * 32) * 2) : kOob);
   };
   // Iteration j of the main loop requests patch j+NP and filters j+2.  With two patch buffers the patch
   // goes first and the filters of the same iteration may still be in flight when the patch is needed;
