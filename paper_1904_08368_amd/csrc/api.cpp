@@ -249,6 +249,8 @@ relay_status relay_pack_input_nhwc4(const relay_conv2d_desc* d, const void* x_nc
   if (!x_nchw || !y) return fail(RELAY_ERR_NULL, "x_nchw and y are required");
   if (x_nchw == y) return fail(RELAY_ERR_UNSUPPORTED, "output must not alias an input");
   if (!aligned(y, 16)) return fail(RELAY_ERR_ALIGN, "y must be 16-byte aligned");
+  if ((long)d->n * (d->h + 2 * d->pad_h) * nhwc4_padded_w(d) * 4 * esize_of(d->dtype) > 0x7fffffffL)
+    return fail(RELAY_ERR_SHAPE, "padded input exceeds 2^31-1 bytes");
   return device_status(relay::launch_pack_input_nhwc4(esize_of(d->dtype), d->n, d->c, d->h, d->w, d->pad_h, d->pad_w,
                                                       nhwc4_padded_w(d), x_nchw, y, static_cast<hipStream_t>(hip_stream)),
                        "NHWC4 input packing");

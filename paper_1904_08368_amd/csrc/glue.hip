@@ -51,13 +51,14 @@ __global__ __launch_bounds__(256) void nchw_to_nhwc_kernel(const T* x, T* y, int
 template <typename T, typename V4>
 __global__ __launch_bounds__(256) void pack_input_nhwc4_kernel(const T* x, V4* y, int N, int C, int H, int W, int ph,
                                                                int pw, int Hp, int Wp) {
-  const long total = (long)N * Hp * Wp;
-  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  // (32-bit index arithmetic: the padded tensor has fewer than 2^31 pixels, checked by the entry point)
+  const unsigned total = (unsigned)N * Hp * Wp;
+  const unsigned idx = blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= total) return;
-  const int wq = (int)(idx % Wp);
-  long t = idx / Wp;
-  const int hq = (int)(t % Hp);
-  const int n = (int)(t / Hp);
+  const int wq = (int)(idx % (unsigned)Wp);
+  const unsigned t = idx / (unsigned)Wp;
+  const int hq = (int)(t % (unsigned)Hp);
+  const int n = (int)(t / (unsigned)Hp);
   const int h = hq - ph, w_ = wq - pw;
   T v[4] = {0, 0, 0, 0};
   if ((unsigned)h < (unsigned)H && (unsigned)w_ < (unsigned)W) {

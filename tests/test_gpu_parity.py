@@ -103,7 +103,7 @@ def test_fp16_conv_full_epilogue(G, case):
 
 
 @pytest.mark.parametrize("c", [64, 24, 128])     # 64, 128: direct-to-LDS kernel (128 admits every chunk length); 24: register-staged kernel
-@pytest.mark.parametrize("tile", list(range(17)))
+@pytest.mark.parametrize("tile", list(range(18)))
 @pytest.mark.parametrize("n", [2, 5])            # filters larger than the activations, and the reverse: both tile orders
 def test_fp16_conv_every_tile_shape(G, tile, c, n):
     g = _rng(50)
@@ -193,7 +193,7 @@ def test_int8_qconv_bit_exact(G, case):
 
 
 @pytest.mark.parametrize("c", [64, 48, 256])     # 256 int8 channels admit every chunk length
-@pytest.mark.parametrize("tile", list(range(17)))
+@pytest.mark.parametrize("tile", list(range(18)))
 def test_int8_every_tile_shape_and_repeatable(G, tile, c):
     g = _rng(150)
     x = g.integers(-127, 128, (2, c, 23, 27)).astype(np.int8)
