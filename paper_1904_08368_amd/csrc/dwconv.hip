@@ -275,18 +275,28 @@ hipError_t launch_dw(const ConvArgs& a, hipStream_t st) {
 }  // namespace
 
 // 2x4 (stride 1) and 2x2 (stride 2) outputs per thread: measured faster than smaller patches
-// on every MobileNet layer, including the 7x7 ones.
+// on every MobileNet layer at batch 32, including the 7x7 ones.
 hipError_t launch_dwconv_f16(const ConvArgs& a, hipStream_t st) {
-  // rows of at least one 28-pixel tile: the LDS-staged kernel (measured faster from 28 x 28 up)
-  // rows of at least one 28-pixel tile: the LDS-staged kernel (measured faster from 28 x 28 up;
-  // small workgroups on the large images, where eight of them share a CU and overlap their
-  // load, compute and store phases)
-  if (a.sh == 1 && a.sw == 1 && a.Wo >= 28 && a.Ho >= 8 && a.C % 32 == 0) {
+  // rows of at least one 28-pixel tile and enough outputs to give every CU several workgroups: the LDS-staged
+  // kernel (measured faster from 28 x 28 up at batch 32; small workgroups on the large images, where eight of
+  // them share a CU and overlap their load, compute and store phases)
+  const long vecs = (long)a.N * a.Ho * a.Wo * (a.C / 8);   // (pixel, 8-channel vector) outputs
+  if (a.sh == 1 && a.sw == 1 && a.Wo >= 28 && a.Ho >= 8 && a.C % 32 == 0 && vecs >= 8 * 65536) {
     if (a.Wo >= 56) return launch_dw_lds<4, 4, 128>(a, st);
     return launch_dw_lds<4, 8, 256>(a, st);
   }
-  if (a.sh == 1) return launch_dw<1, 2, 4>(a, st);
-  return launch_dw<2, 2, 2>(a, st);
+  // Few outputs (small batches, the deep layers): the large per-thread patches would leave most CUs without a
+  // workgroup -- 14 x 14 x 512 at batch 1 is six workgroups of 2 x 4 patches -- and the layer's time is then the
+  // latency of one thread's chain of loads, multiply-adds and stores; smaller patches spread it over the chip.
+  if (a.sh == 1) {
+    // (measured: 14 x 14 x 512 at batch 1, 12.5 k outputs, 6.0 -> 4.4 us with 1 x 1 patches; at batch 32, 401 k
+    // outputs, 6.7 us with 2 x 4 patches against 12.2 us with 1 x 2)
+    if (vecs >= 2 * 65536) return launch_dw<1, 2, 4>(a, st);
+    if (vecs >= 65536) return launch_dw<1, 1, 2>(a, st);
+    return launch_dw<1, 1, 1>(a, st);
+  }
+  if (vecs >= 65536) return launch_dw<2, 2, 2>(a, st);
+  return launch_dw<2, 1, 1>(a, st);
 }
 
 }  // namespace relay
