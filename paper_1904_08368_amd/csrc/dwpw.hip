@@ -13,7 +13,13 @@
 //      scale/shift/relu as the standalone depthwise kernels), narrow them to fp16 and write them into
 //      LDS in the layout the matrix cores read their activation operand from;
 //   3. the matrix cores multiply that tile with the chunk of 1x1 filters that has meanwhile arrived
-//      in a two-stage LDS ring, as in the implicit-GEMM kernel.
+//      in an LDS ring of two or three stages, as in the implicit-GEMM kernel.
+// The chunks are pipelined: one barrier per chunk, behind which the patch two or three chunks ahead and
+// the filters one or two chunks ahead are requested, and the depthwise work of chunk kc + 1 is
+// interleaved with the matrix instructions of chunk kc.  Layers whose channels fit one chunk run a
+// straight-line form with one buffer of everything (little LDS, few registers, many workgroups per CU).
+// Variants with eight waves put two waves on every SIMD, so that one wave's wait for the barrier or for
+// LDS is covered by the other's arithmetic.
 // The fp16 narrowing in the middle is that of the two-kernel pipeline, and the 1x1 reduction runs
 // in the same order with the same instruction, so the result equals the two launches bit for bit.
 // A workgroup per tile of output channels recomputes the depthwise tile; with few output pixels
