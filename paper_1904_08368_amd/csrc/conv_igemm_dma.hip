@@ -103,6 +103,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
                "s"(a.tap_spread), "s"(a.param_vec), "s"(a.n_major), "s"(a.M), "s"(a.Kred), "s"(a.Kp), "s"(a.flags));
   asm volatile("" ::"s"(a.fd_wo.mul), "s"(a.fd_wo.shift), "s"(a.fd_howo.mul), "s"(a.fd_howo.shift), "s"(a.fd_tiles_m.mul),
                "s"(a.fd_tiles_m.shift), "s"(a.fd_tiles_n.mul), "s"(a.fd_tiles_n.shift));
+  if constexpr (IS_I8)   // (the quantized tail's own arguments too: asked for at its first use they cost it a scalar-load round trip per branch)
+    asm volatile("" ::"s"(a.res), "s"(a.y), "s"(a.lshift), "s"(a.rshift), "s"(a.round_add), "s"(a.qmode), "s"(a.clip_lo), "s"(a.clip_hi),
+                 "s"(a.qmult), "s"(a.qshift));
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -458,6 +461,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
     // channels 8 (v / 4) + 4 (lane / 32) + v % 4) and write the narrowed values, four channels at a
     // time, into the patch.
     char* patch_w = reinterpret_cast<char*>(ring);
+    const ClipBounds qb = clip_bounds(a, a.flags & F_RELU);
+    // (the quantized tail in both of its forms, chosen once for the tile)
+    auto narrow = [&](auto sat) {
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
@@ -470,15 +476,11 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
         for (int tm = 0; tm < TM; ++tm) {
           char* dst = patch_w + (wm * WTM + tm * 32 + lrow) * PPITCH + cb * ES;
           if constexpr (IS_I8) {
-            unsigned pk = 0u;
+            int q[4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              int q = shift_round(acc[tn][tm][4 * g + e] + __builtin_bit_cast(int, m4[e]), (unsigned)a.round_add, a.rshift);
-              q = q < a.clip_lo ? a.clip_lo : (q > a.clip_hi ? a.clip_hi : q);
-              if (a.flags & F_RELU) q = q > 0 ? q : 0;
-              pk |= (unsigned)(q & 0xff) << (8 * e);
-            }
-            *reinterpret_cast<unsigned*>(dst) = pk;
+            for (int e = 0; e < 4; ++e)
+              q[e] = shift_round_clip<decltype(sat)::value>(acc[tn][tm][4 * g + e] + __builtin_bit_cast(int, m4[e]), a, qb);
+            *reinterpret_cast<unsigned*>(dst) = pack_low_bytes(q[0], q[1], q[2], q[3]);
           } else {
             typedef _Float16 half4v __attribute__((ext_vector_type(4)));
             half4v hv;
@@ -496,6 +498,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
           }
         }
       }
+    };
+    if (!IS_I8 || qb.sat_ok) narrow(std::true_type{});
+    else narrow(std::false_type{});
   }
   uint4* stg = ring + NW * XCH + wave * (32 * EP);
   constexpr int PPI = 64 / CG;  // pixels per pass of 64 lanes
@@ -865,9 +870,10 @@ int igemm_dma_plan_split(const ConvArgs& a, bool is_i8, int tile, int want, size
     // still be spread over the idle CUs.  Handing a tile over costs about as much as six chunks of
     // the main loop and grows with the number of workgroups (measured on 7x7 and 14x14 layers of
     // 256 and 512 channels at batch 1 to 16): at least six chunks per workgroup, at most 128
-    // workgroups, and only layers of at most 32 tiles.
+    // workgroups, and only layers of at most 32 tiles and at least 24 chunks (int8: 12).
     split = 1;
-    if (tiles <= 32 && chunks >= 12) {
+    // (fp16, 18 chunks, 16 tiles -- 256 channels at 14 x 14, batch 1: 8.5 us unsplit, 9.3 us in three)
+    if (tiles <= 32 && chunks >= (is_i8 ? 12 : 24)) {
       split = 128 / tiles;
       if (split > chunks / 6) split = chunks / 6;
       if (split > 16) split = 16;

@@ -269,6 +269,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, WGS) void conv3x3_stream_ke
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) asm volatile("" : "+v"(resv[tm][tn][q4]));
   };
+  const ClipBounds qb = clip_bounds(a, a.flags & F_RELU);
   auto finish_tile = [&](int tile_m) {
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm) {
@@ -285,16 +286,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, WGS) void conv3x3_stream_ke
             const int ib[4] = {__builtin_bit_cast(int, c0.x), __builtin_bit_cast(int, c0.y), __builtin_bit_cast(int, c0.z),
                                __builtin_bit_cast(int, c0.w)};
             const unsigned rv = (unsigned)resv[tm][tn][q4];
-            unsigned pk = 0u;
+            int q[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-              int t = acc[tn][tm][4 * q4 + e] + ib[e] + (int)(int8_t)(rv >> (8 * e)) * (1 << a.lshift);
-              int q = shift_round(t, (unsigned)a.round_add, a.rshift);
-              q = q < a.clip_lo ? a.clip_lo : (q > a.clip_hi ? a.clip_hi : q);
-              if (a.flags & F_RELU) q = q > 0 ? q : 0;
-              pk |= (unsigned)(q & 0xff) << (8 * e);
+              const int t = acc[tn][tm][4 * q4 + e] + ib[e] + (int)(int8_t)(rv >> (8 * e)) * (1 << a.lshift);
+              q[e] = shift_round_clip<false>(t, a, qb);   // (the exact form: this kernel runs only where a caller forces it)
             }
-            __builtin_amdgcn_raw_buffer_store_b32(pk, rs_y, (int)off, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b32(pack_low_bytes(q[0], q[1], q[2], q[3]), rs_y, (int)off, 0, 0);
           } else {
             const float4 c1 = *reinterpret_cast<const float4*>(cst + BN + cb);
             const float m4[4] = {c0.x, c0.y, c0.z, c0.w}, a4[4] = {c1.x, c1.y, c1.z, c1.w};

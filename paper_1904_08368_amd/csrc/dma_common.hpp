@@ -217,32 +217,40 @@ __device__ __forceinline__ void finish_store8(const ConvArgs& a, const unsigned 
           if (ech + e < a.K) t[e] += (int)rp[e] * (1 << a.lshift);
       }
     }
-    unsigned pk[2] = {0u, 0u};
-    WordStream rng{a.seed_lo, a.seed_hi};
-    // The other scaling rules of the quantized tail, behind one uniform branch and with their
-    // per-channel operands fetched here, behind the main loop, so that the default path holds
-    // nothing for them in registers.
-    int qm[8], qs[8];
-    const bool scaled = !STOCH && a.qmode == QMODE_SCALED;
-    if (scaled) {
+    // Each scaling rule sits behind a uniform branch of its own, the default one first and at its
+    // shortest.
+    const ClipBounds cb = clip_bounds(a, relu);
+    if constexpr (STOCH) {
+      WordStream rng{a.seed_lo, a.seed_hi};
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        t[e] = clip_med3(requant_shift(t[e], a.rshift, ROUND_STOCHASTIC, rng, o + e), cb.lo, cb.hi);
+    } else if (a.qmode == QMODE_SHIFT) {
+      if (cb.sat_ok) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) t[e] = shift_round_clip<true>(t[e], a, cb);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) t[e] = shift_round_clip<false>(t[e], a, cb);
+      }
+    } else if (a.qmode == QMODE_SCALED) {
+      // the per-channel operands are fetched here, behind the main loop: nothing of this rule is
+      // held in registers while the tile accumulates, and nothing of it runs under another rule
+      int qm[8], qs[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        const int c = ech + e < a.K ? ech + e : a.K - 1;
+        int c = ech + e < a.K ? ech + e : a.K - 1;
+        asm volatile("" : "+v"(c));   // keeps the address arithmetic of this rule inside its branch
         qm[e] = a.qmult[c];
         qs[e] = a.qshift[c];
       }
-    }
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      int q;
-      if constexpr (STOCH) q = requant_shift(t[e], a.rshift, ROUND_STOCHASTIC, rng, o + e);
-      else if (scaled) q = scale_round(t[e], qm[e], qs[e]);
-      else q = shift_round(a.qmode == QMODE_ACC16 ? saturate16(t[e]) : t[e], (unsigned)a.round_add, a.rshift);  // arithmetic shift: floor
-      q = q < a.clip_lo ? a.clip_lo : (q > a.clip_hi ? a.clip_hi : q);
-      if (relu) q = q > 0 ? q : 0;
-      t[e] = q;
-      pk[e >> 2] |= (unsigned)(q & 0xff) << (8 * (e & 3));
+      for (int e = 0; e < 8; ++e) t[e] = clip_med3(scale_round(t[e], qm[e], qs[e]), cb.lo, cb.hi);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) t[e] = shift_round_clip<false>(saturate16(t[e]), a, cb);
     }
+    const unsigned pk[2] = {pack_low_bytes(t[0], t[1], t[2], t[3]), pack_low_bytes(t[4], t[5], t[6], t[7])};
     int8_t* yp = static_cast<int8_t*>(a.y) + o;
     if constexpr (EXT)
       if (a.nseg) yp = static_cast<int8_t*>(ol.y) + ((size_t)m * ol.ldy + ol.cho);

@@ -64,6 +64,45 @@ __device__ __forceinline__ int scale_round(int acc, int mult, int s) {
 // the exact sum as a 16-bit accumulator holds it: saturated
 __device__ __forceinline__ int saturate16(int acc) { return acc < -32768 ? -32768 : (acc > 32767 ? 32767 : acc); }
 
+// q clipped to [lo, hi], lo <= hi: the median of the three, one instruction
+__device__ __forceinline__ int clip_med3(int q, int lo, int hi) {
+  int r;
+  asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(q), "v"(lo), "v"(hi));
+  return r;
+}
+
+// the low bytes of four words in one: two byte permutes and an or
+__device__ __forceinline__ unsigned pack_low_bytes(int q0, int q1, int q2, int q3) {
+  return __builtin_amdgcn_perm((unsigned)q1, (unsigned)q0, 0x0c0c0400u) |
+         __builtin_amdgcn_perm((unsigned)q3, (unsigned)q2, 0x04000c0cu);
+}
+
+// The bounds of the quantized tail with relu folded in as a raised lower bound, and whether a
+// saturating add may stand in for the exact rounding: acc + addend leaves int32 only where the
+// quotient is 2^(31 - s), and the saturated sum gives 2^(31 - s) - 1; once that is no smaller than
+// the upper bound, the clip sends both to the same value.
+struct ClipBounds {
+  int lo, hi;
+  bool sat_ok;
+};
+__device__ __forceinline__ ClipBounds clip_bounds(const ConvArgs& a, bool relu) {
+  ClipBounds b;
+  b.lo = relu ? (a.clip_lo > 0 ? a.clip_lo : 0) : a.clip_lo;
+  b.hi = relu ? (a.clip_hi > 0 ? a.clip_hi : 0) : a.clip_hi;
+  b.sat_ok = (0x7fffffff >> a.rshift) >= a.clip_hi;
+  return b;
+}
+
+// round((acc + addend) / 2^s) of the deterministic rules, clipped.  SAT: only under ClipBounds::sat_ok.
+// Every instruction here costs a wave four clocks per result with all waves of a tile in the tail
+// at once, so the common case is kept to three.
+template <bool SAT>
+__device__ __forceinline__ int shift_round_clip(int acc, const ConvArgs& a, const ClipBounds& b) {
+  const int q = SAT ? (__builtin_elementwise_add_sat(acc, a.round_add) >> a.rshift)
+                    : shift_round(acc, (unsigned)a.round_add, a.rshift);
+  return clip_med3(q, b.lo, b.hi);
+}
+
 // acc / 2^s rounded by `mode` (arithmetic shift = floor division): what is added before the shift.
 __device__ __forceinline__ int requant_shift(int acc, int s, int mode, WordStream& rng, unsigned long long index) {
   if (s == 0) return acc;

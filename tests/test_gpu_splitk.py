@@ -95,7 +95,7 @@ def test_library_splits_the_deep_layers_at_batch_1_only(G):
     from paper_1904_08368_amd import binding as B
     d = lambda n, c, hw, k: B.conv_desc(n, c, hw, hw, k, 3, 3, 1, 1, B.RELAY_F16, B.RELAY_NHWC, B.RELU)
     assert B.relay_workspace_bytes(d(1, 512, 7, 512)) > 0
-    assert B.relay_workspace_bytes(d(1, 256, 14, 256)) > 0
+    assert B.relay_workspace_bytes(d(1, 256, 14, 256)) == 0      # 18 chunks: measured faster unsplit
     assert B.relay_workspace_bytes(d(32, 64, 56, 64)) == 0
     assert B.relay_workspace_bytes(d(32, 128, 28, 128)) == 0
     # the layer the library splits by itself: parity at its real shape (sampled: the oracle's full conv
@@ -118,7 +118,7 @@ def test_resnet18_batch1_with_split_layers_matches_the_oracle(G):
     x = inputs.image(3, 1, 3, 224, 224, "f16")
     ref = run_float(ops, params, x, "f16")
     net = FusedNet(ops, params, 1, 224, 224, "f16")
-    assert sum(1 for _, args in net.calls if len(args) == 9 and args[-1] is not None) >= 4     # layers given a workspace
+    assert sum(1 for _, args in net.calls if len(args) == 9 and args[-1] is not None) >= 3     # layers given a workspace
     net.load_input(x)
     net.run()
     torch.cuda.synchronize()

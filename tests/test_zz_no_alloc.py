@@ -34,7 +34,7 @@ def test_static_scratch_conv_equals_the_workspace_form():
     assert torch.cuda.is_available()
     # deep layers at batch 1: few output tiles, long reductions -> the library splits the reduction
     big = _layer(B, G, 1, 512, 7, 512, 901, True)
-    small = _layer(B, G, 1, 256, 14, 256, 902, False)
+    small = _layer(B, G, 1, 384, 7, 256, 902, False)
     for L in (big, small, big):       # in a row, the second smaller than the first, then the first again
         need = B.relay_workspace_bytes(L["d"])
         assert 0 < need <= (4 << 20), need          # the layer really uses scratch, within the static array
