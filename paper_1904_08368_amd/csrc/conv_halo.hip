@@ -47,7 +47,8 @@ struct HaloGeom {
 constexpr int NSW = 3;         // filter ring stages (9 taps per chunk keep step % NSW compile-time)
 constexpr int XS = 11 - NSW;   // taps of a chunk behind which the next chunk's halo is loaded
 
-template <bool IS_I8, int WAVES_M, int WAVES_N, int TM, int TN, int KP>
+// HB: halo blocks a wave loads per issue slot (a halo holds at most XS * HB * waves blocks of 16 positions)
+template <bool IS_I8, int WAVES_M, int WAVES_N, int TM, int TN, int KP, int HB = 1>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_halo_kernel(const ConvArgs a, const HaloGeom g) {
   constexpr int NW = WAVES_M * WAVES_N;
   constexpr int VE = IS_I8 ? 16 : 8;
@@ -58,10 +59,11 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_halo_kernel
   static_assert((BN / 16) % NW == 0, "filter staging blocks must divide over the waves");
   constexpr int WLP = BN / 16 / NW;      // filter blocks per plane per wave
   constexpr int LW = KP * WLP;           // filter loads per step per wave
-  constexpr int L = LW + 1;              // loads per step per wave: filters + one halo block
+  constexpr int L = LW + HB;             // loads per step per wave: filters + HB halo blocks
+  constexpr int XN = XS * HB;            // halo blocks per wave
   constexpr int KSTEPS = KP * (BKV / 2);
   static_assert(L <= TM * TN * KSTEPS, "one load is issued behind each MFMA of a step");
-  static_assert(XS + (NSW - 1) * L + 8 <= 63, "vmcnt is a 6-bit counter");
+  static_assert(XN + (NSW - 1) * L + 8 <= 63, "vmcnt is a 6-bit counter");
   constexpr int WPLANE = BN * BKV;       // 16-byte slots of one filter plane
   constexpr int WSTAGE = KP * WPLANE;
   constexpr int EP = WTN / 4 + 1;
@@ -120,14 +122,15 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_halo_kernel
   }
   const intx4 rs_x = make_rsrc(a.x, (unsigned)((size_t)a.N * a.xs_n * ES));
   const intx4 rs_w = make_rsrc(a.w, (unsigned)((size_t)a.K * a.Kp * ES));
-  auto issue_filters = [&](int s) {  // the filters of step (0, s), s < NSW - 1, and the slot's dump load
+  auto issue_filters = [&](int s) {  // the filters of step (0, s), s < NSW - 1, and the slot's dump loads
 #pragma unroll
     for (int i = 0; i < LW; ++i) {
       const int plane = i / WLP, j = i % WLP;
       lds_dma16(rs_w, wring_base + (unsigned)(s * WSTAGE + plane * WPLANE + (wave * WLP + j) * 64) * 16u,
                 w_off[j] == kOob ? kOob : w_off[j] + (unsigned)((s * a.C + plane * (BKV * VE)) * ES));
     }
-    lds_dma16(rs_x, dump_base, kOob);
+#pragma unroll
+    for (int h = 0; h < HB; ++h) lds_dma16(rs_x, dump_base, kOob);
   };
   issue_filters(0);
 
@@ -147,20 +150,20 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_halo_kernel
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
   __builtin_amdgcn_s_barrier();
 
-  // ---- this lane's part of a halo: block (t * NW + wave) of the KP * xblk blocks, for t < XS; the load of
+  // ---- this lane's part of a halo: block (t * NW + wave) of the KP * xblk blocks, for t < XN; the load of
   //      chunk 0's block goes out as soon as its address is known
-  unsigned x_off[XS];    // byte offset of the 16 bytes this lane fetches (chunk 0), or out of range
-  unsigned x_dst[XS];    // LDS byte offset inside a halo buffer
+  unsigned x_off[XN];    // byte offset of the 16 bytes this lane fetches (chunk 0), or out of range
+  unsigned x_dst[XN];    // LDS byte offset inside a halo buffer
   unsigned x_live = 0;   // bit t: the block exists (else the load goes to the dump block)
-  unsigned x_px[XS];     // (all table reads first: one wait for the eight of them)
+  unsigned x_px[XN];     // (all table reads first: one wait for all of them)
 #pragma unroll
-  for (int t = 0; t < XS; ++t) {
+  for (int t = 0; t < XN; ++t) {
     const int b = t * NW + wave;
     const int plane = (int)fast_div((uint32_t)b, g.fd_xblk), blk = b - plane * g.xblk;
     x_px[t] = ptab[plane < KP ? blk * 16 + srow : 0];
   }
 #pragma unroll
-  for (int t = 0; t < XS; ++t) {
+  for (int t = 0; t < XN; ++t) {
     const int b = t * NW + wave;
     const int plane = (int)fast_div((uint32_t)b, g.fd_xblk), blk = b - plane * g.xblk;
     const bool live = plane < KP;
@@ -176,7 +179,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_halo_kernel
   for (int s = 1; s < NSW - 1; ++s) issue_filters(s);
 
   // the i-th load of the issue slot behind step (cc, t): filters of step (cc, t) + NSW - 1, then
-  // block t of the halo of chunk cc + 1
+  // blocks t * HB ... of the halo of chunk cc + 1
   auto issue_one = [&](int cc, int t, int i) {
     if (i < LW) {
       const int tw = (t + NSW - 1) % 9, ccw = cc + (t + NSW - 1) / 9;  // tap and chunk of the step being fetched
@@ -185,9 +188,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_halo_kernel
       const unsigned voff = live ? w_off[j] + (unsigned)((tw * a.C + ccw * CK + plane * (BKV * VE)) * ES) : kOob;
       lds_dma16(rs_w, wring_base + (unsigned)(((t + NSW - 1) % NSW) * WSTAGE + plane * WPLANE + (wave * WLP + j) * 64) * 16u, voff);
     } else {
-      const bool live = t < XS && ((x_live >> (t < XS ? t : 0)) & 1u) && cc + 1 < g.ncc;
-      const unsigned voff = (live && x_off[t < XS ? t : 0] != kOob) ? x_off[t < XS ? t : 0] + (unsigned)((cc + 1) * CK * ES) : kOob;
-      const unsigned dst = live ? lds_base + (unsigned)((((cc + 1) & 1) * (g.nxbuf - 1)) * xbuf_slots) * 16u + x_dst[t < XS ? t : 0] : dump_base;
+      const int xt = t < XS ? t * HB + (i - LW) : 0;   // which of this wave's halo blocks
+      const bool live = t < XS && ((x_live >> xt) & 1u) && cc + 1 < g.ncc;
+      const unsigned voff = (live && x_off[xt] != kOob) ? x_off[xt] + (unsigned)((cc + 1) * CK * ES) : kOob;
+      const unsigned dst = live ? lds_base + (unsigned)((((cc + 1) & 1) * (g.nxbuf - 1)) * xbuf_slots) * 16u + x_dst[xt] : dump_base;
       lds_dma16(rs_x, dst, voff);
     }
   };
@@ -294,12 +298,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_halo_kernel
 }
 
 struct HaloTile {
-  int waves_m, waves_n, tm, tn;
+  int waves_m, waves_n, tm, tn, hb;
   constexpr int bm() const { return waves_m * tm * 32; }
   constexpr int bn() const { return waves_n * tn * 32; }
 };
-constexpr HaloTile kHalo[] = {{2, 2, 2, 1}, {2, 2, 1, 1}};  // 128 x 64, 64 x 64
-constexpr int kNumHalo = 2;
+// 128 x 64, 64 x 64, and 256 x 64 (four waves of 128 x 32: a layer whose 128-position tiles would take the chip
+// two rounds takes one)
+constexpr HaloTile kHalo[] = {{2, 2, 2, 1, 1}, {2, 2, 1, 1, 1}, {2, 2, 4, 1, 2}};
+constexpr int kNumHalo = 3;
 
 int chunk_planes(const ConvArgs& a, bool is_i8) {
   const int ve = is_i8 ? 16 : 8;
@@ -320,7 +326,7 @@ bool make_geom(const ConvArgs& a, bool is_i8, int v, HaloGeom& g, size_t& lds_by
   g.nxbuf = g.ncc > 1 ? 2 : 1;
   g.fd_f = make_fastdiv((uint32_t)g.F);
   g.fd_xblk = make_fastdiv((uint32_t)g.xblk);
-  if (kp * g.xblk > XS * 4) return false;  // a halo must fit the load slots of XS steps x 4 waves
+  if (kp * g.xblk > XS * kHalo[v].hb * 4) return false;  // a halo must fit the load slots of XS steps x 4 waves
   const int nw = kHalo[v].waves_m * kHalo[v].waves_n;
   const size_t ring = (size_t)g.nxbuf * kp * g.xblk * 64 + (size_t)NSW * kp * kHalo[v].bn() * BKV + 64;
   const size_t epi = (size_t)nw * 32 * (kHalo[v].tn * 32 / 4 + 1);
@@ -329,9 +335,9 @@ bool make_geom(const ConvArgs& a, bool is_i8, int v, HaloGeom& g, size_t& lds_by
   return lds_bytes <= 160 * 1024;
 }
 
-template <bool IS_I8, int WM, int WN, int TM, int TN, int KP>
+template <bool IS_I8, int WM, int WN, int TM, int TN, int KP, int HB = 1>
 hipError_t launch_halo_one(const ConvArgs& a, const HaloGeom& g, size_t lds_bytes, hipStream_t st) {
-  auto kern = conv3x3_halo_kernel<IS_I8, WM, WN, TM, TN, KP>;
+  auto kern = conv3x3_halo_kernel<IS_I8, WM, WN, TM, TN, KP, HB>;
   static std::atomic<bool> raised{false};  // dynamic LDS above the default limit has to be asked for once per kernel
   if (!raised.load(std::memory_order_acquire)) {
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -352,6 +358,8 @@ template <bool IS_I8>
 hipError_t launch_halo_typed(const ConvArgs& a, const HaloGeom& g, size_t lds_bytes, int v, int kp, hipStream_t st) {
   if (v == 0) return kp == 2 ? launch_halo_one<IS_I8, 2, 2, 2, 1, 2>(a, g, lds_bytes, st)
                              : launch_halo_one<IS_I8, 2, 2, 2, 1, 1>(a, g, lds_bytes, st);
+  if (v == 2) return kp == 2 ? launch_halo_one<IS_I8, 2, 2, 4, 1, 2, 2>(a, g, lds_bytes, st)
+                             : launch_halo_one<IS_I8, 2, 2, 4, 1, 1, 2>(a, g, lds_bytes, st);
   return kp == 2 ? launch_halo_one<IS_I8, 2, 2, 1, 1, 2>(a, g, lds_bytes, st)
                  : launch_halo_one<IS_I8, 2, 2, 1, 1, 1>(a, g, lds_bytes, st);
 }
@@ -380,18 +388,30 @@ bool conv_halo_supported(const ConvArgs& a, bool is_i8, int v) {
 // stack 0.8 % faster), slower at 7 x 7 (a quarter of the flat positions are not pixels) and outside
 // the range of tile counts where both kernels get two workgroups per CU.
 int conv_halo_pick(const ConvArgs& a, bool is_i8) {
-  if (a.C < 64 || a.W > 56 || !conv_halo_supported(a, is_i8, 0)) return -1;
+  const bool thin = !is_i8 && a.C == 64 && a.K <= 64;   // (wide images too: 112 x 112 at batch 32 57.4 against 62.8 us, 224 x 224 216.8 against 226.5)
+  if (a.C < 64 || (a.W > 56 && !thin) || !conv_halo_supported(a, is_i8, 0)) return -1;
   const long flat = (long)a.N * (a.H + 1) * (a.W + 1);
   const long t128 = ((flat + 127) / 128) * ((a.K + 63) / 64);
   // (fp16, 256 channels and more: also on layers of thousands of tiles -- VGG-16 at batch 32: 256 -> 512 at 28 x 28
-  // 68.8 against 76.9 us, 512 -> 512 129.3 against 142.7, 256 -> 256 at 56 x 56 147.4 against 151.3)
-  const long cap = is_i8 ? 512 : (a.C >= 256 ? (1L << 40) : (a.C == 64 ? 1024 : 512));
-  return t128 >= 190 && t128 <= cap ? 0 : -1;
+  // 68.8 against 76.9 us, 512 -> 512 129.3 against 142.7, 256 -> 256 at 56 x 56 147.4 against 151.3; 64 -> 64 at any
+  // size: 31.3 against 33.6 us at 56 x 56, batch 64)
+  const bool any_size = !is_i8 && (a.C >= 256 || thin);
+  const long cap = is_i8 ? 512 : (any_size ? (1L << 40) : (a.C == 64 ? 1024 : 512));
+  if (t128 < 190 || t128 > cap) return -1;
+  // 64 -> 64 channels in fp16 where the 128-position tiles would take the chip between one and about three
+  // rounds of its 512 workgroup slots: the 256-position tile halves the rounds (56 x 56 at batch 32: 15.8
+  // against 16.4 us, at batch 64: 30.7 against 31.3)
+  if (thin && t128 > 512 && t128 <= 1700 && conv_halo_supported(a, is_i8, 2)) return 2;
+  return 0;
 }
 
 void conv_halo_kernel_name(const ConvArgs& a, bool is_i8, int v, char* buf, size_t len) {
-  snprintf(buf, len, "conv3x3_halo_kernel<%s, %d, %d, %d, %d, %d>", is_i8 ? "true" : "false", kHalo[v].waves_m,
-           kHalo[v].waves_n, kHalo[v].tm, kHalo[v].tn, chunk_planes(a, is_i8));
+  if (kHalo[v].hb == 1)
+    snprintf(buf, len, "conv3x3_halo_kernel<%s, %d, %d, %d, %d, %d>", is_i8 ? "true" : "false", kHalo[v].waves_m,
+             kHalo[v].waves_n, kHalo[v].tm, kHalo[v].tn, chunk_planes(a, is_i8));
+  else
+    snprintf(buf, len, "conv3x3_halo_kernel<%s, %d, %d, %d, %d, %d, %d>", is_i8 ? "true" : "false", kHalo[v].waves_m,
+             kHalo[v].waves_n, kHalo[v].tm, kHalo[v].tn, chunk_planes(a, is_i8), kHalo[v].hb);
 }
 
 hipError_t launch_conv_halo(const ConvArgs& a, bool is_i8, int v, hipStream_t st) {
