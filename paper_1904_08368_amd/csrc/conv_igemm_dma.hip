@@ -482,19 +482,22 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * SK,
               q[e] = shift_round_clip<decltype(sat)::value>(acc[tn][tm][4 * g + e] + __builtin_bit_cast(int, m4[e]), a, qb);
             *reinterpret_cast<unsigned*>(dst) = pack_low_bytes(q[0], q[1], q[2], q[3]);
           } else {
-            typedef _Float16 half4v __attribute__((ext_vector_type(4)));
-            half4v hv;
+            typedef float float2v __attribute__((ext_vector_type(2)));
+            typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+            unsigned hw[2];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              float t = acc[tn][tm][4 * g + e] * m4[e] + a4[e];
-              // rounded to fp32 before it is narrowed, as in the unpooled kernel's epilogue: left alone the
-              // compiler merges the multiply-add and the conversion into one instruction that rounds
-              // once, and one result in some thousands differs from that kernel's in its last bit
-              asm("" : "+v"(t));
-              if (a.flags & F_RELU) t = t > 0.f ? t : 0.f;
-              hv[e] = (_Float16)t;
+            for (int e = 0; e < 2; ++e) {
+              // rounded to fp32 before it is narrowed, and relu as a packed maximum on the narrowed pair: both as
+              // in the unpooled kernel's epilogue
+              float f0 = acc[tn][tm][4 * g + 2 * e] * m4[2 * e] + a4[2 * e];
+              float f1 = acc[tn][tm][4 * g + 2 * e + 1] * m4[2 * e + 1] + a4[2 * e + 1];
+              asm("" : "+v"(f0), "+v"(f1));   // (left alone the compiler merges the multiply-add and the narrowing into one instruction that rounds once)
+              const float2v f = {f0, f1};
+              half2v h = __builtin_convertvector(f, half2v);
+              if (a.flags & F_RELU) h = __builtin_elementwise_max(h, half2v{(_Float16)0, (_Float16)0});
+              hw[e] = __builtin_bit_cast(unsigned, h);
             }
-            *reinterpret_cast<uint2*>(dst) = __builtin_bit_cast(uint2, hv);
+            *reinterpret_cast<uint2*>(dst) = make_uint2(hw[0], hw[1]);
           }
         }
       }

@@ -167,36 +167,49 @@ __device__ __forceinline__ void finish_store8(const ConvArgs& a, const unsigned 
   const size_t o = (size_t)m * a.K + ech;
   const bool relu = (a.flags & F_RELU) && !(EXT && ol.norelu);
   if constexpr (!IS_I8) {
+    // (as in the quantized tail every instruction counts: the residual enters through a mixed-precision
+    // multiply-add -- 1.0 * r + t, the same sum as convert-then-add -- two results are narrowed by one packed
+    // conversion, and relu is a packed maximum on the narrowed pair: rounding is monotone and keeps the
+    // sign, so max(round(t), 0) == round(max(t, 0)), and the hardware's maximum of -0 and +0 is +0)
+    typedef float float2v __attribute__((ext_vector_type(2)));
+    typedef _Float16 half2v __attribute__((ext_vector_type(2)));
     float t[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) t[e] = __builtin_bit_cast(float, raw[e]) * emul[e] + eadd[e];
     if (a.flags & F_RES) {
       const _Float16* rp = static_cast<const _Float16*>(a.res) + o;
       if (vec_ok) {
-        const half8 rv = have_pre ? __builtin_bit_cast(half8, pre) : *reinterpret_cast<const half8*>(rp);
+        const uint4 rv = have_pre ? pre : *reinterpret_cast<const uint4*>(rp);
+        const unsigned rw[4] = {rv.x, rv.y, rv.z, rv.w};
 #pragma unroll
-        for (int e = 0; e < 8; ++e) t[e] += (float)rv[e];
+        for (int e = 0; e < 4; ++e) {
+          asm("v_fma_mix_f32 %0, %1, 1.0, %0 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "+v"(t[2 * e]) : "v"(rw[e]));
+          asm("v_fma_mix_f32 %0, %1, 1.0, %0 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "+v"(t[2 * e + 1]) : "v"(rw[e]));
+        }
       } else {
 #pragma unroll
         for (int e = 0; e < 8; ++e)
           if (ech + e < a.K) t[e] += (float)rp[e];
       }
     }
-    half8 hv;
+    unsigned hw[4];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      if (relu) t[e] = t[e] > 0.f ? t[e] : 0.f;
-      hv[e] = (_Float16)t[e];
+    for (int e = 0; e < 4; ++e) {
+      asm("" : "+v"(t[2 * e]), "+v"(t[2 * e + 1]));   // (rounded to fp32 first, in every instantiation: never merged with the narrowing)
+      const float2v f = {t[2 * e], t[2 * e + 1]};
+      half2v h = __builtin_convertvector(f, half2v);
+      if (relu) h = __builtin_elementwise_max(h, half2v{(_Float16)0, (_Float16)0});
+      hw[e] = __builtin_bit_cast(unsigned, h);
     }
     _Float16* yp = static_cast<_Float16*>(a.y) + o;
     if constexpr (EXT)
       if (a.nseg) yp = static_cast<_Float16*>(ol.y) + ((size_t)m * ol.ldy + ol.cho);
     if (vec_ok) {
-      *reinterpret_cast<half8*>(yp) = hv;
+      *reinterpret_cast<uint4*>(yp) = make_uint4(hw[0], hw[1], hw[2], hw[3]);
     } else {
 #pragma unroll
       for (int e = 0; e < 8; ++e)
-        if (ech + e < a.K) yp[e] = hv[e];
+        if (ech + e < a.K) yp[e] = __builtin_bit_cast(_Float16, (unsigned short)(hw[e >> 1] >> (16 * (e & 1))));
     }
   } else {
     int t[8];

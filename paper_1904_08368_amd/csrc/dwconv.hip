@@ -120,10 +120,7 @@ __global__ __launch_bounds__(256) void dwconv3x3_f16_kernel(const ConvArgs a) {
     for (int j = 0; j < TW; ++j) {
       const int q = q0 + j;
       if (q >= a.Wo) continue;
-      half8 o;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) o[e] = (_Float16)fmaxf(acc[i][j][e] * mul[e] + add[e], lo);
-      *reinterpret_cast<half8*>(y + ((long)p * a.Wo + q) * a.C) = o;
+      *reinterpret_cast<uint4*>(y + ((long)p * a.Wo + q) * a.C) = scale_shift_narrow8(acc[i][j], mul, add, lo);
     }
   }
 }
@@ -249,10 +246,7 @@ __global__ __launch_bounds__(NT) void dwconv3x3_s1_lds_kernel(const ConvArgs a) 
     for (int j = 0; j < 4; ++j) {
       const int q = ox0 + mtx * 4 + j;
       if (q >= a.Wo) continue;
-      half8 o;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) o[e] = (_Float16)fmaxf(acc[i][j][e] * mul[e] + add[e], lo);
-      *reinterpret_cast<half8*>(y + ((long)p * a.Wo + q) * a.C) = o;
+      *reinterpret_cast<uint4*>(y + ((long)p * a.Wo + q) * a.C) = scale_shift_narrow8(acc[i][j], mul, add, lo);
     }
   }
 }

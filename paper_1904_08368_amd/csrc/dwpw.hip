@@ -357,11 +357,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void dwpw_fused_kernel
         for (int i = 0; i < MH; ++i)
 #pragma unroll
           for (int j = 0; j < MW; ++j) {
-            half8 o;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] = (_Float16)fmaxf(dacc[i][j][e] * mul[e] + add[e], relu_lo);
+            const uint4 o = scale_shift_narrow8(dacc[i][j], mul, add, relu_lo);
             const int row = row_now + i * TW + j;
-            if (has_now) at[(cv / BKV) * APLANE + lds_slot(row, cv % BKV)] = __builtin_bit_cast(uint4, o);
+            if (has_now) at[(cv / BKV) * APLANE + lds_slot(row, cv % BKV)] = o;
           }
       }
     }
