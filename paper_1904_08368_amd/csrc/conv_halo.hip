@@ -302,10 +302,10 @@ struct HaloTile {
   constexpr int bm() const { return waves_m * tm * 32; }
   constexpr int bn() const { return waves_n * tn * 32; }
 };
-// 128 x 64, 64 x 64, and 256 x 64 (four waves of 128 x 32: a layer whose 128-position tiles would take the chip
-// two rounds takes one)
-constexpr HaloTile kHalo[] = {{2, 2, 2, 1, 1}, {2, 2, 1, 1, 1}, {2, 2, 4, 1, 2}};
-constexpr int kNumHalo = 3;
+// 128 x 64, 64 x 64, 256 x 64 (four waves of 64 x 64, a third less LDS operand traffic per matrix instruction:
+// a layer whose 128-position tiles would take the chip two rounds takes one) and 128 x 128
+constexpr HaloTile kHalo[] = {{2, 2, 2, 1, 1}, {2, 2, 1, 1, 1}, {4, 1, 2, 2, 2}, {2, 2, 2, 2, 1}};
+constexpr int kNumHalo = 4;
 
 int chunk_planes(const ConvArgs& a, bool is_i8) {
   const int ve = is_i8 ? 16 : 8;
@@ -358,8 +358,10 @@ template <bool IS_I8>
 hipError_t launch_halo_typed(const ConvArgs& a, const HaloGeom& g, size_t lds_bytes, int v, int kp, hipStream_t st) {
   if (v == 0) return kp == 2 ? launch_halo_one<IS_I8, 2, 2, 2, 1, 2>(a, g, lds_bytes, st)
                              : launch_halo_one<IS_I8, 2, 2, 2, 1, 1>(a, g, lds_bytes, st);
-  if (v == 2) return kp == 2 ? launch_halo_one<IS_I8, 2, 2, 4, 1, 2, 2>(a, g, lds_bytes, st)
-                             : launch_halo_one<IS_I8, 2, 2, 4, 1, 1, 2>(a, g, lds_bytes, st);
+  if (v == 2) return kp == 2 ? launch_halo_one<IS_I8, 4, 1, 2, 2, 2, 2>(a, g, lds_bytes, st)
+                             : launch_halo_one<IS_I8, 4, 1, 2, 2, 1, 2>(a, g, lds_bytes, st);
+  if (v == 3) return kp == 2 ? launch_halo_one<IS_I8, 2, 2, 2, 2, 2>(a, g, lds_bytes, st)
+                             : launch_halo_one<IS_I8, 2, 2, 2, 2, 1>(a, g, lds_bytes, st);
   return kp == 2 ? launch_halo_one<IS_I8, 2, 2, 1, 1, 2>(a, g, lds_bytes, st)
                  : launch_halo_one<IS_I8, 2, 2, 1, 1, 1>(a, g, lds_bytes, st);
 }
@@ -398,9 +400,13 @@ int conv_halo_pick(const ConvArgs& a, bool is_i8) {
   const bool any_size = !is_i8 && (a.C >= 256 || thin);
   const long cap = is_i8 ? 512 : (any_size ? (1L << 40) : (a.C == 64 ? 1024 : 512));
   if (t128 < 190 || t128 > cap) return -1;
+  // very many tiles of wide layers: 128 x 128 tiles, two thirds of the LDS operand traffic per matrix
+  // instruction (256 -> 256 at 56 x 56, batch 32: 130.0 against 147.1 us; a loss at 844 tiles, 512 at 28 x 28)
+  const long t128sq = ((flat + 127) / 128) * ((a.K + 127) / 128);
+  if (!is_i8 && a.C >= 256 && t128sq >= 1500 && conv_halo_supported(a, is_i8, 3)) return 3;
   // 64 -> 64 channels in fp16 where the 128-position tiles would take the chip between one and about three
-  // rounds of its 512 workgroup slots: the 256-position tile halves the rounds (56 x 56 at batch 32: 15.8
-  // against 16.4 us, at batch 64: 30.7 against 31.3)
+  // rounds of its 512 workgroup slots: the 256-position tile halves the rounds (56 x 56 at batch 32: 15.0
+  // against 16.2 us)
   if (thin && t128 > 512 && t128 <= 1700 && conv_halo_supported(a, is_i8, 2)) return 2;
   return 0;
 }

@@ -303,7 +303,7 @@ HALO_SHAPES = [  # n, c, h, w, k
 ]
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3])
 @pytest.mark.parametrize("shape", HALO_SHAPES)
 def test_fp16_halo_kernel(G, shape, variant):
     from paper_1904_08368_amd import binding as B
@@ -328,7 +328,7 @@ def test_fp16_halo_kernel(G, shape, variant):
     assert O.max_rel_err(G.run_conv_f16(x, wt, 1, 1, tile=100 + variant), ref0) <= TOL_F16
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3])
 @pytest.mark.parametrize("shape", [(2, 64, 23, 27, 192), (1, 128, 9, 11, 40), (2, 256, 14, 14, 64), (1, 64, 56, 56, 64)])
 def test_int8_halo_kernel_bit_exact(G, shape, variant):
     n, c, h, w, k = shape
