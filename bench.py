@@ -87,6 +87,15 @@ def _layer_table(net, ops, batch, reps, trials):
             row["gbs"] = row["mbytes"] / row["us"] * 1e3
             _bounds(row, False, False)
             row["frac_hbm"] = row["gbs"] / HBM_PEAK_GBS
+        elif fn is B.relay_fused_conv2d_first_layer:
+            # the first layer read straight from the NCHW image: plain vector arithmetic, bound by its tensors
+            ho, wo = B.relay_conv2d_out_shape(d)
+            row["gflop"] = 2 * d.n * ho * wo * d.k * d.c * 9 / 1e9
+            row["kernel"] = "conv_first_kernel"
+            row["mbytes"] = (d.n * d.h * d.w * d.c + d.n * ho * wo * d.k + d.k * d.c * 9) * 2 / 1e6
+            row["tflops"] = row["gflop"] / row["us"] * 1e3
+            row["gbs"] = row["mbytes"] / row["us"] * 1e3
+            _bounds(row, False, True)
         elif fn in (B.relay_fused_conv2d_bn_relu_maxpool, B.relay_qconv2d_requant_maxpool):
             # the conv with its max pool in the same launch: the conv's FLOP, input + pooled output + filters
             ho, wo = B.relay_conv2d_out_shape(d)

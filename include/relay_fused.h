@@ -242,6 +242,30 @@ relay_status relay_fused_dwconv_bias_relu(const relay_conv2d_desc* d, const void
                                           const float* bias, const float* bn_scale, const float* bn_shift,
                                           void* y, void* hip_stream);
 
+/* The first layer of an image network as a fused primitive function (paper Section 4.1: conv2d with the
+ * elementwise operators behind it; Section 5.2: the cost of every launch and of every tensor that goes
+ * through memory), read from the image as it arrives:
+ *   y[n,p,q,k] = sum_{c,r,s} x[n,c,2p-1+r,2q-1+s] * w[k,c,r,s] -> [+bias] -> [*bn_scale + bn_shift] -> [relu] -> fp16
+ * with fp32 accumulation.  d: F16, layout RELAY_NCHW (the layout of x; y is NHWC), c == 3, 3x3, stride 2,
+ * pad 1, k % 16 == 0, k <= 128, w % 8 == 0, h even, no residual.  x_nchw [n,3,h,w] and y_nhwc [n,h/2,w/2,k]
+ * device, 16-byte aligned, caller-owned, distinct; bias / bn_scale / bn_shift fp32 [k] device or NULL with
+ * the flag clear.  No layout conversion or padded copy of the image is needed in front of this call.
+ * w_packed: the filters as relay_prepack_first_layer_weights writes them from w_oihw [k,3,3,3] fp16 (both
+ * device; compile-time work; relay_first_layer_packed_weight_bytes bytes, 16-byte aligned): pairs of
+ * filter taps per output channel, in the order the kernel's two-element dot products consume them.  The
+ * kernel reads this table through the scalar cache: it must be complete before the launch and is
+ * never written by it.
+ * relay_conv2d_first_layer_supported: 1 where these calls take the descriptor, else 0 (and RELAY_OK).
+ * Errors: RELAY_ERR_DTYPE, _UNSUPPORTED (layout, window, stride, padding, channel counts, sizes, residual,
+ * aliasing), _SHAPE, _NULL, _ALIGN, _DEVICE; nothing is launched on an error. */
+relay_status relay_conv2d_first_layer_supported(const relay_conv2d_desc* d, int32_t* supported);
+relay_status relay_first_layer_packed_weight_bytes(const relay_conv2d_desc* d, size_t* bytes);
+relay_status relay_prepack_first_layer_weights(const relay_conv2d_desc* d, const void* w_oihw, void* w_packed,
+                                               void* hip_stream);
+relay_status relay_fused_conv2d_first_layer(const relay_conv2d_desc* d, const void* x_nchw, const void* w_packed,
+                                            const float* bias, const float* bn_scale, const float* bn_shift,
+                                            void* y_nhwc, void* hip_stream);
+
 /* A depthwise conv2d and the 1x1 conv2d that consumes it, each with its fused tail, as ONE launch
  * (paper Section 4.1: a primitive function is one kernel; Section 5.2: the cost of every extra launch and
  * every intermediate that goes through memory; MobileNet's separable block, Section 5.1):

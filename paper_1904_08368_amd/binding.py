@@ -56,6 +56,10 @@ SIGNATURES = {
     "relay_qconv2d_requant_u8": [_DP, _P, _P, _P, _I, _I, _P, _P, _SZ, _P],
     "relay_prepack_dwconv_weights": [_DP, _P, _P, _P],
     "relay_fused_dwconv_bias_relu": [_DP, _P, _P, _P, _P, _P, _P, _P],
+    "relay_fused_conv2d_first_layer": [_DP, _P, _P, _P, _P, _P, _P, _P],
+    "relay_conv2d_first_layer_supported": [_DP, C.POINTER(C.c_int32)],
+    "relay_first_layer_packed_weight_bytes": [_DP, C.POINTER(C.c_size_t)],
+    "relay_prepack_first_layer_weights": [_DP, _P, _P, _P],
     "relay_dwconv_pwconv_fusion_pays": [_DP, C.c_int32, C.POINTER(C.c_int32)],
     "relay_fused_dwconv_pwconv": [_DP, _P, _P, _P, _P, _P, C.c_int32, C.c_uint32, _P, _P, _P, _P, _P, _P],
     "relay_fused_dense_bias_act": [_I, _I, _I, _I, _P, _P, _P, _I, _P, _P],
@@ -199,6 +203,27 @@ def relay_prepack_dwconv_weights(d: ConvDesc, w_crs, w_rsc) -> None:
 def relay_fused_dwconv_bias_relu(d: ConvDesc, x, w_rsc, bias, bn_scale, bn_shift, y) -> None:
     _check(lib().relay_fused_dwconv_bias_relu(C.byref(d), _ptr(x), _ptr(w_rsc), _ptr(bias), _ptr(bn_scale),
                                               _ptr(bn_shift), _ptr(y), _stream()))
+
+
+def relay_conv2d_first_layer_supported(d: ConvDesc) -> bool:
+    ok = C.c_int32(0)
+    _check(lib().relay_conv2d_first_layer_supported(C.byref(d), C.byref(ok)))
+    return bool(ok.value)
+
+
+def relay_first_layer_packed_weight_bytes(d: ConvDesc) -> int:
+    n = C.c_size_t(0)
+    _check(lib().relay_first_layer_packed_weight_bytes(C.byref(d), C.byref(n)))
+    return n.value
+
+
+def relay_prepack_first_layer_weights(d: ConvDesc, w_oihw, w_packed) -> None:
+    _check(lib().relay_prepack_first_layer_weights(C.byref(d), _ptr(w_oihw), _ptr(w_packed), _stream()))
+
+
+def relay_fused_conv2d_first_layer(d: ConvDesc, x_nchw, w_packed, bias, bn_scale, bn_shift, y_nhwc) -> None:
+    _check(lib().relay_fused_conv2d_first_layer(C.byref(d), _ptr(x_nchw), _ptr(w_packed), _ptr(bias), _ptr(bn_scale),
+                                                _ptr(bn_shift), _ptr(y_nhwc), _stream()))
 
 
 def relay_dwconv_pwconv_fusion_pays(dw: ConvDesc, k: int) -> bool:

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librelayfused.so")
-SOURCES = ["api.cpp", "fusion.cpp", "conv_igemm.hip", "conv_igemm_dma.hip", "conv_halo.hip", "conv_stream.hip", "conv_direct_f32.hip", "dwconv.hip", "dwpw.hip", "dense.hip", "glue.hip", "quant.hip", "realize.hip", "probe.hip", "qschemes.hip"]
+SOURCES = ["api.cpp", "fusion.cpp", "conv_igemm.hip", "conv_igemm_dma.hip", "conv_halo.hip", "conv_stream.hip", "conv_direct_f32.hip", "conv_first.hip", "dwconv.hip", "dwpw.hip", "dense.hip", "glue.hip", "quant.hip", "realize.hip", "probe.hip", "qschemes.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-command-line-argument"]

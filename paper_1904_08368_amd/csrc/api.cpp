@@ -453,6 +453,70 @@ relay_status relay_fused_conv2d_bias_bn_relu_static(const relay_conv2d_desc* d, 
   return device_status(launch_igemm(a, false, s), "conv2d fp16 launch");
 }
 
+// ---- the first layer of an image network, read from the NCHW image -----------------------------------
+static relay_status first_layer_args(const relay_conv2d_desc* d, relay::ConvArgs* out) {
+  int ho, wo;
+  relay_status st = check_geometry(d, &ho, &wo);
+  if (st != RELAY_OK) return st;
+  if (d->dtype != RELAY_F16) return fail(RELAY_ERR_DTYPE, "the first-layer conv2d takes F16");
+  if (d->layout != RELAY_NCHW) return fail(RELAY_ERR_UNSUPPORTED, "the first-layer conv2d reads an NCHW image (layout RELAY_NCHW)");
+  relay::ConvArgs a = make_args(d, ho, wo);
+  if (!relay::conv_first_supported(a))
+    return fail(RELAY_ERR_UNSUPPORTED,
+                "the first-layer conv2d takes c == 3, 3x3 / stride 2 / pad 1, k %% 16 == 0, k <= 128, w %% 8 == 0, h even, no "
+                "residual, an output below 2^31 elements (c=%d r=%d s=%d stride=%d pad=%d k=%d h=%d w=%d)",
+                d->c, d->r, d->s, d->stride_h, d->pad_h, d->k, d->h, d->w);
+  *out = a;
+  return RELAY_OK;
+}
+
+relay_status relay_conv2d_first_layer_supported(const relay_conv2d_desc* d, int32_t* supported) {
+  if (!supported) return fail(RELAY_ERR_NULL, "supported is NULL");
+  int ho, wo;
+  relay_status st = check_geometry(d, &ho, &wo);
+  if (st != RELAY_OK) return st;
+  const relay::ConvArgs a = make_args(d, ho, wo);
+  *supported = (d->dtype == RELAY_F16 && d->layout == RELAY_NCHW && relay::conv_first_supported(a)) ? 1 : 0;
+  return RELAY_OK;
+}
+
+relay_status relay_first_layer_packed_weight_bytes(const relay_conv2d_desc* d, size_t* bytes) {
+  if (!bytes) return fail(RELAY_ERR_NULL, "bytes is NULL");
+  relay::ConvArgs a;
+  relay_status st = first_layer_args(d, &a);
+  if (st != RELAY_OK) return st;
+  *bytes = relay::conv_first_packed_bytes(a.K);
+  return RELAY_OK;
+}
+
+relay_status relay_prepack_first_layer_weights(const relay_conv2d_desc* d, const void* w_oihw, void* w_packed,
+                                               void* hip_stream) {
+  relay::ConvArgs a;
+  relay_status st = first_layer_args(d, &a);
+  if (st != RELAY_OK) return st;
+  if (!w_oihw || !w_packed) return fail(RELAY_ERR_NULL, "w_oihw and w_packed are required");
+  if (!aligned(w_oihw, 2) || !aligned(w_packed, 16)) return fail(RELAY_ERR_ALIGN, "w_oihw must be 2-byte, w_packed 16-byte aligned");
+  return device_status(relay::launch_pack_first_filters(w_oihw, w_packed, a.K, static_cast<hipStream_t>(hip_stream)),
+                       "first-layer filter packing launch");
+}
+
+relay_status relay_fused_conv2d_first_layer(const relay_conv2d_desc* d, const void* x_nchw, const void* w_packed,
+                                            const float* bias, const float* bn_scale, const float* bn_shift,
+                                            void* y_nhwc, void* hip_stream) {
+  relay::ConvArgs a;
+  relay_status st = first_layer_args(d, &a);
+  if (st != RELAY_OK) return st;
+  if (!x_nchw || !w_packed || !y_nhwc) return fail(RELAY_ERR_NULL, "x_nchw, w_packed and y_nhwc are required");
+  if ((st = check_optional(bias, d->flags & RELAY_HAS_BIAS, "bias")) != RELAY_OK) return st;
+  if ((st = check_optional(bn_scale, d->flags & RELAY_HAS_BN, "bn_scale")) != RELAY_OK) return st;
+  if ((st = check_optional(bn_shift, d->flags & RELAY_HAS_BN, "bn_shift")) != RELAY_OK) return st;
+  if (y_nhwc == x_nchw) return fail(RELAY_ERR_UNSUPPORTED, "output must not alias an input");
+  if (!aligned(x_nchw, 16) || !aligned(y_nhwc, 16) || !aligned(w_packed, 16))
+    return fail(RELAY_ERR_ALIGN, "x_nchw, w_packed and y_nhwc must be 16-byte aligned");
+  a.x = x_nchw; a.w = w_packed; a.y = y_nhwc; a.bias = bias; a.scale = bn_scale; a.shift = bn_shift;
+  return device_status(relay::launch_conv_first(a, static_cast<hipStream_t>(hip_stream)), "first-layer conv2d launch");
+}
+
 // quantized form of a combined launch: the int32 bias and the scaling rule of the tail (NULL: the float form)
 struct CombinedQuant {
   const int32_t* bias;

@@ -136,6 +136,11 @@ int conv_stream_pick(const ConvArgs& a, bool is_i8);  // variant, or -1
 int conv_stream_variant_count();
 hipError_t launch_conv_stream(const ConvArgs& a, bool is_i8, int variant, hipStream_t st);
 void conv_stream_kernel_name(const ConvArgs& a, bool is_i8, int variant, char* buf, size_t len);
+// The first layer of an image network: 3 channels, 3x3 / stride 2 / pad 1, NCHW fp16 in, NHWC fp16 out (conv_first.hip).
+bool conv_first_supported(const ConvArgs& a);
+size_t conv_first_packed_bytes(int K);
+hipError_t launch_pack_first_filters(const void* w_oihw, void* out, int K, hipStream_t st);
+hipError_t launch_conv_first(const ConvArgs& a, hipStream_t st);   // a.w: the packed filters
 hipError_t launch_dwconv_f16(const ConvArgs& a, hipStream_t st);
 // The depthwise conv and its 1x1 conv in one launch (dwpw.hip).
 int dwpw_variant_count();

@@ -27,7 +27,8 @@ class FusedNet:
     def __init__(self, ops, params: List[dict], batch: int, h: int, w: int, mode: str = "f16",
                  shifts: Optional[List[dict]] = None, in_channels: int = 3, device: str = "cuda:0",
                  overlap_shortcuts: bool = False, fused: bool = True, combine: bool = False,
-                 fold_scale: bool = False, fuse_pool: bool = True, fuse_dwpw: bool = True):
+                 fold_scale: bool = False, fuse_pool: bool = True, fuse_dwpw: bool = True,
+                 first_layer_direct: bool = True):
         assert mode in ("f16", "i8")
         assert fused or mode == "f16"
         # combine: convs that share input, window and tail run as one launch ("windows": also a 1x1 conv
@@ -61,10 +62,24 @@ class FusedNet:
         self.x_nchw = torch.zeros((batch, in_channels, h, w), dtype=self.tdtype, device=self.dev)
         self.shape["x"] = (in_channels, h, w)
         first = ops[0]
-        # a first-layer conv on <= 4 channels reads the pre-padded NHWC4 form of the image
-        self.stem_nhwc4 = first.kind == "conv" and first.src == "x" and in_channels <= 4 and \
+        only_reader = first.kind == "conv" and first.src == "x" and \
             sum(1 for o in ops if o.src == "x" or o.res == "x") == 1
-        if self.stem_nhwc4:
+        # a first-layer conv the library reads straight from the NCHW image (3 channels, 3x3 / stride 2): no
+        # converted or padded copy of the image at all
+        self.stem_direct = False
+        if only_reader and fused and mode == "f16" and not (combine or fold_scale) and first_layer_direct and \
+                not first.res:
+            d0 = B.conv_desc(batch, in_channels, h, w, first.cout, first.r, first.r, first.stride, first.pad,
+                             self.dtype, B.RELAY_NCHW, 0)
+            try:
+                self.stem_direct = B.relay_conv2d_first_layer_supported(d0)
+            except B.RelayError:
+                self.stem_direct = False
+        # a first-layer conv on <= 4 channels reads the pre-padded NHWC4 form of the image
+        self.stem_nhwc4 = only_reader and in_channels <= 4 and not self.stem_direct
+        if self.stem_direct:
+            self.bufs["x"] = self.x_nchw
+        elif self.stem_nhwc4:
             d0 = B.conv_desc(batch, in_channels, h, w, first.cout, first.r, first.r, first.stride, first.pad,
                              self.dtype, B.RELAY_NHWC4_PADDED, 0)
             hp, wp = B.relay_nhwc4_padded_shape(d0)
@@ -94,6 +109,18 @@ class FusedNet:
             elif op.kind == "conv" and (i in group_of or op.dst in self.view_of or not src.is_contiguous()):
                 idxs = group_of.get(i, [i])
                 self._emit_conv_views([ops[j] for j in idxs], [params[j] for j in idxs], batch)
+            elif op.kind == "conv" and i == 0 and self.stem_direct:
+                flags = B.flags_of(p.get("bias"), p.get("scale"), None, op.relu)
+                d = B.conv_desc(batch, cin_l, hi, wi, op.cout, op.r, op.r, op.stride, op.pad, self.dtype, B.RELAY_NCHW, flags)
+                ho, wo = B.relay_conv2d_out_shape(d)
+                wsrc = torch.from_numpy(np.ascontiguousarray(p["w"])).to(self.dev)
+                y = torch.empty((batch, ho, wo, op.cout), dtype=self.tdtype, device=self.dev)
+                bias, sc, sf = (self._f32(p.get(k)) for k in ("bias", "scale", "shift"))
+                wp = torch.empty(B.relay_first_layer_packed_weight_bytes(d), dtype=torch.uint8, device=self.dev)
+                B.relay_prepack_first_layer_weights(d, wsrc, wp)
+                self._add(op.name, B.relay_fused_conv2d_first_layer, (d, src, wp, bias, sc, sf, y))
+                self.keep += [wp, d]
+                self.bufs[op.dst], self.shape[op.dst] = y, (op.cout, ho, wo)
             elif op.kind == "conv":
                 flags = B.flags_of(p.get("bias"), p.get("scale"), op.res, op.relu)
                 if i == 0 and self.stem_nhwc4:

@@ -122,6 +122,20 @@ def run_dwconv_f16(x, w, stride, pad, bias=None, scale=None, shift=None, relu=Fa
     return from_nhwc(y, c)
 
 
+def run_first_layer_f16(x, w, bias=None, scale=None, shift=None, relu=False):
+    """The first-layer entry point: NCHW image in, NHWC out (returned as NCHW)."""
+    n, c, h, wd = x.shape
+    k = w.shape[0]
+    d = B.conv_desc(n, c, h, wd, k, 3, 3, 2, 1, B.RELAY_F16, B.RELAY_NCHW, B.flags_of(bias, scale, None, relu))
+    ho, wo = B.relay_conv2d_out_shape(d)
+    y = torch.full((n, ho, wo, k), float("nan"), dtype=torch.float16, device=DEV)
+    wp = torch.empty(B.relay_first_layer_packed_weight_bytes(d), dtype=torch.uint8, device=DEV)
+    B.relay_prepack_first_layer_weights(d, up(w), wp)
+    B.relay_fused_conv2d_first_layer(d, up(x), wp, up(bias), up(scale), up(shift), y)
+    torch.cuda.synchronize()
+    return from_nhwc(y, k)
+
+
 def run_conv_pool_f16(x, w, stride, pad, bias=None, scale=None, shift=None, relu=False, nhwc4=True, fused=True):
     """conv -> 3x3/s2/p1 max pool, fp16: one pooled launch (fused) or the two separate calls."""
     n, c, h, wd = x.shape

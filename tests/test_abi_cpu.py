@@ -207,6 +207,29 @@ def test_dwconv_dense_and_glue_checks():
     assert buf.value.decode().startswith("igemm_conv_kernel<false")
 
 
+def test_first_layer_checks():
+    fl = "relay_fused_conv2d_first_layer"
+    good = dict(c=3, k=32, h=32, w=32, stride=2, pad=1, layout=B.RELAY_NCHW)
+    args = (FAKE, FAKE + 4096, None, None, None, FAKE + 8192, None)
+    assert _status(fl, C.byref(_d(**good)), None, *args[1:]) == 1
+    assert _status(fl, C.byref(_d(**{**good, "dtype": B.RELAY_I8})), *args) == 3
+    assert _status(fl, C.byref(_d(**{**good, "layout": B.RELAY_NHWC})), *args) == 4
+    for bad in (dict(c=4), dict(k=24), dict(k=256), dict(w=36), dict(h=31), dict(stride=1), dict(pad=0), dict(r=5, s=5, pad=2),
+                dict(flags=B.HAS_RESIDUAL)):
+        assert _status(fl, C.byref(_d(**{**good, **bad})), *args) == 4, bad
+    assert _status(fl, C.byref(_d(**good)), FAKE + 2, *args[1:]) == 5
+    assert _status(fl, C.byref(_d(**{**good, "flags": B.HAS_BIAS})), *args) == 1       # flag set, array missing
+    nb = C.c_size_t(0)
+    assert _status("relay_first_layer_packed_weight_bytes", C.byref(_d(**good)), C.byref(nb)) == 0 and nb.value == 32 * 14 * 4
+    assert _status("relay_first_layer_packed_weight_bytes", C.byref(_d(**{**good, "k": 24})), C.byref(nb)) == 4
+    assert _status("relay_prepack_first_layer_weights", C.byref(_d(**good)), None, FAKE, None) == 1
+    assert _status("relay_prepack_first_layer_weights", C.byref(_d(**good)), FAKE, FAKE + 8, None) == 5
+    ok = C.c_int32(-1)
+    assert _status("relay_conv2d_first_layer_supported", C.byref(_d(**good)), C.byref(ok)) == 0 and ok.value == 1
+    assert _status("relay_conv2d_first_layer_supported", C.byref(_d(**{**good, "c": 4})), C.byref(ok)) == 0 and ok.value == 0
+    assert _status("relay_conv2d_first_layer_supported", C.byref(_d(**good)), None) == 1
+
+
 def test_product_path_does_not_import_the_oracle():
     pkg = os.path.join(ROOT, "paper_1904_08368_amd")
     for dirpath, _, files in os.walk(pkg):
