@@ -152,6 +152,45 @@ def _measured_ceilings():
     return res
 
 
+def _layer_boundary_costs():
+    """What a boundary between two dependent layers costs on this machine: as a kernel boundary (back-to-back
+    empty launches replayed from a HIP graph) and as a barrier across a resident grid inside one launch
+    (the library's probe: device-scope release + atomic arrival + bounded poll + acquire, every thread
+    storing one word per round), for the three grid sizes a batch-1 layer chain would use."""
+    import torch
+    from paper_1904_08368_amd import binding as B
+    cells = torch.zeros(4, dtype=torch.int32, device="cuda")
+
+    def timed(fn, reps):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for _ in range(reps):
+                fn()
+        g.replay()
+        ts = []
+        for _ in range(5):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            g.replay()
+            e1.record()
+            e1.synchronize()
+            ts.append(e0.elapsed_time(e1) * 1e3 / reps)
+        return statistics.median(ts)
+
+    res = {"kernel_boundary_us": round(timed(lambda: B.relay_probe_grid_barrier(256, 0, 1, cells), 20), 2), "grid_barrier_us": {}}
+    rounds = 100
+    for wgs in (64, 128, 256):
+        data = torch.zeros(wgs * 256, dtype=torch.float32, device="cuda")
+        us = timed(lambda: B.relay_probe_grid_barrier(wgs, rounds, 1 << 22, cells, data), 4)
+        res["grid_barrier_us"][str(wgs)] = round((us - res["kernel_boundary_us"]) / rounds, 2)
+    torch.cuda.synchronize()
+    res["waits_ran_out"] = int(cells[1].item())
+    return res
+
+
 def _dominant(rows, peak):
     """The conv kernel variant with the most time per step among `rows`: (name, roofline dict)."""
     by_kernel = {}
@@ -288,6 +327,7 @@ def main() -> int:
         "roofline": roofline,
     }
     extra = {"measured_ceilings": ceil,
+             "layer_boundary_costs": _layer_boundary_costs(),
              "fusion_extraction": {"operators": len(graph.nodes), "groups": len(groups),
                                    "host_us_per_call_incl_marshalling": round(fuse_us, 1)},
              "conv_kernels_only_tflops": round(conv_gf / conv_us * 1e3, 2),

@@ -518,7 +518,19 @@ relay_status relay_set_conv_workgroups(int32_t workgroups);
  *                     out: device, 4 bytes (practically never written).
  *   relay_probe_copy  dst[i] = src[i] over `bytes` bytes (a multiple of 16) in 16-byte pieces, a
  *                     grid-stride loop of 4096 workgroups: reads and writes `bytes` each.
+ *   relay_probe_grid_barrier  one launch of `workgroups` (1..1024) workgroups of 256 threads that meet in
+ *                     `rounds` barriers across the whole grid: a device-scope release and an atomic arrival,
+ *                     a bounded poll (at most spin_limit device-scope loads per wait), an acquire -- what a
+ *                     boundary between dependent layers inside ONE launch costs, to set beside the cost
+ *                     of a kernel boundary (paper Section 5.2, launch overhead at small batch).  cells: 16
+ *                     bytes on the device, zero before the first launch; a launch whose waits all
+ *                     succeed leaves cells[0] = cells[2] = 0 for the next one.  cells[1] != 0 afterwards:
+ *                     a wait ran out (every workgroup then leaves; clear cells before the next launch).
+ *                     data: NULL, or workgroups * 256 floats that every thread adds to before each barrier
+ *                     (gives the release something to write back).  rounds == 0: an empty kernel.
  * Device pointers owned by the caller; only enqueue on hip_stream. */
+relay_status relay_probe_grid_barrier(int32_t workgroups, int32_t rounds, uint32_t spin_limit, void* cells, void* data,
+                                      void* hip_stream);
 relay_status relay_probe_mfma(int32_t dtype, int32_t iters, int32_t workgroups, void* out, void* hip_stream);
 relay_status relay_probe_copy(const void* src, void* dst, int64_t bytes, void* hip_stream);
 

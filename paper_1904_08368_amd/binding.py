@@ -86,6 +86,7 @@ SIGNATURES = {
     "relay_realize_conv": [_I, C.c_int64, _P, _P, _P, _P, C.c_float, C.c_float, C.c_float, _P, _P, _P, _P, _SZ, _P],
     "relay_probe_mfma": [_I, _I, _I, _P, _P],
     "relay_probe_copy": [_P, _P, C.c_int64, _P],
+    "relay_probe_grid_barrier": [_I, _I, C.c_uint32, _P, _P, _P],
     "relay_set_conv_tile": [_I],
     "relay_set_conv_split": [_I],
     "relay_set_conv_workgroups": [_I],
@@ -425,6 +426,10 @@ def relay_conv2d_maxpool_kernel_name(d: ConvDesc) -> str:
 
 def relay_probe_mfma(dtype: int, iters: int, workgroups: int, out) -> None:
     _check(lib().relay_probe_mfma(dtype, iters, workgroups, _ptr(out), _stream()))
+
+
+def relay_probe_grid_barrier(workgroups: int, rounds: int, spin_limit: int, cells, data=None) -> None:
+    _check(lib().relay_probe_grid_barrier(workgroups, rounds, spin_limit, _ptr(cells), _ptr(data), _stream()))
 
 
 def relay_probe_copy(src, dst, nbytes: int) -> None:

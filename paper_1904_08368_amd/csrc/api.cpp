@@ -1177,6 +1177,21 @@ relay_status relay_probe_mfma(int32_t dtype, int32_t iters, int32_t workgroups, 
                        "probe launch");
 }
 
+relay_status relay_probe_grid_barrier(int32_t workgroups, int32_t rounds, uint32_t spin_limit, void* cells, void* data,
+                                      void* hip_stream) {
+  // every workgroup must be resident at once, or the first barrier could never complete: 256 threads, no
+  // LDS to speak of, a handful of registers -- eight such workgroups fit a compute unit; four per unit
+  // of the smallest chip this library is built for is the limit taken here
+  if (workgroups < 1 || workgroups > 1024) return fail(RELAY_ERR_UNSUPPORTED, "workgroups=%d outside 1..1024", workgroups);
+  if (rounds < 0 || rounds > (1 << 20)) return fail(RELAY_ERR_UNSUPPORTED, "rounds=%d outside 0..2^20", rounds);
+  if (spin_limit < 1) return fail(RELAY_ERR_UNSUPPORTED, "spin_limit must be at least 1");
+  if (!cells) return fail(RELAY_ERR_NULL, "cells is NULL");
+  if (!aligned(cells, 4) || (data && !aligned(data, 4))) return fail(RELAY_ERR_ALIGN, "cells and data must be 4-byte aligned");
+  return device_status(relay::launch_probe_grid_barrier(workgroups, rounds, spin_limit, static_cast<unsigned*>(cells),
+                                                        static_cast<float*>(data), static_cast<hipStream_t>(hip_stream)),
+                       "grid barrier probe launch");
+}
+
 relay_status relay_probe_copy(const void* src, void* dst, int64_t bytes, void* hip_stream) {
   if (!src || !dst) return fail(RELAY_ERR_NULL, "src and dst are required");
   if (bytes < 16 || bytes % 16 || bytes > ((int64_t)1 << 40)) return fail(RELAY_ERR_SHAPE, "bytes=%lld must be a multiple of 16 in 16..2^40", (long long)bytes);

@@ -194,6 +194,7 @@ hipError_t launch_recode_u8_padded(const void* x, void* y, int N, int H, int W, 
 hipError_t launch_fold_zero_point(int K, long per_k, const int8_t* w, const int32_t* bias, int zero_point, int32_t* out, hipStream_t st);
 hipError_t launch_qconv16_direct(const ConvArgs& a, hipStream_t st);
 // measured ceilings (probe.hip): register-only matrix-instruction loop, streaming copy
+hipError_t launch_probe_grid_barrier(int workgroups, int rounds, unsigned spin_limit, unsigned* cells, float* data, hipStream_t st);
 hipError_t launch_probe_mfma(bool is_i8, int iters, int workgroups, unsigned* out, hipStream_t st);
 hipError_t launch_probe_copy(const void* src, void* dst, long bytes, hipStream_t st);
 hipError_t launch_pack_filters_rows(const void* w_oihw, void* w_packed, int K, int Csrc, int R, int S, int ck,

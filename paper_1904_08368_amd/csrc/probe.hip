@@ -1,6 +1,8 @@
 // Measured ceilings of the chip, for the roofline figures of the benchmark: a register-only loop of
 // matrix instructions (what the matrix cores deliver when nothing feeds them from memory) and a
-// streaming copy (what HBM delivers to a kernel with nothing else to do).  Not part of any fused
+// streaming copy (what HBM delivers to a kernel with nothing else to do), and the cost of a barrier
+// across all workgroups of a resident grid (what a kernel that runs several dependent layers in one
+// launch would pay between them, to set beside the cost of a kernel boundary).  Not part of any fused
 // primitive function; a profiler run of these gives the "measured peak" beside the nominal one.
 #include "dma_common.hpp"
 
@@ -37,7 +39,48 @@ __global__ __launch_bounds__(256) void stream_copy_kernel(const uint4* src, uint
   for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
 
+// `rounds` barriers across the whole grid.  cells[0] counts arrivals (it only grows during a launch: round r
+// is over once it reaches (r + 1) * workgroups), cells[1] is set when a wait ran out of its `spin_limit`
+// polls, cells[2] counts workgroups that are done: the last one puts cells[0] and cells[2] back to zero for
+// the next launch.  Arrival is a device-scope release (the L2s of the chip's dies are not coherent with each
+// other) and an atomic add, the wait polls with device-scope loads and ends in an acquire -- what a layer
+// boundary inside one launch needs.  data (or NULL): every thread adds to a word of its own before each
+// barrier, so that the release has something to write back.  Every wait is bounded: a workgroup whose
+// wait runs out raises the flag and leaves, and so, one after another, do the others.
+__global__ __launch_bounds__(256) void grid_barrier_kernel(unsigned* cells, int rounds, unsigned spin_limit, float* data) {
+  __shared__ int ok;
+  const int tid = threadIdx.x;
+  for (int r = 0; r < rounds; ++r) {
+    if (data) data[(size_t)blockIdx.x * 256 + tid] += 1.0f;
+    __syncthreads();
+    if (tid == 0) {
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+      atomicAdd(cells, 1u);
+      const unsigned target = (unsigned)(r + 1) * gridDim.x;
+      bool good = false;
+      for (unsigned i = 0; i < spin_limit && !good; ++i) {
+        good = __hip_atomic_load(cells, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= target;
+        if (!good) __builtin_amdgcn_s_sleep(1);
+      }
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+      if (!good) atomicExch(cells + 1, 1u);
+      ok = good;
+    }
+    __syncthreads();
+    if (!ok) return;   // (the counters stay as they are: the caller clears them after a failed launch)
+  }
+  if (tid == 0 && atomicAdd(cells + 2, 1u) == gridDim.x - 1) {
+    atomicExch(cells, 0u);
+    atomicExch(cells + 2, 0u);
+  }
+}
+
 }  // namespace
+
+hipError_t launch_probe_grid_barrier(int workgroups, int rounds, unsigned spin_limit, unsigned* cells, float* data, hipStream_t st) {
+  hipLaunchKernelGGL(grid_barrier_kernel, dim3(workgroups), dim3(256), 0, st, cells, rounds, spin_limit, data);
+  return hipGetLastError();
+}
 
 hipError_t launch_probe_mfma(bool is_i8, int iters, int workgroups, unsigned* out, hipStream_t st) {
   if (is_i8) hipLaunchKernelGGL((mfma_loop_kernel<true>), dim3(workgroups), dim3(256), 0, st, iters, out);

@@ -230,6 +230,16 @@ def test_first_layer_checks():
     assert _status("relay_conv2d_first_layer_supported", C.byref(_d(**good)), None) == 1
 
 
+def test_grid_barrier_probe_checks():
+    gb = "relay_probe_grid_barrier"
+    assert _status(gb, 0, 1, 10, FAKE, None, None) == 4
+    assert _status(gb, 2048, 1, 10, FAKE, None, None) == 4        # more workgroups than are sure to be resident at once
+    assert _status(gb, 64, -1, 10, FAKE, None, None) == 4
+    assert _status(gb, 64, 1, 0, FAKE, None, None) == 4           # a wait that may not poll at all
+    assert _status(gb, 64, 1, 10, None, None, None) == 1
+    assert _status(gb, 64, 1, 10, FAKE + 2, None, None) == 5
+
+
 def test_product_path_does_not_import_the_oracle():
     pkg = os.path.join(ROOT, "paper_1904_08368_amd")
     for dirpath, _, files in os.walk(pkg):

@@ -97,3 +97,25 @@ def test_stream_kernel_is_not_chosen_by_default(G):
         for c, hw in ((64, 56), (128, 28), (256, 14), (512, 7)):
             d = B.conv_desc(n, c, hw, hw, c, 3, 3, 1, 1, dtype, B.RELAY_NHWC, B.RELU)
             assert "stream" not in B.relay_conv2d_kernel_name(d)
+
+
+def test_grid_barrier_probe_completes_and_its_bounded_wait_gives_up(G):
+    """The probe behind the layer-boundary figures of the benchmark: with a generous poll limit every
+    barrier completes, the counters come back to zero and every thread has counted every round; with a
+    limit of one poll (forced from the host) the kernel still ends -- a wait that runs out raises the flag
+    and the workgroups leave -- whatever the flag then says."""
+    from paper_1904_08368_amd import binding as B
+    cells = torch.zeros(4, dtype=torch.int32, device=G.DEV)
+    data = torch.zeros(128 * 256, dtype=torch.float32, device=G.DEV)
+    for _ in range(2):                                   # twice: the second launch starts from what the first left
+        B.relay_probe_grid_barrier(128, 50, 1 << 22, cells, data)
+        torch.cuda.synchronize()
+        assert cells.tolist() == [0, 0, 0, 0]
+    assert bool((data == 100).all())
+    B.relay_probe_grid_barrier(256, 20, 1, cells, None)
+    torch.cuda.synchronize()                             # returns: no wait is unbounded
+    assert cells[1].item() in (0, 1)
+    cells.zero_()
+    B.relay_probe_grid_barrier(64, 5, 1 << 22, cells, None)
+    torch.cuda.synchronize()
+    assert cells.tolist() == [0, 0, 0, 0]
