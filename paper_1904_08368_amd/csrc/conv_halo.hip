@@ -412,12 +412,8 @@ int conv_halo_pick(const ConvArgs& a, bool is_i8) {
 }
 
 void conv_halo_kernel_name(const ConvArgs& a, bool is_i8, int v, char* buf, size_t len) {
-  if (kHalo[v].hb == 1)
-    snprintf(buf, len, "conv3x3_halo_kernel<%s, %d, %d, %d, %d, %d>", is_i8 ? "true" : "false", kHalo[v].waves_m,
-             kHalo[v].waves_n, kHalo[v].tm, kHalo[v].tn, chunk_planes(a, is_i8));
-  else
-    snprintf(buf, len, "conv3x3_halo_kernel<%s, %d, %d, %d, %d, %d, %d>", is_i8 ? "true" : "false", kHalo[v].waves_m,
-             kHalo[v].waves_n, kHalo[v].tm, kHalo[v].tn, chunk_planes(a, is_i8), kHalo[v].hb);
+  snprintf(buf, len, "conv3x3_halo_kernel<%s, %d, %d, %d, %d, %d, %d>", is_i8 ? "true" : "false", kHalo[v].waves_m,
+           kHalo[v].waves_n, kHalo[v].tm, kHalo[v].tn, chunk_planes(a, is_i8), kHalo[v].hb);
 }
 
 hipError_t launch_conv_halo(const ConvArgs& a, bool is_i8, int v, hipStream_t st) {

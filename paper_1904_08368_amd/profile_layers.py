@@ -81,6 +81,8 @@ def main() -> int:
     conv_case("halo_f16_c64_56", 32, 64, 56, 64, 3, 1, 1, False, True)
     conv_case("halo_f16_c128_28", 32, 128, 28, 128, 3, 1, 1, False, False)
     conv_case("halo_f16_c256_14", 32, 256, 14, 256, 3, 1, 1, False, True)
+    conv_case("halo_f16_c64_56_tile_128x64", 32, 64, 56, 64, 3, 1, 1, False, True, tile=100)   # (the default there is the 256 x 64 tile)
+    conv_case("halo_f16_c256_56", 32, 256, 56, 256, 3, 1, 1, False, False)                      # (VGG-16's third stage: the 128 x 128 tile)
     conv_case("halo_i8_c64_56", 16, 64, 56, 64, 3, 1, 1, True, True)
     conv_case("halo_i8_c128_28", 16, 128, 28, 128, 3, 1, 1, True, False)
     # ---- the implicit-GEMM kernel: 64 x 64 tile with 256-byte chunks (stage 4), the stride-2 layers, 1x1 layers
@@ -110,6 +112,16 @@ def main() -> int:
         es = 1 if i8 else 2
         run("stem_pool_" + ("i8" if i8 else "f16"), B.relay_conv2d_maxpool_kernel_name(d), fn,
             2.0 * n * 112 * 112 * 64 * 147 / 1e9, (n * 224 * 224 * 3 + n * 56 * 56 * 64 + 64 * 147) * es / 1e6)
+
+    # ---- MobileNet-v1's first layer read from the NCHW image
+    d = B.conv_desc(32, 3, 224, 224, 32, 3, 3, 2, 1, B.RELAY_F16, B.RELAY_NCHW, B.flags_of(None, 1, None, True))
+    x = tensor((32, 3, 224, 224), False)
+    wpk = torch.empty(B.relay_first_layer_packed_weight_bytes(d), dtype=torch.uint8, device=dev)
+    B.relay_prepack_first_layer_weights(d, (tensor((32, 3, 3, 3), False) * 0.1).to(torch.float16), wpk)
+    y = torch.empty((32, 112, 112, 32), dtype=torch.float16, device=dev)
+    sc, sf = torch.ones(32, device=dev), torch.zeros(32, device=dev)
+    run("first_f16_c3_224", "conv_first_kernel", lambda d=d, x=x, wpk=wpk, sc=sc, sf=sf, y=y: B.relay_fused_conv2d_first_layer(d, x, wpk, None, sc, sf, y),
+        2.0 * 32 * 112 * 112 * 32 * 27 / 1e9, (32 * 224 * 224 * 3 + 32 * 112 * 112 * 32 + 32 * 27) * 2 / 1e6)
 
     # ---- depthwise 3x3 (MobileNet-v1, batch 32): the LDS-staged stride-1 kernel and the register-patch kernel
     for name, c, hw, stride, kernel in (("dw_s1_c128_56", 128, 56, 1, "dwconv3x3_s1_lds_kernel"), ("dw_s1_c64_112", 64, 112, 1, "dwconv3x3_s1_lds_kernel"),

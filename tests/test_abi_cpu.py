@@ -200,7 +200,7 @@ def test_dwconv_dense_and_glue_checks():
     assert _status("relay_conv2d_kernel_name", C.byref(_d(n=32, h=56, w=56)), buf, 128) == 0
     assert buf.value.decode() == "conv3x3_halo_kernel<false, 4, 1, 2, 2, 2, 2>"   # 3x3 / stride 1, 64 channels, 813 tiles of 128: the 256 x 64 variant
     assert _status("relay_conv2d_kernel_name", C.byref(_d(n=16, h=56, w=56)), buf, 128) == 0
-    assert buf.value.decode() == "conv3x3_halo_kernel<false, 2, 2, 2, 1, 2>"      # 407 tiles: one round of 128 x 64 tiles
+    assert buf.value.decode() == "conv3x3_halo_kernel<false, 2, 2, 2, 1, 2, 1>"   # 407 tiles: one round of 128 x 64 tiles
     assert _status("relay_conv2d_kernel_name", C.byref(_d(n=32, h=56, w=56, stride=2)), buf, 128) == 0
     assert buf.value.decode().startswith("igemm_dma_kernel<false")
     assert _status("relay_conv2d_kernel_name", C.byref(_d(c=24)), buf, 128) == 0
