@@ -327,7 +327,6 @@ def main() -> int:
         "roofline": roofline,
     }
     extra = {"measured_ceilings": ceil,
-             "layer_boundary_costs": _layer_boundary_costs(),
              "fusion_extraction": {"operators": len(graph.nodes), "groups": len(groups),
                                    "host_us_per_call_incl_marshalling": round(fuse_us, 1)},
              "conv_kernels_only_tflops": round(conv_gf / conv_us * 1e3, 2),
@@ -335,6 +334,7 @@ def main() -> int:
              "layers": [{k: (round(v, 3) if isinstance(v, float) else v) for k, v in r.items()} for r in rows]}
 
     if not a.no_extra:
+        extra["layer_boundary_costs"] = _layer_boundary_costs()
         # ---- the same stack with operator fusion switched off (the paper's fusion ablation, Section 5.2):
         #      contraction, bias add, scale/shift, residual add and relu as separate launches and tensors
         un = FusedNet(ops, params, a.batch, 224, 224, "f16", fused=False)
@@ -374,6 +374,12 @@ def main() -> int:
             "frac_of_int8_mfma_peak": round(qgf / qus * 1e3 / PEAK["i8"], 4),
             "layers": [{k: (round(v, 3) if isinstance(v, float) else v) for k, v in r.items()} for r in qrows]}
         del qn
+        q1 = FusedNet(qops, qp, 1, 224, 224, "i8", shifts=inputs.chain_shifts(qops))     # (config 4 names batch 1 too)
+        q1.load_input(inputs.image(4, 1, 3, 224, 224, "i8"))
+        if use_graph:
+            q1.capture()
+        extra["resnet18_int8_batch16"]["batch1_ms_per_img"] = round(_time_steps(q1, a.steps, a.warmup, use_graph) * 1e3, 4)
+        del q1
         # ---- config 5: MobileNet-v1, batch 32
         mops = fusion.fuse(graphs.mobilenet_v1())
         mp = inputs.net_params(mops, 5, "f16")
