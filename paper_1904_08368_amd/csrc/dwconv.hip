@@ -32,7 +32,8 @@ template <int STRIDE, int TH, int TW>
 __global__ __launch_bounds__(256) void dwconv3x3_f16_kernel(const ConvArgs a) {
   // all arguments as one batch of scalar loads with one wait (the compiler would load them where first used)
   asm volatile("" ::"s"(a.x), "s"(a.w), "s"(a.y), "s"(a.bias), "s"(a.scale), "s"(a.shift), "s"(a.N), "s"(a.H), "s"(a.W),
-               "s"(a.C), "s"(a.Ho), "s"(a.Wo), "s"(a.sh), "s"(a.ph), "s"(a.pw), "s"(a.flags));
+               "s"(a.C), "s"(a.Ho), "s"(a.Wo), "s"(a.sh), "s"(a.ph), "s"(a.pw), "s"(a.flags), "s"(a.fd_tiles_n.mul),
+               "s"(a.fd_tiles_n.shift), "s"(a.fd_wo.mul), "s"(a.fd_wo.shift), "s"(a.fd_howo.mul), "s"(a.fd_howo.shift));
   constexpr int IH = (TH - 1) * STRIDE + 3, IW = (TW - 1) * STRIDE + 3;
   constexpr unsigned kOob = 0x80000000u;
   const int cvecs = a.C >> 3;
@@ -40,12 +41,13 @@ __global__ __launch_bounds__(256) void dwconv3x3_f16_kernel(const ConvArgs a) {
   const unsigned total = (unsigned)(a.N * tiles_h * tiles_w * cvecs);  // < 2^31: checked by the launcher
   unsigned idx = (unsigned)xcd_remap(blockIdx.x, gridDim.x) * blockDim.x + threadIdx.x;
   if (idx >= total) return;
-  const int cv = (int)(idx % (unsigned)cvecs);
-  idx /= (unsigned)cvecs;
-  const int tw = (int)(idx % (unsigned)tiles_w);
-  idx /= (unsigned)tiles_w;
-  const int th = (int)(idx % (unsigned)tiles_h);
-  const int n = (int)(idx / (unsigned)tiles_h);
+  // (divisions by multiply-high with the launcher's constants -- fd_tiles_n: cvecs, fd_wo: tiles_w, fd_howo:
+  // tiles_h --: three software divisions per thread sat in front of the first load)
+  const unsigned i1 = fast_div(idx, a.fd_tiles_n), i2 = fast_div(i1, a.fd_wo);
+  const int cv = (int)(idx - i1 * (unsigned)cvecs);
+  const int tw = (int)(i1 - i2 * (unsigned)tiles_w);
+  const int n = (int)fast_div(i2, a.fd_howo);
+  const int th = (int)i2 - n * tiles_h;
   const int c0 = cv * 8;
   const int p0 = th * TH, q0 = tw * TW;
   const int ih0 = p0 * STRIDE - a.ph, iw0 = q0 * STRIDE - a.pw;
@@ -155,13 +157,14 @@ __global__ __launch_bounds__(NT) void dwconv3x3_s1_lds_kernel(const ConvArgs a) 
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int cblocks = a.C / (8 * CBV);
   const int tiles_w = (a.Wo + TW - 1) / TW, tiles_h = (a.Ho + TH - 1) / TH;
-  int t = xcd_remap(blockIdx.x, gridDim.x);  // (n, tile row, tile column, channel block), channel block fastest
-  const int cb = t % cblocks;
-  t /= cblocks;
-  const int tx = t % tiles_w;
-  t /= tiles_w;
-  const int ty = t % tiles_h;
-  const int n = t / tiles_h;
+  // (n, tile row, tile column, channel block), channel block fastest; divisions by multiply-high with the
+  // launcher's constants (fd_tiles_n: cblocks, fd_wo: tiles_w, fd_howo: tiles_h)
+  const unsigned t0 = (unsigned)xcd_remap(blockIdx.x, gridDim.x);
+  const unsigned t1 = fast_div(t0, a.fd_tiles_n), t2 = fast_div(t1, a.fd_wo);
+  const int cb = (int)(t0 - t1 * (unsigned)cblocks);
+  const int tx = (int)(t1 - t2 * (unsigned)tiles_w);
+  const int n = (int)fast_div(t2, a.fd_howo);
+  const int ty = (int)t2 - n * tiles_h;
   const int oy0 = ty * TH, ox0 = tx * TW;
   const int iy0 = oy0 - a.ph, ix0 = ox0 - a.pw;  // input coordinates of patch pixel (0, 0)
   const int c0 = cb * 8 * CBV;
@@ -254,7 +257,11 @@ __global__ __launch_bounds__(NT) void dwconv3x3_s1_lds_kernel(const ConvArgs a) 
 template <int CBV, int MTH, int NT>
 hipError_t launch_dw_lds(const ConvArgs& a, hipStream_t st) {
   const long tiles = (long)a.N * ((a.Ho + 2 * MTH - 1) / (2 * MTH)) * ((a.Wo + 27) / 28) * (a.C / (8 * CBV));
-  hipLaunchKernelGGL((dwconv3x3_s1_lds_kernel<CBV, MTH, NT>), dim3((unsigned)tiles), dim3(NT), 0, st, a);
+  ConvArgs b = a;   // the kernel's index decoding divides by these three
+  b.fd_tiles_n = make_fastdiv((uint32_t)(a.C / (8 * CBV)));
+  b.fd_wo = make_fastdiv((uint32_t)((a.Wo + 27) / 28));
+  b.fd_howo = make_fastdiv((uint32_t)((a.Ho + 2 * MTH - 1) / (2 * MTH)));
+  hipLaunchKernelGGL((dwconv3x3_s1_lds_kernel<CBV, MTH, NT>), dim3((unsigned)tiles), dim3(NT), 0, st, b);
   return hipGetLastError();
 }
 
@@ -262,7 +269,11 @@ template <int STRIDE, int TH, int TW>
 hipError_t launch_dw(const ConvArgs& a, hipStream_t st) {
   const long total = (long)a.N * ((a.Ho + TH - 1) / TH) * ((a.Wo + TW - 1) / TW) * (a.C / 8);
   dim3 grid((unsigned)((total + 255) / 256)), block(256);
-  hipLaunchKernelGGL((dwconv3x3_f16_kernel<STRIDE, TH, TW>), grid, block, 0, st, a);
+  ConvArgs b = a;   // the kernel's index decoding divides by these three
+  b.fd_tiles_n = make_fastdiv((uint32_t)(a.C / 8));
+  b.fd_wo = make_fastdiv((uint32_t)((a.Wo + TW - 1) / TW));
+  b.fd_howo = make_fastdiv((uint32_t)((a.Ho + TH - 1) / TH));
+  hipLaunchKernelGGL((dwconv3x3_f16_kernel<STRIDE, TH, TW>), grid, block, 0, st, b);
   return hipGetLastError();
 }
 

@@ -107,20 +107,22 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, OCC) void dwpw_fused_kernel
 
   const ConvArgs& pw = a.pw;
   asm volatile("" ::"s"(a.x), "s"(a.dw_w), "s"(a.dw_bias), "s"(a.dw_scale), "s"(a.dw_shift), "s"(a.dw_flags), "s"(a.N), "s"(a.H),
-               "s"(a.W), "s"(a.C), "s"(a.Ho), "s"(a.Wo), "s"(a.tiles_x), "s"(a.tiles_y), "s"(a.tiles_n));
+               "s"(a.W), "s"(a.C), "s"(a.Ho), "s"(a.Wo), "s"(a.tiles_x), "s"(a.tiles_y), "s"(a.tiles_n), "s"(a.fd_x.mul), "s"(a.fd_x.shift),
+               "s"(a.fd_y.mul), "s"(a.fd_y.shift), "s"(a.fd_n.mul), "s"(a.fd_n.shift));
   asm volatile("" ::"s"(pw.w), "s"(pw.y), "s"(pw.bias), "s"(pw.scale), "s"(pw.shift), "s"(pw.K), "s"(pw.Kp), "s"(pw.flags),
                "s"(pw.param_vec));
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave % WAVES_M, wn = wave / WAVES_M;
   // (image, tile row, tile column, channel tile), channel tile fastest: the workgroups that share a patch are neighbours
-  int t = xcd_remap(blockIdx.x, gridDim.x);
-  const int tile_n = t % a.tiles_n;
-  t /= a.tiles_n;
-  const int tx = t % a.tiles_x;
-  t /= a.tiles_x;
-  const int ty = t % a.tiles_y;
-  const int n = t / a.tiles_y;
+  // (divisions by multiply-high with host-computed constants: three software divisions would be a fifth of the
+  // vector instructions of a single-chunk tile)
+  const unsigned t0 = (unsigned)xcd_remap(blockIdx.x, gridDim.x);
+  const unsigned t1 = fast_div(t0, a.fd_n), t2 = fast_div(t1, a.fd_x);
+  const int tile_n = (int)(t0 - t1 * (unsigned)a.tiles_n);
+  const int tx = (int)(t1 - t2 * (unsigned)a.tiles_x);
+  const int n = (int)fast_div(t2, a.fd_y);
+  const int ty = (int)t2 - n * a.tiles_y;
   const int oy0 = ty * TH, ox0 = tx * TW, n0 = tile_n * BN;
   const int iy0 = oy0 * STRIDE - 1, ix0 = ox0 * STRIDE - 1;   // input coordinates of patch pixel (0, 0)
   const int nch = a.C / CK;
@@ -454,6 +456,9 @@ hipError_t launch_one(const DwPwArgs& a, hipStream_t st) {
   b.tiles_x = (a.Wo + TW - 1) / TW;
   b.tiles_y = (a.Ho + TH - 1) / TH;
   b.tiles_n = (a.pw.K + WAVES_N * TN * 32 - 1) / (WAVES_N * TN * 32);
+  b.fd_x = make_fastdiv((uint32_t)b.tiles_x);
+  b.fd_y = make_fastdiv((uint32_t)b.tiles_y);
+  b.fd_n = make_fastdiv((uint32_t)b.tiles_n);
   const long wgs = (long)a.N * b.tiles_y * b.tiles_x * b.tiles_n;
   hipLaunchKernelGGL((dwpw_fused_kernel<STRIDE, TH, TW, MH, MW, WAVES_M, WAVES_N, TM, TN, KP, NP, NFS, CMAX, OCC>), dim3((unsigned)wgs),
                      dim3(64 * WAVES_M * WAVES_N), 0, st, b);

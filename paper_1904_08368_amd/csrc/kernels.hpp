@@ -93,7 +93,8 @@ struct DwPwArgs {
   const float* dw_shift;
   unsigned dw_flags;
   int N, H, W, C, Ho, Wo, stride;
-  int tiles_x, tiles_y, tiles_n;   // set by the launcher of the kernel variant
+  int tiles_x, tiles_y, tiles_n;   // set by the launcher of the kernel variant,
+  FastDiv fd_x, fd_y, fd_n;        // with the divisions by them
   ConvArgs pw;
 };
 
