@@ -307,13 +307,17 @@ struct HaloTile {
 constexpr HaloTile kHalo[] = {{2, 2, 2, 1, 1}, {2, 2, 1, 1, 1}, {4, 1, 2, 2, 2}, {2, 2, 2, 2, 1}};
 constexpr int kNumHalo = 4;
 
-int chunk_planes(const ConvArgs& a, bool is_i8) {
+int chunk_planes(const ConvArgs& a, bool is_i8, int v) {
   const int ve = is_i8 ? 16 : 8;
+  // the 64 x 64 tile takes 256-byte chunks (half the barriers per product) where the channel count allows and
+  // the halo still fits the load slots
+  if (v == 1 && a.C % (4 * BKV * ve) == 0 && 4 * ((kHalo[v].bm() + 2 * (a.W + 1) + 2 + 15) / 16) <= XS * kHalo[v].hb * 4)
+    return 4;
   return a.C % (2 * BKV * ve) == 0 ? 2 : 1;
 }
 
 bool make_geom(const ConvArgs& a, bool is_i8, int v, HaloGeom& g, size_t& lds_bytes) {
-  const int kp = chunk_planes(a, is_i8), ve = is_i8 ? 16 : 8;
+  const int kp = chunk_planes(a, is_i8, v), ve = is_i8 ? 16 : 8;
   g.P = a.W + 1;
   g.F = (a.H + 1) * g.P;
   if ((long)a.N * g.F > 0x3fffffffL || g.F >= (1 << 21)) return false;
@@ -362,6 +366,7 @@ hipError_t launch_halo_typed(const ConvArgs& a, const HaloGeom& g, size_t lds_by
                              : launch_halo_one<IS_I8, 4, 1, 2, 2, 1, 2>(a, g, lds_bytes, st);
   if (v == 3) return kp == 2 ? launch_halo_one<IS_I8, 2, 2, 2, 2, 2>(a, g, lds_bytes, st)
                              : launch_halo_one<IS_I8, 2, 2, 2, 2, 1>(a, g, lds_bytes, st);
+  if (kp == 4) return launch_halo_one<IS_I8, 2, 2, 1, 1, 4>(a, g, lds_bytes, st);
   return kp == 2 ? launch_halo_one<IS_I8, 2, 2, 1, 1, 2>(a, g, lds_bytes, st)
                  : launch_halo_one<IS_I8, 2, 2, 1, 1, 1>(a, g, lds_bytes, st);
 }
@@ -391,6 +396,12 @@ bool conv_halo_supported(const ConvArgs& a, bool is_i8, int v) {
 // the range of tile counts where both kernels get two workgroups per CU.
 int conv_halo_pick(const ConvArgs& a, bool is_i8) {
   const bool thin = !is_i8 && a.C == 64 && a.K <= 64;   // (wide images too: 112 x 112 at batch 32 57.4 against 62.8 us, 224 x 224 216.8 against 226.5)
+  // fp16, 512 and more channels at 7 x 7 and below: the 64 x 64 tile with 256-byte chunks (a third of the global->LDS
+  // traffic of the implicit GEMM's 64 x 64 tile; 512 -> 512 at batch 32: 14.9 against 16.4 us)
+  if (!is_i8 && a.C >= 512 && a.W <= 7 && chunk_planes(a, is_i8, 1) == 4 && conv_halo_supported(a, is_i8, 1)) {
+    const long t64 = (((long)a.N * (a.H + 1) * (a.W + 1) + 63) / 64) * ((a.K + 63) / 64);
+    if (t64 >= 190 && t64 <= 512) return 1;
+  }
   if (a.C < 64 || (a.W > 56 && !thin) || !conv_halo_supported(a, is_i8, 0)) return -1;
   const long flat = (long)a.N * (a.H + 1) * (a.W + 1);
   const long t128 = ((flat + 127) / 128) * ((a.K + 63) / 64);
@@ -413,14 +424,14 @@ int conv_halo_pick(const ConvArgs& a, bool is_i8) {
 
 void conv_halo_kernel_name(const ConvArgs& a, bool is_i8, int v, char* buf, size_t len) {
   snprintf(buf, len, "conv3x3_halo_kernel<%s, %d, %d, %d, %d, %d, %d>", is_i8 ? "true" : "false", kHalo[v].waves_m,
-           kHalo[v].waves_n, kHalo[v].tm, kHalo[v].tn, chunk_planes(a, is_i8), kHalo[v].hb);
+           kHalo[v].waves_n, kHalo[v].tm, kHalo[v].tn, chunk_planes(a, is_i8, v), kHalo[v].hb);
 }
 
 hipError_t launch_conv_halo(const ConvArgs& a, bool is_i8, int v, hipStream_t st) {
   HaloGeom g;
   size_t lds_bytes;
   if (!make_geom(a, is_i8, v, g, lds_bytes)) return hipErrorInvalidValue;
-  const int kp = chunk_planes(a, is_i8);
+  const int kp = chunk_planes(a, is_i8, v);
   return is_i8 ? launch_halo_typed<true>(a, g, lds_bytes, v, kp, st) : launch_halo_typed<false>(a, g, lds_bytes, v, kp, st);
 }
 

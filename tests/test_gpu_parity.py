@@ -300,6 +300,8 @@ def test_maxpool_window_stride_and_padding(G, geom):
 HALO_SHAPES = [  # n, c, h, w, k
     (2, 64, 23, 27, 192), (1, 32, 9, 11, 37), (3, 128, 14, 14, 128), (1, 256, 7, 7, 64), (2, 64, 56, 56, 64),
     (5, 96, 5, 6, 72), (1, 64, 1, 1, 64), (2, 64, 2, 40, 24),
+    # several 256-byte chunks (the 64 x 64 tile's long-chunk form), one chunk, a halo too wide for it
+    (1, 512, 7, 7, 192), (2, 128, 9, 11, 72), (1, 384, 5, 20, 24), (1, 384, 5, 40, 24),
 ]
 
 
@@ -329,7 +331,8 @@ def test_fp16_halo_kernel(G, shape, variant):
 
 
 @pytest.mark.parametrize("variant", [0, 1, 2, 3])
-@pytest.mark.parametrize("shape", [(2, 64, 23, 27, 192), (1, 128, 9, 11, 40), (2, 256, 14, 14, 64), (1, 64, 56, 56, 64)])
+@pytest.mark.parametrize("shape", [(2, 64, 23, 27, 192), (1, 128, 9, 11, 40), (2, 256, 14, 14, 64), (1, 64, 56, 56, 64), (1, 512, 7, 7, 136),
+                                   (3, 768, 5, 6, 72)])
 def test_int8_halo_kernel_bit_exact(G, shape, variant):
     n, c, h, w, k = shape
     g = _rng(950 + c + h)
