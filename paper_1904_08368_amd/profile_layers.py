@@ -86,7 +86,8 @@ def main() -> int:
     conv_case("halo_i8_c64_56", 16, 64, 56, 64, 3, 1, 1, True, True)
     conv_case("halo_i8_c128_28", 16, 128, 28, 128, 3, 1, 1, True, False)
     # ---- the implicit-GEMM kernel: 64 x 64 tile with 256-byte chunks (stage 4), the stride-2 layers, 1x1 layers
-    conv_case("igemm_f16_c512_7", 32, 512, 7, 512, 3, 1, 1, False, True)
+    conv_case("igemm_f16_c512_7", 32, 512, 7, 512, 3, 1, 1, False, True, tile=15)   # (forced: the default there is the kernel of the next case)
+    conv_case("halo_f16_c512_7", 32, 512, 7, 512, 3, 1, 1, False, True)
     conv_case("igemm_i8_c512_7", 16, 512, 7, 512, 3, 1, 1, True, True)
     conv_case("igemm_i8_c256_14", 16, 256, 14, 256, 3, 1, 1, True, False)
     conv_case("igemm_f16_s2_c64_56", 32, 64, 56, 128, 3, 2, 1, False, False)
