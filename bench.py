@@ -156,7 +156,7 @@ def _layer_boundary_costs():
     """What a boundary between two dependent layers costs on this machine: as a kernel boundary (back-to-back
     empty launches replayed from a HIP graph) and as a barrier across a resident grid inside one launch
     (the library's probe: device-scope release + atomic arrival + bounded poll + acquire, every thread
-    storing one word per round), for the three grid sizes a batch-1 layer chain would use."""
+    storing one word per round), for the grid sizes a batch-1 layer chain would use."""
     import torch
     from paper_1904_08368_amd import binding as B
     cells = torch.zeros(4, dtype=torch.int32, device="cuda")
@@ -182,7 +182,7 @@ def _layer_boundary_costs():
 
     res = {"kernel_boundary_us": round(timed(lambda: B.relay_probe_grid_barrier(256, 0, 1, cells), 20), 2), "grid_barrier_us": {}}
     rounds = 100
-    for wgs in (64, 128, 256):
+    for wgs in (16, 64, 128, 256):
         data = torch.zeros(wgs * 256, dtype=torch.float32, device="cuda")
         us = timed(lambda: B.relay_probe_grid_barrier(wgs, rounds, 1 << 22, cells, data), 4)
         res["grid_barrier_us"][str(wgs)] = round((us - res["kernel_boundary_us"]) / rounds, 2)
