@@ -43,7 +43,7 @@ __global__ __launch_bounds__(128) void conv_first_kernel(const ConvArgs a) {
   typedef const unsigned __attribute__((address_space(4)))* const_words;
   const const_words wt = (const_words)(unsigned long)a.w;
   const int tid = threadIdx.x;
-  // ---- this thread's four pixels: (n, p, q0 .. q0 + 3)
+  // ---- this thread's kPix pixels: (n, p, q0 .. q0 + kPix - 1)
   const int wq = a.Wo / kPix;                                // threads per output row
   const unsigned t_raw = blockIdx.x * blockDim.x + tid, t_end = (unsigned)(a.N * a.Ho * wq);
   const bool live = t_raw < t_end;                           // (threads past the end load the last pixels again and store nothing)
